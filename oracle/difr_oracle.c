@@ -1,0 +1,407 @@
+/*
+ * difr_oracle.c -- CPU oracle for the per-token verification scores.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+ * verifier's vocabulary pass computes.  It exists so that the GPU library can be
+ * checked against something independent of it.  It shares no code, header,
+ * table or constant generator with the HIP path, and nothing in the product
+ * path may call it: only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg do.
+ *
+ * Everything is IEEE double, one row at a time, one vocabulary entry at a time,
+ * in the order the paper states the steps.  Rows are independent, so the batch
+ * entry points parallelise the OUTERMOST row loop with OpenMP and nothing else.
+ *
+ * What each function follows (paper: "Verifying LLM Inference to Detect Model
+ * Weight Exfiltration"):
+ *   - temperature softmax ................. Sec. 3.2, the softmax(z/T) equation
+ *   - IPT sampler (CDF, first C_t > u) .... Sec. 3.2, Algorithm "IPT Sampler"
+ *   - Gumbel-max sampler .................. Sec. 3.2, Algorithm "Gumbel-Max Sampler"
+ *   - Token-IPT-DiFR interval and score ... Sec. 6.2 and the appendix algorithm
+ *                                           "convolved Gaussian score"
+ *   - Token-DiFR noise, ranking, A_{sigma,i}  Sec. 6.3 and the appendix algorithm
+ *                                           for the Gumbel likelihood estimator
+ *   - regenerate-and-compare per position . Sec. 5.1 and the appendix algorithm
+ *                                           "verification via prefill"
+ *   - pooling and flagging ................ Sec. 5.2 (threshold rule), Sec. 6.4,
+ *                                           appendix "Response to detecting
+ *                                           exfiltration attempts" (score, pool, flag)
+ *
+ * Readings taken where the paper is silent or inconsistent:
+ *   - H(seed || i) is Philox4x32-10 (Salmon et al., SC'11), key = the two halves
+ *     of the 64-bit sequence seed, counter = (v >> 2, position, sequence, stream),
+ *     output word v & 3.  stream 0 = Gumbel noise, stream 1 = the IPT uniform.
+ *   - 32 bits r -> uniform: k = r >> 9, u = (2k + 1) * 2^-24, strictly inside (0,1)
+ *     and exactly representable in single and double precision.
+ *   - Gumbel: g = -ln(-ln u), natural logarithm.
+ *   - the Gumbel-max sampler's printed "p_t + z_t" is read as log p_t + g_t, which
+ *     has the same argmax as x_t / T + g_t (Sec. 3.2 text; Sec. 6.3 ranks by
+ *     l_i + T G_i, again the same argmax for T > 0).
+ *   - margin = max_v (x_v/T + g_v) - (x_t/T + g_t) for the claimed token t, i.e.
+ *     -min_i A_{sigma,i} / T in the appendix algorithm's notation.
+ *   - argmax ties go to the lowest index.
+ *   - CDF in ascending vocabulary index, no sorting, no filtering; the claimed
+ *     token's interval is [a, b) (sampler rule C_t > u).
+ *   - Token-IPT-DiFR: mu = x = u in the printed algorithm; sigma is the Gaussian
+ *     width, eps the small constant inside the logarithm.
+ *   - pooling is the per-sequence mean; scores are suspiciousness, so a sequence
+ *     is flagged unless mean <= tau (a NaN mean is flagged).
+ *
+ * Parity pins (tests/test_oracle_*.py): Philox known-answer vectors; closed forms
+ * of the k -> u -> g map and its moments; brute force with exact rationals and
+ * multi-precision on tiny vocabularies; library softmax / cumsum / searchsorted;
+ * chi-square of sample frequencies; Gumbel max-stability; scipy / mpmath normal
+ * CDF.  No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_DTYPE_BF16 0
+#define ORACLE_DTYPE_F32 1
+
+#define ORACLE_FLAG_MATCH 1u
+#define ORACLE_FLAG_INVALID_CLAIM 2u
+#define ORACLE_FLAG_NONFINITE 4u
+
+#define ORACLE_STREAM_GUMBEL 0u
+#define ORACLE_STREAM_IPT 1u
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10, from the published round definition.                        */
+/* One round maps (c0,c1,c2,c3) with key (k0,k1) to                           */
+/*   (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1, lo(M0*c0));                */
+/* the key is bumped by the Weyl constants between rounds.                    */
+/* ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+    const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += W0;
+            k1 += W1;
+        }
+        uint64_t p0 = M0 * (uint64_t)c0;
+        uint64_t p1 = M1 * (uint64_t)c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* The 32 noise bits of vocabulary entry v at (seed, sequence, position, stream). */
+uint32_t oracle_noise_word(uint64_t seed, uint32_t seq, uint32_t pos, uint32_t stream, uint64_t v)
+{
+    uint32_t ctr[4] = { (uint32_t)(v >> 2), pos, seq, stream };
+    uint32_t key[2] = { (uint32_t)(seed & 0xFFFFFFFFu), (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[v & 3u];
+}
+
+/* 32 bits -> uniform strictly inside (0,1): 23 bits, midpoint of each cell. */
+double oracle_bits_to_uniform(uint32_t r)
+{
+    uint32_t k = r >> 9;
+    return (2.0 * (double)k + 1.0) * 0x1p-24;
+}
+
+/* Standard Gumbel from a uniform: g = -ln(-ln u).  For u > 1/2 the inner
+ * logarithm is taken as log1p(-(1-u)); 1-u is exact for the u above, so this is
+ * the same real number evaluated without cancellation. */
+double oracle_uniform_to_gumbel(double u)
+{
+    double t;
+    if (u > 0.5)
+        t = -log1p(-(1.0 - u));
+    else
+        t = -log(u);
+    return -log(t);
+}
+
+/* Exact value of a stored logit as a double. */
+static double decode_bf16(uint16_t h)
+{
+    uint32_t w = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &w, sizeof f);
+    return (double)f;
+}
+
+void oracle_decode_row(const void *row, int dtype, int64_t V, double *x)
+{
+    if (dtype == ORACLE_DTYPE_BF16) {
+        const uint16_t *p = (const uint16_t *)row;
+        for (int64_t v = 0; v < V; ++v) x[v] = decode_bf16(p[v]);
+    } else {
+        const float *p = (const float *)row;
+        for (int64_t v = 0; v < V; ++v) x[v] = (double)p[v];
+    }
+}
+
+/* Fill bits[v] with the raw noise words of one row (Gumbel or IPT stream). */
+void oracle_noise_row(uint64_t seed, uint32_t seq, uint32_t pos, uint32_t stream, int64_t V, uint32_t *bits)
+{
+    for (int64_t v = 0; v < V; ++v) bits[v] = oracle_noise_word(seed, seq, pos, stream, (uint64_t)v);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-DiFR, one row.                                                       */
+/*   y_v = x_v / T + g_v  for every v;  vhat = lowest index attaining max y;  */
+/*   margin = y_vhat - y_t;  gap2 = y_vhat - (largest y over v != vhat).      */
+/* claimed < 0 or >= V: margin and claimed_score are NaN, INVALID_CLAIM set   */
+/* (claimed == -1 is how the sampler is asked for, see oracle_gumbel_score).  */
+/* Optionally writes every y_v into y_out (tests use it).                     */
+/* ------------------------------------------------------------------------- */
+void oracle_gumbel_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
+                       int64_t claimed, double *margin, int32_t *argmax, double *max_score,
+                       double *claimed_score, double *gap2, uint8_t *flags, double *y_out)
+{
+    double best = -INFINITY, second = -INFINITY, yt = NAN;
+    int64_t best_v = -1;
+    int nonfinite = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        uint32_t r = oracle_noise_word(seed, seq, pos, ORACLE_STREAM_GUMBEL, (uint64_t)v);
+        double u = oracle_bits_to_uniform(r);
+        double g = oracle_uniform_to_gumbel(u);
+        double y = x[v] / T + g;
+        if (isnan(x[v]) || x[v] == INFINITY) nonfinite = 1;
+        if (y_out) y_out[v] = y;
+        if (v == claimed) yt = y;
+        if (best_v < 0 || y > best) {
+            second = best;
+            best = y;
+            best_v = v;
+        } else if (y > second) {
+            second = y;
+        }
+    }
+    uint8_t f = 0;
+    if (claimed < 0 || claimed >= V) {
+        f |= ORACLE_FLAG_INVALID_CLAIM;
+        *margin = NAN;
+        *claimed_score = NAN;
+    } else {
+        *margin = best - yt;
+        *claimed_score = yt;
+        if (best_v == claimed) f |= ORACLE_FLAG_MATCH;
+    }
+    if (nonfinite) f |= ORACLE_FLAG_NONFINITE;
+    *argmax = (int32_t)best_v;
+    *max_score = best;
+    *gap2 = best - second;
+    *flags = f;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gaussian log-mass of Token-IPT-DiFR:                                       */
+/*   S = ln( Phi((b-u)/sigma) - Phi((a-u)/sigma) + eps ),                     */
+/*   Phi(z) = (1 + erf(z / sqrt 2)) / 2.                                      */
+/* The difference of the two normal CDF values is taken on the side where it  */
+/* does not cancel (erfc in the tails); it is the same real number.           */
+/* ------------------------------------------------------------------------- */
+double oracle_gaussian_log_mass(double a, double b, double u, double sigma, double eps)
+{
+    double za = (a - u) / (sigma * M_SQRT2);
+    double zb = (b - u) / (sigma * M_SQRT2);
+    double mass;
+    if (za >= 0.0)
+        mass = 0.5 * (erfc(za) - erfc(zb));
+    else if (zb <= 0.0)
+        mass = 0.5 * (erfc(-zb) - erfc(-za));
+    else
+        mass = 0.5 * (erf(zb) + erf(-za));
+    if (mass < 0.0) mass = 0.0;
+    return log(mass + eps);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-IPT-DiFR, one row.                                                   */
+/*   u from stream 1; p = softmax(x/T); Fbar = (0, cumsum p) in index order;  */
+/*   a = Fbar[t], b = Fbar[t+1] (0-based t); d = max(a-u, u-b, 0);            */
+/*   match = a <= u < b;  tok = first v with Fbar[v+1] > u.                   */
+/* edge = min(|u-a|, |u-b|) is reported for the tests' near-tie rule.         */
+/* ------------------------------------------------------------------------- */
+void oracle_ipt_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
+                    int64_t claimed, double sigma, double eps, double *u_out, double *a_out, double *b_out,
+                    double *dist, int32_t *tok, double *log_mass, double *edge, uint8_t *flags)
+{
+    uint32_t r = oracle_noise_word(seed, seq, pos, ORACLE_STREAM_IPT, 0);
+    double u = oracle_bits_to_uniform(r);
+    int nonfinite = 0;
+    double m = -INFINITY;
+    for (int64_t v = 0; v < V; ++v) {
+        double s = x[v] / T;
+        if (isnan(x[v]) || x[v] == INFINITY) nonfinite = 1;
+        if (s > m) m = s;
+    }
+    double Z = 0.0;
+    for (int64_t v = 0; v < V; ++v) Z += exp(x[v] / T - m);
+
+    int valid = (claimed >= 0 && claimed < V);
+    double c = 0.0, a = NAN, b = NAN;
+    int64_t first = -1;
+    for (int64_t v = 0; v < V; ++v) {
+        double e = exp(x[v] / T - m);
+        if (valid && v == claimed) {
+            a = c / Z;
+            b = a + e / Z;
+        }
+        c += e;
+        if (first < 0 && c / Z > u) first = v;
+    }
+    if (first < 0) first = V - 1;
+
+    uint8_t f = 0;
+    if (!valid) {
+        f |= ORACLE_FLAG_INVALID_CLAIM;
+        *dist = NAN;
+        *edge = NAN;
+        *log_mass = NAN;
+    } else {
+        double d = 0.0;
+        if (a - u > d) d = a - u;
+        if (u - b > d) d = u - b;
+        *dist = d;
+        if (a <= u && u < b) f |= ORACLE_FLAG_MATCH;
+        *edge = fmin(fabs(u - a), fabs(u - b));
+        *log_mass = oracle_gaussian_log_mass(a, b, u, sigma, eps);
+    }
+    if (nonfinite) f |= ORACLE_FLAG_NONFINITE;
+    *u_out = u;
+    *a_out = a;
+    *b_out = b;
+    *tok = (int32_t)first;
+    *flags = f;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Batch entry points: rows are independent; parallel over rows only.         */
+/* logits: [N, ld] row-major host memory, dtype ORACLE_DTYPE_*.               */
+/* temperatures may be NULL (then T = temperature for every row).             */
+/* claimed may be NULL (every row is then treated as claimed = -1: sampling). */
+/* ------------------------------------------------------------------------- */
+static size_t elt_size(int dtype) { return dtype == ORACLE_DTYPE_BF16 ? 2u : 4u; }
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+int oracle_gumbel_score(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, double temperature,
+                        const float *temperatures, const uint64_t *seeds, const int32_t *seq_ids,
+                        const uint32_t *positions, const int32_t *claimed, double *margin, int32_t *argmax,
+                        double *max_score, double *claimed_score, double *gap2, uint8_t *flags)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t s = seq_ids[n];
+            int64_t t = claimed ? (int64_t)claimed[n] : -1;
+            oracle_gumbel_row(x, V, T, seeds[s], (uint32_t)s, positions[n], t, &margin[n], &argmax[n],
+                              &max_score[n], &claimed_score[n], &gap2[n], &flags[n], NULL);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+int oracle_ipt_score(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, double temperature,
+                     const float *temperatures, const uint64_t *seeds, const int32_t *seq_ids,
+                     const uint32_t *positions, const int32_t *claimed, double sigma, double eps, double *u,
+                     double *cdf_lo, double *cdf_hi, double *dist, int32_t *tok, double *log_mass, double *edge,
+                     uint8_t *flags)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t s = seq_ids[n];
+            int64_t t = claimed ? (int64_t)claimed[n] : -1;
+            oracle_ipt_row(x, V, T, seeds[s], (uint32_t)s, positions[n], t, sigma, eps, &u[n], &cdf_lo[n],
+                           &cdf_hi[n], &dist[n], &tok[n], &log_mass[n], &edge[n], &flags[n]);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Pooling and flagging.  Rows of sequence s are [offsets[s], offsets[s+1]).  */
+/*   mean_s = (1/L_s) sum score;  max_s;  mismatch_s = rows without MATCH;    */
+/*   flag_s = !(mean_s <= tau).  An empty sequence has mean 0, max 0, flag 0. */
+/* row_flags may be NULL (then mismatch_s = 0).                               */
+/* ------------------------------------------------------------------------- */
+void oracle_seq_reduce(const double *scores, const uint8_t *row_flags, const int64_t *offsets, int64_t S,
+                       double tau, double *seq_mean, double *seq_max, int32_t *seq_mismatch, uint8_t *seq_flag)
+{
+    for (int64_t s = 0; s < S; ++s) {
+        int64_t lo = offsets[s], hi = offsets[s + 1];
+        if (hi <= lo) {
+            seq_mean[s] = 0.0;
+            seq_max[s] = 0.0;
+            seq_mismatch[s] = 0;
+            seq_flag[s] = 0;
+            continue;
+        }
+        double sum = 0.0, mx = -INFINITY;
+        int any_nan = 0;
+        int32_t mis = 0;
+        for (int64_t n = lo; n < hi; ++n) {
+            sum += scores[n];
+            if (isnan(scores[n])) any_nan = 1;
+            if (scores[n] > mx) mx = scores[n];
+            if (row_flags && !(row_flags[n] & ORACLE_FLAG_MATCH)) ++mis;
+        }
+        double mean = sum / (double)(hi - lo);
+        seq_mean[s] = mean;
+        seq_max[s] = any_nan ? NAN : mx;
+        seq_mismatch[s] = mis;
+        seq_flag[s] = (mean <= tau) ? 0 : 1;
+    }
+}

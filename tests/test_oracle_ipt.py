@@ -1,0 +1,236 @@
+"""Pins for the oracle's Token-IPT-DiFR row and for pooling / flagging: library
+softmax, cumsum and searchsorted; multi-precision brute force; tiling of [0,1);
+the sampler's exactness (chi-square); normal-CDF mass in multi-precision."""
+import math
+
+import mpmath
+import numpy as np
+import pytest
+from scipy import special, stats
+
+from test_oracle_noise import _philox_bigint
+
+
+def _u_expected(seed, seq, pos):
+    r = _philox_bigint([0, pos, seq, 1], [seed & 0xFFFFFFFF, seed >> 32])[0]
+    return (2 * (r >> 9) + 1) / 2.0 ** 24
+
+
+def test_interval_equals_library_softmax_cumsum(oracle_lib):
+    rng = np.random.default_rng(21)
+    for V in (2, 7, 64, 1000):
+        x = rng.normal(0, 3, size=V)
+        T = float(rng.choice([0.6, 1.0, 1.7]))
+        p = special.softmax(x / T)
+        F = np.concatenate([[0.0], np.cumsum(p)])
+        seed = int(rng.integers(0, 1 << 63))
+        for t in sorted(set([0, V - 1] + [int(v) for v in rng.integers(0, V, size=5)])):
+            got = oracle_lib.ipt_row(x, T, seed, 4, 17, t)
+            assert got["u"] == _u_expected(seed, 4, 17)
+            assert abs(got["cdf_lo"] - F[t]) < 1e-13 and abs(got["cdf_hi"] - F[t + 1]) < 1e-13
+            assert abs((got["cdf_hi"] - got["cdf_lo"]) - p[t]) < 1e-13
+            u = got["u"]
+            want_d = max(F[t] - u, u - F[t + 1], 0.0)
+            assert abs(got["dist"] - want_d) < 1e-13
+            assert 0.0 <= got["dist"] < 1.0
+            assert bool(got["flags"] & 1) == (F[t] <= u < F[t + 1])
+            assert got["ipt_token"] == min(int(np.searchsorted(F[1:], u, side="right")), V - 1)
+            assert abs(got["edge"] - min(abs(u - F[t]), abs(u - F[t + 1]))) < 1e-13
+
+
+def test_multiprecision_brute_force(oracle_lib):
+    mpmath.mp.dps = 50
+    rng = np.random.default_rng(22)
+    for V in (2, 3, 6, 11):
+        for trial in range(6):
+            x = rng.normal(0, 4, size=V)
+            T = float(rng.choice([0.6, 0.7, 1.0]))
+            seed, seq, pos = int(rng.integers(0, 1 << 63)), int(rng.integers(0, 9)), int(rng.integers(0, 999))
+            e = [mpmath.exp(mpmath.mpf(float(v)) / mpmath.mpf(T)) for v in x]
+            Z = sum(e)
+            F = [mpmath.mpf(0)]
+            for v in range(V):
+                F.append(F[-1] + e[v] / Z)
+            u = mpmath.mpf(_u_expected(seed, seq, pos))
+            tok = next(v for v in range(V) if F[v + 1] > u or v == V - 1)
+            for t in range(V):
+                got = oracle_lib.ipt_row(x, T, seed, seq, pos, t)
+                assert abs(mpmath.mpf(got["cdf_lo"]) - F[t]) < 1e-14
+                assert abs(mpmath.mpf(got["cdf_hi"]) - F[t + 1]) < 1e-14
+                d = max(F[t] - u, u - F[t + 1], mpmath.mpf(0))
+                assert abs(mpmath.mpf(got["dist"]) - d) < 1e-14
+                assert got["ipt_token"] == tok
+                assert bool(got["flags"] & 1) == (t == tok)
+                assert (got["dist"] == 0.0) == (t == tok)
+
+
+def test_intervals_tile_and_honest_claim_scores_zero(oracle_lib):
+    rng = np.random.default_rng(23)
+    V = 300
+    for trial in range(30):
+        x = rng.normal(0, 2.5, size=V)
+        seed = int(rng.integers(0, 1 << 63))
+        rows = [oracle_lib.ipt_row(x, 0.9, seed, 0, trial, t) for t in range(V)]
+        a = np.array([r["cdf_lo"] for r in rows])
+        b = np.array([r["cdf_hi"] for r in rows])
+        assert a[0] == 0.0 and abs(b[-1] - 1.0) < 1e-12
+        assert np.max(np.abs(b[:-1] - a[1:])) < 1e-14
+        matches = [t for t in range(V) if rows[t]["flags"] & 1]
+        assert matches == [rows[0]["ipt_token"]]              # exactly one interval holds u
+        assert rows[matches[0]]["dist"] == 0.0
+        sample = oracle_lib.ipt_row(x, 0.9, seed, 0, trial, -1)
+        assert sample["flags"] & 2 and math.isnan(sample["dist"]) and sample["ipt_token"] == matches[0]
+        for t in range(V):
+            assert (rows[t]["dist"] > 0) == (t != matches[0])
+        # the distance grows with the token's distance from the sampled one
+        d = np.array([r["dist"] for r in rows])
+        assert np.all(np.diff(d[matches[0]:]) >= -1e-15) and np.all(np.diff(d[: matches[0] + 1]) <= 1e-15)
+
+
+def test_invariances_masked_entries_and_extremes(oracle_lib):
+    rng = np.random.default_rng(24)
+    V = 120
+    x = rng.normal(0, 2, size=V)
+    seed, t = 987654321, 37
+    base = oracle_lib.ipt_row(x, 0.8, seed, 1, 5, t)
+    for other in (oracle_lib.ipt_row(x + 11.5, 0.8, seed, 1, 5, t), oracle_lib.ipt_row(x * 3, 2.4, seed, 1, 5, t)):
+        for k in ("cdf_lo", "cdf_hi", "dist", "u"):
+            assert abs(other[k] - base[k]) < 1e-12
+        assert other["ipt_token"] == base["ipt_token"]
+    # large logits do not overflow (softmax is shifted by the maximum)
+    big = oracle_lib.ipt_row(x + 5000.0, 0.8, seed, 1, 5, t)
+    assert abs(big["cdf_lo"] - base["cdf_lo"]) < 1e-9
+    # a -inf entry has zero mass
+    xm = x.copy()
+    xm[10] = -np.inf
+    m = oracle_lib.ipt_row(xm, 0.8, seed, 1, 5, 10)
+    assert m["cdf_hi"] == m["cdf_lo"] and not m["flags"] & 1
+    # near one-hot: the heavy token owns almost all of [0,1)
+    xo = np.full(V, -40.0)
+    xo[77] = 0.0
+    o = oracle_lib.ipt_row(xo, 1.0, seed, 1, 5, 77)
+    assert o["cdf_hi"] - o["cdf_lo"] > 1 - 1e-12 and o["dist"] == 0.0 and o["ipt_token"] == 77
+
+
+def test_exact_boundary_is_half_open(oracle_lib):
+    # 2^24 equal logits: every CDF value j / 2^24 is exact, and u = (2k+1) / 2^24 lands exactly on one.
+    # Sampler rule "first t with C_t > u" (Sec. 3.2, IPT sampler): the token whose interval STARTS at u.
+    V = 1 << 24
+    x = np.zeros(V)
+    seed, seq, pos = 424242, 2, 11
+    u = _u_expected(seed, seq, pos)
+    j = int(round(u * V))                      # odd, F_j == u
+    assert j / V == u and j % 2 == 1
+    at = oracle_lib.ipt_row(x, 1.0, seed, seq, pos, j)          # interval [u, u + 2^-24)
+    assert at["cdf_lo"] == u and at["ipt_token"] == j and at["flags"] & 1 and at["dist"] == 0.0
+    below = oracle_lib.ipt_row(x, 1.0, seed, seq, pos, j - 1)   # interval [u - 2^-24, u): u excluded
+    assert below["cdf_hi"] == u and not below["flags"] & 1 and below["dist"] == 0.0 and below["edge"] == 0.0
+
+
+def test_ipt_sample_frequencies_match_softmax(oracle_lib):
+    V, T = 10, 1.2
+    rng = np.random.default_rng(25)
+    x = rng.normal(0, 1.5, size=V).astype(np.float32)
+    S, L = 400, 500
+    logits = np.broadcast_to(x, (S * L, V)).copy()
+    seeds = rng.integers(0, 1 << 63, size=S).astype(np.uint64)
+    seq_ids = np.repeat(np.arange(S, dtype=np.int32), L)
+    positions = np.tile(np.arange(L, dtype=np.uint32), S)
+    out = oracle_lib.ipt_score(logits, V, T, seeds, seq_ids, positions)
+    assert stats.kstest(out["u"], "uniform").pvalue > 1e-4
+    counts = np.bincount(out["ipt_token"], minlength=V)
+    p = special.softmax(x.astype(np.float64) / T)
+    assert stats.chisquare(counts, p * counts.sum()).pvalue > 1e-4
+    # the Gumbel noise stream and the IPT stream are different draws
+    g = oracle_lib.gumbel_score(logits[:2000], V, T, seeds, seq_ids[:2000], positions[:2000])
+    assert (g["argmax"] != out["ipt_token"][:2000]).mean() > 0.3
+
+
+def test_batch_matches_row(oracle_lib):
+    import torch
+
+    rng = np.random.default_rng(26)
+    N, V, ld = 7, 33, 40
+    x = torch.from_numpy(rng.normal(0, 2, size=(N, ld)).astype(np.float32)).to(torch.bfloat16)
+    xb = x.view(torch.int16).numpy().view(np.uint16)
+    seeds = np.array([5, 6], dtype=np.uint64)
+    seq_ids = np.array([0, 0, 0, 0, 1, 1, 1], dtype=np.int32)
+    positions = np.array([0, 1, 2, 3, 0, 1, 2], dtype=np.uint32)
+    claimed = rng.integers(0, V, size=N).astype(np.int32)
+    claimed[2] = -5
+    out = oracle_lib.ipt_score(xb, V, 0.7, seeds, seq_ids, positions, claimed, sigma=0.05, eps=1e-20)
+    for n in range(N):
+        row = oracle_lib.ipt_row(x[n, :V].to(torch.float64).numpy(), float(np.float64(0.7)), int(seeds[seq_ids[n]]),
+                                 int(seq_ids[n]), int(positions[n]), int(claimed[n]), sigma=0.05, eps=1e-20)
+        for k in ("u", "cdf_lo", "cdf_hi", "dist", "log_mass", "edge"):
+            assert (out[k][n] == row[k]) or (math.isnan(out[k][n]) and math.isnan(row[k])), (k, n)
+        assert out["ipt_token"][n] == row["ipt_token"] and out["flags"][n] == row["flags"]
+    assert out["flags"][2] & 2
+
+
+def test_gaussian_log_mass_multiprecision(oracle_lib):
+    # S = ln(Phi((b-u)/s) - Phi((a-u)/s) + eps) with Phi the normal CDF (appendix algorithm)
+    mpmath.mp.dps = 60
+    rng = np.random.default_rng(27)
+    cases = [(0.2, 0.5, 0.3, 0.01, 1e-30), (0.2, 0.5, 0.6, 0.01, 1e-30), (0.2, 0.5, 0.1, 0.01, 1e-30),
+             (0.0, 1.0, 0.5, 0.001, 1e-30), (0.40, 0.41, 0.45, 0.01, 1e-30), (0.40, 0.41, 0.9, 0.01, 1e-30),
+             (0.3, 0.3, 0.3, 0.01, 1e-12), (0.25, 0.75, 0.25, 1.0, 1e-30)]
+    for _ in range(200):
+        a = float(rng.uniform(0, 1))
+        b = float(min(1.0, a + rng.exponential(0.05)))
+        cases.append((a, b, float(rng.uniform(0, 1)), float(rng.choice([0.001, 0.01, 0.1, 1.0])), 1e-30))
+    for a, b, u, s, eps in cases:
+        za = (mpmath.mpf(a) - mpmath.mpf(u)) / mpmath.mpf(s)
+        zb = (mpmath.mpf(b) - mpmath.mpf(u)) / mpmath.mpf(s)
+        want = mpmath.log(mpmath.ncdf(zb) - mpmath.ncdf(za) + mpmath.mpf(eps))
+        got = oracle_lib.gaussian_log_mass(a, b, u, s, eps)
+        assert abs(mpmath.mpf(got) - want) <= mpmath.mpf(1e-10) * max(1, abs(want)), (a, b, u, s)
+    # whole unit interval with a narrow Gaussian inside it: mass -> 1, S -> 0
+    assert abs(oracle_lib.gaussian_log_mass(0.0, 1.0, 0.5, 0.001, 1e-30)) < 1e-12
+    # well-conditioned case against scipy's normal CDF
+    got = oracle_lib.gaussian_log_mass(0.2, 0.5, 0.3, 0.1, 0.0)
+    want = math.log(stats.norm.cdf(0.5, 0.3, 0.1) - stats.norm.cdf(0.2, 0.3, 0.1))
+    assert abs(got - want) < 1e-12
+    # the row function feeds its own a, b, u into it
+    x = rng.normal(0, 2, size=50)
+    r = oracle_lib.ipt_row(x, 1.0, 99, 0, 3, 20, sigma=0.02, eps=1e-25)
+    assert r["log_mass"] == oracle_lib.gaussian_log_mass(r["cdf_lo"], r["cdf_hi"], r["u"], 0.02, 1e-25)
+
+
+def test_pooling_and_flagging(oracle_lib):
+    rng = np.random.default_rng(28)
+    lens = [5, 0, 17, 1, 300]
+    offsets = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    N = int(offsets[-1])
+    scores = rng.exponential(0.3, size=N)
+    flags = (rng.uniform(size=N) < 0.8).astype(np.uint8)       # bit 0 = match
+    tau = 0.3
+    out = oracle_lib.seq_reduce(scores, flags, offsets, tau)
+    for s, L in enumerate(lens):
+        seg = scores[offsets[s]:offsets[s + 1]]
+        if L == 0:
+            assert out["seq_mean"][s] == 0 and out["seq_flag"][s] == 0 and out["seq_mismatch"][s] == 0
+            continue
+        assert abs(out["seq_mean"][s] - np.mean(seg)) < 1e-15
+        assert out["seq_max"][s] == np.max(seg)
+        assert out["seq_mismatch"][s] == int((flags[offsets[s]:offsets[s + 1]] & 1 == 0).sum())
+        assert out["seq_flag"][s] == int(np.mean(seg) > tau)
+    # a mean exactly at the threshold is not flagged (flag = mean above tau)
+    o3 = oracle_lib.seq_reduce(np.array([0.25, 0.75, 0.5, 0.5000001]), None, np.array([0, 2, 3, 4]), 0.5)
+    assert list(o3["seq_flag"]) == [0, 0, 1] and o3["seq_mean"][0] == 0.5
+    # a NaN score (invalid claim) makes the sequence suspicious
+    scores2 = scores.copy()
+    scores2[2] = np.nan
+    o2 = oracle_lib.seq_reduce(scores2, None, offsets, 1e9)
+    assert o2["seq_flag"][0] == 1 and math.isnan(o2["seq_mean"][0]) and o2["seq_flag"][2] == 0
+    assert (o2["seq_mismatch"] == 0).all()
+
+
+def test_threshold_calibration(oracle_lib):
+    rng = np.random.default_rng(29)
+    for n, fpr in [(253, 1e-2), (100, 0.01), (1000, 0.001), (50, 0.1), (7, 0.5)]:
+        means = rng.exponential(1.0, size=n)
+        tau = oracle_lib.calibrate_threshold(means, fpr)
+        flagged = int((means > tau).sum())
+        assert flagged <= math.floor(fpr * n + 1e-9)
+        assert flagged == math.floor(fpr * n + 1e-9)          # distinct values: the bound is attained
