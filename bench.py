@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the verifier's per-token vocabulary pass on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic token rows that are
+already resident in HBM: Token-DiFR scoring (difr_gumbel_score), Token-IPT-DiFR scoring
+(difr_ipt_score) and the per-sequence pooling / flagging of both score arrays
+(difr_seq_reduce twice).  The default workload is the 30B-MoE-class streaming config:
+N = 65536 token rows (64 sequences x 1024), V = 151936, bf16 logits, T = 1.0.
+
+Prints ONE JSON line: verified tokens/s for the step, the roofline record of the dominant
+kernel (achieved algorithmic HBM GB/s against the 8 TB/s peak, from HIP events recorded on
+the launch stream inside the timed region) and the CPU oracle timed on a bounded sample of
+the same rows.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+AUX_BYTES_PER_ROW = 12         # seq_id, position, claimed token (seeds are per sequence)
+GUMBEL_OUT_BYTES = 17          # margin, argmax, max_score, claimed_score (fp32/int32) + flags
+IPT_OUT_BYTES = 17             # dist, cdf_lo, cdf_hi, u (fp32) + flags
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
+# in bytes, keyed by (kernel, workload).  None until a counter run has been made for that pair.
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(wl, difr, dev):
+    """Fill HBM with the workload: verifier logits [N, V] plus honest claims for both samplers.
+
+    Honest claims are what an honest server would have logged: the library's own samplers
+    (argmax output of the Gumbel kernel, ipt_token output of the IPT kernel) run on the
+    prover's slightly drifted logits, then passed through the workload's mutation recipe."""
+    N, V = wl.N, wl.V
+    logits = torch.empty(N, V, dtype=wl.dtype, device=dev)
+    seeds, sid, pos = wl.seeds().to(dev), wl.seq_ids().to(dev), wl.positions().to(dev)
+    cg = torch.empty(N, dtype=torch.int32, device=dev)
+    ci = torch.empty(N, dtype=torch.int32, device=dev)
+    t0 = time.time()
+    for c in range(wl.n_chunks):
+        r0, r1 = c * wl.chunk_rows, (c + 1) * wl.chunk_rows
+        ver, prov = wl.logits_chunk(c, dev)
+        logits[r0:r1] = ver
+        hg = difr.gumbel_score(prov, wl.temperature, seeds, sid[r0:r1], pos[r0:r1], None, want_scores=False)["argmax"]
+        hi = difr.ipt_score(prov, wl.temperature, seeds, sid[r0:r1], pos[r0:r1], None, want_token=True,
+                            want_interval=False)["ipt_token"]
+        cg[r0:r1] = wl.mutate_claims(c, hg, ver)
+        ci[r0:r1] = wl.mutate_claims(c, hi, ver)
+        del ver, prov
+        if c % 16 == 15 or c == wl.n_chunks - 1:
+            torch.cuda.synchronize()
+            log("  generated %d/%d rows (%.1f s)" % (r1, N, time.time() - t0))
+    return dict(logits=logits, seeds=seeds, seq_ids=sid, positions=pos, claims_g=cg, claims_i=ci,
+                seq_offsets=wl.seq_offsets().to(dev))
+
+
+def cpu_baseline(wl, data, sample_rows):
+    """The oracle, as it stands, on the first `sample_rows` rows (whole sequences) of the same batch:
+    its own honest-claim-agnostic scoring of both estimators plus pooling, on the host cores."""
+    import oracle
+
+    oracle.build()
+    n = min(sample_rows, wl.N)
+    n -= n % wl.L if n >= wl.L else 0
+    n = max(n, 1)
+    host = data["logits"][:n].cpu()
+    host = host.view(torch.int16).numpy().view(np.uint16) if host.dtype == torch.bfloat16 else host.numpy()
+    seeds = data["seeds"].cpu().numpy().view(np.uint64)
+    sid = data["seq_ids"][:n].cpu().numpy()
+    pos = data["positions"][:n].cpu().numpy().view(np.uint32)
+    cg = data["claims_g"][:n].cpu().numpy()
+    ci = data["claims_i"][:n].cpu().numpy()
+    S = max(1, n // wl.L)
+    off = np.minimum(np.arange(S + 1, dtype=np.int64) * wl.L, n)
+    T = float(np.float32(wl.temperature))
+    t0 = time.time()
+    og = oracle.gumbel_score(host, wl.V, T, seeds, sid, pos, cg)
+    oi = oracle.ipt_score(host, wl.V, T, seeds, sid, pos, ci)
+    oracle.seq_reduce(og["margin"], og["flags"], off, 0.05)
+    oracle.seq_reduce(oi["dist"], oi["flags"], off, 0.05)
+    dt = time.time() - t0
+    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "first %d rows (%d whole sequences) of the same batch, both estimators + pooling, %.1f s"
+                      % (n, S, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3_30b_moe_class", help="workload name (see paper_2511_02620_amd.workloads)")
+    ap.add_argument("--temperature", type=float, default=None)
+    ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this path has no multi-GPU part (rows are independent; "
+                 "see DESIGN.md for how it would shard). Run with --gpus 1.")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (there is no CPU fallback for the product path)")
+
+    import paper_2511_02620_amd as difr
+    from paper_2511_02620_amd import workloads as W
+
+    difr.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = W.WORKLOADS[args.workload]
+    if args.temperature is not None:
+        wl = wl.with_temperature(args.temperature)
+    log("workload %s: N=%d V=%d %s T=%g (%.2f GB of logits)" % (wl.name, wl.N, wl.V, wl.dtype, wl.temperature,
+                                                              wl.N * wl.V * (2 if wl.dtype == torch.bfloat16 else 4) / 1e9))
+    data = build_workload(wl, difr, dev)
+    esz = 2 if wl.dtype == torch.bfloat16 else 4
+    tau_g, tau_i = 0.05, 0.01
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        g = difr.gumbel_score(data["logits"], wl.temperature, data["seeds"], data["seq_ids"], data["positions"],
+                              data["claims_g"])
+        if ev is not None:
+            ev[1].record()
+        i = difr.ipt_score(data["logits"], wl.temperature, data["seeds"], data["seq_ids"], data["positions"],
+                           data["claims_i"])
+        if ev is not None:
+            ev[2].record()
+        sg = difr.seq_reduce(g["margin"], g["flags"], data["seq_offsets"], tau_g)
+        si = difr.seq_reduce(i["dist"], i["flags"], data["seq_offsets"], tau_i)
+        if ev is not None:
+            ev[3].record()
+        return g, i, sg, si
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        out = step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    t_r = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    g, i, sg, si = out
+    match_g = float((g["flags"] & 1).float().mean())
+    match_i = float((i["flags"] & 1).float().mean())
+    log("gumbel %.3f ms, ipt %.3f ms, pooling %.3f ms per step; match rates %.4f / %.4f; flagged %d / %d"
+        % (t_g, t_i, t_r, match_g, match_i, int(sg["seq_flag"].sum()), int(si["seq_flag"].sum())))
+
+    per_row_g = wl.V * esz + AUX_BYTES_PER_ROW + GUMBEL_OUT_BYTES
+    per_row_i = wl.V * esz + AUX_BYTES_PER_ROW + IPT_OUT_BYTES
+    gbs_g = wl.N * per_row_g / (t_g * 1e-3) / 1e9
+    gbs_i = wl.N * per_row_i / (t_i * 1e-3) / 1e9
+    dominant = ("difr_gumbel_score", gbs_g, t_g) if t_g >= t_i else ("difr_ipt_score", gbs_i, t_i)
+    roofline = {"bound": "hbm", "achieved": round(dominant[1], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dominant[1] / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get((dominant[0], wl.name)),
+                "kernel": dominant[0], "kernel_ms": round(dominant[2], 4),
+                "algorithmic_bytes_per_launch": wl.N * (per_row_g if dominant[0] == "difr_gumbel_score" else per_row_i)}
+    result = {
+        "metric": "verified tokens/sec at V=151936 bf16; achieved HBM GB/s vs MI355X peak",
+        "value": round(wl.N / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "N": wl.N, "V": wl.V, "logits_dtype": "bf16" if esz == 2 else "f32",
+                   "temperature": wl.temperature,
+                   "step": "difr_gumbel_score + difr_ipt_score + 2x difr_seq_reduce over the whole batch"},
+        "roofline": roofline,
+        "kernels": {"difr_gumbel_score": {"ms": round(t_g, 4), "tokens_per_s": round(wl.N / (t_g * 1e-3), 1),
+                                          "hbm_gbs": round(gbs_g, 1), "frac_of_peak": round(gbs_g / HBM_PEAK_GBS, 4)},
+                    "difr_ipt_score": {"ms": round(t_i, 4), "tokens_per_s": round(wl.N / (t_i * 1e-3), 1),
+                                       "hbm_gbs": round(gbs_i, 1), "frac_of_peak": round(gbs_i / HBM_PEAK_GBS, 4)},
+                    "difr_seq_reduce_x2": {"ms": round(t_r, 4)}},
+        "match_rate": {"gumbel": round(match_g, 5), "ipt": round(match_i, 5)},
+    }
+    if args.cpu_rows > 0:
+        result["cpu_baseline"] = cpu_baseline(wl, data, args.cpu_rows)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,183 @@
+/*
+ * difr.h -- C ABI of the MI355X (gfx950) verifier scoring library, libdifr.so.
+ *
+ * The library scores claimed sampled tokens against verifier logits, one token
+ * row (one position of one logged response) at a time, in a single streaming pass
+ * over the row's full vocabulary:
+ *
+ *   difr_gumbel_score  Token-DiFR.  Regenerates the sampler's seeded Gumbel noise
+ *                      g_v for every vocabulary entry, forms y_v = x_v / T + g_v,
+ *                      and reports argmax_v y_v (the token the honest Gumbel-max
+ *                      sampler would have produced) and the claimed token's margin
+ *                      max_v y_v - y_t.           [Sec. 3.2 Gumbel-max sampler;
+ *                      Sec. 6.3 and the appendix algorithm of the Gumbel likelihood
+ *                      estimator: noise regeneration, ranking by l_i + T G_i, and
+ *                      A_{sigma,i}, of which the margin is -min_i A_{sigma,i} / T]
+ *   difr_ipt_score     Token-IPT-DiFR.  Regenerates the sampler's seeded uniform u,
+ *                      forms p = softmax(x / T), the CDF in ascending token order,
+ *                      the claimed token's interval [a, b) and the distance of u
+ *                      from it; optionally the Gaussian log-mass score and the token
+ *                      the honest inverse-CDF sampler would have produced.
+ *                      [Sec. 3.2 IPT sampler; Sec. 6.2 and the appendix algorithm
+ *                      "convolved Gaussian score"]
+ *   difr_seq_reduce    Pools token scores per sequence (mean, max, mismatch count)
+ *                      and flags sequences whose mean exceeds a threshold.
+ *                      [Sec. 5.2 threshold rule; Sec. 6.4; appendix "Response to
+ *                      detecting exfiltration attempts": score, pool, flag]
+ *
+ * The regenerate-and-compare form (one prefill gives logits at every position; each
+ * position is sampled with the logged seed and compared with the logged token) is
+ * the appendix algorithm "verification via prefill"; MATCH in the row flags is its
+ * per-position comparison.
+ *
+ * Seeded randomness.  The paper's H(seed || i) is instantiated as Philox4x32-10:
+ *   key     = (low 32 bits, high 32 bits) of the sequence's 64-bit seed
+ *   counter = (v >> 2, position i, sequence id, stream)      output word v & 3
+ *   stream 0: Gumbel noise of vocabulary entry v;  stream 1: the IPT uniform (v = 0)
+ *   32 bits r -> u = (2 (r >> 9) + 1) * 2^-24  in (0,1);   g = -ln(-ln u).
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers documented DEVICE must be device pointers (HBM) valid on the current
+ *     HIP device; the caller owns every buffer; the library allocates nothing, keeps
+ *     no state between calls and is thread-safe.
+ *   - Work is enqueued on the given hipStream_t (passed as void*; NULL = the null
+ *     stream) and the call returns without synchronising.  The return value reports
+ *     host-side argument validation and the launch status only.
+ *   - Return value: a difr_status (0 = DIFR_OK).  Nothing aborts or throws.  On an
+ *     error return no kernel has been launched and no output has been touched.
+ *   - Problems that are only visible on the device are reported per row in `flags`.
+ *   - N == 0 (or S == 0 for difr_seq_reduce) is a successful no-op.
+ */
+#ifndef DIFR_H
+#define DIFR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DIFR_OK = 0,
+    DIFR_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    DIFR_ERR_SHAPE = 2,       /* N, V, S or ld negative, V == 0 with N > 0, ld < V,  */
+                              /* V >= 2^31, or N >= 2^31                             */
+    DIFR_ERR_DTYPE = 3,       /* dtype is not a difr_dtype                           */
+    DIFR_ERR_TEMPERATURE = 4, /* temperature not finite or <= 0 (greedy T = 0 is a   */
+                              /* different sampling rule and is not this path)       */
+    DIFR_ERR_ALIGN = 5,       /* logits base not aligned to its element size         */
+    DIFR_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
+    DIFR_ERR_UNSUPPORTED = 7, /* the current device is not gfx950                    */
+    DIFR_ERR_ARGUMENT = 8     /* sigma <= 0, eps < 0, or NaN where a number is needed */
+} difr_status;
+
+typedef enum { DIFR_BF16 = 0, DIFR_F32 = 1 } difr_dtype;
+
+/* Per-row flag bits written to `flags`. */
+#define DIFR_FLAG_MATCH 1u         /* the regenerated token equals the claimed token  */
+#define DIFR_FLAG_INVALID_CLAIM 2u /* claimed token outside [0, V) (or claimed==NULL): */
+                                   /* scores of the claimed token are NaN; the         */
+                                   /* regenerated token and its score are still valid  */
+#define DIFR_FLAG_NONFINITE 4u     /* a NaN or +inf logit was seen in the row; the     */
+                                   /* row's other outputs are unspecified.  -inf is    */
+                                   /* a legal "masked" entry: zero probability, never  */
+                                   /* the argmax                                       */
+#define DIFR_FLAG_SLOW_PATH 8u     /* informational: the row left the streaming fast   */
+                                   /* path (re-read of the row)                        */
+
+/*
+ * One batch of token rows: "claimed token t*, verifier logits, seed, temperature"
+ * (inputs of the appendix scoring algorithms) plus "context position i".
+ * All pointers are DEVICE pointers owned by the caller.
+ */
+typedef struct {
+    const void *logits;        /* [N, ld] row-major, element type `dtype`; base aligned to */
+                               /* the element size.  Fast path: base and ld*sizeof(elt)    */
+                               /* multiples of 16 bytes; otherwise a slower generic path   */
+    int32_t dtype;             /* difr_dtype                                               */
+    int64_t N;                 /* token rows, 0 <= N < 2^31                                */
+    int64_t V;                 /* vocabulary size, 0 < V < 2^31                            */
+    int64_t ld;                /* row pitch in elements, ld >= V                           */
+    float temperature;         /* T > 0, finite; used when temperatures == NULL            */
+    const float *temperatures; /* optional [N] per-row T (a row with T <= 0 or NaN gets    */
+                               /* NaN scores and DIFR_FLAG_NONFINITE)                      */
+    const uint64_t *seeds;     /* [S] one 64-bit sampling seed per sequence                */
+    int64_t S;                 /* number of sequences, S >= 1 when N > 0                   */
+    const int32_t *seq_ids;    /* [N] sequence of each row, in [0, S) (rows with an id     */
+                               /* outside get NaN scores and DIFR_FLAG_INVALID_CLAIM)      */
+    const uint32_t *positions; /* [N] response index i of the row's token                  */
+    const int32_t *claimed;    /* [N] claimed token id; NULL = sampling mode (every row is */
+                               /* treated as claimed = -1)                                 */
+} difr_rows;
+
+/*
+ * Token-DiFR over a batch.  Outputs are DEVICE arrays of N elements; those marked
+ * optional may be NULL.
+ *   margin        max_v y_v - y_t >= 0, in units of x/T + g; exactly 0 when the claimed
+ *                 token is the regenerated one; NaN for an invalid claim
+ *   argmax        lowest index attaining max_v y_v (the regenerated token)
+ *   max_score     (optional) max_v y_v
+ *   claimed_score (optional) y_t, NaN for an invalid claim
+ *   flags         DIFR_FLAG_* bits
+ * Arithmetic: fp32 on exact fp32 images of the stored logits; noise bits are
+ * bit-identical to the definition above.
+ */
+int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
+                      float *claimed_score, uint8_t *flags, void *hip_stream);
+
+/*
+ * Token-IPT-DiFR over a batch.  Outputs are DEVICE arrays of N elements; those marked
+ * optional may be NULL.
+ *   dist       max(a - u, u - b, 0): distance of the seeded uniform from the claimed
+ *              token's CDF interval; 0 when u lies in [a, b]; NaN for an invalid claim
+ *   cdf_lo     (optional) a = sum_{v < t} p_v
+ *   cdf_hi     (optional) b = a + p_t
+ *   u          (optional) the regenerated uniform
+ *   ipt_token  (optional) min{ v : sum_{w <= v} p_w > u }, the token the honest sampler
+ *              draws.  Rows whose claim does not match take a second pass over the row
+ *              (DIFR_FLAG_SLOW_PATH) when this output is requested
+ *   log_mass   (optional) ln( Phi((b-u)/sigma) - Phi((a-u)/sigma) + eps ), evaluated in
+ *              fp64 from the fp32 a, b, u; needs sigma > 0 and eps >= 0
+ *   flags      DIFR_FLAG_* bits; MATCH means a <= u < b
+ */
+int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                   int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
+                   void *hip_stream);
+
+/*
+ * Pooling and flagging.  scores [N] DEVICE fp32 token scores (margin or dist);
+ * row_flags [N] DEVICE or NULL; seq_offsets [S+1] DEVICE, non-decreasing, rows of
+ * sequence s are [seq_offsets[s], seq_offsets[s+1]) and seq_offsets[S] <= N.
+ * Outputs are DEVICE arrays of S elements, each optional:
+ *   seq_mean      mean of the sequence's scores (fp64 accumulation in a fixed order,
+ *                 rounded to fp32); 0 for an empty sequence
+ *   seq_max       maximum score (NaN if any score is NaN); 0 for an empty sequence
+ *   seq_mismatch  rows of the sequence without DIFR_FLAG_MATCH (0 if row_flags == NULL)
+ *   seq_flag      1 unless mean <= threshold (so a NaN mean is flagged); 0 if empty
+ */
+int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,
+                    int64_t S, float threshold, float *seq_mean, float *seq_max, int32_t *seq_mismatch,
+                    uint8_t *seq_flag, void *hip_stream);
+
+/*
+ * Test and audit helper: writes the raw 32 noise bits of vocabulary entries
+ * 0..V-1 of one row (`stream` 0 = Gumbel, 1 = IPT) to the DEVICE array bits[V],
+ * using the same device code path as the scoring kernels.
+ */
+int difr_debug_noise(const difr_rows *in, int64_t row, int32_t stream, uint32_t *bits, void *hip_stream);
+
+/*
+ * Test and audit helper: evaluates the device's bits -> Gumbel map for the n raw
+ * words in the DEVICE array bits[n] and writes g[n] (DEVICE, fp32).
+ */
+int difr_debug_gumbel_map(const uint32_t *bits, int64_t n, float *g, void *hip_stream);
+
+/* Host-side helpers (no device access). */
+void difr_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+const char *difr_status_string(int status);
+int difr_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DIFR_H */

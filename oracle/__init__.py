@@ -62,6 +62,8 @@ def _load():
     lib.oracle_bits_to_uniform.restype = C.c_double
     lib.oracle_uniform_to_gumbel.argtypes = [C.c_double]
     lib.oracle_uniform_to_gumbel.restype = C.c_double
+    lib.oracle_gumbel_from_bits_array.argtypes = [u32p, C.c_int64, f64p]
+    lib.oracle_gumbel_from_bits_array.restype = None
     lib.oracle_noise_row.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int64, u32p]
     lib.oracle_noise_row.restype = None
     lib.oracle_decode_row.argtypes = [C.c_void_p, C.c_int, C.c_int64, f64p]
@@ -136,6 +138,14 @@ def bits_to_uniform(r: int) -> float:
 
 def uniform_to_gumbel(u: float) -> float:
     return float(_load().oracle_uniform_to_gumbel(float(u)))
+
+
+def gumbel_from_bits(bits):
+    """bits -> uniform -> Gumbel for an array of raw noise words."""
+    b = np.ascontiguousarray(bits, dtype=np.uint32)
+    g = np.zeros(b.shape[0], dtype=np.float64)
+    _load().oracle_gumbel_from_bits_array(_ptr(b, C.c_uint32), b.shape[0], _ptr(g, C.c_double))
+    return g
 
 
 def gaussian_log_mass(a, b, u, sigma, eps) -> float:
@@ -272,7 +282,7 @@ def seq_reduce(scores, row_flags, offsets, tau):
     return out
 
 
-def calibrate_threshold(honest_means, fpr: float) -> float:
+def calibrate_threshold(honest_means, fpr: float, as_float32: bool = True) -> float:
     """Threshold from benign pooled scores (appendix on score statistics: pick the
     percentile of the benign distribution that meets the target false-positive rate).
     Scores here are suspiciousness, so tau is the ceil((1-fpr)*n)-th smallest benign
@@ -283,4 +293,12 @@ def calibrate_threshold(honest_means, fpr: float) -> float:
         raise ValueError("no benign scores")
     k = int(np.ceil((1.0 - fpr) * n))
     k = min(max(k, 1), n)
-    return float(m[k - 1])
+    tau = float(m[k - 1])
+    if as_float32:
+        # the library's threshold argument is fp32: return the smallest fp32 value that is not
+        # below the chosen benign mean, so that mean stays on the unflagged side after rounding
+        t32 = np.float32(tau)
+        if float(t32) < tau:
+            t32 = np.nextafter(t32, np.float32(np.inf))
+        tau = float(t32)
+    return tau

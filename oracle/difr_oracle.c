@@ -130,6 +130,12 @@ double oracle_uniform_to_gumbel(double u)
     return -log(t);
 }
 
+/* The map above applied to n raw noise words (used to check a device map exhaustively). */
+void oracle_gumbel_from_bits_array(const uint32_t *bits, int64_t n, double *g)
+{
+    for (int64_t i = 0; i < n; ++i) g[i] = oracle_uniform_to_gumbel(oracle_bits_to_uniform(bits[i]));
+}
+
 /* Exact value of a stored logit as a double. */
 static double decode_bf16(uint16_t h)
 {

@@ -1,0 +1,24 @@
+"""MI355X-native scoring of claimed sampled tokens against verifier logits.
+
+The product is ``libdifr.so`` (hand-written HIP kernels for gfx950 behind the C ABI of
+``include/difr.h``).  This package is only its Python binding: ``gumbel_score``,
+``ipt_score`` and ``seq_reduce`` marshal torch device tensors into the C calls and
+return torch tensors.  There is no CPU fallback; if the library is missing the import
+of :mod:`paper_2511_02620_amd.binding` fails loudly.
+"""
+from .binding import (  # noqa: F401
+    DifrError,
+    FLAG_INVALID_CLAIM,
+    FLAG_MATCH,
+    FLAG_NONFINITE,
+    FLAG_SLOW_PATH,
+    debug_gumbel_map,
+    debug_noise,
+    gumbel_score,
+    ipt_score,
+    lib_path,
+    load_library,
+    philox4x32_10,
+    seq_reduce,
+    version,
+)

@@ -1,0 +1,243 @@
+"""ctypes binding of libdifr.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, hands their device
+pointers and the current HIP stream to the C entry point of the same name, and returns
+freshly allocated output tensors.  No arithmetic of the method happens here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdifr.so")
+_lib = None
+
+FLAG_MATCH = 1
+FLAG_INVALID_CLAIM = 2
+FLAG_NONFINITE = 4
+FLAG_SLOW_PATH = 8
+
+DTYPE_BF16 = 0
+DTYPE_F32 = 1
+
+
+class DifrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().difr_status_string(status).decode()
+        super().__init__("%s: difr_status %d (%s)" % (where, status, msg))
+
+
+class _Rows(C.Structure):
+    _fields_ = [
+        ("logits", C.c_void_p),
+        ("dtype", C.c_int32),
+        ("N", C.c_int64),
+        ("V", C.c_int64),
+        ("ld", C.c_int64),
+        ("temperature", C.c_float),
+        ("temperatures", C.c_void_p),
+        ("seeds", C.c_void_p),
+        ("S", C.c_int64),
+        ("seq_ids", C.c_void_p),
+        ("positions", C.c_void_p),
+        ("claimed", C.c_void_p),
+    ]
+
+
+EXPORTS = ("difr_gumbel_score", "difr_ipt_score", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+           "difr_philox4x32_10", "difr_status_string", "difr_version")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdifr.so.  Raises if it has not been built: there is no fallback path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libdifr.so is missing at %s: build it with `python -m paper_2511_02620_amd.build` "
+                          "(there is no CPU fallback)" % _LIB_PATH)
+    lib = C.CDLL(_LIB_PATH)
+    vp = C.c_void_p
+    lib.difr_gumbel_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp]
+    lib.difr_gumbel_score.restype = C.c_int
+    lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp]
+    lib.difr_ipt_score.restype = C.c_int
+    lib.difr_seq_reduce.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_float, vp, vp, vp, vp, vp]
+    lib.difr_seq_reduce.restype = C.c_int
+    lib.difr_debug_noise.argtypes = [C.POINTER(_Rows), C.c_int64, C.c_int32, vp, vp]
+    lib.difr_debug_noise.restype = C.c_int
+    lib.difr_debug_gumbel_map.argtypes = [vp, C.c_int64, vp, vp]
+    lib.difr_debug_gumbel_map.restype = C.c_int
+    lib.difr_philox4x32_10.argtypes = [C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    lib.difr_philox4x32_10.restype = None
+    lib.difr_status_string.argtypes = [C.c_int]
+    lib.difr_status_string.restype = C.c_char_p
+    lib.difr_version.argtypes = []
+    lib.difr_version.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().difr_version())
+
+
+def philox4x32_10(ctr, key):
+    """Host helper: one Philox4x32-10 block (4 counter words, 2 key words) -> 4 words."""
+    c = (C.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (C.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = (C.c_uint32 * 4)()
+    load_library().difr_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def _stream_ptr(device) -> int:
+    return int(torch.cuda.current_stream(device).cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _check(t, dtype, n, name, device):
+    if t is None:
+        return
+    if t.device != device:
+        raise ValueError("%s must live on %s" % (name, device))
+    if t.dtype != dtype or t.dim() != 1 or t.shape[0] != n or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous 1-D %s tensor of %d elements" % (name, dtype, n))
+
+
+def _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures):
+    if not logits.is_cuda:
+        raise ValueError("logits must be a GPU tensor")
+    if logits.dim() != 2 or logits.stride(1) != 1 and logits.shape[1] > 1:
+        raise ValueError("logits must be 2-D with unit column stride")
+    if logits.dtype == torch.bfloat16:
+        dt = DTYPE_BF16
+    elif logits.dtype == torch.float32:
+        dt = DTYPE_F32
+    else:
+        raise ValueError("logits must be bfloat16 or float32")
+    dev = logits.device
+    N = logits.shape[0]
+    V = logits.shape[1] if V is None else int(V)
+    ld = logits.stride(0) if N > 1 else max(logits.shape[1], logits.stride(0) if N else 0)
+    _check(seq_ids, torch.int32, N, "seq_ids", dev)
+    _check(positions, torch.int32, N, "positions", dev)   # uint32 bit patterns held in int32
+    _check(claimed, torch.int32, N, "claimed", dev)
+    _check(temperatures, torch.float32, N, "temperatures", dev)
+    if seeds.device != dev or seeds.dtype != torch.int64 or seeds.dim() != 1 or not seeds.is_contiguous():
+        raise ValueError("seeds must be a contiguous 1-D int64 GPU tensor (uint64 bit patterns)")
+    r = _Rows()
+    r.logits = logits.data_ptr()
+    r.dtype = dt
+    r.N, r.V, r.ld = N, V, ld
+    r.temperature = float(temperature)
+    r.temperatures = None if temperatures is None else temperatures.data_ptr()
+    r.seeds = seeds.data_ptr()
+    r.S = seeds.shape[0]
+    r.seq_ids = seq_ids.data_ptr()
+    r.positions = positions.data_ptr()
+    r.claimed = None if claimed is None else claimed.data_ptr()
+    return r, N, dev
+
+
+def gumbel_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temperatures=None, V=None,
+                 want_scores=True):
+    """difr_gumbel_score.  logits [N, >=V] bf16/fp32 on the GPU; seeds int64 [S] (uint64 bits);
+    seq_ids, positions, claimed int32 [N].  Returns a dict of device tensors."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
+    out = dict(margin=torch.empty(N, dtype=torch.float32, device=dev),
+               argmax=torch.empty(N, dtype=torch.int32, device=dev),
+               flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_scores:
+        out["max_score"] = torch.empty(N, dtype=torch.float32, device=dev)
+        out["claimed_score"] = torch.empty(N, dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        rc = lib.difr_gumbel_score(C.byref(r), _ptr(out["margin"]), _ptr(out["argmax"]), _ptr(out.get("max_score")),
+                                   _ptr(out.get("claimed_score")), _ptr(out["flags"]), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_gumbel_score")
+    return out
+
+
+def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temperatures=None, V=None,
+              want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30, want_interval=True):
+    """difr_ipt_score.  Same inputs as :func:`gumbel_score`.  Returns a dict of device tensors."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(dist=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_interval:
+        out.update(cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32), u=torch.empty(N, **f32))
+    if want_token:
+        out["ipt_token"] = torch.empty(N, dtype=torch.int32, device=dev)
+    if want_log_mass:
+        out["log_mass"] = torch.empty(N, **f32)
+    with torch.cuda.device(dev):
+        rc = lib.difr_ipt_score(C.byref(r), _ptr(out["dist"]), _ptr(out.get("cdf_lo")), _ptr(out.get("cdf_hi")),
+                                _ptr(out.get("u")), _ptr(out.get("ipt_token")), float(sigma), float(eps),
+                                _ptr(out.get("log_mass")), _ptr(out["flags"]), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_ipt_score")
+    return out
+
+
+def seq_reduce(scores, row_flags, seq_offsets, threshold):
+    """difr_seq_reduce.  scores fp32 [N], row_flags uint8 [N] or None, seq_offsets int64 [S+1]."""
+    lib = load_library()
+    if not scores.is_cuda or scores.dtype != torch.float32 or scores.dim() != 1 or not scores.is_contiguous():
+        raise ValueError("scores must be a contiguous 1-D float32 GPU tensor")
+    dev = scores.device
+    N = scores.shape[0]
+    _check(row_flags, torch.uint8, N, "row_flags", dev)
+    if (seq_offsets.device != dev or seq_offsets.dtype != torch.int64 or seq_offsets.dim() != 1
+            or seq_offsets.shape[0] < 1 or not seq_offsets.is_contiguous()):
+        raise ValueError("seq_offsets must be a contiguous 1-D int64 GPU tensor of S+1 elements")
+    S = seq_offsets.shape[0] - 1
+    out = dict(seq_mean=torch.empty(S, dtype=torch.float32, device=dev),
+               seq_max=torch.empty(S, dtype=torch.float32, device=dev),
+               seq_mismatch=torch.empty(S, dtype=torch.int32, device=dev),
+               seq_flag=torch.empty(S, dtype=torch.uint8, device=dev))
+    with torch.cuda.device(dev):
+        rc = lib.difr_seq_reduce(_ptr(scores), _ptr(row_flags), _ptr(seq_offsets), N, S, float(threshold),
+                                 _ptr(out["seq_mean"]), _ptr(out["seq_max"]), _ptr(out["seq_mismatch"]),
+                                 _ptr(out["seq_flag"]), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_seq_reduce")
+    return out
+
+
+def debug_noise(logits, temperature, seeds, seq_ids, positions, row, stream, V=None):
+    """difr_debug_noise: raw noise words (int32 tensor holding uint32 bits) of one row."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, None, None)
+    bits = torch.empty(int(r.V), dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        rc = lib.difr_debug_noise(C.byref(r), int(row), int(stream), _ptr(bits), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_debug_noise")
+    return bits
+
+
+def debug_gumbel_map(bits):
+    """difr_debug_gumbel_map: device bits -> Gumbel map for an int32 tensor of raw words."""
+    lib = load_library()
+    if not bits.is_cuda or bits.dtype != torch.int32 or not bits.is_contiguous():
+        raise ValueError("bits must be a contiguous int32 GPU tensor")
+    g = torch.empty(bits.numel(), dtype=torch.float32, device=bits.device)
+    with torch.cuda.device(bits.device):
+        rc = lib.difr_debug_gumbel_map(_ptr(bits), bits.numel(), _ptr(g), _stream_ptr(bits.device))
+    if rc:
+        raise DifrError(rc, "difr_debug_gumbel_map")
+    return g

@@ -1,0 +1,164 @@
+// C ABI of libdifr.so: argument validation and kernel launches.  See include/difr.h for
+// the meaning, layout and ownership of every argument.
+#include <math.h>
+#include <string.h>
+
+#include <atomic>
+
+#include "../../include/difr.h"
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+// 0 = not checked yet, 1 = gfx950, 2 = something else.  A cache, not state: the answer
+// for a device never changes.
+std::atomic<int> g_arch_ok[kMaxDevices];
+
+int check_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return DIFR_ERR_UNSUPPORTED;
+    if (dev < kMaxDevices) {
+        const int c = g_arch_ok[dev].load(std::memory_order_relaxed);
+        if (c) return c == 1 ? DIFR_OK : DIFR_ERR_UNSUPPORTED;
+    }
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return DIFR_ERR_UNSUPPORTED;
+    const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+    if (dev < kMaxDevices) g_arch_ok[dev].store(ok ? 1 : 2, std::memory_order_relaxed);
+    return ok ? DIFR_OK : DIFR_ERR_UNSUPPORTED;
+}
+
+int validate_rows(const difr_rows *in, difr::RowBatch *b, bool *aligned)
+{
+    if (!in) return DIFR_ERR_NULL;
+    if (in->N < 0 || in->V < 0 || in->ld < 0 || in->S < 0) return DIFR_ERR_SHAPE;
+    if (in->N >= (int64_t)1 << 31 || in->V >= (int64_t)1 << 31) return DIFR_ERR_SHAPE;
+    if (in->dtype != DIFR_BF16 && in->dtype != DIFR_F32) return DIFR_ERR_DTYPE;
+    if (in->N > 0) {
+        if (in->V == 0 || in->ld < in->V || in->S < 1) return DIFR_ERR_SHAPE;
+        if (!in->logits || !in->seeds || !in->seq_ids || !in->positions) return DIFR_ERR_NULL;
+        if (!in->temperatures && !(in->temperature > 0.0f && isfinite(in->temperature))) return DIFR_ERR_TEMPERATURE;
+    }
+    const uintptr_t esz = in->dtype == DIFR_BF16 ? 2u : 4u;
+    const uintptr_t base = (uintptr_t)in->logits;
+    if (base % esz) return DIFR_ERR_ALIGN;
+    *aligned = (base % 16u == 0) && (((uint64_t)in->ld * esz) % 16u == 0);
+    b->logits = in->logits;
+    b->dtype = in->dtype;
+    b->N = in->N;
+    b->V = in->V;
+    b->ld = in->ld;
+    b->temperature = in->temperature;
+    b->temperatures = in->temperatures;
+    b->seeds = in->seeds;
+    b->S = in->S;
+    b->seq_ids = in->seq_ids;
+    b->positions = in->positions;
+    b->claimed = in->claimed;
+    return DIFR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
+                      uint8_t *flags, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    return difr::launch_gumbel_score(b, aligned, margin, argmax, max_score, claimed_score, flags,
+                                     (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token,
+                   double sigma, double eps, float *log_mass, uint8_t *flags, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
+    if (b.N == 0) return DIFR_OK;
+    if (!dist || !flags) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    return difr::launch_ipt_score(b, aligned, dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags,
+                                  (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N, int64_t S,
+                    float threshold, float *seq_mean, float *seq_max, int32_t *seq_mismatch, uint8_t *seq_flag,
+                    void *hip_stream)
+{
+    if (N < 0 || S < 0 || S >= (int64_t)1 << 31) return DIFR_ERR_SHAPE;
+    if (threshold != threshold) return DIFR_ERR_ARGUMENT;
+    if (S == 0) return DIFR_OK;
+    if (!seq_offsets || (N > 0 && !scores)) return DIFR_ERR_NULL;
+    int rc = check_device();
+    if (rc != DIFR_OK) return rc;
+    return difr::launch_seq_reduce(scores, row_flags, seq_offsets, N, S, threshold, seq_mean, seq_max, seq_mismatch,
+                                   seq_flag, (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_debug_noise(const difr_rows *in, int64_t row, int32_t stream, uint32_t *bits, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (row < 0 || row >= b.N || stream < 0) return DIFR_ERR_SHAPE;
+    if (!bits) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    return difr::launch_debug_noise(b, row, (uint32_t)stream, bits, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH
+                                                                                            : DIFR_OK;
+}
+
+int difr_debug_gumbel_map(const uint32_t *bits, int64_t n, float *g, void *hip_stream)
+{
+    if (n < 0) return DIFR_ERR_SHAPE;
+    if (n == 0) return DIFR_OK;
+    if (!bits || !g) return DIFR_ERR_NULL;
+    int rc = check_device();
+    if (rc != DIFR_OK) return rc;
+    return difr::launch_debug_gumbel_map(bits, n, g, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
+
+void difr_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    difr::PhiloxKey k{key[0], key[1]};
+    difr::philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], k, out);
+}
+
+const char *difr_status_string(int status)
+{
+    switch (status) {
+        case DIFR_OK: return "ok";
+        case DIFR_ERR_NULL: return "a required pointer is NULL";
+        case DIFR_ERR_SHAPE: return "bad shape (N, V, S, ld or row index)";
+        case DIFR_ERR_DTYPE: return "unknown logits dtype";
+        case DIFR_ERR_TEMPERATURE: return "temperature must be finite and > 0";
+        case DIFR_ERR_ALIGN: return "logits pointer not aligned to its element size";
+        case DIFR_ERR_LAUNCH: return "HIP kernel launch failed";
+        case DIFR_ERR_UNSUPPORTED: return "current device is not gfx950";
+        case DIFR_ERR_ARGUMENT: return "bad scalar argument (sigma, eps or threshold)";
+        default: return "unknown status";
+    }
+}
+
+int difr_version(void) { return 100; }
+
+}  // extern "C"

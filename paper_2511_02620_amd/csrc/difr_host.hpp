@@ -1,0 +1,23 @@
+// Host-side launch functions implemented next to each kernel; called by the C ABI layer.
+// Each returns 0 on success, non-zero if the HIP runtime refused the launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "difr_device.hpp"
+
+namespace difr {
+
+int launch_gumbel_score(const RowBatch &b, bool aligned, float *margin, int32_t *argmax, float *max_score,
+                        float *claimed_score, uint8_t *flags, hipStream_t stream);
+int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                     int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
+                     hipStream_t stream);
+int launch_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,
+                      int64_t S, float threshold, float *seq_mean, float *seq_max, int32_t *seq_mismatch,
+                      uint8_t *seq_flag, hipStream_t stream);
+int launch_debug_noise(const RowBatch &b, int64_t row, uint32_t stream_id, uint32_t *bits, hipStream_t stream);
+int launch_debug_gumbel_map(const uint32_t *bits, int64_t n, float *g, hipStream_t stream);
+
+}  // namespace difr

@@ -1,0 +1,153 @@
+// Token-DiFR row kernel: regenerate the seeded Gumbel noise over the whole vocabulary,
+// rank by y_v = x_v / T + g_v, report the regenerated token (argmax) and the claimed
+// token's margin  max_v y_v - y_t  (= -min_i A_{sigma,i} / T in the notation of the
+// appendix algorithm of the Gumbel likelihood estimator; Sec. 6.3, Sec. 3.2).
+//
+// One workgroup (4 wavefronts) per token row; the row is streamed exactly once with
+// 128-bit loads; noise is generated in registers, four vocabulary entries per Philox
+// block; nothing of size V is ever stored.
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+
+namespace difr {
+
+template <int DT, bool ALIGNED>
+__global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float *__restrict__ margin,
+                                                              int32_t *__restrict__ argmax,
+                                                              float *__restrict__ max_score,
+                                                              float *__restrict__ claimed_score,
+                                                              uint8_t *__restrict__ flags)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ float lds_y[kWaves];
+    __shared__ int32_t lds_i[kWaves];
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    const int tid = threadIdx.x;
+    const float nan = __builtin_nanf("");
+
+    if (!ri.seq_ok || !ri.temp_ok) {  // uniform over the workgroup
+        if (tid == 0) {
+            margin[row] = nan;
+            argmax[row] = -1;
+            if (max_score) max_score[row] = nan;
+            if (claimed_score) claimed_score[row] = nan;
+            flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
+        }
+        return;
+    }
+
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const int64_t V = b.V;
+    const float inv_T = 1.0f / ri.T;
+
+    float best_y = -__builtin_inff();
+    int32_t best_v = 0x7FFFFFFF;
+    uint32_t bad = 0;
+
+    for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
+        float x[E];
+        load_elems<DT, ALIGNED>(x_row, base, V, x);
+#pragma unroll
+        for (int q = 0; q < E / 4; ++q) {
+            uint32_t r[4];
+            noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)((base >> 2) + q), r);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float xv = x[4 * q + j];
+                const float y = perturbed_score(xv, inv_T, r[j]);
+                bad |= (uint32_t)!(xv < __builtin_inff());  // NaN or +inf
+                if (y > best_y) {
+                    best_y = y;
+                    best_v = (int32_t)(base + 4 * q + j);
+                }
+            }
+        }
+    }
+
+    block_argmax(best_y, best_v, lds_y, lds_i);
+    const int any_bad = __syncthreads_or((int)bad);
+
+    if (tid == 0) {
+        if (best_v == 0x7FFFFFFF) best_v = 0;  // every entry masked: all scores are -inf
+        uint32_t f = any_bad ? kFlagNonfinite : 0u;
+        float yt = nan, mg = nan;
+        const int32_t t = ri.claimed;
+        if (t >= 0 && (int64_t)t < V) {
+            uint32_t r[4];
+            noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)t >> 2, r);
+            const uint32_t rt = (t & 3) == 0 ? r[0] : (t & 3) == 1 ? r[1] : (t & 3) == 2 ? r[2] : r[3];
+            yt = perturbed_score(Elem<DT>::to_float(x_row[t]), inv_T, rt);
+            mg = best_y - yt;
+            if (best_v == t) f |= kFlagMatch;
+        } else {
+            f |= kFlagInvalidClaim;
+        }
+        margin[row] = mg;
+        argmax[row] = best_v;
+        if (max_score) max_score[row] = best_y;
+        if (claimed_score) claimed_score[row] = yt;
+        flags[row] = (uint8_t)f;
+    }
+}
+
+// Raw noise words of one row, through the same device code as the scoring kernels.
+__global__ __launch_bounds__(kBlock) void debug_noise_kernel(RowBatch b, int64_t row, uint32_t stream,
+                                                             uint32_t *__restrict__ bits)
+{
+    const RowInfo ri = load_row_info(b, row);
+    const int64_t nq = (b.V + 3) >> 2;
+    for (int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x; q < nq; q += (int64_t)gridDim.x * kBlock) {
+        uint32_t r[4];
+        noise_block(ri.key, ri.pos, ri.seq, stream, (uint32_t)q, r);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (4 * q + j < b.V) bits[4 * q + j] = r[j];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void debug_gumbel_map_kernel(const uint32_t *__restrict__ bits, int64_t n,
+                                                                  float *__restrict__ g)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
+        g[i] = gumbel_from_bits(bits[i]);
+}
+
+int launch_gumbel_score(const RowBatch &b, bool aligned, float *margin, int32_t *argmax, float *max_score,
+                        float *claimed_score, uint8_t *flags, hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    if (b.dtype == 0) {
+        if (aligned)
+            gumbel_score_kernel<0, true><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+        else
+            gumbel_score_kernel<0, false><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+    } else {
+        if (aligned)
+            gumbel_score_kernel<1, true><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+        else
+            gumbel_score_kernel<1, false><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_debug_noise(const RowBatch &b, int64_t row, uint32_t stream_id, uint32_t *bits, hipStream_t stream)
+{
+    const int64_t nq = (b.V + 3) >> 2;
+    int64_t blocks = (nq + kBlock - 1) / kBlock;
+    if (blocks > 4096) blocks = 4096;
+    debug_noise_kernel<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(b, row, stream_id, bits);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_debug_gumbel_map(const uint32_t *bits, int64_t n, float *g, hipStream_t stream)
+{
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 8192) blocks = 8192;
+    debug_gumbel_map_kernel<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(bits, n, g);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

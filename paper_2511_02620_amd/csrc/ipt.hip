@@ -1,0 +1,274 @@
+// Token-IPT-DiFR row kernel: regenerate the seeded uniform u, form p = softmax(x / T)
+// and its CDF in ascending token order, and report the claimed token's interval
+// [a, b) = [Fbar_{t-1}, Fbar_t), the distance of u from it, and optionally the Gaussian
+// log-mass and the honest sampler's token  min{ v : C_v > u }.
+// (Sec. 3.2 softmax and IPT sampler; Sec. 6.2 and the appendix algorithm
+// "convolved Gaussian score".)
+//
+// One workgroup per token row, one streaming pass: every thread keeps an online
+// (max, sum) pair for the exponentials it has seen, plus a snapshot of its sum at the
+// point where its walk crosses the claimed token, which is its share of the prefix
+// sum_{v < t} e_v.  Nothing of size V is stored.  Only when the honest sampler's token
+// is asked for and differs from the claim is the row read a second time (block scan).
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+
+namespace difr {
+
+// Inclusive scan (fp64) over the 256 threads in thread order; returns the inclusive value and
+// the block total.  Fixed shape.
+__device__ __forceinline__ double block_inclusive_scan(double v, double *lds /* kWaves */, double &total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double o = __shfl_up(v, off, 64);
+        if (lane >= off) v += o;
+    }
+    __syncthreads();
+    if (lane == 63) lds[wave] = v;
+    __syncthreads();
+    double before = 0.0, tot = 0.0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const double s = lds[w];
+        if (w < wave) before += s;
+        tot += s;
+    }
+    total = tot;
+    return v + before;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double *lds /* kWaves */)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double s = lds[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) s += lds[i];
+    return s;
+}
+
+// Sum of the E exponentials of one vector as a fixed binary tree in fp32.
+template <int E>
+__device__ __forceinline__ float tree_sum(const float e[E])
+{
+    float t[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) t[j] = e[j];
+#pragma unroll
+    for (int w = E / 2; w >= 1; w >>= 1) {
+#pragma unroll
+        for (int j = 0; j < w; ++j) t[j] += t[j + w];
+    }
+    return t[0];
+}
+
+// Gaussian log-mass of [a,b] under N(u, sigma^2), fp64:
+//   ln( Phi((b-u)/sigma) - Phi((a-u)/sigma) + eps ),
+// with the difference taken on the non-cancelling side (erfc in the tails).
+__device__ double gaussian_log_mass(double a, double b, double u, double sigma, double eps)
+{
+    const double s = 1.0 / (sigma * 1.4142135623730951);
+    const double za = (a - u) * s, zb = (b - u) * s;
+    double mass;
+    if (za >= 0.0)
+        mass = 0.5 * (erfc(za) - erfc(zb));
+    else if (zb <= 0.0)
+        mass = 0.5 * (erfc(-zb) - erfc(-za));
+    else
+        mass = 0.5 * (erf(zb) + erf(-za));
+    if (mass < 0.0) mass = 0.0;
+    return log(mass + eps);
+}
+
+template <int DT, bool ALIGNED>
+__global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, float *__restrict__ dist,
+                                                           float *__restrict__ cdf_lo, float *__restrict__ cdf_hi,
+                                                           float *__restrict__ u_out, int32_t *__restrict__ ipt_token,
+                                                           double sigma, double eps, float *__restrict__ log_mass,
+                                                           uint8_t *__restrict__ flags)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ float lds_f[kWaves];
+    __shared__ double lds_d[kWaves];
+    __shared__ int32_t lds_tok;
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    const int tid = threadIdx.x;
+    const float nan = __builtin_nanf("");
+    const float ninf = -__builtin_inff();
+
+    if (!ri.seq_ok || !ri.temp_ok) {
+        if (tid == 0) {
+            dist[row] = nan;
+            if (cdf_lo) cdf_lo[row] = nan;
+            if (cdf_hi) cdf_hi[row] = nan;
+            if (u_out) u_out[row] = nan;
+            if (ipt_token) ipt_token[row] = -1;
+            if (log_mass) log_mass[row] = nan;
+            flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
+        }
+        return;
+    }
+
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const int64_t V = b.V;
+    const float c = kLog2e / ri.T;  // exponent scale: exp(x/T) = 2^(x c)
+    const int64_t t = ri.claimed;
+    const bool valid = (t >= 0 && t < V);
+    const int64_t tcut = valid ? t : 0;  // prefix is over v < tcut
+
+    // Online softmax statistics of this thread's entries: m = running maximum logit, Z = sum of
+    // 2^((x - m) c).  Each vector's eight terms are summed as an fp32 tree and the vector sums are
+    // accumulated in fp64, so the CDF values are good to fp32 rounding.  (P, mP): the same sum
+    // restricted to v < t, frozen when the thread's walk crosses the claimed token.
+    float m = ninf, neg_mc = 0.0f, mP = ninf;
+    double Z = 0.0, P = 0.0;
+
+    for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
+        float x[E], e[E];
+        load_elems<DT, ALIGNED>(x_row, base, V, x);
+        float m8 = x[0];
+#pragma unroll
+        for (int j = 1; j < E; ++j) m8 = fmaxf(m8, x[j]);
+        if (m8 > m) {  // rebase the running sum (m = -inf: Z is still 0 and stays 0)
+            Z *= (double)fast_exp2((m - m8) * c);
+            m = m8;
+            neg_mc = -(m8 * c);
+        }
+        // while only masked entries have been seen neg_mc is 0, so the exponent stays -inf, not NaN
+#pragma unroll
+        for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, neg_mc));
+        const float vs = tree_sum<E>(e);
+        if (base + E <= tcut) {  // wholly below the claimed token
+            Z += (double)vs;
+            P = Z;
+            mP = m;
+        } else if (base < tcut) {  // the claimed token sits inside this vector
+            float pre = 0.0f;
+#pragma unroll
+            for (int j = 0; j < E; ++j)
+                if (base + j < tcut) pre += e[j];
+            P = Z + (double)pre;
+            mP = m;
+            Z += (double)vs;
+        } else {
+            Z += (double)vs;
+        }
+    }
+
+    // Combine the 256 partial (max, sum) pairs in a fixed order.
+    const float M = block_max(m, lds_f);
+    const float neg_Mc = -(M * c);
+    // a thread that saw only masked entries has m = -inf and Z = 0: its scale is 2^-inf = 0
+    const double Zs = Z * (double)fast_exp2((m - M) * c);
+    const double Ps = (mP > ninf) ? P * (double)fast_exp2((mP - M) * c) : 0.0;
+    const double Ztot = block_sum_f64(Zs, lds_d);
+    const double Ptot = block_sum_f64(Ps, lds_d);
+
+    // Regenerated uniform: stream 1, vocabulary index 0.
+    uint32_t r[4];
+    noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r);
+    const float u = uniform_from_bits(r[0]);
+
+    // Z is NaN if a NaN logit was seen, +inf if a +inf logit was (then M = +inf); M = -inf if every
+    // entry is masked.  All of these make the distribution undefined.
+    const bool bad = !(Ztot > 0.0) || !(Ztot < (double)__builtin_inff()) || !(M < __builtin_inff()) || !(M > ninf);
+
+    float a = nan, bb = nan, d = nan;
+    bool match = false;
+    if (valid && !bad) {
+        const double et = (double)fast_exp2(__fmaf_rn(Elem<DT>::to_float(x_row[t]), c, neg_Mc));
+        const double ad = Ptot / Ztot, bd = (Ptot + et) / Ztot, ud = (double)u;
+        a = (float)ad;
+        bb = (float)bd;
+        d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+        match = (ad <= ud) && (ud < bd);
+    }
+
+    uint32_t f = 0;
+    if (!valid) f |= kFlagInvalidClaim;
+    if (bad) f |= kFlagNonfinite;
+    if (match) f |= kFlagMatch;
+
+    int32_t tok = match ? (int32_t)t : -1;
+    if (ipt_token != nullptr && !match && !bad) {
+        // Second pass: walk the CDF in token order until it exceeds u * Z.
+        f |= kFlagSlowPath;
+        const double target = (double)u * Ztot;
+        double before = 0.0;  // mass of all entries before the current step
+        if (tid == 0) lds_tok = -1;
+        __syncthreads();
+        for (int64_t step0 = 0; step0 < V; step0 += (int64_t)kBlock * E) {
+            const int64_t base = step0 + (int64_t)tid * E;
+            float e[E];
+            if (base < V) {
+                float x[E];
+                load_elems<DT, ALIGNED>(x_row, base, V, x);
+#pragma unroll
+                for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+            } else {
+#pragma unroll
+                for (int j = 0; j < E; ++j) e[j] = 0.0f;
+            }
+            const double ls = (double)tree_sum<E>(e);
+            double total;
+            const double incl = block_inclusive_scan(ls, lds_d, total);
+            if (before + total > target) {  // uniform: the token is inside this step
+                const double excl = before + (incl - ls);
+                if (excl <= target && before + incl > target) {  // exactly one thread
+                    double cacc = excl;
+                    int32_t found = -1;
+#pragma unroll
+                    for (int j = 0; j < E; ++j) {
+                        cacc += (double)e[j];
+                        if (found < 0 && cacc > target) found = (int32_t)(base + j);
+                    }
+                    if (found < 0) found = (int32_t)((base + E - 1 < V) ? base + E - 1 : V - 1);
+                    lds_tok = found;
+                }
+                break;
+            }
+            before += total;
+        }
+        __syncthreads();
+        tok = lds_tok;
+        if (tok < 0) tok = (int32_t)(V - 1);  // u * Z at or beyond the accumulated total
+    }
+
+    if (tid == 0) {
+        dist[row] = d;
+        if (cdf_lo) cdf_lo[row] = a;
+        if (cdf_hi) cdf_hi[row] = bb;
+        if (u_out) u_out[row] = u;
+        if (ipt_token) ipt_token[row] = bad ? -1 : tok;
+        if (log_mass)
+            log_mass[row] = (valid && !bad) ? (float)gaussian_log_mass((double)a, (double)bb, (double)u, sigma, eps) : nan;
+        flags[row] = (uint8_t)f;
+    }
+}
+
+int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                     int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
+                     hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+#define DIFR_IPT_LAUNCH(DT, AL)                                                                              \
+    ipt_score_kernel<DT, AL><<<grid, block, 0, stream>>>(b, dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, \
+                                                          log_mass, flags)
+    if (b.dtype == 0) {
+        if (aligned) DIFR_IPT_LAUNCH(0, true); else DIFR_IPT_LAUNCH(0, false);
+    } else {
+        if (aligned) DIFR_IPT_LAUNCH(1, true); else DIFR_IPT_LAUNCH(1, false);
+    }
+#undef DIFR_IPT_LAUNCH
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

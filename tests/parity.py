@@ -1,0 +1,143 @@
+"""Comparison rules between the HIP path and the CPU oracle.
+
+Bars (from the build's contract): noise bits, indices and flags bit-exact, except where
+floating point decides them and the oracle's own gap is below 1e-6 relative (those are
+excused AND counted); fp32 margins, CDF values and distances within 1e-4 absolute.
+"""
+import numpy as np
+import torch
+
+import oracle
+
+ABS_TOL = 1e-4          # fp32 margins, interval ends, distances
+TIE_REL = 1e-6          # oracle gap below this (relative) => either answer is accepted
+
+
+def to_host_logits(t: torch.Tensor) -> np.ndarray:
+    """Device or host logits tensor -> numpy array the oracle accepts (uint16 bf16 bits / float32)."""
+    t = t.detach().cpu().contiguous()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    assert t.dtype == torch.float32
+    return t.numpy()
+
+
+def seeds_u64(seeds: torch.Tensor) -> np.ndarray:
+    return seeds.cpu().numpy().view(np.uint64)
+
+
+def positions_u32(pos: torch.Tensor) -> np.ndarray:
+    return pos.cpu().numpy().view(np.uint32)
+
+
+def _np(d):
+    return {k: (v.detach().cpu().numpy() if isinstance(v, torch.Tensor) else v) for k, v in d.items()}
+
+
+def _close(gpu, ref, tol, what):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    both_nan = np.isnan(gpu) & np.isnan(ref)
+    both_inf = np.isinf(gpu) & np.isinf(ref) & (np.sign(gpu) == np.sign(ref))
+    err = np.where(both_nan | both_inf, 0.0, np.abs(gpu - ref))
+    bad = ~(err <= tol)
+    assert not bad.any(), "%s: %d rows beyond %g, worst %g at row %d (gpu %r, oracle %r)" % (
+        what, int(bad.sum()), tol, float(np.nanmax(err)), int(np.argmax(np.nan_to_num(err, nan=np.inf))),
+        gpu[np.argmax(np.nan_to_num(err, nan=np.inf))], ref[np.argmax(np.nan_to_num(err, nan=np.inf))])
+    return float(err.max()) if err.size else 0.0
+
+
+def compare_gumbel(gpu: dict, ref: dict):
+    """gpu: outputs of the binding (torch), ref: outputs of oracle.gumbel_score (numpy).
+    Returns a dict of counters (near ties that were excused, worst errors)."""
+    g = _np(gpu)
+    n = ref["margin"].shape[0]
+    scale = np.maximum(1.0, np.abs(ref["max_score"]))
+    near_tie = ref["gap2"] < TIE_REL * scale
+    stats = {"rows": n, "near_ties": int(near_tie.sum())}
+    stats["margin_err"] = _close(g["margin"], ref["margin"], ABS_TOL, "margin")
+    if "max_score" in g:
+        stats["max_err"] = _close(g["max_score"], ref["max_score"], ABS_TOL, "max_score")
+        stats["claimed_err"] = _close(g["claimed_score"], ref["claimed_score"], ABS_TOL, "claimed_score")
+    diff = g["argmax"] != ref["argmax"]
+    assert not (diff & ~near_tie).any(), "argmax differs on %d rows that are not near ties: rows %s" % (
+        int((diff & ~near_tie).sum()), np.nonzero(diff & ~near_tie)[0][:10])
+    stats["argmax_excused"] = int(diff.sum())
+    fdiff = (g["flags"] ^ ref["flags"]).astype(np.uint8)
+    assert not (fdiff & ~np.uint8(1)).any(), "non-MATCH flag bits differ on rows %s" % np.nonzero(fdiff & 0xFE)[0][:10]
+    assert not ((fdiff & 1).astype(bool) & ~near_tie).any(), "MATCH differs outside near ties"
+    stats["match_excused"] = int((fdiff & 1).sum())
+    assert (g["margin"][~np.isnan(g["margin"])] >= 0).all()
+    return stats
+
+
+def compare_ipt(gpu: dict, ref: dict, logits_host=None, V=None, row_args=None, log_mass_sigma=None):
+    """ref: outputs of oracle.ipt_score.  If tokens are compared and some differ, `logits_host`
+    (numpy, as given to the oracle), `V` and `row_args` (T or per-row temps, seeds, seq_ids,
+    positions as numpy) let the near-tie rule look at the oracle interval of the GPU's token."""
+    g = _np(gpu)
+    n = ref["dist"].shape[0]
+    stats = {"rows": n}
+    stats["dist_err"] = _close(g["dist"], ref["dist"], ABS_TOL, "dist")
+    if "cdf_lo" in g:
+        stats["cdf_err"] = max(_close(g["cdf_lo"], ref["cdf_lo"], ABS_TOL, "cdf_lo"),
+                               _close(g["cdf_hi"], ref["cdf_hi"], ABS_TOL, "cdf_hi"))
+        ok = ~np.isnan(g["u"])
+        assert np.array_equal(g["u"][ok].astype(np.float64), ref["u"][ok]), "regenerated uniform differs"
+    near_edge = np.nan_to_num(ref["edge"], nan=np.inf) < TIE_REL
+    stats["near_edges"] = int(near_edge.sum())
+    slow = np.uint8(8)
+    fdiff = ((g["flags"] & ~slow) ^ ref["flags"]).astype(np.uint8)
+    assert not (fdiff & ~np.uint8(1)).any(), "non-MATCH flag bits differ on rows %s" % np.nonzero(fdiff & 0xFE)[0][:10]
+    assert not ((fdiff & 1).astype(bool) & ~near_edge).any(), "MATCH differs outside near ties: rows %s" % (
+        np.nonzero((fdiff & 1).astype(bool) & ~near_edge)[0][:10])
+    stats["match_excused"] = int((fdiff & 1).sum())
+    if "ipt_token" in g:
+        diff = np.nonzero(g["ipt_token"] != ref["ipt_token"])[0]
+        excused = 0
+        for r in diff:
+            assert logits_host is not None, "ipt_token differs on row %d" % r
+            T, seeds, seq_ids, positions = row_args
+            Tr = float(T[r]) if np.ndim(T) else float(T)
+            x = oracle.decode_row(np.ascontiguousarray(logits_host[r, :V]))
+            alt = oracle.ipt_row(x, Tr, int(seeds[seq_ids[r]]), int(seq_ids[r]), int(positions[r]),
+                                 int(g["ipt_token"][r]))
+            # the GPU's token must own an interval that touches u within the tie width
+            assert alt["dist"] < TIE_REL and alt["cdf_hi"] > alt["cdf_lo"], \
+                "ipt_token differs on row %d beyond a near tie (oracle %d, gpu %d, dist %g)" % (
+                    r, ref["ipt_token"][r], g["ipt_token"][r], alt["dist"])
+            excused += 1
+        stats["token_excused"] = excused
+    if "log_mass" in g and log_mass_sigma is not None:
+        # The log-mass is evaluated in fp64 from the kernel's fp32 a, b, u, so it inherits their error da.
+        # S = ln(mass + eps), mass = Phi(zb) - Phi(za):  dS = (phi(zb) db - phi(za) da) / (sigma (mass + eps)).
+        # u inside a narrow interval: mass ~ phi(z) (b-a)/sigma, so |dS| <~ da / (b-a) + |z| da / sigma;
+        # u outside (Gaussian tail):  mass ~ phi(z)/|z|,         so |dS| <~ |z| da / sigma, |z| = dist/sigma.
+        da = np.maximum(np.abs(np.nan_to_num(g["cdf_lo"] - ref["cdf_lo"])),
+                        np.abs(np.nan_to_num(g["cdf_hi"] - ref["cdf_hi"]))) + 1e-7
+        z = np.nan_to_num(ref["dist"], nan=0.0) / log_mass_sigma
+        width = np.maximum(ref["cdf_hi"] - ref["cdf_lo"], 1e-30)
+        tol = 1e-4 + 4.0 * da * (1.0 + z) / log_mass_sigma + 4.0 * da / np.nan_to_num(width, nan=1.0)
+        gl, rl = g["log_mass"].astype(np.float64), ref["log_mass"]
+        ok = ~(np.isnan(gl) & np.isnan(rl))
+        err = np.abs(gl[ok] - rl[ok])
+        assert (err <= np.maximum(tol[ok], 1e-4 * np.abs(rl[ok]))).all(), "log_mass beyond its error bound: worst %g" % err.max()
+        stats["log_mass_err"] = float(err.max()) if err.size else 0.0
+    d = g["dist"][~np.isnan(g["dist"])]
+    assert (d >= 0).all() and (d < 1).all()
+    return stats
+
+
+def compare_seq(gpu: dict, ref: dict, tau: float, mismatch_slack: int = 0):
+    """mismatch_slack: number of MATCH bits that the row comparison excused as near ties; the
+    per-sequence mismatch counts may differ by that many in total."""
+    g = _np(gpu)
+    stats = {"seqs": ref["seq_mean"].shape[0]}
+    stats["mean_err"] = _close(g["seq_mean"], ref["seq_mean"], ABS_TOL, "seq_mean")
+    _close(g["seq_max"], ref["seq_max"], ABS_TOL, "seq_max")
+    assert int(np.abs(g["seq_mismatch"].astype(np.int64) - ref["seq_mismatch"]).sum()) <= mismatch_slack
+    near = np.abs(np.nan_to_num(ref["seq_mean"], nan=np.inf) - tau) <= TIE_REL * max(1.0, abs(tau))
+    diff = g["seq_flag"] != ref["seq_flag"]
+    assert not (diff & ~near).any(), "seq_flag differs outside near ties"
+    stats["flag_excused"] = int(diff.sum())
+    return stats

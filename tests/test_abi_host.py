@@ -1,0 +1,115 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every function that
+include/difr.h declares, rejects bad arguments before touching the device, and its host Philox
+agrees with the published vectors."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "difr.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2511_02620_amd import binding
+
+    if not os.path.exists(binding.lib_path()):
+        from paper_2511_02620_amd import build
+
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(difr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2511_02620_amd import binding
+
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS), names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings_and_version(lib):
+    assert lib.difr_version() >= 100
+    seen = set()
+    for code in range(0, 9):
+        s = lib.difr_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in lib.difr_status_string(99).decode()
+
+
+def test_host_philox_known_answers(lib):
+    from paper_2511_02620_amd import binding
+
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        t = line.split()
+        got = binding.philox4x32_10([int(x, 16) for x in t[0:4]], [int(x, 16) for x in t[4:6]])
+        for j, w in enumerate(t[6:10]):
+            if set(w) != {"-"}:
+                assert got[j] == int(w, 16)
+
+
+def test_argument_validation_needs_no_device(lib):
+    from paper_2511_02620_amd.binding import _Rows
+
+    OK, NULL, SHAPE, DTYPE, TEMP, ALIGN, _, _, ARG = range(9)
+    fake = 0x1000                       # never dereferenced: every call below fails validation first
+
+    def rows(**kw):
+        r = _Rows()
+        r.logits, r.dtype, r.N, r.V, r.ld = fake, 0, 4, 16, 16
+        r.temperature, r.temperatures = 1.0, None
+        r.seeds, r.S, r.seq_ids, r.positions, r.claimed = fake, 1, fake, fake, fake
+        for k, v in kw.items():
+            setattr(r, k, v)
+        return r
+
+    def g(r, margin=fake, argmax=fake, flags=fake):
+        return lib.difr_gumbel_score(C.byref(r), margin, argmax, None, None, flags, None)
+
+    def i(r, dist=fake, flags=fake, sigma=0.01, eps=1e-30, log_mass=None):
+        return lib.difr_ipt_score(C.byref(r), dist, None, None, None, None, sigma, eps, log_mass, flags, None)
+
+    assert lib.difr_gumbel_score(None, fake, fake, None, None, fake, None) == NULL
+    for bad, want in ((rows(N=-1), SHAPE), (rows(V=0), SHAPE), (rows(ld=15), SHAPE), (rows(S=0), SHAPE),
+                      (rows(N=1 << 31), SHAPE), (rows(V=1 << 31, ld=1 << 31), SHAPE), (rows(dtype=2), DTYPE),
+                      (rows(temperature=0.0), TEMP), (rows(temperature=-1.0), TEMP),
+                      (rows(temperature=float("nan")), TEMP), (rows(temperature=float("inf")), TEMP),
+                      (rows(logits=None), NULL), (rows(seeds=None), NULL), (rows(seq_ids=None), NULL),
+                      (rows(positions=None), NULL), (rows(logits=0x1001), ALIGN), (rows(dtype=1, logits=0x1002), ALIGN)):
+        assert g(bad) == want, want
+        assert i(bad) == want, want
+    assert g(rows(), margin=None) == NULL and g(rows(), argmax=None) == NULL and g(rows(), flags=None) == NULL
+    assert i(rows(), dist=None) == NULL and i(rows(), flags=None) == NULL
+    assert i(rows(), sigma=0.0, log_mass=fake) == ARG and i(rows(), eps=-1.0, log_mass=fake) == ARG
+    # an empty batch is a successful no-op and needs nothing else
+    assert g(rows(N=0, logits=None, seeds=None)) == OK and i(rows(N=0)) == OK
+    # pooling
+    assert lib.difr_seq_reduce(fake, None, fake, -1, 1, 0.0, None, None, None, None, None) == SHAPE
+    assert lib.difr_seq_reduce(fake, None, None, 4, 1, 0.0, None, None, None, None, None) == NULL
+    assert lib.difr_seq_reduce(None, None, fake, 4, 1, 0.0, None, None, None, None, None) == NULL
+    assert lib.difr_seq_reduce(fake, None, fake, 4, 1, float("nan"), None, None, None, None, None) == ARG
+    assert lib.difr_seq_reduce(None, None, None, 0, 0, 0.0, None, None, None, None, None) == OK
+    assert lib.difr_debug_noise(C.byref(rows()), 4, 0, fake, None) == SHAPE
+    assert lib.difr_debug_gumbel_map(None, 4, fake, None) == NULL
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    from paper_2511_02620_amd import binding
+
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libdifr.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

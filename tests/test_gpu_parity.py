@@ -1,0 +1,328 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the CPU
+oracle on identical seeded inputs.  Every test here needs a real MI355X."""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import parity
+from paper_2511_02620_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def difr():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2511_02620_amd as d
+
+    d.load_library()
+    return d
+
+
+DEV = "cuda:0"
+
+
+def f32(x):
+    """The temperature argument of the C ABI is a float: the oracle gets the same fp32 value."""
+    return float(np.float32(x))
+
+
+def u32_as_i32(t):
+    t = t.to(torch.int64) % (1 << 32)
+    return torch.where(t >= (1 << 31), t - (1 << 32), t).to(torch.int32)
+
+
+def _aux(wl, dev=DEV):
+    return (wl.seeds().to(dev), wl.seq_ids().to(dev), wl.positions().to(dev), wl.seq_offsets().to(dev))
+
+
+def _oracle_claims(wl, prover_host, row0):
+    """Honest claims of rows [row0, row0+R): the oracle samplers run on the prover logits."""
+    R = prover_host.shape[0]
+    seeds = parity.seeds_u64(wl.seeds())
+    sid = wl.seq_ids().numpy()[row0:row0 + R]
+    pos = parity.positions_u32(wl.positions())[row0:row0 + R]
+    g = oracle.gumbel_score(prover_host, wl.V, f32(wl.temperature), seeds, sid, pos)["argmax"]
+    i = oracle.ipt_score(prover_host, wl.V, f32(wl.temperature), seeds, sid, pos)["ipt_token"]
+    return torch.from_numpy(g.copy()), torch.from_numpy(i.copy())
+
+
+def _build_small(wl):
+    """Whole workload on the GPU plus oracle-made claims (small workloads only)."""
+    ver, cg, ci = [], [], []
+    for c in range(wl.n_chunks):
+        v, p = wl.logits_chunk(c, DEV)
+        hg, hi = _oracle_claims(wl, parity.to_host_logits(p), c * wl.chunk_rows)
+        cg.append(wl.mutate_claims(c, hg, v))
+        ci.append(wl.mutate_claims(c, hi, v))
+        ver.append(v)
+        del p
+    return torch.cat(ver), torch.cat(cg).to(DEV), torch.cat(ci).to(DEV)
+
+
+def _score_both_ways(difr, wl, logits, claims_g, claims_i, sigma=0.01, eps=1e-30, temps=None):
+    seeds, sid, pos, _ = _aux(wl)
+    host = parity.to_host_logits(logits)
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    ht = None if temps is None else temps.cpu().numpy()
+    gg = difr.gumbel_score(logits, wl.temperature, seeds, sid, pos, claims_g, temperatures=temps, V=wl.V)
+    gi = difr.ipt_score(logits, wl.temperature, seeds, sid, pos, claims_i, temperatures=temps, V=wl.V,
+                        want_token=True, want_log_mass=True, sigma=sigma, eps=eps)
+    torch.cuda.synchronize()
+    og = oracle.gumbel_score(host, wl.V, f32(wl.temperature), hs, hsid, hpos, claims_g.cpu().numpy(), ht)
+    oi = oracle.ipt_score(host, wl.V, f32(wl.temperature), hs, hsid, hpos, claims_i.cpu().numpy(), ht, sigma, eps)
+    sg = parity.compare_gumbel(gg, og)
+    si = parity.compare_ipt(gi, oi, host, wl.V, (f32(wl.temperature) if ht is None else ht, hs, hsid, hpos), sigma)
+    return gg, gi, og, oi, sg, si
+
+
+def test_noise_bits_bit_exact(difr):
+    wl = W.scaled(W.C3_30B, S=3, L=4, chunk_rows=12)
+    seeds, sid, pos, _ = _aux(wl)
+    logits = torch.zeros(wl.N, wl.V, dtype=torch.bfloat16, device=DEV)
+    hs = parity.seeds_u64(seeds)
+    for row in (0, 5, 11):
+        for stream in (0, 1):
+            bits = difr.debug_noise(logits, 1.0, seeds, sid, pos, row, stream).cpu().numpy().view(np.uint32)
+            s = int(sid[row])
+            want = oracle.noise_row(int(hs[s]), s, int(pos[row]), stream, wl.V)
+            assert np.array_equal(bits, want), (row, stream)
+    # ragged vocabulary: the last Philox block is partial
+    wl2 = W.scaled(W.C1_TINY, S=1, L=1, V=1023, chunk_rows=1)
+    seeds, sid, pos, _ = _aux(wl2)
+    bits = difr.debug_noise(torch.zeros(1, 1023, device=DEV), 1.0, seeds, sid, pos, 0, 0).cpu().numpy().view(np.uint32)
+    assert np.array_equal(bits, oracle.noise_row(int(parity.seeds_u64(seeds)[0]), 0, 0, 0, 1023))
+    # host helper agrees with the oracle block function
+    assert difr.philox4x32_10([1, 2, 3, 4], [5, 6]) == [int(x) for x in oracle.philox4x32_10([1, 2, 3, 4], [5, 6])]
+
+
+def test_gumbel_map_exhaustive(difr):
+    """Every one of the 2^23 uniforms: device fp32 g against the oracle's double."""
+    k = torch.arange(1 << 23, dtype=torch.int64, device=DEV)
+    bits = u32_as_i32(k << 9)
+    g = difr.debug_gumbel_map(bits).cpu().numpy().astype(np.float64)
+    want = oracle.gumbel_from_bits(np.arange(1 << 23, dtype=np.uint32) << np.uint32(9))
+    err = np.abs(g - want)
+    say("gumbel map: max abs err %.3g at k=%d" % (err.max(), int(err.argmax())))
+    assert err.max() <= 4e-6
+    # low 9 bits of the word are not used
+    g2 = difr.debug_gumbel_map(bits[:4096] | 0x1FF).cpu().numpy()
+    assert np.array_equal(g2.astype(np.float64), g[:4096])
+
+
+def test_c1_tiny_every_row(difr):
+    wl = W.C1_TINY
+    logits, cg, ci = _build_small(wl)
+    gg, gi, og, oi, sg, si = _score_both_ways(difr, wl, logits, cg, ci)
+    say("C1 gumbel", sg)
+    say("C1 ipt", si)
+    # about 90% of the claims are honest (drift 1e-3 rarely flips the sample)
+    assert 0.75 < (og["flags"] & 1).mean() <= 1.0 and 0.75 < (oi["flags"] & 1).mean() <= 1.0
+    for name, scores_g, scores_o, fl_g, fl_o, excused in (("margin", gg["margin"], og["margin"], gg["flags"], og["flags"], sg["match_excused"]),
+                                                          ("dist", gi["dist"], oi["dist"], gi["flags"], oi["flags"], si["match_excused"])):
+        tau = 0.05
+        off = wl.seq_offsets()
+        gs = difr.seq_reduce(scores_g, fl_g, off.to(DEV), tau)
+        os_ = oracle.seq_reduce(scores_o, fl_o, off.numpy(), tau)
+        say("C1 pool", name, parity.compare_seq(gs, os_, tau, excused))
+
+
+def test_honest_claims_identical_logits_margin_zero(difr):
+    """Scoring the sampler's own output on the same logits gives margin exactly 0 / dist exactly 0."""
+    wl = W.scaled(W.C2_3B, S=4, L=32, V=4104, chunk_rows=128)
+    v, _ = wl.logits_chunk(0, DEV)
+    seeds, sid, pos, _ = _aux(wl)
+    samp = difr.gumbel_score(v, wl.temperature, seeds, sid, pos)
+    assert ((samp["flags"] & 2) != 0).all() and torch.isnan(samp["margin"]).all()
+    again = difr.gumbel_score(v, wl.temperature, seeds, sid, pos, samp["argmax"])
+    assert (again["margin"] == 0).all() and ((again["flags"] & 1) == 1).all()
+    isamp = difr.ipt_score(v, wl.temperature, seeds, sid, pos, want_token=True)
+    iagain = difr.ipt_score(v, wl.temperature, seeds, sid, pos, isamp["ipt_token"], want_token=True)
+    assert (iagain["dist"] == 0).all()
+    # MATCH is the half-open test; the sampler's token can only miss it when u sits on an edge in fp32
+    assert ((iagain["flags"] & 1) == 1).float().mean() > 0.99
+    assert (iagain["ipt_token"] == isamp["ipt_token"]).float().mean() > 0.99
+
+
+def test_c2_3b_class_every_row(difr):
+    wl = W.C2_3B
+    logits, cg, ci = _build_small(wl)
+    gg, gi, og, oi, sg, si = _score_both_ways(difr, wl, logits, cg, ci)
+    say("C2 gumbel", sg)
+    say("C2 ipt", si)
+    mism_g = 1.0 - (og["flags"] & 1).mean()
+    mism_i = 1.0 - (oi["flags"] & 1).mean()
+    say("C2 oracle mismatch rates: gumbel %.4f ipt %.4f" % (mism_g, mism_i))
+    assert 0.005 < mism_g < 0.08 and 0.005 < mism_i < 0.08       # ~2% swapped + benign drift flips
+    tau = 0.02
+    off = wl.seq_offsets()
+    gs = difr.seq_reduce(gg["margin"], gg["flags"], off.to(DEV), tau)
+    say("C2 pool margin", parity.compare_seq(gs, oracle.seq_reduce(og["margin"], og["flags"], off.numpy(), tau), tau,
+                                             sg["match_excused"]))
+    gs = difr.seq_reduce(gi["dist"], gi["flags"], off.to(DEV), tau)
+    say("C2 pool dist", parity.compare_seq(gs, oracle.seq_reduce(oi["dist"], oi["flags"], off.numpy(), tau), tau,
+                                           si["match_excused"]))
+
+
+@pytest.mark.parametrize("dtype,V,ld,offset", [
+    (torch.bfloat16, 1, 8, 0), (torch.bfloat16, 7, 7, 0), (torch.bfloat16, 1000, 1000, 0),
+    (torch.bfloat16, 2055, 2064, 0), (torch.bfloat16, 4099, 4099, 1), (torch.bfloat16, 8192, 8200, 3),
+    (torch.float32, 1, 1, 0), (torch.float32, 5, 8, 0), (torch.float32, 1023, 1023, 0),
+    (torch.float32, 4100, 4104, 0), (torch.float32, 3001, 3001, 1),
+])
+def test_ragged_shapes_and_unaligned_rows(difr, dtype, V, ld, offset):
+    """Vocabulary sizes that are not a multiple of the vector width, padded pitches whose padding
+    holds garbage, and rows that are not 16-byte aligned (generic load path)."""
+    N = 37
+    g = torch.Generator(device=DEV).manual_seed(1234 + V)
+    store = torch.randn(N * ld + offset + 8, generator=g, device=DEV, dtype=torch.float32).mul_(2.5).to(dtype)
+    logits = store[offset:offset + N * ld].view(N, ld)
+    if ld > V:
+        logits[:, V:] = float("nan")                                # padding must never be read as data
+    wl = W.scaled(W.C1_TINY, S=3, L=13, V=V, chunk_rows=39)
+    seeds = wl.seeds().to(DEV)
+    sid = wl.seq_ids()[:N].to(DEV)
+    pos = u32_as_i32(wl.positions()[:N].to(torch.int64) * 1000003 + 4000000000).to(DEV)   # large uint32 positions
+    claims = torch.randint(0, V, (N,), generator=torch.Generator().manual_seed(V), dtype=torch.int32).to(DEV)
+    host = parity.to_host_logits(logits)
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    gg = difr.gumbel_score(logits, 0.9, seeds, sid, pos, claims, V=V)
+    gi = difr.ipt_score(logits, 0.9, seeds, sid, pos, claims, V=V, want_token=True, want_log_mass=True)
+    og = oracle.gumbel_score(host, V, np.float32(0.9), hs, hsid, hpos, claims.cpu().numpy())
+    oi = oracle.ipt_score(host, V, np.float32(0.9), hs, hsid, hpos, claims.cpu().numpy())
+    parity.compare_gumbel(gg, og)
+    parity.compare_ipt(gi, oi, host, V, (np.float32(0.9), hs, hsid, hpos), 0.01)
+
+
+def test_row_level_conditions(difr):
+    """Invalid claims, masked (-inf) entries, NaN / +inf logits, per-row temperatures, bad sequence ids."""
+    N, V = 24, 3000
+    g = torch.Generator(device=DEV).manual_seed(99)
+    logits = torch.randn(N, V, generator=g, device=DEV).mul_(2).to(torch.bfloat16)
+    logits[3, 100:2900] = float("-inf")             # heavily masked row
+    logits[4, :] = float("-inf")
+    logits[4, 17] = 1.0                              # one live entry
+    logits[5, 7] = float("nan")
+    logits[6, 2999] = float("inf")
+    wl = W.scaled(W.C1_TINY, S=4, L=6, V=V, chunk_rows=24)
+    seeds, sid, pos, _ = _aux(wl)
+    claims = torch.randint(0, V, (N,), generator=torch.Generator().manual_seed(5), dtype=torch.int32)
+    claims[0] = -1
+    claims[1] = V
+    claims[4] = 17
+    claims[3] = 150                                  # a masked token is claimed
+    claims = claims.to(DEV)
+    temps = torch.linspace(0.5, 1.6, N).to(DEV)
+    host = parity.to_host_logits(logits)
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    gg = difr.gumbel_score(logits, 1.0, seeds, sid, pos, claims, temperatures=temps)
+    gi = difr.ipt_score(logits, 1.0, seeds, sid, pos, claims, temperatures=temps, want_token=True, want_log_mass=True)
+    og = oracle.gumbel_score(host, V, 1.0, hs, hsid, hpos, claims.cpu().numpy(), temps.cpu().numpy())
+    oi = oracle.ipt_score(host, V, 1.0, hs, hsid, hpos, claims.cpu().numpy(), temps.cpu().numpy())
+    ok = np.ones(N, bool)
+    ok[[5, 6]] = False                               # outputs unspecified on non-finite rows, flag only
+    fg, fi = gg["flags"].cpu().numpy(), gi["flags"].cpu().numpy()
+    assert fg[5] & 4 and fg[6] & 4 and fi[5] & 4 and fi[6] & 4
+    assert not (fg[ok] & 4).any() and not (fi[ok] & 4).any()
+    sel = torch.from_numpy(np.nonzero(ok)[0]).to(DEV)
+    parity.compare_gumbel({k: v[sel] for k, v in gg.items()}, {k: v[ok] for k, v in og.items()})
+    parity.compare_ipt({k: v[sel] for k, v in gi.items()}, {k: v[ok] for k, v in oi.items()}, host[ok], V,
+                       (temps.cpu().numpy()[ok], hs, hsid[ok], hpos[ok]), 0.01)
+    assert fg[0] & 2 and fg[1] & 2 and math.isnan(float(gg["margin"][0])) and int(gg["argmax"][0]) == int(og["argmax"][0])
+    assert int(gg["argmax"][4]) == 17 and float(gg["margin"][4]) == 0.0 and float(gi["dist"][4]) == 0.0
+    # a bad temperature or sequence id poisons only its own row
+    temps2 = temps.clone()
+    temps2[2] = 0.0
+    temps2[7] = float("nan")
+    sid2 = sid.clone()
+    sid2[9] = 4
+    sid2[10] = -1
+    g2 = difr.gumbel_score(logits, 1.0, seeds, sid2, pos, claims, temperatures=temps2)
+    i2 = difr.ipt_score(logits, 1.0, seeds, sid2, pos, claims, temperatures=temps2)
+    for out in (g2, i2):
+        f = out["flags"].cpu().numpy()
+        assert f[2] & 4 and f[7] & 4 and f[9] & 2 and f[10] & 2
+    keep = [r for r in range(N) if r not in (2, 7, 9, 10, 5, 6)]
+    same = lambda a, b: torch.equal(torch.nan_to_num(a[keep], nan=-7.0), torch.nan_to_num(b[keep], nan=-7.0))
+    assert same(g2["margin"], gg["margin"]) and same(i2["dist"], gi["dist"])
+
+
+def test_empty_batch_and_determinism(difr):
+    wl = W.scaled(W.C2_3B, S=2, L=64, V=20000, chunk_rows=128)
+    v, _ = wl.logits_chunk(0, DEV)
+    seeds, sid, pos, off = _aux(wl)
+    empty = difr.gumbel_score(v[:0], 1.0, seeds, sid[:0], pos[:0], None, V=wl.V)
+    assert empty["margin"].numel() == 0
+    assert difr.ipt_score(v[:0], 1.0, seeds, sid[:0], pos[:0], None, V=wl.V)["dist"].numel() == 0
+    claims = torch.randint(0, wl.V, (wl.N,), dtype=torch.int32).to(DEV)
+    a = difr.gumbel_score(v, 0.7, seeds, sid, pos, claims)
+    b = difr.gumbel_score(v, 0.7, seeds, sid, pos, claims)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    a = difr.ipt_score(v, 0.7, seeds, sid, pos, claims, want_token=True, want_log_mass=True)
+    b = difr.ipt_score(v, 0.7, seeds, sid, pos, claims, want_token=True, want_log_mass=True)
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    # a non-default stream gives the same answer
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        c = difr.gumbel_score(v, 0.7, seeds, sid, pos, claims)
+    s.synchronize()
+    ref = difr.gumbel_score(v, 0.7, seeds, sid, pos, claims)
+    assert torch.equal(c["margin"], ref["margin"]) and torch.equal(c["argmax"], ref["argmax"])
+
+
+def test_seq_reduce_ragged(difr):
+    rng = np.random.default_rng(3)
+    lens = [0, 1, 255, 256, 257, 1024, 0, 3000, 5]
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    N = int(off[-1])
+    scores = rng.exponential(0.2, size=N).astype(np.float32)
+    flags = (rng.uniform(size=N) < 0.9).astype(np.uint8)
+    tau = 0.2
+    gs = difr.seq_reduce(torch.from_numpy(scores).to(DEV), torch.from_numpy(flags).to(DEV), torch.from_numpy(off).to(DEV), tau)
+    os_ = oracle.seq_reduce(scores.astype(np.float64), flags, off, np.float32(tau))
+    say("seq_reduce ragged", parity.compare_seq(gs, os_, tau))
+    assert list(gs["seq_flag"].cpu().numpy()[[0, 6]]) == [0, 0]
+    scores[600] = np.nan                                             # inside sequence 4
+    gs = difr.seq_reduce(torch.from_numpy(scores).to(DEV), None, torch.from_numpy(off).to(DEV), tau)
+    os_ = oracle.seq_reduce(scores.astype(np.float64), None, off, np.float32(tau))
+    parity.compare_seq(gs, os_, tau)
+    assert int(gs["seq_flag"][4]) == 1 and math.isnan(float(gs["seq_mean"][4])) and math.isnan(float(gs["seq_max"][4]))
+    assert difr.seq_reduce(torch.zeros(0, device=DEV), None, torch.zeros(1, dtype=torch.int64, device=DEV), 0.0)["seq_mean"].numel() == 0
+
+
+def test_c5_stego_audit_scaled(difr):
+    """The stego-audit recipe at a vocabulary the oracle can afford for every row: stego sequences pick among
+    their top-4 tokens, per-sequence means, threshold calibrated on the oracle's honest means at FPR 1e-2."""
+    wl = W.scaled(W.C5_STEGO, S=256, L=32, V=8200, chunk_rows=512)
+    logits, cg, ci = _build_small(wl)
+    gg, gi, og, oi, sg, si = _score_both_ways(difr, wl, logits, cg, ci)
+    say("C5s gumbel", sg)
+    say("C5s ipt", si)
+    off = wl.seq_offsets()
+    stego = wl.stego_sequences()
+    honest = np.array([s for s in range(wl.S) if s not in stego])
+    assert len(stego) == 3
+    for name, sc_g, sc_o, fl_g, fl_o, exc in (("margin", gg["margin"], og["margin"], gg["flags"], og["flags"], sg["match_excused"]),
+                                              ("dist", gi["dist"], oi["dist"], gi["flags"], oi["flags"], si["match_excused"])):
+        means = oracle.seq_reduce(sc_o, fl_o, off.numpy(), 0.0)["seq_mean"]
+        tau = np.float32(oracle.calibrate_threshold(means[honest], 1e-2))
+        os_ = oracle.seq_reduce(sc_o, fl_o, off.numpy(), tau)
+        gs = difr.seq_reduce(sc_g, fl_g, off.to(DEV), float(tau))
+        st = parity.compare_seq(gs, os_, float(tau), exc)
+        flags = gs["seq_flag"].cpu().numpy()
+        say("C5s pool", name, st, "tau %.5g" % tau, "stego flagged", flags[stego].tolist(), "honest flagged", int(flags[honest].sum()))
+        assert flags[stego].all() and os_["seq_flag"][stego].all()      # every stego sequence is caught
+        assert os_["seq_flag"][honest].sum() <= 2                       # floor(0.01 * 253), by construction of tau
+        assert flags[honest].sum() <= 2 + st["flag_excused"]            # the sequence tau was read from may tip over

@@ -231,6 +231,9 @@ def test_threshold_calibration(oracle_lib):
     for n, fpr in [(253, 1e-2), (100, 0.01), (1000, 0.001), (50, 0.1), (7, 0.5)]:
         means = rng.exponential(1.0, size=n)
         tau = oracle_lib.calibrate_threshold(means, fpr)
+        assert float(np.float32(tau)) == tau                  # usable as the library's fp32 threshold
+        raw = oracle_lib.calibrate_threshold(means, fpr, as_float32=False)
+        assert tau >= raw > float(np.nextafter(np.float32(tau), np.float32(0)))      # smallest fp32 not below it
         flagged = int((means > tau).sum())
         assert flagged <= math.floor(fpr * n + 1e-9)
         assert flagged == math.floor(fpr * n + 1e-9)          # distinct values: the bound is attained
