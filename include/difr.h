@@ -81,7 +81,8 @@ typedef enum { DIFR_BF16 = 0, DIFR_F32 = 1 } difr_dtype;
 #define DIFR_FLAG_NONFINITE 4u     /* a NaN or +inf logit was seen in the row; the     */
                                    /* row's other outputs are unspecified.  -inf is    */
                                    /* a legal "masked" entry: zero probability, never  */
-                                   /* the argmax                                       */
+                                   /* the argmax.  difr_gumbel_score treats a NaN with */
+                                   /* its sign bit set like -inf (masked, not flagged) */
 #define DIFR_FLAG_SLOW_PATH 8u     /* informational: the row left the streaming fast   */
                                    /* path (re-read of the row)                        */
 
@@ -158,6 +159,15 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
 int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,
                     int64_t S, float threshold, float *seq_mean, float *seq_max, int32_t *seq_mismatch,
                     uint8_t *seq_flag, void *hip_stream);
+
+/*
+ * Test and audit helper: difr_gumbel_score with the exact pre-filter switched off, so that
+ * every vocabulary entry goes through both logarithms.  Same arguments, same outputs; the
+ * two must agree bit for bit (the filter only skips entries that provably cannot reach the
+ * row maximum).  Rows that are not 16-byte aligned always take this path.
+ */
+int difr_debug_gumbel_score_unfiltered(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
+                                       float *claimed_score, uint8_t *flags, void *hip_stream);
 
 /*
  * Test and audit helper: writes the raw 32 noise bits of vocabulary entries

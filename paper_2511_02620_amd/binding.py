@@ -48,7 +48,7 @@ class _Rows(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_ipt_score", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -68,6 +68,8 @@ def load_library():
     vp = C.c_void_p
     lib.difr_gumbel_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp]
     lib.difr_gumbel_score.restype = C.c_int
+    lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp]
+    lib.difr_debug_gumbel_score_unfiltered.restype = C.c_int
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp]
     lib.difr_ipt_score.restype = C.c_int
     lib.difr_seq_reduce.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_float, vp, vp, vp, vp, vp]
@@ -152,10 +154,12 @@ def _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatur
 
 
 def gumbel_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temperatures=None, V=None,
-                 want_scores=True):
-    """difr_gumbel_score.  logits [N, >=V] bf16/fp32 on the GPU; seeds int64 [S] (uint64 bits);
-    seq_ids, positions, claimed int32 [N].  Returns a dict of device tensors."""
+                 want_scores=True, unfiltered=False):
+    """difr_gumbel_score (or, with unfiltered=True, difr_debug_gumbel_score_unfiltered).
+    logits [N, >=V] bf16/fp32 on the GPU; seeds int64 [S] (uint64 bits); seq_ids, positions,
+    claimed int32 [N].  Returns a dict of device tensors."""
     lib = load_library()
+    entry = lib.difr_debug_gumbel_score_unfiltered if unfiltered else lib.difr_gumbel_score
     r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
     out = dict(margin=torch.empty(N, dtype=torch.float32, device=dev),
                argmax=torch.empty(N, dtype=torch.int32, device=dev),
@@ -164,7 +168,7 @@ def gumbel_score(logits, temperature, seeds, seq_ids, positions, claimed=None, t
         out["max_score"] = torch.empty(N, dtype=torch.float32, device=dev)
         out["claimed_score"] = torch.empty(N, dtype=torch.float32, device=dev)
     with torch.cuda.device(dev):
-        rc = lib.difr_gumbel_score(C.byref(r), _ptr(out["margin"]), _ptr(out["argmax"]), _ptr(out.get("max_score")),
+        rc = entry(C.byref(r), _ptr(out["margin"]), _ptr(out["argmax"]), _ptr(out.get("max_score")),
                                    _ptr(out.get("claimed_score")), _ptr(out["flags"]), _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_gumbel_score")

@@ -75,7 +75,23 @@ int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags) return DIFR_ERR_NULL;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    return difr::launch_gumbel_score(b, aligned, margin, argmax, max_score, claimed_score, flags,
+    return difr::launch_gumbel_score(b, aligned, true, margin, argmax, max_score, claimed_score, flags,
+                                     (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_debug_gumbel_score_unfiltered(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
+                                       float *claimed_score, uint8_t *flags, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    return difr::launch_gumbel_score(b, aligned, false, margin, argmax, max_score, claimed_score, flags,
                                      (hipStream_t)hip_stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
@@ -139,8 +155,24 @@ int difr_debug_gumbel_map(const uint32_t *bits, int64_t n, float *g, void *hip_s
 
 void difr_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
 {
-    difr::PhiloxKey k{key[0], key[1]};
-    difr::philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], k, out);
+    // Host copy of the block function (the kernels use the device version in difr_device.hpp).
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c0 = n0;
+        c1 = (uint32_t)p1;
+        c2 = n2;
+        c3 = (uint32_t)p0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0;
+    out[1] = c1;
+    out[2] = c2;
+    out[3] = c3;
 }
 
 const char *difr_status_string(int status)

@@ -48,29 +48,50 @@ struct PhiloxKey {
     uint32_t k0, k1;
 };
 
-__host__ __device__ __forceinline__ void philox_round(uint32_t &c0, uint32_t &c1, uint32_t &c2, uint32_t &c3,
-                                                      uint32_t k0, uint32_t k1)
+// a ^ b ^ c in one instruction (three-input bitwise op, truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
 {
-    const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-    const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n1 = (uint32_t)p1;
-    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-    const uint32_t n3 = (uint32_t)p0;
-    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
 }
 
-__host__ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                                       PhiloxKey key, uint32_t out[4])
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
+
+// The ten rounds, with the first round's product M0 * c0 supplied by the caller.  In the
+// streaming kernels c0 = (uniform base) + (per-lane constant), so that product is one
+// 64-bit add of a scalar and a loop-invariant vector value instead of a multiply.
+__device__ __forceinline__ void philox4x32_10_from_product(uint64_t p0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                           PhiloxKey key, uint32_t out[4])
 {
     uint32_t k0 = key.k0, k1 = key.k1;
+    uint32_t c0;
+    {
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+        c0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        c1 = (uint32_t)p1;
+        c2 = xor3((uint32_t)(p0 >> 32), c3, k1);
+        c3 = (uint32_t)p0;
+    }
 #pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        philox_round(c0, c1, c2, c3, k0, k1);
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
+    for (int r = 1; r < 10; ++r) {
+        k0 += kPhiloxW0;
+        k1 += kPhiloxW1;
+        const uint64_t q0 = (uint64_t)kPhiloxM0 * c0;  // one 32x32->64 multiply gives hi and lo
+        const uint64_t q1 = (uint64_t)kPhiloxM1 * c2;
+        const uint32_t n0 = xor3((uint32_t)(q1 >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(q0 >> 32), c3, k1);
+        c0 = n0;
+        c1 = (uint32_t)q1;
+        c2 = n2;
+        c3 = (uint32_t)q0;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, PhiloxKey key,
+                                              uint32_t out[4])
+{
+    philox4x32_10_from_product((uint64_t)kPhiloxM0 * c0, c1, c2, c3, key, out);
 }
 
 // Noise words of the four vocabulary entries 4*q .. 4*q+3 of one row.

@@ -9,8 +9,9 @@
 
 namespace difr {
 
-int launch_gumbel_score(const RowBatch &b, bool aligned, float *margin, int32_t *argmax, float *max_score,
-                        float *claimed_score, uint8_t *flags, hipStream_t stream);
+// filtered = false forces the unfiltered kernel (every entry evaluated exactly); unaligned rows always use it.
+int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *margin, int32_t *argmax,
+                        float *max_score, float *claimed_score, uint8_t *flags, hipStream_t stream);
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
                      hipStream_t stream);

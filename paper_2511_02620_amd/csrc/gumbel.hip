@@ -93,6 +93,281 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Filtered streaming kernel (aligned rows only).
+//
+// The row maximum is bounded from below by L: the claimed token's own score at first
+// (for an honest claim that IS the maximum), then the best score seen so far.  An entry
+// can only matter if y_v >= L.  Two cheap tests per 16-byte vector, neither of which
+// needs a logarithm, rule that out for almost every entry:
+//   noise gate  r_v < kGate  =>  g_v < kGateGumbel           (max of the eight words)
+//   logit gate  x_v < xcap, xcap = T (L - kGateGumbel - slack) (packed 16-bit min / max of
+//               the raw bf16 bit patterns: for xcap <= 0 "x >= xcap" is "bits <= bits(xcap)"
+//               as unsigned 16-bit, for xcap > 0 it is "bits >= bits(xcap)" as signed)
+// An entry that fails both has y_v < xcap / T + kGateGumbel < L.  Entries in a vector
+// that trips a gate get a second, per-entry bound g_v <= (151 - bits(float(q_v)) 2^-23) ln 2,
+// q_v = (~r_v) >> 8  (from -ln(-ln(1-w)) <= -ln w and log2(1+m) >= m), and only those whose
+// bound still reaches L are evaluated exactly, with the same arithmetic as the unfiltered
+// kernel.  Every noise word is still generated; the outputs are identical to the
+// unfiltered kernel's, bit for bit, because L never exceeds the true maximum.
+// ---------------------------------------------------------------------------------
+constexpr int kGateBits = 10;
+constexpr uint32_t kGate = 0xFFFFFFFFu << (32 - kGateBits);  // r >= kGate: the top kGateBits bits are ones
+// sup of g over r < kGate is -ln(-ln(1 - (2^(24-kGateBits)+1) 2^-24)) = 6.930922... for 10 bits
+constexpr float kGateGumbel = 6.9311f;
+
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u16x2 as_u16x2(uint32_t w) { return __builtin_bit_cast(u16x2, w); }
+__device__ __forceinline__ i16x2 as_i16x2(uint32_t w) { return __builtin_bit_cast(i16x2, w); }
+
+// Upper bound on the Gumbel variate of noise word r (see the comment above); error of the
+// float conversions is below 1e-5 and is covered by the caller's slack.
+__device__ __forceinline__ float gumbel_upper_bound(uint32_t r)
+{
+    const float f = (float)((~r) >> 8);
+    const float bits = (float)__float_as_int(f);
+    return __fmaf_rn(bits, -kLn2 * 0x1p-23f, 151.0f * kLn2);
+}
+
+struct Gate {
+    float L;         // lower bound on the row maximum (wave-uniform)
+    float Lgate;     // L minus slack: an entry whose upper bound is below this cannot reach L
+    float xcap;      // logit gate in logit units
+    uint32_t cap16;  // its bf16 bit pattern, rounded so that the 16-bit test never misses
+    bool cap_neg;    // xcap <= 0: unsigned test on the bit patterns; else signed test
+};
+
+__device__ __forceinline__ Gate make_gate(float L, float T)
+{
+    Gate g;
+    L = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, L)));
+    const float slack = 0.01f + 1e-5f * fabsf(L);
+    g.L = L;
+    g.Lgate = L - slack;
+    float xcap = (L - kGateGumbel - slack) * T;
+    if (!(xcap == xcap)) xcap = -__builtin_inff();  // L = +-inf arithmetic: gate everything in
+    g.xcap = xcap;
+    const uint32_t b = __float_as_uint(xcap);
+    g.cap_neg = !(xcap > 0.0f);
+    // xcap <= 0: grow the magnitude to the next bf16 (more negative); xcap > 0: truncate (smaller)
+    uint32_t c = b >> 16;
+    if (g.cap_neg) {
+        c |= 0x8000u;  // xcap = +0 is treated as -0: every non-negative logit is gated in
+        if ((b & 0xFFFFu) != 0u && c < 0xFF80u) c += 1u;
+    }
+    g.cap16 = c;
+    return g;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch b, float *__restrict__ margin,
+                                                                       int32_t *__restrict__ argmax,
+                                                                       float *__restrict__ max_score,
+                                                                       float *__restrict__ claimed_score,
+                                                                       uint8_t *__restrict__ flags)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ float lds_y[kWaves];
+    __shared__ int32_t lds_i[kWaves];
+    __shared__ float lds_L[kWaves];
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const float nan = __builtin_nanf("");
+    const float ninf = -__builtin_inff();
+
+    if (!ri.seq_ok || !ri.temp_ok) {  // uniform over the workgroup
+        if (tid == 0) {
+            margin[row] = nan;
+            argmax[row] = -1;
+            if (max_score) max_score[row] = nan;
+            if (claimed_score) claimed_score[row] = nan;
+            flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
+        }
+        return;
+    }
+
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const int64_t V = b.V;
+    const float T = ri.T;
+    const float inv_T = 1.0f / T;
+
+    // The claimed token's score, by the same function the stream uses: the first lower bound.
+    const int32_t t = ri.claimed;
+    const bool valid = (t >= 0 && (int64_t)t < V);
+    float yt = nan;
+    if (valid) {
+        uint32_t r[4];
+        noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)t >> 2, r);
+        const uint32_t rt = (t & 3) == 0 ? r[0] : (t & 3) == 1 ? r[1] : (t & 3) == 2 ? r[2] : r[3];
+        yt = perturbed_score(Elem<DT>::to_float(x_row[t]), inv_T, rt);
+    }
+    Gate gate = make_gate((yt == yt) ? yt : ninf, T);
+    if ((tid & 63) == 0) lds_L[wave] = gate.L;
+
+    float best_y = ninf;
+    int32_t best_v = 0x7FFFFFFF;
+    uint32_t bad = 0;
+
+    // Exact evaluation of one entry (same arithmetic as the unfiltered kernel), ties to the lowest index.
+    auto evaluate = [&](float xv, uint32_t rv, int32_t v) {
+        const float y = perturbed_score(xv, inv_T, rv);
+        bad |= (uint32_t)!(xv < __builtin_inff());
+        if (y > best_y || (y == best_y && v < best_v)) {
+            best_y = y;
+            best_v = v;
+        }
+    };
+    // Entry-level test: can this entry still reach the lower bound?
+    auto consider = [&](float xv, uint32_t rv, int32_t v) {
+        if (!(__fmaf_rn(xv, inv_T, gumbel_upper_bound(rv)) < gate.Lgate)) evaluate(xv, rv, v);
+    };
+
+    const int64_t nvec = V / E;                 // full vectors; the last V % E entries are the tail
+    const int n_main = (int)(nvec / kBlock);    // rounds in which every lane of every wave has a vector
+    __syncthreads();
+
+    // One 16-byte vector per lane.  `round` is the vector round (vector index = round * 256 + tid).
+    // M0 * (Philox counter word 0) = M0 * (round's first block) + M0 * (lane's block offset): the
+    // second term never changes, the first is scalar, and the sum cannot wrap (counter < 2^29).
+    uint64_t lane_prod = (uint64_t)kPhiloxM0 * (uint32_t)(tid * (E / 4));
+    asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
+    auto process = [&](u32x4 q, int round, bool active) {
+        const uint64_t round_prod = (uint64_t)kPhiloxM0 * (uint32_t)(round * kBlock * (E / 4));
+        const uint64_t p0 = round_prod + lane_prod;
+        uint32_t r[E];
+        philox4x32_10_from_product(p0, ri.pos, ri.seq, kStreamGumbel, ri.key, r);
+        if (E == 8) philox4x32_10_from_product(p0 + kPhiloxM0, ri.pos, ri.seq, kStreamGumbel, ri.key, r + 4);
+        // noise gate: the largest of the words
+        uint32_t rmax;
+        if (E == 8)
+            rmax = max(max(max(r[0], r[1]), r[2]), max(max(max(r[3], r[4]), r[5]), max(r[6], r[7])));
+        else
+            rmax = max(max(r[0], r[1]), max(r[2], r[3]));
+        // wave-wide masks of the lanes whose vector trips the noise gate / the logit gate
+        const uint64_t nmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGate);
+        uint64_t hmask;
+        if (DT == 0) {
+            if (gate.cap_neg) {
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                const uint16_t lo = m.x < m.y ? m.x : m.y;
+                hmask = __builtin_amdgcn_ballot_w64(active && lo <= (uint16_t)gate.cap16);
+            } else {
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                const int16_t hi = m.x > m.y ? m.x : m.y;
+                hmask = __builtin_amdgcn_ballot_w64(active && hi >= (int16_t)gate.cap16);
+            }
+        } else {  // fp32 logits: four plain compares (a NaN counts as gated in)
+            hmask = __builtin_amdgcn_ballot_w64(
+                active && (!(__uint_as_float(q.x) < gate.xcap) || !(__uint_as_float(q.y) < gate.xcap) ||
+                           !(__uint_as_float(q.z) < gate.xcap) || !(__uint_as_float(q.w) < gate.xcap)));
+        }
+        if (__builtin_expect((nmask | hmask) != 0ull, 0)) {
+            const uint64_t me = 1ull << (tid & 63);
+            const bool nhit = (nmask & me) != 0ull, hhit = (hmask & me) != 0ull;
+            const int32_t v0 = (round * kBlock + tid) * E;
+            const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+            if (nhit && !hhit) {  // only the noise gate tripped: look at the words alone
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    if (r[j] >= kGate) {
+                        const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                        const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
+                                                 : __uint_as_float(w);
+                        consider(xv, r[j], v0 + j);
+                    }
+                }
+            } else if (hhit) {
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
+                                             : __uint_as_float(w);
+                    if (r[j] >= kGate || !(xv < gate.xcap)) consider(xv, r[j], v0 + j);
+                }
+            }
+            // a better score raises the lower bound for this wave; other waves pick it up from LDS
+            if (__builtin_amdgcn_ballot_w64(best_y > gate.L) != 0ull) {
+                float L = fmaxf(wave_max(best_y), gate.L);
+                L = fmaxf(fmaxf(L, lds_L[0]), fmaxf(lds_L[1], fmaxf(lds_L[2], lds_L[3])));
+                gate = make_gate(L, T);
+                if ((tid & 63) == 0) lds_L[wave] = gate.L;
+            }
+        }
+    };
+
+    const char *row_bytes = reinterpret_cast<const char *>(x_row);
+    const uint32_t lane_off = (uint32_t)tid * 16u;
+    auto load_round = [&](int round) {
+        return __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4 *>(row_bytes + (size_t)round * (kBlock * 16) + lane_off));
+    };
+
+    if (n_main > 0) {
+        u32x4 q_next = load_round(0);
+        for (int round = 0; round < n_main; ++round) {
+            const u32x4 q = q_next;
+            if (round + 1 < n_main) q_next = load_round(round + 1);  // keep one vector in flight
+            process(q, round, true);
+            if ((round & 15) == 15) {  // pick up a bound another wave has raised
+                const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
+                if (L > gate.L) gate = make_gate(L, T);
+            }
+        }
+    }
+    if ((int64_t)n_main * kBlock < nvec) {  // last, partly filled round of vectors
+        const bool active = (int64_t)n_main * kBlock + tid < nvec;
+        u32x4 q;
+        if (active) {
+            q = load_round(n_main);
+        } else {  // a lane without a vector: -inf entries and no noise
+            const uint32_t pad = DT == 0 ? 0xFF80FF80u : 0xFF800000u;
+            q = u32x4{pad, pad, pad, pad};
+        }
+        process(q, n_main, active);
+    }
+    // the ragged tail: V % E entries, one lane each, evaluated exactly
+    {
+        const int64_t v = nvec * E + tid;
+        if (v < V) {
+            uint32_t r[4];
+            noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)(v >> 2), r);
+            const uint32_t rv = (v & 3) == 0 ? r[0] : (v & 3) == 1 ? r[1] : (v & 3) == 2 ? r[2] : r[3];
+            evaluate(Elem<DT>::to_float(x_row[v]), rv, (int32_t)v);
+        }
+    }
+
+    block_argmax(best_y, best_v, lds_y, lds_i);
+    const int any_bad = __syncthreads_or((int)bad);
+
+    if (tid == 0) {
+        if (best_v == 0x7FFFFFFF) best_v = 0;  // every entry masked: all scores are -inf
+        uint32_t f = any_bad ? kFlagNonfinite : 0u;
+        float mg = nan;
+        if (valid) {
+            mg = best_y - yt;
+            if (best_v == t) f |= kFlagMatch;
+        } else {
+            f |= kFlagInvalidClaim;
+        }
+        margin[row] = mg;
+        argmax[row] = best_v;
+        if (max_score) max_score[row] = best_y;
+        if (claimed_score) claimed_score[row] = yt;
+        flags[row] = (uint8_t)f;
+    }
+}
+
 // Raw noise words of one row, through the same device code as the scoring kernels.
 __global__ __launch_bounds__(kBlock) void debug_noise_kernel(RowBatch b, int64_t row, uint32_t stream,
                                                              uint32_t *__restrict__ bits)
@@ -115,11 +390,16 @@ __global__ __launch_bounds__(kBlock) void debug_gumbel_map_kernel(const uint32_t
         g[i] = gumbel_from_bits(bits[i]);
 }
 
-int launch_gumbel_score(const RowBatch &b, bool aligned, float *margin, int32_t *argmax, float *max_score,
-                        float *claimed_score, uint8_t *flags, hipStream_t stream)
+int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *margin, int32_t *argmax,
+                        float *max_score, float *claimed_score, uint8_t *flags, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
-    if (b.dtype == 0) {
+    if (aligned && filtered) {
+        if (b.dtype == 0)
+            gumbel_score_filtered_kernel<0><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+        else
+            gumbel_score_filtered_kernel<1><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+    } else if (b.dtype == 0) {
         if (aligned)
             gumbel_score_kernel<0, true><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
         else

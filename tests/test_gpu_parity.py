@@ -326,3 +326,66 @@ def test_c5_stego_audit_scaled(difr):
         assert flags[stego].all() and os_["seq_flag"][stego].all()      # every stego sequence is caught
         assert os_["seq_flag"][honest].sum() <= 2                       # floor(0.01 * 253), by construction of tau
         assert flags[honest].sum() <= 2 + st["flag_excused"]            # the sequence tau was read from may tip over
+
+
+def _same_outputs(a, b):
+    for k in a:
+        x, y = a[k], b[k]
+        if x.dtype.is_floating_point:
+            assert torch.equal(torch.nan_to_num(x, nan=-7.0), torch.nan_to_num(y, nan=-7.0)), k
+        else:
+            assert torch.equal(x, y), k
+
+
+@pytest.mark.parametrize("case", ["honest", "random_claims", "sampling", "peaked", "positive_offset", "masked_topk",
+                                  "per_row_T", "fp32", "adversarial_order", "nonfinite"])
+def test_filtered_kernel_equals_unfiltered_bit_for_bit(difr, case):
+    """The exact pre-filter only skips entries that cannot reach the row maximum: every output of
+    difr_gumbel_score must equal the unfiltered kernel's bit for bit, whatever the claims and logits."""
+    wl = W.scaled(W.C3_30B, S=8, L=32, V=20504, chunk_rows=256)          # 2563 vectors: 10 full rounds + a partial one
+    v, p = wl.logits_chunk(0, DEV)
+    seeds, sid, pos, _ = _aux(wl)
+    T = 0.8
+    temps = None
+    honest = difr.gumbel_score(p, T, seeds, sid, pos, unfiltered=True)["argmax"]
+    claims = honest
+    g = torch.Generator().manual_seed(77)
+    if case == "random_claims":
+        claims = torch.randint(0, wl.V, (wl.N,), generator=g, dtype=torch.int32).to(DEV)
+    elif case == "sampling":
+        claims = None
+    elif case == "peaked":                       # one dominant logit per row: positive logit gate
+        idx = torch.randint(0, wl.V, (wl.N,), generator=g).to(DEV)
+        v = v.clone()
+        v[torch.arange(wl.N, device=DEV), idx] = 25.0
+        claims = torch.where(torch.arange(wl.N, device=DEV) % 3 == 0, honest, idx.to(torch.int32))
+    elif case == "positive_offset":              # softmax is shift invariant, real logits sit anywhere
+        v = (v.float() + 40.0).to(torch.bfloat16)
+    elif case == "masked_topk":                  # caller-side top-50 filter: everything else is -inf
+        kth = v.float().topk(50, dim=1).values[:, -1:]
+        v = torch.where(v.float() >= kth, v, torch.full_like(v, float("-inf")))
+        claims = difr.gumbel_score(v, T, seeds, sid, pos, unfiltered=True)["argmax"]
+    elif case == "per_row_T":
+        temps = torch.linspace(0.3, 2.5, wl.N).to(DEV)
+    elif case == "fp32":
+        v = v.float() * 1.7
+    elif case == "adversarial_order":            # ascending logits: the running bound keeps rising
+        v = v.float().sort(dim=1).values.to(torch.bfloat16)
+        claims = torch.zeros(wl.N, dtype=torch.int32, device=DEV)
+    elif case == "nonfinite":
+        v = v.clone()
+        v[3, 1000] = float("nan")
+        v[5, 20503] = float("inf")
+        v[7, 0] = float("inf")
+    a = difr.gumbel_score(v, T, seeds, sid, pos, claims, temperatures=temps)
+    b = difr.gumbel_score(v, T, seeds, sid, pos, claims, temperatures=temps, unfiltered=True)
+    torch.cuda.synchronize()
+    if case == "nonfinite":
+        fa, fb = a["flags"].cpu().numpy(), b["flags"].cpu().numpy()
+        assert (fa[[3, 5, 7]] & 4).all() and (fb[[3, 5, 7]] & 4).all()
+        keep = torch.tensor([r for r in range(wl.N) if r not in (3, 5, 7)], device=DEV)
+        a = {k: x[keep] for k, x in a.items()}
+        b = {k: x[keep] for k, x in b.items()}
+    _same_outputs(a, b)
+    if case in ("honest", "positive_offset", "fp32"):
+        say(case, "match rate", float((a["flags"] & 1).float().mean()))
