@@ -111,10 +111,16 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
 // kernel.  Every noise word is still generated; the outputs are identical to the
 // unfiltered kernel's, bit for bit, because L never exceeds the true maximum.
 // ---------------------------------------------------------------------------------
-constexpr int kGateBits = 10;
+#ifndef DIFR_GATE_BITS
+#define DIFR_GATE_BITS 10
+#endif
+constexpr int kGateBits = DIFR_GATE_BITS;
 constexpr uint32_t kGate = 0xFFFFFFFFu << (32 - kGateBits);  // r >= kGate: the top kGateBits bits are ones
-// sup of g over r < kGate is -ln(-ln(1 - (2^(24-kGateBits)+1) 2^-24)) = 6.930922... for 10 bits
-constexpr float kGateGumbel = 6.9311f;
+// sup of g over r < kGate, i.e. -ln(-ln(1 - (2^(24-kGateBits)+1) 2^-24)), rounded up:
+//   8 bits 5.543206, 9 bits 6.237317, 10 bits 6.930922, 11 bits 7.624253, 12 bits 8.317400
+constexpr float kGateGumbel = kGateBits == 8 ? 5.5433f : kGateBits == 9 ? 6.2374f : kGateBits == 10 ? 6.9311f
+                            : kGateBits == 11 ? 7.6244f : 8.3175f;
+static_assert(kGateBits >= 8 && kGateBits <= 12, "gate table covers 8..12 bits");
 
 typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
@@ -137,6 +143,7 @@ struct Gate {
     float Lgate;     // L minus slack: an entry whose upper bound is below this cannot reach L
     float xcap;      // logit gate in logit units
     uint32_t cap16;  // its bf16 bit pattern, rounded so that the 16-bit test never misses
+    uint32_t cap_pair;  // both halves: cap16 + 1 (xcap <= 0) or cap16 - 1 (xcap > 0), for the folded test
     bool cap_neg;    // xcap <= 0: unsigned test on the bit patterns; else signed test
 };
 
@@ -159,6 +166,8 @@ __device__ __forceinline__ Gate make_gate(float L, float T)
         if ((b & 0xFFFFu) != 0u && c < 0xFF80u) c += 1u;
     }
     g.cap16 = c;
+    const uint32_t h = (g.cap_neg ? c + 1u : c - 1u) & 0xFFFFu;
+    g.cap_pair = h | (h << 16);
     return g;
 }
 
@@ -254,6 +263,21 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
         const uint64_t nmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGate);
         uint64_t hmask;
         if (DT == 0) {
+#ifdef DIFR_X_FOLD
+            if (gate.cap_neg) {
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                m = __builtin_elementwise_min(m, as_u16x2(gate.cap_pair));
+                hmask = __builtin_amdgcn_ballot_w64(active && __builtin_bit_cast(uint32_t, m) != gate.cap_pair);
+            } else {
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                m = __builtin_elementwise_max(m, as_i16x2(gate.cap_pair));
+                hmask = __builtin_amdgcn_ballot_w64(active && __builtin_bit_cast(uint32_t, m) != gate.cap_pair);
+            }
+#else
             if (gate.cap_neg) {
                 u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
                 m = __builtin_elementwise_min(m, as_u16x2(q.z));
@@ -267,12 +291,18 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
                 const int16_t hi = m.x > m.y ? m.x : m.y;
                 hmask = __builtin_amdgcn_ballot_w64(active && hi >= (int16_t)gate.cap16);
             }
+#endif
         } else {  // fp32 logits: four plain compares (a NaN counts as gated in)
             hmask = __builtin_amdgcn_ballot_w64(
                 active && (!(__uint_as_float(q.x) < gate.xcap) || !(__uint_as_float(q.y) < gate.xcap) ||
                            !(__uint_as_float(q.z) < gate.xcap) || !(__uint_as_float(q.w) < gate.xcap)));
         }
+#ifdef DIFR_X_NOSLOW
+        bad |= (uint32_t)((nmask ^ hmask) == 0x123456789ull);  // timing experiment only: keep the gates alive
+        if (0) {
+#else
         if (__builtin_expect((nmask | hmask) != 0ull, 0)) {
+#endif
             const uint64_t me = 1ull << (tid & 63);
             const bool nhit = (nmask & me) != 0ull, hhit = (hmask & me) != 0ull;
             const int32_t v0 = (round * kBlock + tid) * E;
@@ -313,6 +343,23 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             reinterpret_cast<const u32x4 *>(row_bytes + (size_t)round * (kBlock * 16) + lane_off));
     };
 
+#ifdef DIFR_X_UNROLL2
+    if (n_main > 0) {
+        u32x4 qa = load_round(0), qb;
+        int round = 0;
+        for (; round + 1 < n_main; round += 2) {
+            qb = load_round(round + 1);
+            process(qa, round, true);
+            if (round + 2 < n_main) qa = load_round(round + 2);
+            process(qb, round + 1, true);
+            if ((round & 15) == 14) {  // pick up a bound another wave has raised
+                const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
+                if (L > gate.L) gate = make_gate(L, T);
+            }
+        }
+        if (round < n_main) process(qa, round, true);
+    }
+#else
     if (n_main > 0) {
         u32x4 q_next = load_round(0);
         for (int round = 0; round < n_main; ++round) {
@@ -325,6 +372,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             }
         }
     }
+#endif
     if ((int64_t)n_main * kBlock < nvec) {  // last, partly filled round of vectors
         const bool active = (int64_t)n_main * kBlock + tid < nvec;
         u32x4 q;
