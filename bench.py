@@ -108,6 +108,9 @@ def main():
     ap.add_argument("--workload", default="c3_30b_moe_class", help="workload name (see paper_2511_02620_amd.workloads)")
     ap.add_argument("--temperature", type=float, default=None)
     ap.add_argument("--cpu-rows", type=int, default=8192, help="rows of the batch the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="before the timed region, run one plain device copy of 4 GiB (a kernel of known HBM "
+                         "traffic: 4 GiB read + 4 GiB written) so that counter runs can be scaled against it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path has no multi-GPU part (rows are independent; "
@@ -147,6 +150,13 @@ def main():
             ev[3].record()
         return g, i, sg, si
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

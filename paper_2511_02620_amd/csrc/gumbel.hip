@@ -6,6 +6,8 @@
 // One workgroup (4 wavefronts) per token row; the row is streamed exactly once with
 // 128-bit loads; noise is generated in registers, four vocabulary entries per Philox
 // block; nothing of size V is ever stored.
+#include <type_traits>
+
 #include "difr_device.hpp"
 #include "difr_host.hpp"
 
@@ -98,29 +100,28 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
 //
 // The row maximum is bounded from below by L: the claimed token's own score at first
 // (for an honest claim that IS the maximum), then the best score seen so far.  An entry
-// can only matter if y_v >= L.  Two cheap tests per 16-byte vector, neither of which
-// needs a logarithm, rule that out for almost every entry:
-//   noise gate  r_v < kGate  =>  g_v < kGateGumbel           (max of the eight words)
-//   logit gate  x_v < xcap, xcap = T (L - kGateGumbel - slack) (packed 16-bit min / max of
-//               the raw bf16 bit patterns: for xcap <= 0 "x >= xcap" is "bits <= bits(xcap)"
-//               as unsigned 16-bit, for xcap > 0 it is "bits >= bits(xcap)" as signed)
-// An entry that fails both has y_v < xcap / T + kGateGumbel < L.  Entries in a vector
-// that trips a gate get a second, per-entry bound g_v <= (151 - bits(float(q_v)) 2^-23) ln 2,
-// q_v = (~r_v) >> 8  (from -ln(-ln(1-w)) <= -ln w and log2(1+m) >= m), and only those whose
-// bound still reaches L are evaluated exactly, with the same arithmetic as the unfiltered
-// kernel.  Every noise word is still generated; the outputs are identical to the
-// unfiltered kernel's, bit for bit, because L never exceeds the true maximum.
+// can only matter if y_v = x_v / T + g_v >= L.  Cheap tests per 16-byte vector, none of
+// which needs a logarithm, rule that out for almost every entry.  With two noise levels
+// G_lo < G_hi (top 8 / top 13 bits of the word all ones) and the Gumbel bounds
+// g < g_lo for r < G_lo, g < g_hi for r < G_hi:
+//   A  some word r >= G_hi                                   (very large noise)
+//   B  some logit x >= T (L - g_lo - slack)                  (very heavy logit)
+//   C  some word r >= G_lo  and  some logit x >= T (L - g_hi - slack)   (both moderate)
+// An entry of a vector that trips none of A, B, C has y_v < L.  A uses the maximum of the
+// eight words; B and C use packed 16-bit min / max of the raw bf16 bit patterns (for a
+// cap <= 0, "x >= cap" is "bits <= bits(cap)" as unsigned 16-bit; for a cap > 0 it is
+// "bits >= bits(cap)" as signed 16-bit).  Entries of a vector that trips a test get a
+// per-entry bound g_v <= (151 - bits(float(q_v)) 2^-23) ln 2, q_v = (~r_v) >> 8  (from
+// -ln(-ln(1-w)) <= -ln w and log2(1+m) >= m), and only those whose bound still reaches L
+// are evaluated exactly, with the same arithmetic as the unfiltered kernel.  Every noise
+// word is still generated; the outputs are identical to the unfiltered kernel's, bit for
+// bit, because L never exceeds the true maximum.
 // ---------------------------------------------------------------------------------
-#ifndef DIFR_GATE_BITS
-#define DIFR_GATE_BITS 10
-#endif
-constexpr int kGateBits = DIFR_GATE_BITS;
-constexpr uint32_t kGate = 0xFFFFFFFFu << (32 - kGateBits);  // r >= kGate: the top kGateBits bits are ones
-// sup of g over r < kGate, i.e. -ln(-ln(1 - (2^(24-kGateBits)+1) 2^-24)), rounded up:
-//   8 bits 5.543206, 9 bits 6.237317, 10 bits 6.930922, 11 bits 7.624253, 12 bits 8.317400
-constexpr float kGateGumbel = kGateBits == 8 ? 5.5433f : kGateBits == 9 ? 6.2374f : kGateBits == 10 ? 6.9311f
-                            : kGateBits == 11 ? 7.6244f : 8.3175f;
-static_assert(kGateBits >= 8 && kGateBits <= 12, "gate table covers 8..12 bits");
+constexpr int kGateLoBits = 8, kGateHiBits = 13;  // best pair of a sweep on the Zipf-profile workload
+constexpr uint32_t kGateLo = 0xFFFFFFFFu << (32 - kGateLoBits);  // r >= kGateLo: top 8 bits are ones
+constexpr uint32_t kGateHi = 0xFFFFFFFFu << (32 - kGateHiBits);  // r >= kGateHi: top 13 bits are ones
+// sup of g over r < gate, -ln(-ln(1 - (2^(24-bits)+1) 2^-24)), rounded up: 8 bits 5.543206, 13 bits 9.010365
+constexpr float kGumbelLo = 5.5433f, kGumbelHi = 9.0104f;
 
 typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
@@ -138,13 +139,26 @@ __device__ __forceinline__ float gumbel_upper_bound(uint32_t r)
     return __fmaf_rn(bits, -kLn2 * 0x1p-23f, 151.0f * kLn2);
 }
 
+// bf16 bit pattern of a logit cap, rounded so that the 16-bit test never misses an entry:
+// cap <= 0: sign bit forced (+0 counts as -0) and magnitude rounded up; cap > 0: truncated.
+__device__ __forceinline__ uint32_t cap_bits(float cap, bool neg)
+{
+    const uint32_t b = __float_as_uint(cap);
+    uint32_t c = b >> 16;
+    if (neg) {
+        c |= 0x8000u;
+        if ((b & 0xFFFFu) != 0u && c < 0xFF80u) c += 1u;
+    }
+    return c;
+}
+
 struct Gate {
-    float L;         // lower bound on the row maximum (wave-uniform)
-    float Lgate;     // L minus slack: an entry whose upper bound is below this cannot reach L
-    float xcap;      // logit gate in logit units
-    uint32_t cap16;  // its bf16 bit pattern, rounded so that the 16-bit test never misses
-    uint32_t cap_pair;  // both halves: cap16 + 1 (xcap <= 0) or cap16 - 1 (xcap > 0), for the folded test
-    bool cap_neg;    // xcap <= 0: unsigned test on the bit patterns; else signed test
+    float L;          // lower bound on the row maximum (wave-uniform)
+    float Lgate;      // L minus slack: an entry whose upper bound is below this cannot reach L
+    float xcap_hi;    // test B: T (L - g_lo - slack), in logit units
+    float xcap_lo;    // test C: T (L - g_hi - slack)
+    uint32_t cap16_hi, cap16_lo;  // their bf16 bit patterns
+    int mode;         // 0: both caps <= 0 (unsigned min test); 1: both > 0 (signed max test); 2: hi > 0 >= lo
 };
 
 __device__ __forceinline__ Gate make_gate(float L, float T)
@@ -154,20 +168,15 @@ __device__ __forceinline__ Gate make_gate(float L, float T)
     const float slack = 0.01f + 1e-5f * fabsf(L);
     g.L = L;
     g.Lgate = L - slack;
-    float xcap = (L - kGateGumbel - slack) * T;
-    if (!(xcap == xcap)) xcap = -__builtin_inff();  // L = +-inf arithmetic: gate everything in
-    g.xcap = xcap;
-    const uint32_t b = __float_as_uint(xcap);
-    g.cap_neg = !(xcap > 0.0f);
-    // xcap <= 0: grow the magnitude to the next bf16 (more negative); xcap > 0: truncate (smaller)
-    uint32_t c = b >> 16;
-    if (g.cap_neg) {
-        c |= 0x8000u;  // xcap = +0 is treated as -0: every non-negative logit is gated in
-        if ((b & 0xFFFFu) != 0u && c < 0xFF80u) c += 1u;
-    }
-    g.cap16 = c;
-    const uint32_t h = (g.cap_neg ? c + 1u : c - 1u) & 0xFFFFu;
-    g.cap_pair = h | (h << 16);
+    float hi = (L - kGumbelLo - slack) * T, lo = (L - kGumbelHi - slack) * T;
+    if (!(hi == hi)) hi = -__builtin_inff();  // L = +-inf arithmetic: gate everything in
+    if (!(lo == lo)) lo = -__builtin_inff();
+    g.xcap_hi = hi;
+    g.xcap_lo = lo;
+    const bool hi_neg = !(hi > 0.0f), lo_neg = !(lo > 0.0f);
+    g.cap16_hi = cap_bits(hi, hi_neg);
+    g.cap16_lo = cap_bits(lo, lo_neg);
+    g.mode = hi_neg ? 0 : (lo_neg ? 2 : 1);
     return g;
 }
 
@@ -247,83 +256,60 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
     // second term never changes, the first is scalar, and the sum cannot wrap (counter < 2^29).
     uint64_t lane_prod = (uint64_t)kPhiloxM0 * (uint32_t)(tid * (E / 4));
     asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
-    auto process = [&](u32x4 q, int round, bool active) {
+    auto process = [&](auto mode_tag, u32x4 q, int round, bool active) {
+        constexpr int MODE = decltype(mode_tag)::value;  // the gate's mode, fixed for this instantiation
         const uint64_t round_prod = (uint64_t)kPhiloxM0 * (uint32_t)(round * kBlock * (E / 4));
         const uint64_t p0 = round_prod + lane_prod;
         uint32_t r[E];
         philox4x32_10_from_product(p0, ri.pos, ri.seq, kStreamGumbel, ri.key, r);
         if (E == 8) philox4x32_10_from_product(p0 + kPhiloxM0, ri.pos, ri.seq, kStreamGumbel, ri.key, r + 4);
-        // noise gate: the largest of the words
-        uint32_t rmax;
-        if (E == 8)
-            rmax = max(max(max(r[0], r[1]), r[2]), max(max(max(r[3], r[4]), r[5]), max(r[6], r[7])));
-        else
-            rmax = max(max(r[0], r[1]), max(r[2], r[3]));
-        // wave-wide masks of the lanes whose vector trips the noise gate / the logit gate
-        const uint64_t nmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGate);
-        uint64_t hmask;
-        if (DT == 0) {
-#ifdef DIFR_X_FOLD
-            if (gate.cap_neg) {
-                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
-                m = __builtin_elementwise_min(m, as_u16x2(q.z));
-                m = __builtin_elementwise_min(m, as_u16x2(q.w));
-                m = __builtin_elementwise_min(m, as_u16x2(gate.cap_pair));
-                hmask = __builtin_amdgcn_ballot_w64(active && __builtin_bit_cast(uint32_t, m) != gate.cap_pair);
-            } else {
-                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
-                m = __builtin_elementwise_max(m, as_i16x2(q.z));
-                m = __builtin_elementwise_max(m, as_i16x2(q.w));
-                m = __builtin_elementwise_max(m, as_i16x2(gate.cap_pair));
-                hmask = __builtin_amdgcn_ballot_w64(active && __builtin_bit_cast(uint32_t, m) != gate.cap_pair);
-            }
-#else
-            if (gate.cap_neg) {
-                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
-                m = __builtin_elementwise_min(m, as_u16x2(q.z));
-                m = __builtin_elementwise_min(m, as_u16x2(q.w));
-                const uint16_t lo = m.x < m.y ? m.x : m.y;
-                hmask = __builtin_amdgcn_ballot_w64(active && lo <= (uint16_t)gate.cap16);
-            } else {
-                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
-                m = __builtin_elementwise_max(m, as_i16x2(q.z));
-                m = __builtin_elementwise_max(m, as_i16x2(q.w));
-                const int16_t hi = m.x > m.y ? m.x : m.y;
-                hmask = __builtin_amdgcn_ballot_w64(active && hi >= (int16_t)gate.cap16);
-            }
-#endif
-        } else {  // fp32 logits: four plain compares (a NaN counts as gated in)
-            hmask = __builtin_amdgcn_ballot_w64(
-                active && (!(__uint_as_float(q.x) < gate.xcap) || !(__uint_as_float(q.y) < gate.xcap) ||
-                           !(__uint_as_float(q.z) < gate.xcap) || !(__uint_as_float(q.w) < gate.xcap)));
-        }
-#ifdef DIFR_X_NOSLOW
-        bad |= (uint32_t)((nmask ^ hmask) == 0x123456789ull);  // timing experiment only: keep the gates alive
-        if (0) {
-#else
-        if (__builtin_expect((nmask | hmask) != 0ull, 0)) {
-#endif
-            const uint64_t me = 1ull << (tid & 63);
-            const bool nhit = (nmask & me) != 0ull, hhit = (hmask & me) != 0ull;
-            const int32_t v0 = (round * kBlock + tid) * E;
-            const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
-            if (nhit && !hhit) {  // only the noise gate tripped: look at the words alone
+        // the largest of the words, for tests A and C
+        uint32_t rmax = r[0];
 #pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    if (r[j] >= kGate) {
-                        const uint32_t w = qw[DT == 0 ? j >> 1 : j];
-                        const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
-                                                 : __uint_as_float(w);
-                        consider(xv, r[j], v0 + j);
-                    }
-                }
-            } else if (hhit) {
+        for (int j = 1; j < E; ++j) rmax = max(rmax, r[j]);
+        // wave-wide masks of the lanes whose vector trips A, B, or both halves of C
+        const uint64_t amask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateHi);
+        const uint64_t cnmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateLo);
+        uint64_t bmask, cxmask;
+        if (DT == 0) {
+            uint16_t lo = 0, hi = 0;
+            if (MODE != 1) {  // smallest bit pattern as unsigned: the largest logit if it is <= 0 ...
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                lo = m.x < m.y ? m.x : m.y;
+            }
+            if (MODE != 0) {  // ... largest bit pattern as signed: the largest logit if it is > 0
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                hi = (uint16_t)(m.x > m.y ? m.x : m.y);
+            }
+            const bool b_hit = MODE == 0 ? lo <= (uint16_t)gate.cap16_hi : (int16_t)hi >= (int16_t)gate.cap16_hi;
+            const bool c_hit = MODE == 1 ? (int16_t)hi >= (int16_t)gate.cap16_lo : lo <= (uint16_t)gate.cap16_lo;
+            bmask = __builtin_amdgcn_ballot_w64(active && b_hit);
+            cxmask = __builtin_amdgcn_ballot_w64(active && c_hit);
+        } else {  // fp32 logits: plain compares (a NaN counts as gated in)
+            const float x0 = __uint_as_float(q.x), x1 = __uint_as_float(q.y), x2 = __uint_as_float(q.z),
+                        x3 = __uint_as_float(q.w);
+            bmask = __builtin_amdgcn_ballot_w64(active && (!(x0 < gate.xcap_hi) || !(x1 < gate.xcap_hi) ||
+                                                           !(x2 < gate.xcap_hi) || !(x3 < gate.xcap_hi)));
+            cxmask = __builtin_amdgcn_ballot_w64(active && (!(x0 < gate.xcap_lo) || !(x1 < gate.xcap_lo) ||
+                                                            !(x2 < gate.xcap_lo) || !(x3 < gate.xcap_lo)));
+        }
+        const uint64_t hitmask = amask | bmask | (cnmask & cxmask);
+        if (__builtin_expect(hitmask != 0ull, 0)) {
+            if ((hitmask >> (tid & 63)) & 1ull) {
+                // Entries that could matter are those with moderate noise or a moderate logit; each of
+                // them is then tested against its own noise bound before anything exact is computed.
+                const int32_t v0 = (round * kBlock + tid) * E;
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
                 for (int j = 0; j < E; ++j) {
                     const uint32_t w = qw[DT == 0 ? j >> 1 : j];
                     const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
                                              : __uint_as_float(w);
-                    if (r[j] >= kGate || !(xv < gate.xcap)) consider(xv, r[j], v0 + j);
+                    if (r[j] >= kGateLo || !(xv < gate.xcap_lo)) consider(xv, r[j], v0 + j);
                 }
             }
             // a better score raises the lower bound for this wave; other waves pick it up from LDS
@@ -343,36 +329,32 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             reinterpret_cast<const u32x4 *>(row_bytes + (size_t)round * (kBlock * 16) + lane_off));
     };
 
-#ifdef DIFR_X_UNROLL2
-    if (n_main > 0) {
-        u32x4 qa = load_round(0), qb;
-        int round = 0;
-        for (; round + 1 < n_main; round += 2) {
-            qb = load_round(round + 1);
-            process(qa, round, true);
-            if (round + 2 < n_main) qa = load_round(round + 2);
-            process(qb, round + 1, true);
-            if ((round & 15) == 14) {  // pick up a bound another wave has raised
-                const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
-                if (L > gate.L) gate = make_gate(L, T);
-            }
-        }
-        if (round < n_main) process(qa, round, true);
-    }
-#else
-    if (n_main > 0) {
-        u32x4 q_next = load_round(0);
-        for (int round = 0; round < n_main; ++round) {
+    // Full rounds.  The loop body is instantiated once per gate mode so that it carries no mode
+    // branches; a change of mode (only possible when the bound L moves) leaves the inner loop.
+    int round = 0;
+    auto run_rounds = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        u32x4 q_next = load_round(round);
+        while (round < n_main) {
             const u32x4 q = q_next;
             if (round + 1 < n_main) q_next = load_round(round + 1);  // keep one vector in flight
-            process(q, round, true);
-            if ((round & 15) == 15) {  // pick up a bound another wave has raised
+            process(mode_tag, q, round, true);
+            ++round;
+            if ((round & 15) == 0) {  // pick up a bound another wave has raised
                 const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
                 if (L > gate.L) gate = make_gate(L, T);
             }
+            if (gate.mode != MODE) break;
         }
+    };
+    while (round < n_main) {
+        if (gate.mode == 0)
+            run_rounds(std::integral_constant<int, 0>());
+        else if (gate.mode == 1)
+            run_rounds(std::integral_constant<int, 1>());
+        else
+            run_rounds(std::integral_constant<int, 2>());
     }
-#endif
     if ((int64_t)n_main * kBlock < nvec) {  // last, partly filled round of vectors
         const bool active = (int64_t)n_main * kBlock + tid < nvec;
         u32x4 q;
@@ -382,7 +364,12 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             const uint32_t pad = DT == 0 ? 0xFF80FF80u : 0xFF800000u;
             q = u32x4{pad, pad, pad, pad};
         }
-        process(q, n_main, active);
+        if (gate.mode == 0)
+            process(std::integral_constant<int, 0>(), q, n_main, active);
+        else if (gate.mode == 1)
+            process(std::integral_constant<int, 1>(), q, n_main, active);
+        else
+            process(std::integral_constant<int, 2>(), q, n_main, active);
     }
     // the ragged tail: V % E entries, one lane each, evaluated exactly
     {

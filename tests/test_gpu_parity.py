@@ -337,7 +337,8 @@ def _same_outputs(a, b):
             assert torch.equal(x, y), k
 
 
-@pytest.mark.parametrize("case", ["honest", "random_claims", "sampling", "peaked", "positive_offset", "masked_topk",
+@pytest.mark.parametrize("case", ["honest", "random_claims", "sampling", "peaked", "positive_offset", "small_offset",
+                                  "masked_topk",
                                   "per_row_T", "fp32", "adversarial_order", "nonfinite"])
 def test_filtered_kernel_equals_unfiltered_bit_for_bit(difr, case):
     """The exact pre-filter only skips entries that cannot reach the row maximum: every output of
@@ -361,6 +362,9 @@ def test_filtered_kernel_equals_unfiltered_bit_for_bit(difr, case):
         claims = torch.where(torch.arange(wl.N, device=DEV) % 3 == 0, honest, idx.to(torch.int32))
     elif case == "positive_offset":              # softmax is shift invariant, real logits sit anywhere
         v = (v.float() + 40.0).to(torch.bfloat16)
+    elif case == "small_offset":                 # row maximum between the two noise bounds: logit caps of both signs
+        v = (v.float() + 4.0).to(torch.bfloat16)
+        claims = difr.gumbel_score(v, T, seeds, sid, pos, unfiltered=True)["argmax"]
     elif case == "masked_topk":                  # caller-side top-50 filter: everything else is -inf
         kth = v.float().topk(50, dim=1).values[:, -1:]
         v = torch.where(v.float() >= kth, v, torch.full_like(v, float("-inf")))
