@@ -138,7 +138,9 @@ int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float
  *              draws.  Rows whose claim does not match take a second pass over the row
  *              (DIFR_FLAG_SLOW_PATH) when this output is requested
  *   log_mass   (optional) ln( Phi((b-u)/sigma) - Phi((a-u)/sigma) + eps ), evaluated in
- *              fp64 from the fp32 a, b, u; needs sigma > 0 and eps >= 0
+ *              fp64 from the kernel's fp64 interval (a token whose probability is below
+ *              fp32 resolution of its CDF position still has a non-zero width there);
+ *              needs sigma > 0 and eps >= 0
  *   flags      DIFR_FLAG_* bits; MATCH means a <= u < b
  */
 int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_hi, float *u,

@@ -137,10 +137,13 @@ __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri,
     const bool bad = !(Ztot > 0.0) || !(Ztot < (double)__builtin_inff()) || !(M < __builtin_inff()) || !(M > ninf);
 
     float a = nan, bb = nan, d = nan;
+    double ad = 0.0, bd = 0.0;
     bool match = false;
     if (valid && !bad) {
         const double et = (double)fast_exp2(__fmaf_rn(Elem<DT>::to_float(x_row[t]), c, neg_Mc));
-        const double ad = Ptot / Ztot, bd = (Ptot + et) / Ztot, ud = (double)u;
+        const double ud = (double)u;
+        ad = Ptot / Ztot;
+        bd = (Ptot + et) / Ztot;
         a = (float)ad;
         bb = (float)bd;
         d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
@@ -205,7 +208,7 @@ __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri,
         if (o.ipt_token) o.ipt_token[row] = bad ? -1 : tok;
         if (o.log_mass)
             o.log_mass[row] =
-                (valid && !bad) ? (float)gaussian_log_mass((double)a, (double)bb, (double)u, o.sigma, o.eps) : nan;
+                (valid && !bad) ? (float)gaussian_log_mass(ad, bd, (double)u, o.sigma, o.eps) : nan;
         o.flags[row] = (uint8_t)f;
     }
 }
