@@ -120,11 +120,15 @@ typedef struct {
  *   max_score     (optional) max_v y_v
  *   claimed_score (optional) y_t, NaN for an invalid claim
  *   flags         DIFR_FLAG_* bits
+ *   logit_rank    (optional) number of entries whose raw logit is strictly above the claimed
+ *                 token's (rank 0 = the highest logit; the rank signal of Sec. 7.1, taken before
+ *                 temperature and filtering); -1 for an invalid claim.  Asking for it costs
+ *                 about one extra vector instruction per vocabulary entry
  * Arithmetic: fp32 on exact fp32 images of the stored logits; noise bits are
  * bit-identical to the definition above.
  */
 int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
-                      float *claimed_score, uint8_t *flags, void *hip_stream);
+                      float *claimed_score, uint8_t *flags, int32_t *logit_rank, void *hip_stream);
 
 /*
  * Token-IPT-DiFR over a batch.  Outputs are DEVICE arrays of N elements; those marked
@@ -142,10 +146,25 @@ int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float
  *              fp32 resolution of its CDF position still has a non-zero width there);
  *              needs sigma > 0 and eps >= 0
  *   flags      DIFR_FLAG_* bits; MATCH means a <= u < b
+ *   logit_rank (optional) as in difr_gumbel_score
  */
 int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                    int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
-                   void *hip_stream);
+                   int32_t *logit_rank, void *hip_stream);
+
+/*
+ * Three-class token classification and per-token exfiltratable information.  [Sec. 7.1 and the
+ * appendix algorithm "per-token risk classification via score and rank".]  Scores are
+ * suspiciousness (margin or dist), so the paper's "FSSL >= tau" reads score <= tau:
+ *   class 0 SAFE        score <= tau                            bits = log2|A_t| if known, else 0
+ *   class 1 SUSPICIOUS  score >  tau and 0 <= rank < rank_cutoff  bits = log2(rank_cutoff)
+ *   class 2 DANGEROUS   otherwise (also a NaN score or rank -1)   bits = log2(V)
+ * scores [N] fp32, ranks [N] int32 (logit_rank output above), log2_admissible [N] fp32 or NULL,
+ * all DEVICE; outputs cls [N] uint8 and bits [N] fp32 (optional), DEVICE.  rank_cutoff <= 0
+ * switches the rank tier off (two-class baseline).  V >= 1.
+ */
+int difr_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t rank_cutoff, int64_t V,
+                  const float *log2_admissible, uint8_t *cls, float *bits, void *hip_stream);
 
 /*
  * Pooling and flagging.  scores [N] DEVICE fp32 token scores (margin or dist);
@@ -169,7 +188,7 @@ int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t
  * row maximum).  Rows that are not 16-byte aligned always take this path.
  */
 int difr_debug_gumbel_score_unfiltered(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
-                                       float *claimed_score, uint8_t *flags, void *hip_stream);
+                                       float *claimed_score, uint8_t *flags, int32_t *logit_rank, void *hip_stream);
 
 /*
  * Test and audit helper: writes the raw 32 noise bits of vocabulary entries

@@ -378,6 +378,70 @@ int oracle_ipt_score(const void *logits, int dtype, int64_t N, int64_t V, int64_
 }
 
 /* ------------------------------------------------------------------------- */
+/* Logit rank of the claimed token (Sec. 7.1: rank by raw logits, before        */
+/* temperature and filtering; rank 0 = the highest logit):                      */
+/*   rank = #{ v : x_v > x_t }.   Invalid claim: -1.                            */
+/* ------------------------------------------------------------------------- */
+int32_t oracle_logit_rank_row(const double *x, int64_t V, int64_t claimed)
+{
+    if (claimed < 0 || claimed >= V) return -1;
+    int64_t r = 0;
+    for (int64_t v = 0; v < V; ++v)
+        if (x[v] > x[claimed]) ++r;
+    return (int32_t)r;
+}
+
+int oracle_logit_rank(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, const int32_t *claimed,
+                      int32_t *rank)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            rank[n] = oracle_logit_rank_row(x, V, claimed ? (int64_t)claimed[n] : -1);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Three-class token classification and per-token exfiltratable information    */
+/* (Sec. 7.1 and the appendix algorithm "risk classification via score and      */
+/* rank").  Scores here are suspiciousness, so "FSSL >= tau" reads score <= tau: */
+/*   SAFE (0)        score <= tau                      bits = log2|A_t| if the   */
+/*                                                     caller knows it, else 0   */
+/*   SUSPICIOUS (1)  score >  tau and rank in [0, R)   bits = log2 R             */
+/*   DANGEROUS (2)   otherwise (also NaN score, rank -1) bits = log2 V           */
+/* R <= 0 means no rank tier (two-class baseline).                              */
+/* ------------------------------------------------------------------------- */
+void oracle_classify(const double *scores, const int32_t *ranks, int64_t N, double tau, int64_t R, int64_t V,
+                     const double *log2_admissible, uint8_t *cls, double *bits)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        if (scores[n] <= tau) {
+            cls[n] = 0;
+            bits[n] = log2_admissible ? log2_admissible[n] : 0.0;
+        } else if (scores[n] > tau && R > 0 && ranks[n] >= 0 && (int64_t)ranks[n] < R) {
+            cls[n] = 1;
+            bits[n] = log2((double)R);
+        } else {
+            cls[n] = 2;
+            bits[n] = log2((double)V);
+        }
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Pooling and flagging.  Rows of sequence s are [offsets[s], offsets[s+1]).  */
 /*   mean_s = (1/L_s) sum score;  max_s;  mismatch_s = rows without MATCH;    */
 /*   flag_s = !(mean_s <= tau).  An empty sequence has mean 0, max 0, flag 0. */

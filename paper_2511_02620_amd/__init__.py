@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     FLAG_MATCH,
     FLAG_NONFINITE,
     FLAG_SLOW_PATH,
+    classify,
     debug_gumbel_map,
     debug_noise,
     gumbel_score,

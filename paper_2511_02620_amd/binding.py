@@ -48,7 +48,7 @@ class _Rows(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -66,11 +66,13 @@ def load_library():
                           "(there is no CPU fallback)" % _LIB_PATH)
     lib = C.CDLL(_LIB_PATH)
     vp = C.c_void_p
-    lib.difr_gumbel_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp]
+    lib.difr_gumbel_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.difr_gumbel_score.restype = C.c_int
-    lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp]
+    lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.difr_debug_gumbel_score_unfiltered.restype = C.c_int
-    lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp]
+    lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
+    lib.difr_classify.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_int64, C.c_int64, vp, vp, vp, vp]
+    lib.difr_classify.restype = C.c_int
     lib.difr_ipt_score.restype = C.c_int
     lib.difr_seq_reduce.argtypes = [vp, vp, vp, C.c_int64, C.c_int64, C.c_float, vp, vp, vp, vp, vp]
     lib.difr_seq_reduce.restype = C.c_int
@@ -154,7 +156,7 @@ def _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatur
 
 
 def gumbel_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temperatures=None, V=None,
-                 want_scores=True, unfiltered=False):
+                 want_scores=True, unfiltered=False, want_rank=False):
     """difr_gumbel_score (or, with unfiltered=True, difr_debug_gumbel_score_unfiltered).
     logits [N, >=V] bf16/fp32 on the GPU; seeds int64 [S] (uint64 bits); seq_ids, positions,
     claimed int32 [N].  Returns a dict of device tensors."""
@@ -167,16 +169,19 @@ def gumbel_score(logits, temperature, seeds, seq_ids, positions, claimed=None, t
     if want_scores:
         out["max_score"] = torch.empty(N, dtype=torch.float32, device=dev)
         out["claimed_score"] = torch.empty(N, dtype=torch.float32, device=dev)
+    if want_rank:
+        out["logit_rank"] = torch.empty(N, dtype=torch.int32, device=dev)
     with torch.cuda.device(dev):
         rc = entry(C.byref(r), _ptr(out["margin"]), _ptr(out["argmax"]), _ptr(out.get("max_score")),
-                                   _ptr(out.get("claimed_score")), _ptr(out["flags"]), _stream_ptr(dev))
+                                   _ptr(out.get("claimed_score")), _ptr(out["flags"]), _ptr(out.get("logit_rank")),
+                                   _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_gumbel_score")
     return out
 
 
 def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temperatures=None, V=None,
-              want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30, want_interval=True):
+              want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30, want_interval=True, want_rank=False):
     """difr_ipt_score.  Same inputs as :func:`gumbel_score`.  Returns a dict of device tensors."""
     lib = load_library()
     r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
@@ -188,10 +193,13 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
         out["ipt_token"] = torch.empty(N, dtype=torch.int32, device=dev)
     if want_log_mass:
         out["log_mass"] = torch.empty(N, **f32)
+    if want_rank:
+        out["logit_rank"] = torch.empty(N, dtype=torch.int32, device=dev)
     with torch.cuda.device(dev):
         rc = lib.difr_ipt_score(C.byref(r), _ptr(out["dist"]), _ptr(out.get("cdf_lo")), _ptr(out.get("cdf_hi")),
                                 _ptr(out.get("u")), _ptr(out.get("ipt_token")), float(sigma), float(eps),
-                                _ptr(out.get("log_mass")), _ptr(out["flags"]), _stream_ptr(dev))
+                                _ptr(out.get("log_mass")), _ptr(out["flags"]), _ptr(out.get("logit_rank")),
+                                _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_ipt_score")
     return out
@@ -219,6 +227,23 @@ def seq_reduce(scores, row_flags, seq_offsets, threshold):
                                  _ptr(out["seq_flag"]), _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_seq_reduce")
+    return out
+
+
+def classify(scores, ranks, tau, rank_cutoff, V, log2_admissible=None):
+    """difr_classify.  scores fp32 [N], ranks int32 [N] on the GPU.  Returns dict(cls uint8, bits fp32)."""
+    lib = load_library()
+    if not scores.is_cuda or scores.dtype != torch.float32 or scores.dim() != 1 or not scores.is_contiguous():
+        raise ValueError("scores must be a contiguous 1-D float32 GPU tensor")
+    dev, N = scores.device, scores.shape[0]
+    _check(ranks, torch.int32, N, "ranks", dev)
+    _check(log2_admissible, torch.float32, N, "log2_admissible", dev)
+    out = dict(cls=torch.empty(N, dtype=torch.uint8, device=dev), bits=torch.empty(N, dtype=torch.float32, device=dev))
+    with torch.cuda.device(dev):
+        rc = lib.difr_classify(_ptr(scores), _ptr(ranks), N, float(tau), int(rank_cutoff), int(V),
+                               _ptr(log2_admissible), _ptr(out["cls"]), _ptr(out["bits"]), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_classify")
     return out
 
 

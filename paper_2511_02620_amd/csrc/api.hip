@@ -66,7 +66,7 @@ int validate_rows(const difr_rows *in, difr::RowBatch *b, bool *aligned)
 extern "C" {
 
 int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
-                      uint8_t *flags, void *hip_stream)
+                      uint8_t *flags, int32_t *logit_rank, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
@@ -75,14 +75,14 @@ int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags) return DIFR_ERR_NULL;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    return difr::launch_gumbel_score(b, aligned, true, margin, argmax, max_score, claimed_score, flags,
+    return difr::launch_gumbel_score(b, aligned, true, margin, argmax, max_score, claimed_score, flags, logit_rank,
                                      (hipStream_t)hip_stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
 }
 
 int difr_debug_gumbel_score_unfiltered(const difr_rows *in, float *margin, int32_t *argmax, float *max_score,
-                                       float *claimed_score, uint8_t *flags, void *hip_stream)
+                                       float *claimed_score, uint8_t *flags, int32_t *logit_rank, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
@@ -91,14 +91,14 @@ int difr_debug_gumbel_score_unfiltered(const difr_rows *in, float *margin, int32
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags) return DIFR_ERR_NULL;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    return difr::launch_gumbel_score(b, aligned, false, margin, argmax, max_score, claimed_score, flags,
+    return difr::launch_gumbel_score(b, aligned, false, margin, argmax, max_score, claimed_score, flags, logit_rank,
                                      (hipStream_t)hip_stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
 }
 
 int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token,
-                   double sigma, double eps, float *log_mass, uint8_t *flags, void *hip_stream)
+                   double sigma, double eps, float *log_mass, uint8_t *flags, int32_t *logit_rank, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
@@ -109,7 +109,7 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
     if (!dist || !flags) return DIFR_ERR_NULL;
     if ((rc = check_device()) != DIFR_OK) return rc;
     return difr::launch_ipt_score(b, aligned, dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags,
-                                  (hipStream_t)hip_stream)
+                                  logit_rank, (hipStream_t)hip_stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
 }
@@ -126,6 +126,21 @@ int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t
     if (rc != DIFR_OK) return rc;
     return difr::launch_seq_reduce(scores, row_flags, seq_offsets, N, S, threshold, seq_mean, seq_max, seq_mismatch,
                                    seq_flag, (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t rank_cutoff, int64_t V,
+                  const float *log2_admissible, uint8_t *cls, float *bits, void *hip_stream)
+{
+    if (N < 0 || V < 1) return DIFR_ERR_SHAPE;
+    if (tau != tau) return DIFR_ERR_ARGUMENT;
+    if (N == 0) return DIFR_OK;
+    if (!scores || !ranks || !cls) return DIFR_ERR_NULL;
+    int rc = check_device();
+    if (rc != DIFR_OK) return rc;
+    return difr::launch_classify(scores, ranks, N, tau, rank_cutoff, V, log2_admissible, cls, bits,
+                                 (hipStream_t)hip_stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
 }

@@ -216,6 +216,19 @@ __device__ __forceinline__ float block_sum(float v, float *lds /* >= kWaves floa
     return s;
 }
 
+__device__ __forceinline__ int32_t block_sum_i32(int32_t v, int32_t *lds /* >= kWaves ints */)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int32_t s = lds[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) s += lds[i];
+    return s;
+}
+
 __device__ __forceinline__ float block_max(float v, float *lds /* >= kWaves floats */)
 {
     v = wave_max(v);

@@ -11,10 +11,13 @@ namespace difr {
 
 // filtered = false forces the unfiltered kernel (every entry evaluated exactly); unaligned rows always use it.
 int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *margin, int32_t *argmax,
-                        float *max_score, float *claimed_score, uint8_t *flags, hipStream_t stream);
+                        float *max_score, float *claimed_score, uint8_t *flags, int32_t *logit_rank,
+                        hipStream_t stream);
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
-                     hipStream_t stream);
+                     int32_t *logit_rank, hipStream_t stream);
+int launch_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t R, int64_t V,
+                    const float *log2_admissible, uint8_t *cls, float *bits, hipStream_t stream);
 int launch_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,
                       int64_t S, float threshold, float *seq_mean, float *seq_max, int32_t *seq_mismatch,
                       uint8_t *seq_flag, hipStream_t stream);

@@ -18,12 +18,14 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
                                                               int32_t *__restrict__ argmax,
                                                               float *__restrict__ max_score,
                                                               float *__restrict__ claimed_score,
-                                                              uint8_t *__restrict__ flags)
+                                                              uint8_t *__restrict__ flags,
+                                                              int32_t *__restrict__ logit_rank)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
     __shared__ float lds_y[kWaves];
     __shared__ int32_t lds_i[kWaves];
+    __shared__ int32_t lds_rank[kWaves];
 
     const int64_t row = blockIdx.x;
     const RowInfo ri = load_row_info(b, row);
@@ -36,6 +38,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
             argmax[row] = -1;
             if (max_score) max_score[row] = nan;
             if (claimed_score) claimed_score[row] = nan;
+            if (logit_rank) logit_rank[row] = -1;
             flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
         }
         return;
@@ -44,10 +47,13 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
     const int64_t V = b.V;
     const float inv_T = 1.0f / ri.T;
+    const bool claim_ok = ri.claimed >= 0 && (int64_t)ri.claimed < V;
+    const float xt = claim_ok ? Elem<DT>::to_float(x_row[ri.claimed]) : nan;
 
     float best_y = -__builtin_inff();
     int32_t best_v = 0x7FFFFFFF;
     uint32_t bad = 0;
+    int32_t above = 0;  // entries whose raw logit exceeds the claimed token's
 
     for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
         float x[E];
@@ -61,6 +67,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
                 const float xv = x[4 * q + j];
                 const float y = perturbed_score(xv, inv_T, r[j]);
                 bad |= (uint32_t)!(xv < __builtin_inff());  // NaN or +inf
+                above += (int32_t)(xv > xt);
                 if (y > best_y) {
                     best_y = y;
                     best_v = (int32_t)(base + 4 * q + j);
@@ -71,6 +78,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
 
     block_argmax(best_y, best_v, lds_y, lds_i);
     const int any_bad = __syncthreads_or((int)bad);
+    above = block_sum_i32(above, lds_rank);
 
     if (tid == 0) {
         if (best_v == 0x7FFFFFFF) best_v = 0;  // every entry masked: all scores are -inf
@@ -91,6 +99,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_kernel(RowBatch b, float 
         argmax[row] = best_v;
         if (max_score) max_score[row] = best_y;
         if (claimed_score) claimed_score[row] = yt;
+        if (logit_rank) logit_rank[row] = claim_ok ? above : -1;
         flags[row] = (uint8_t)f;
     }
 }
@@ -180,18 +189,24 @@ __device__ __forceinline__ Gate make_gate(float L, float T)
     return g;
 }
 
-template <int DT>
+// RANK: also count the entries whose raw logit exceeds the claimed token's (logit rank, Sec. 7.1).
+// For bf16 the count works on the raw bit patterns, two per dword, without unpacking: for a claimed
+// logit >= +0 "x > x_t" is "bits > bits(x_t)" as signed 16-bit, for a negative one it is
+// "bits < bits(x_t)" as unsigned 16-bit (a claimed -0 is treated as +0).
+template <int DT, bool RANK>
 __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch b, float *__restrict__ margin,
                                                                        int32_t *__restrict__ argmax,
                                                                        float *__restrict__ max_score,
                                                                        float *__restrict__ claimed_score,
-                                                                       uint8_t *__restrict__ flags)
+                                                                       uint8_t *__restrict__ flags,
+                                                                       int32_t *__restrict__ logit_rank)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
     __shared__ float lds_y[kWaves];
     __shared__ int32_t lds_i[kWaves];
     __shared__ float lds_L[kWaves];
+    __shared__ int32_t lds_rank[kWaves];
 
     const int64_t row = blockIdx.x;
     const RowInfo ri = load_row_info(b, row);
@@ -206,6 +221,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             argmax[row] = -1;
             if (max_score) max_score[row] = nan;
             if (claimed_score) claimed_score[row] = nan;
+            if (RANK) logit_rank[row] = -1;
             flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
         }
         return;
@@ -219,13 +235,43 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
     // The claimed token's score, by the same function the stream uses: the first lower bound.
     const int32_t t = ri.claimed;
     const bool valid = (t >= 0 && (int64_t)t < V);
-    float yt = nan;
+    float yt = nan, xt = nan;
     if (valid) {
         uint32_t r[4];
         noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)t >> 2, r);
         const uint32_t rt = (t & 3) == 0 ? r[0] : (t & 3) == 1 ? r[1] : (t & 3) == 2 ? r[2] : r[3];
-        yt = perturbed_score(Elem<DT>::to_float(x_row[t]), inv_T, rt);
+        xt = Elem<DT>::to_float(x_row[t]);
+        yt = perturbed_score(xt, inv_T, rt);
     }
+    // logit rank: wave-uniform count of entries above the claimed logit
+    uint32_t above = 0;
+    const uint32_t xt_bits = (xt == 0.0f) ? 0u : __float_as_uint(xt);  // -0 counts as +0
+    const bool xt_pos = (xt_bits >> 31) == 0u;
+    const uint32_t xt16 = xt_bits >> 16;
+    auto count_above = [&](u32x4 q, bool active) {
+        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+        uint32_t n = 0;
+        if (DT == 0) {
+            if (xt_pos) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(active && (int16_t)(qw[j] & 0xFFFFu) > (int16_t)xt16));
+                    n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(active && (int16_t)(qw[j] >> 16) > (int16_t)xt16));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(active && (uint16_t)(qw[j] & 0xFFFFu) < (uint16_t)xt16));
+                    n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(active && (uint16_t)(qw[j] >> 16) < (uint16_t)xt16));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(active && __uint_as_float(qw[j]) > xt));
+        }
+        above += n;
+    };
     Gate gate = make_gate((yt == yt) ? yt : ninf, T);
     if ((tid & 63) == 0) lds_L[wave] = gate.L;
 
@@ -298,6 +344,7 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
                                                             !(x2 < gate.xcap_lo) || !(x3 < gate.xcap_lo)));
         }
         const uint64_t hitmask = amask | bmask | (cnmask & cxmask);
+        if (RANK) count_above(q, active);
         if (__builtin_expect(hitmask != 0ull, 0)) {
             if ((hitmask >> (tid & 63)) & 1ull) {
                 // Entries that could matter are those with moderate noise or a moderate logit; each of
@@ -380,12 +427,15 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
             const uint32_t rv = (v & 3) == 0 ? r[0] : (v & 3) == 1 ? r[1] : (v & 3) == 2 ? r[2] : r[3];
             evaluate(Elem<DT>::to_float(x_row[v]), rv, (int32_t)v);
         }
+        if (RANK) above += __builtin_popcountll(__builtin_amdgcn_ballot_w64(v < V && Elem<DT>::to_float(x_row[v < V ? v : 0]) > xt));
     }
 
     block_argmax(best_y, best_v, lds_y, lds_i);
+    if (RANK && (tid & 63) == 0) lds_rank[wave] = (int32_t)above;
     const int any_bad = __syncthreads_or((int)bad);
 
     if (tid == 0) {
+        if (RANK) logit_rank[row] = valid ? lds_rank[0] + lds_rank[1] + lds_rank[2] + lds_rank[3] : -1;
         if (best_v == 0x7FFFFFFF) best_v = 0;  // every entry masked: all scores are -inf
         uint32_t f = any_bad ? kFlagNonfinite : 0u;
         float mg = nan;
@@ -426,25 +476,35 @@ __global__ __launch_bounds__(kBlock) void debug_gumbel_map_kernel(const uint32_t
 }
 
 int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *margin, int32_t *argmax,
-                        float *max_score, float *claimed_score, uint8_t *flags, hipStream_t stream)
+                        float *max_score, float *claimed_score, uint8_t *flags, int32_t *logit_rank,
+                        hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
+#define DIFR_ARGS b, margin, argmax, max_score, claimed_score, flags, logit_rank
     if (aligned && filtered) {
-        if (b.dtype == 0)
-            gumbel_score_filtered_kernel<0><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
-        else
-            gumbel_score_filtered_kernel<1><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+        if (b.dtype == 0) {
+            if (logit_rank)
+                gumbel_score_filtered_kernel<0, true><<<grid, block, 0, stream>>>(DIFR_ARGS);
+            else
+                gumbel_score_filtered_kernel<0, false><<<grid, block, 0, stream>>>(DIFR_ARGS);
+        } else {
+            if (logit_rank)
+                gumbel_score_filtered_kernel<1, true><<<grid, block, 0, stream>>>(DIFR_ARGS);
+            else
+                gumbel_score_filtered_kernel<1, false><<<grid, block, 0, stream>>>(DIFR_ARGS);
+        }
     } else if (b.dtype == 0) {
         if (aligned)
-            gumbel_score_kernel<0, true><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+            gumbel_score_kernel<0, true><<<grid, block, 0, stream>>>(DIFR_ARGS);
         else
-            gumbel_score_kernel<0, false><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+            gumbel_score_kernel<0, false><<<grid, block, 0, stream>>>(DIFR_ARGS);
     } else {
         if (aligned)
-            gumbel_score_kernel<1, true><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+            gumbel_score_kernel<1, true><<<grid, block, 0, stream>>>(DIFR_ARGS);
         else
-            gumbel_score_kernel<1, false><<<grid, block, 0, stream>>>(b, margin, argmax, max_score, claimed_score, flags);
+            gumbel_score_kernel<1, false><<<grid, block, 0, stream>>>(DIFR_ARGS);
     }
+#undef DIFR_ARGS
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

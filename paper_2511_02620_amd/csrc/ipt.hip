@@ -102,13 +102,14 @@ struct IptOutputs {
     double sigma, eps;
     float *log_mass;
     uint8_t *flags;
+    int32_t *logit_rank;
 };
 
 template <int DT, bool ALIGNED>
 __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri, int64_t row,
                                            const typename Elem<DT>::type *x_row, float c, float m, double Z,
-                                           double P, float mP, const IptOutputs &o, float *lds_f, double *lds_d,
-                                           int32_t *lds_tok)
+                                           double P, float mP, int32_t above, const IptOutputs &o, float *lds_f,
+                                           double *lds_d, int32_t *lds_tok)
 {
     constexpr int E = Elem<DT>::kPerVec;
     const int tid = threadIdx.x;
@@ -209,6 +210,7 @@ __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri,
         if (o.log_mass)
             o.log_mass[row] =
                 (valid && !bad) ? (float)gaussian_log_mass(ad, bd, (double)u, o.sigma, o.eps) : nan;
+        if (o.logit_rank) o.logit_rank[row] = valid ? above : -1;
         o.flags[row] = (uint8_t)f;
     }
 }
@@ -224,6 +226,7 @@ __device__ __forceinline__ bool ipt_row_rejected(const RowInfo &ri, int64_t row,
         if (o.u) o.u[row] = nan;
         if (o.ipt_token) o.ipt_token[row] = -1;
         if (o.log_mass) o.log_mass[row] = nan;
+        if (o.logit_rank) o.logit_rank[row] = -1;
         o.flags[row] = (uint8_t)(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
     }
     return true;
@@ -250,12 +253,17 @@ __global__ __launch_bounds__(kBlock) void ipt_score_generic_kernel(RowBatch b, I
     const float c = kLog2e / ri.T;  // exponent scale: exp(x/T) = 2^(x c)
     const int64_t t = ri.claimed;
     const int64_t tcut = (t >= 0 && t < V) ? t : 0;  // prefix is over v < tcut
+    const float xt = (t >= 0 && t < V) ? Elem<DT>::to_float(x_row[t]) : __builtin_nanf("");
+    __shared__ int32_t lds_rank[kWaves];
+    int32_t above = 0;  // entries whose raw logit exceeds the claimed token's (logit rank)
 
     float m = ninf, neg_mc = 0.0f, mP = ninf;
     double Z = 0.0, P = 0.0;
     for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
         float x[E], e[E];
         load_elems<DT, false>(x_row, base, V, x);
+#pragma unroll
+        for (int j = 0; j < E; ++j) above += (int32_t)(x[j] > xt);
         float m8 = x[0];
 #pragma unroll
         for (int j = 1; j < E; ++j) m8 = fmaxf(m8, x[j]);
@@ -276,7 +284,8 @@ __global__ __launch_bounds__(kBlock) void ipt_score_generic_kernel(RowBatch b, I
         }
         Z += (double)tree_sum<E>(e);
     }
-    ipt_finish<DT, false>(b, ri, row, x_row, c, m, Z, P, mP, o, lds_f, lds_d, &lds_tok);
+    above = block_sum_i32(above, lds_rank);
+    ipt_finish<DT, false>(b, ri, row, x_row, c, m, Z, P, mP, above, o, lds_f, lds_d, &lds_tok);
 }
 
 // Streaming kernel for 16-byte aligned rows.
@@ -310,6 +319,12 @@ __global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, IptOutput
 
     float m = ninf, neg_mc = 0.0f, mP = ninf;
     double Z = 0.0, P = 0.0;
+    // logit rank (Sec. 7.1): entries whose raw logit exceeds the claimed token's, counted per wave
+    // with ballots so that it costs one compare per entry and only when asked for
+    __shared__ int32_t lds_rank[kWaves];
+    const bool want_rank = o.logit_rank != nullptr;
+    const float xt = valid ? Elem<DT>::to_float(x_row[t]) : __builtin_nanf("");
+    uint32_t above = 0;
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const char *row_bytes = reinterpret_cast<const char *>(x_row);
@@ -352,13 +367,21 @@ __global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, IptOutput
 #pragma unroll
         for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, neg_mc));
     };
+    auto count_above = [&](const float x[E]) {
+        uint32_t n = 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[j] > xt));
+        above += n;
+    };
     auto fast_round = [&](u32x4 q) {
         float x[E], e[E];
         unpack(q, x);
+        if (want_rank) count_above(x);
         terms(x, e);
         Z += (double)tree_sum<E>(e);
     };
     // a round that needs index tests: the one holding the claimed token and the last, ragged one
+    uint32_t lane_above = 0;
     auto careful_round = [&](int round, bool prefix_open) {
         const int64_t v0 = ((int64_t)round * kBlock + tid) * E;
         if (v0 < V) {
@@ -367,6 +390,12 @@ __global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, IptOutput
 #pragma unroll
             for (int j = 0; j < E; ++j)
                 if (v0 + j >= V) x[j] = ninf;
+            if (want_rank) {  // divergent here: add this lane's own count, the wave sum comes at the end
+                uint32_t n = 0;
+#pragma unroll
+                for (int j = 0; j < E; ++j) n += (uint32_t)(x[j] > xt);
+                lane_above += n;
+            }
             terms(x, e);
             if (prefix_open) {
                 float pre = 0.0f;
@@ -410,15 +439,20 @@ __global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, IptOutput
         }
         if (n_rounds > full_rounds) careful_round(full_rounds, valid);
     }
-    ipt_finish<DT, true>(b, ri, row, x_row, c, m, Z, P, mP, o, lds_f, lds_d, &lds_tok);
+    int32_t total_above = 0;
+    if (want_rank) {  // wave-uniform ballot counts (lane 0 carries them) plus the per-lane counts of careful rounds
+        const int32_t mine = (int32_t)lane_above + ((tid & 63) == 0 ? (int32_t)above : 0);
+        total_above = block_sum_i32(mine, lds_rank);
+    }
+    ipt_finish<DT, true>(b, ri, row, x_row, c, m, Z, P, mP, total_above, o, lds_f, lds_d, &lds_tok);
 }
 
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
-                     hipStream_t stream)
+                     int32_t *logit_rank, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
-    const IptOutputs o{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags};
+    const IptOutputs o{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags, logit_rank};
     if (b.dtype == 0) {
         if (aligned)
             ipt_score_kernel<0><<<grid, block, 0, stream>>>(b, o);

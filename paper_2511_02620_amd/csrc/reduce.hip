@@ -4,6 +4,8 @@
 //
 // One workgroup per sequence.  Each thread accumulates a strided share in fp64, then a
 // fixed binary tree over the 256 partials: no atomics, so the result is reproducible.
+#include <math.h>
+
 #include "difr_device.hpp"
 #include "difr_host.hpp"
 
@@ -69,6 +71,49 @@ __global__ __launch_bounds__(kBlock) void seq_reduce_kernel(const float *__restr
         if (seq_mismatch) seq_mismatch[s] = mo;
         if (seq_flag) seq_flag[s] = fl;
     }
+}
+
+// Three-class token classification and per-token exfiltratable information (Sec. 7.1 and the
+// appendix algorithm "risk classification via score and rank").  Scores are suspiciousness:
+//   SAFE (0)        score <= tau                        bits = log2|A_t| if supplied, else 0
+//   SUSPICIOUS (1)  score >  tau and 0 <= rank < R      bits = log2 R
+//   DANGEROUS (2)   otherwise (NaN score, rank -1)      bits = log2 V
+__global__ __launch_bounds__(kBlock) void classify_kernel(const float *__restrict__ scores,
+                                                          const int32_t *__restrict__ ranks, int64_t N, float tau,
+                                                          int64_t R, float log2_R, float log2_V,
+                                                          const float *__restrict__ log2_admissible,
+                                                          uint8_t *__restrict__ cls, float *__restrict__ bits)
+{
+    for (int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x; n < N; n += (int64_t)gridDim.x * kBlock) {
+        const float s = scores[n];
+        const int32_t r = ranks[n];
+        uint8_t c;
+        float b;
+        if (s <= tau) {
+            c = 0;
+            b = log2_admissible ? log2_admissible[n] : 0.0f;
+        } else if (s > tau && R > 0 && r >= 0 && (int64_t)r < R) {
+            c = 1;
+            b = log2_R;
+        } else {
+            c = 2;
+            b = log2_V;
+        }
+        cls[n] = c;
+        if (bits) bits[n] = b;
+    }
+}
+
+int launch_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t R, int64_t V,
+                    const float *log2_admissible, uint8_t *cls, float *bits, hipStream_t stream)
+{
+    int64_t blocks = (N + kBlock - 1) / kBlock;
+    if (blocks > 65536) blocks = 65536;
+    const float log2_R = R > 0 ? (float)log2((double)R) : 0.0f;
+    const float log2_V = (float)log2((double)V);
+    classify_kernel<<<dim3((unsigned)blocks), dim3(kBlock), 0, stream>>>(scores, ranks, N, tau, R, log2_R, log2_V,
+                                                                         log2_admissible, cls, bits);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 
 int launch_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,

@@ -77,12 +77,12 @@ def test_argument_validation_needs_no_device(lib):
         return r
 
     def g(r, margin=fake, argmax=fake, flags=fake):
-        return lib.difr_gumbel_score(C.byref(r), margin, argmax, None, None, flags, None)
+        return lib.difr_gumbel_score(C.byref(r), margin, argmax, None, None, flags, None, None)
 
     def i(r, dist=fake, flags=fake, sigma=0.01, eps=1e-30, log_mass=None):
-        return lib.difr_ipt_score(C.byref(r), dist, None, None, None, None, sigma, eps, log_mass, flags, None)
+        return lib.difr_ipt_score(C.byref(r), dist, None, None, None, None, sigma, eps, log_mass, flags, None, None)
 
-    assert lib.difr_gumbel_score(None, fake, fake, None, None, fake, None) == NULL
+    assert lib.difr_gumbel_score(None, fake, fake, None, None, fake, None, None) == NULL
     for bad, want in ((rows(N=-1), SHAPE), (rows(V=0), SHAPE), (rows(ld=15), SHAPE), (rows(S=0), SHAPE),
                       (rows(N=1 << 31), SHAPE), (rows(V=1 << 31, ld=1 << 31), SHAPE), (rows(dtype=2), DTYPE),
                       (rows(temperature=0.0), TEMP), (rows(temperature=-1.0), TEMP),
@@ -102,6 +102,14 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_seq_reduce(None, None, fake, 4, 1, 0.0, None, None, None, None, None) == NULL
     assert lib.difr_seq_reduce(fake, None, fake, 4, 1, float("nan"), None, None, None, None, None) == ARG
     assert lib.difr_seq_reduce(None, None, None, 0, 0, 0.0, None, None, None, None, None) == OK
+    # classification
+    assert lib.difr_classify(fake, fake, -1, 0.0, 8, 100, None, fake, None, None) == SHAPE
+    assert lib.difr_classify(fake, fake, 4, 0.0, 8, 0, None, fake, None, None) == SHAPE
+    assert lib.difr_classify(None, fake, 4, 0.0, 8, 100, None, fake, None, None) == NULL
+    assert lib.difr_classify(fake, None, 4, 0.0, 8, 100, None, fake, None, None) == NULL
+    assert lib.difr_classify(fake, fake, 4, 0.0, 8, 100, None, None, None, None) == NULL
+    assert lib.difr_classify(fake, fake, 4, float("nan"), 8, 100, None, fake, None, None) == ARG
+    assert lib.difr_classify(None, None, 0, 0.0, 8, 100, None, None, None, None) == OK
     assert lib.difr_debug_noise(C.byref(rows()), 4, 0, fake, None) == SHAPE
     assert lib.difr_debug_gumbel_map(None, 4, fake, None) == NULL
 

@@ -393,3 +393,56 @@ def test_filtered_kernel_equals_unfiltered_bit_for_bit(difr, case):
     _same_outputs(a, b)
     if case in ("honest", "positive_offset", "fp32"):
         say(case, "match rate", float((a["flags"] & 1).float().mean()))
+
+
+@pytest.mark.parametrize("dtype,V,ld,offset", [(torch.bfloat16, 20504, 20504, 0), (torch.bfloat16, 4099, 4099, 1),
+                                               (torch.float32, 4100, 4104, 0), (torch.float32, 3001, 3001, 1)])
+def test_logit_rank_and_classifier(difr, dtype, V, ld, offset):
+    """Logit rank of the claimed token (an integer count: bit-exact) from both score kernels and from the
+    unfiltered reference, and the three-class classifier with its exfiltratable-bits output."""
+    N = 96
+    g = torch.Generator(device=DEV).manual_seed(4321 + V)
+    store = torch.randn(N * ld + offset + 8, generator=g, device=DEV, dtype=torch.float32).mul_(3.0).to(dtype)
+    logits = store[offset:offset + N * ld].view(N, ld)
+    logits[:, 5] = logits[:, 9]                                     # exact ties in every row
+    logits[0, :40] = 0.0
+    logits[0, 40:80] = -0.0                                         # signed zeros compare equal
+    logits[1, 100:900] = float("-inf")
+    wl = W.scaled(W.C1_TINY, S=3, L=32, V=V, chunk_rows=96)
+    seeds, sid, pos, _ = _aux(wl)
+    cpu_gen = torch.Generator().manual_seed(V)
+    claims = torch.randint(0, V, (N,), generator=cpu_gen, dtype=torch.int32)
+    claims[0], claims[1], claims[2], claims[3], claims[4], claims[5] = 3, 50, 5, 9, -1, V
+    top = logits[:, :V].float().topk(4, dim=1).indices.cpu()
+    claims[6:30] = top[6:30, 0].to(torch.int32)                     # highest logit: rank 0
+    claims[30:50] = top[30:50, 3].to(torch.int32)                   # rank 3
+    claims = claims.to(DEV)
+    host = parity.to_host_logits(logits)
+    want = oracle.logit_rank(host, V, claims.cpu().numpy())
+    assert want[0] == int((logits[0, :V].float() > 0).sum()) and want[4] == -1 and want[5] == -1
+    assert (want[6:30] == 0).all()
+    a = difr.gumbel_score(logits, 0.9, seeds, sid, pos, claims, V=V, want_rank=True)
+    b = difr.gumbel_score(logits, 0.9, seeds, sid, pos, claims, V=V, want_rank=True, unfiltered=True)
+    c = difr.ipt_score(logits, 0.9, seeds, sid, pos, claims, V=V, want_rank=True)
+    plain = difr.gumbel_score(logits, 0.9, seeds, sid, pos, claims, V=V)
+    for out in (a, b, c):
+        assert np.array_equal(out["logit_rank"].cpu().numpy(), want)
+    _same_outputs({k: v for k, v in a.items() if k != "logit_rank"}, plain)      # asking for the rank changes nothing else
+    # classifier on the library's own scores and ranks against the oracle on the oracle's
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    og = oracle.gumbel_score(host, V, f32(0.9), hs, hsid, hpos, claims.cpu().numpy())
+    tau = np.float32(0.75)
+    for R in (0, 1, 4, 8):
+        got = difr.classify(a["margin"], a["logit_rank"], float(tau), R, V)
+        ref = oracle.classify(og["margin"], want, tau, R, V)
+        near = np.abs(np.nan_to_num(og["margin"], nan=np.inf) - tau) <= parity.TIE_REL * max(1.0, abs(float(tau)))
+        diff = got["cls"].cpu().numpy() != ref["cls"]
+        assert not (diff & ~near).any()
+        assert np.allclose(got["bits"].cpu().numpy()[~diff], ref["bits"][~diff], atol=1e-6)
+        if R == 8:
+            cls = ref["cls"]
+            assert (cls == 0).any() and (cls == 1).any() and (cls == 2).any()
+    adm = torch.rand(N, generator=cpu_gen).to(DEV)
+    got = difr.classify(a["margin"], a["logit_rank"], float(tau), 8, V, adm)
+    ref = oracle.classify(og["margin"], want, tau, 8, V, adm.cpu().numpy().astype(np.float64))
+    assert np.allclose(got["bits"].cpu().numpy(), ref["bits"], atol=1e-6)
