@@ -2,9 +2,12 @@
 """Benchmark of the verifier's per-token vocabulary pass on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic token rows that are
-already resident in HBM: Token-DiFR scoring (difr_gumbel_score), Token-IPT-DiFR scoring
-(difr_ipt_score) and the per-sequence pooling / flagging of both score arrays
-(difr_seq_reduce twice).  The default workload is the 30B-MoE-class streaming config:
+already resident in HBM: Token-DiFR and Token-IPT-DiFR scoring of every row and the per-sequence
+pooling / flagging of both score arrays (difr_seq_reduce twice).  By default the two scores come
+from difr_score_both, which reads each row once for both; `--step separate` runs
+difr_gumbel_score and difr_ipt_score one after the other instead (same outputs, two reads).  The
+two single-estimator kernels are also timed on their own after the timed region, for the
+per-estimator figures.  The default workload is the 30B-MoE-class streaming config:
 N = 65536 token rows (64 sequences x 1024), V = 151936, bf16 logits, T = 1.0.
 
 Prints ONE JSON line: verified tokens/s for the step, the roofline record of the dominant
@@ -40,12 +43,15 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # the entry against the running maximum.  The two logarithms and the fma of entries that provably
 # cannot reach the maximum are not counted: the exact pre-filter removes them.
 GUMBEL_ALU_OPS_PER_ENTRY = 11
+# ... and of the softmax statistics of the IPT estimator: scale-and-shift, exponential, sum, running maximum.
+IPT_ALU_OPS_PER_ENTRY = 4
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 4 GiB device copy (profiles/c3_gumbel_ipt_hbm_traffic.md).
 MEASURED_TRAFFIC = {
     ("difr_gumbel_score", "c3_30b_moe_class"): 1.9936e10,
     ("difr_ipt_score", "c3_30b_moe_class"): 1.9944e10,
+    ("difr_score_both", "c3_30b_moe_class"): None,
 }
 
 
@@ -119,6 +125,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3_30b_moe_class", help="workload name (see paper_2511_02620_amd.workloads)")
     ap.add_argument("--temperature", type=float, default=None)
+    ap.add_argument("--step", choices=("fused", "separate"), default="fused",
+                    help="fused: difr_score_both (one read of the logits for both estimators); "
+                         "separate: difr_gumbel_score then difr_ipt_score")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="rows of the batch the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one plain device copy of 4 GiB (a kernel of known HBM "
@@ -145,15 +154,18 @@ def main():
     esz = 2 if wl.dtype == torch.bfloat16 else 4
     tau_g, tau_i = 0.05, 0.01
 
+    row_args = (data["logits"], wl.temperature, data["seeds"], data["seq_ids"], data["positions"])
+
     def step(ev=None):
         if ev is not None:
             ev[0].record()
-        g = difr.gumbel_score(data["logits"], wl.temperature, data["seeds"], data["seq_ids"], data["positions"],
-                              data["claims_g"])
-        if ev is not None:
-            ev[1].record()
-        i = difr.ipt_score(data["logits"], wl.temperature, data["seeds"], data["seq_ids"], data["positions"],
-                           data["claims_i"])
+        if args.step == "fused":
+            g, i = difr.score_both(*row_args, data["claims_g"], data["claims_i"])
+        else:
+            g = difr.gumbel_score(*row_args, data["claims_g"])
+            if ev is not None:
+                ev[1].record()
+            i = difr.ipt_score(*row_args, data["claims_i"])
         if ev is not None:
             ev[2].record()
         sg = difr.seq_reduce(g["margin"], g["flags"], data["seq_offsets"], tau_g)
@@ -161,6 +173,16 @@ def main():
         if ev is not None:
             ev[3].record()
         return g, i, sg, si
+
+    def time_alone(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
 
     if args.copy_probe:
         src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(7)
@@ -179,30 +201,46 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     t_r = float(np.mean([e[2].elapsed_time(e[3]) for e in events]))
+    if args.step == "fused":
+        t_b = float(np.mean([e[0].elapsed_time(e[2]) for e in events]))
+        # the single-estimator kernels on their own, after the timed region
+        reps = max(1, min(args.steps, 5))
+        t_g = time_alone(lambda: difr.gumbel_score(*row_args, data["claims_g"]), reps)
+        t_i = time_alone(lambda: difr.ipt_score(*row_args, data["claims_i"]), reps)
+    else:
+        t_b = None
+        t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+        t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
     match_g = float((g["flags"] & 1).float().mean())
     match_i = float((i["flags"] & 1).float().mean())
-    log("gumbel %.3f ms, ipt %.3f ms, pooling %.3f ms per step; match rates %.4f / %.4f; flagged %d / %d"
-        % (t_g, t_i, t_r, match_g, match_i, int(sg["seq_flag"].sum()), int(si["seq_flag"].sum())))
+    log("%sgumbel %.3f ms, ipt %.3f ms, pooling %.3f ms per step; match rates %.4f / %.4f; flagged %d / %d"
+        % ("both %.3f ms, " % t_b if t_b else "", t_g, t_i, t_r, match_g, match_i, int(sg["seq_flag"].sum()),
+           int(si["seq_flag"].sum())))
 
     per_row_g = wl.V * esz + AUX_BYTES_PER_ROW + GUMBEL_OUT_BYTES
     per_row_i = wl.V * esz + AUX_BYTES_PER_ROW + IPT_OUT_BYTES
+    per_row_b = wl.V * esz + AUX_BYTES_PER_ROW + 4 + GUMBEL_OUT_BYTES + IPT_OUT_BYTES
     gbs_g = wl.N * per_row_g / (t_g * 1e-3) / 1e9
     gbs_i = wl.N * per_row_i / (t_i * 1e-3) / 1e9
-    if t_g >= t_i:
-        # The Gumbel kernel is bound by vector-ALU issue (Philox), not by HBM: its roofline is the plain
-        # ALU one; its HBM rate is reported next to it because the headline metric asks for it.
-        tops = GUMBEL_ALU_OPS_PER_ENTRY * wl.N * wl.V / (t_g * 1e-3) / 1e12
-        roofline = {"bound": "alu", "achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
-                    "frac": round(tops / VALU_PEAK_TOPS, 4),
-                    "traffic": MEASURED_TRAFFIC.get(("difr_gumbel_score", wl.name)),
-                    "kernel": "difr_gumbel_score", "kernel_ms": round(t_g, 4),
-                    "algorithmic_ops_per_launch": GUMBEL_ALU_OPS_PER_ENTRY * wl.N * wl.V,
-                    "algorithmic_bytes_per_launch": wl.N * per_row_g,
-                    "hbm_achieved_gbs": round(gbs_g, 1), "hbm_frac": round(gbs_g / HBM_PEAK_GBS, 4)}
+
+    def alu_roofline(kernel, ms, ops_per_entry, row_bytes):
+        tops = ops_per_entry * wl.N * wl.V / (ms * 1e-3) / 1e12
+        gbs = wl.N * row_bytes / (ms * 1e-3) / 1e9
+        return {"bound": "alu", "achieved": round(tops, 2), "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
+                "frac": round(tops / VALU_PEAK_TOPS, 4), "traffic": MEASURED_TRAFFIC.get((kernel, wl.name)),
+                "kernel": kernel, "kernel_ms": round(ms, 4),
+                "algorithmic_ops_per_launch": ops_per_entry * wl.N * wl.V,
+                "algorithmic_bytes_per_launch": wl.N * row_bytes,
+                "hbm_achieved_gbs": round(gbs, 1), "hbm_frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+    # Every kernel that regenerates the Gumbel noise is bound by vector-ALU issue (Philox), not by HBM: its
+    # roofline is the plain ALU one; its HBM rate is reported next to it because the headline metric asks for it.
+    if t_b is not None:
+        roofline = alu_roofline("difr_score_both", t_b, GUMBEL_ALU_OPS_PER_ENTRY + IPT_ALU_OPS_PER_ENTRY, per_row_b)
+    elif t_g >= t_i:
+        roofline = alu_roofline("difr_gumbel_score", t_g, GUMBEL_ALU_OPS_PER_ENTRY, per_row_g)
     else:
         roofline = {"bound": "hbm", "achieved": round(gbs_i, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(gbs_i / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC.get(("difr_ipt_score", wl.name)),
@@ -223,9 +261,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "N": wl.N, "V": wl.V, "logits_dtype": "bf16" if esz == 2 else "f32",
                    "temperature": wl.temperature,
-                   "step": "difr_gumbel_score + difr_ipt_score + 2x difr_seq_reduce over the whole batch"},
+                   "step": ("difr_score_both" if args.step == "fused" else "difr_gumbel_score + difr_ipt_score")
+                           + " + 2x difr_seq_reduce over the whole batch"},
         "roofline": roofline,
-        "kernels": {"difr_gumbel_score": {"ms": round(t_g, 4), "tokens_per_s": round(wl.N / (t_g * 1e-3), 1),
+        "kernels": {"difr_score_both": None if t_b is None else
+                    {"ms": round(t_b, 4), "tokens_per_s": round(wl.N / (t_b * 1e-3), 1),
+                     "hbm_gbs": round(wl.N * per_row_b / (t_b * 1e-3) / 1e9, 1),
+                     "frac_of_peak": round(wl.N * per_row_b / (t_b * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
+                    "difr_gumbel_score": {"ms": round(t_g, 4), "tokens_per_s": round(wl.N / (t_g * 1e-3), 1),
                                           "hbm_gbs": round(gbs_g, 1), "frac_of_peak": round(gbs_g / HBM_PEAK_GBS, 4)},
                     "difr_ipt_score": {"ms": round(t_i, 4), "tokens_per_s": round(wl.N / (t_i * 1e-3), 1),
                                        "hbm_gbs": round(gbs_i, 1), "frac_of_peak": round(gbs_i / HBM_PEAK_GBS, 4)},

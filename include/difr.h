@@ -153,6 +153,19 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
                    int32_t *logit_rank, void *hip_stream);
 
 /*
+ * Both estimators in one pass over the logits: difr_gumbel_score with the claims in->claimed and
+ * difr_ipt_score with the claims claimed_ipt (DEVICE [N], or NULL for sampling mode), reading each
+ * row from HBM once instead of twice.  Outputs have the meaning, layout and optionality of the
+ * two single-estimator calls and are bit-identical to theirs; flags_gumbel and flags_ipt are the
+ * two calls' `flags`.  The optional honest-token, log-mass and logit-rank outputs are not offered
+ * here.  [Sec. 6.2 and Sec. 6.3 together: a verifier that does not know which sampler the server
+ * ran, or that feeds both scores to one classifier.]
+ */
+int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
+                    float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                    uint8_t *flags_ipt, void *hip_stream);
+
+/*
  * Three-class token classification and per-token exfiltratable information.  [Sec. 7.1 and the
  * appendix algorithm "per-token risk classification via score and rank".]  Scores are
  * suspiciousness (margin or dist), so the paper's "FSSL >= tau" reads score <= tau:

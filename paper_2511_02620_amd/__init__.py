@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     philox4x32_10,
+    score_both,
     seq_reduce,
     version,
 )

@@ -48,7 +48,7 @@ class _Rows(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -71,6 +71,8 @@ def load_library():
     lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.difr_debug_gumbel_score_unfiltered.restype = C.c_int
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
+    lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
+    lib.difr_score_both.restype = C.c_int
     lib.difr_classify.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_int64, C.c_int64, vp, vp, vp, vp]
     lib.difr_classify.restype = C.c_int
     lib.difr_ipt_score.restype = C.c_int
@@ -203,6 +205,28 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
     if rc:
         raise DifrError(rc, "difr_ipt_score")
     return out
+
+
+def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+               temperatures=None, V=None):
+    """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
+    _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    g = dict(margin=torch.empty(N, **f32), argmax=torch.empty(N, dtype=torch.int32, device=dev),
+             max_score=torch.empty(N, **f32), claimed_score=torch.empty(N, **f32),
+             flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    i = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
+             u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    with torch.cuda.device(dev):
+        rc = lib.difr_score_both(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
+                                 _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]),
+                                 _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]),
+                                 _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_score_both")
+    return g, i
 
 
 def seq_reduce(scores, row_flags, seq_offsets, threshold):

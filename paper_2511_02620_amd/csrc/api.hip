@@ -8,6 +8,8 @@
 #include "../../include/difr.h"
 #include "difr_device.hpp"
 #include "difr_host.hpp"
+#include "gumbel_stream.hpp"
+#include "ipt_stream.hpp"
 
 namespace {
 
@@ -126,6 +128,34 @@ int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t
     if (rc != DIFR_OK) return rc;
     return difr::launch_seq_reduce(scores, row_flags, seq_offsets, N, S, threshold, seq_mean, seq_max, seq_mismatch,
                                    seq_flag, (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
+int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
+                    float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                    uint8_t *flags_ipt, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (aligned) {
+        const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
+        const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+        return difr::launch_score_both(b, claimed_ipt, og, oi, stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+    }
+    // rows that are not 16-byte aligned: the two generic kernels, one after the other
+    if (difr::launch_gumbel_score(b, false, true, margin, argmax, max_score, claimed_score, flags_gumbel, nullptr, stream))
+        return DIFR_ERR_LAUNCH;
+    difr::RowBatch bi = b;
+    bi.claimed = claimed_ipt;
+    return difr::launch_ipt_score(bi, false, dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr,
+                                  stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
 }

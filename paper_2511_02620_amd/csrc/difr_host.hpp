@@ -16,6 +16,11 @@ int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *m
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
                      int32_t *logit_rank, hipStream_t stream);
+struct GumbelOutputs;
+struct IptOutputs;
+// Both estimators in one pass (aligned rows only).
+int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
+                      hipStream_t stream);
 int launch_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t R, int64_t V,
                     const float *log2_admissible, uint8_t *cls, float *bits, hipStream_t stream);
 int launch_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,

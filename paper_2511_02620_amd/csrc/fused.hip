@@ -1,0 +1,110 @@
+// Both estimators in one pass over the row: Token-DiFR (Sec. 6.3) and Token-IPT-DiFR (Sec. 6.2)
+// share the 16-byte vector each lane has just loaded, so the logits are read from HBM once for
+// the two scores.  The two row streams are the ones the single-estimator kernels use
+// (gumbel_stream.hpp, ipt_stream.hpp); outputs are bit-identical to theirs.
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+#include "gumbel_stream.hpp"
+#include "ipt_stream.hpp"
+
+namespace difr {
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void score_both_kernel(RowBatch b, const int32_t *__restrict__ claimed_ipt,
+                                                            GumbelOutputs og, IptOutputs oi)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ float lds_y[kWaves];
+    __shared__ int32_t lds_i[kWaves];
+    __shared__ float lds_L[kWaves];
+    __shared__ int32_t lds_rank[kWaves];
+    __shared__ float lds_f[kWaves];
+    __shared__ double lds_d[kWaves];
+    __shared__ int32_t lds_tok;
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    RowInfo ri_ipt = ri;
+    ri_ipt.claimed = claimed_ipt ? claimed_ipt[row] : -1;
+    if (!ri.seq_ok || !ri.temp_ok) {  // uniform over the workgroup
+        gumbel_row_rejected(ri, row, og);
+        ipt_row_rejected(ri_ipt, row, oi);
+        return;
+    }
+    const int tid = threadIdx.x;
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const int64_t V = b.V;
+
+    GumbelStream<DT, false> g(ri, x_row, V, lds_L);
+    IptStream<DT> s(ri_ipt, x_row, V, false);
+    __syncthreads();
+
+    const int64_t nvec = V / E;                                      // complete vectors
+    const int64_t nvec_total = (V + E - 1) / E;                      // the last vector may be partial
+    const int full_rounds = (int)(nvec / kBlock);                    // rounds of 256 complete vectors
+    const int n_rounds = (int)((nvec_total + kBlock - 1) / kBlock);  // full_rounds or full_rounds + 1
+    const int round_t = s.valid ? (int)((s.t / E) / kBlock) : -1;    // round holding the IPT claim
+
+    // Full rounds [round, r_end): Gumbel gates + IPT accumulation on the same vector.  The loop body is
+    // instantiated once per Gumbel gate mode; a change of mode leaves the inner loop.
+    int round = 0;
+    auto run_rounds = [&](auto mode_tag, int r_end) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        u32x4 q_next = load_round(x_row, round);
+        while (round < r_end) {
+            const u32x4 q = q_next;
+            if (round + 1 < r_end) q_next = load_round(x_row, round + 1);  // keep one vector in flight
+            g.template process<MODE>(q, round, true);
+            s.fast_round(q);
+            ++round;
+            if ((round & 15) == 0) g.pickup();
+            if (g.gate.mode != MODE) break;
+        }
+    };
+    auto run_to = [&](int r_end) {
+        while (round < r_end) {
+            if (g.gate.mode == 0)
+                run_rounds(std::integral_constant<int, 0>(), r_end);
+            else if (g.gate.mode == 1)
+                run_rounds(std::integral_constant<int, 1>(), r_end);
+            else
+                run_rounds(std::integral_constant<int, 2>(), r_end);
+        }
+    };
+    // a round in which the IPT stream must look at indices (it holds the claimed token, or it is ragged)
+    auto careful = [&](int r, bool prefix_open) {
+        u32x4 q = u32x4{0u, 0u, 0u, 0u};
+        if (s.has_vector(r)) q = load_round(x_row, r);
+        g.process_any(q, r, (int64_t)r * kBlock + tid < nvec);
+        s.careful_round(q, r, prefix_open);
+    };
+
+    if (s.valid && round_t < full_rounds) {
+        run_to(round_t);
+        careful(round_t, true);
+        round = round_t + 1;
+        run_to(full_rounds);
+        if (n_rounds > full_rounds) careful(full_rounds, false);
+    } else {
+        run_to(full_rounds);
+        if (s.valid) s.snapshot();  // everything so far lies below the IPT claim
+        if (n_rounds > full_rounds) careful(full_rounds, s.valid);
+    }
+    g.tail();
+    g.finish(row, og, lds_y, lds_i, lds_rank);
+    ipt_finish<DT, true>(b, ri_ipt, row, x_row, s.c, s.m, s.Z, s.P, s.mP, 0, oi, lds_f, lds_d, &lds_tok);
+}
+
+int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
+                      hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    if (b.dtype == 0)
+        score_both_kernel<0><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi);
+    else
+        score_both_kernel<1><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

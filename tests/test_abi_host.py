@@ -82,7 +82,11 @@ def test_argument_validation_needs_no_device(lib):
     def i(r, dist=fake, flags=fake, sigma=0.01, eps=1e-30, log_mass=None):
         return lib.difr_ipt_score(C.byref(r), dist, None, None, None, None, sigma, eps, log_mass, flags, None, None)
 
+    def both(r, margin=fake, argmax=fake, fg=fake, dist=fake, fi=fake):
+        return lib.difr_score_both(C.byref(r), fake, margin, argmax, None, None, fg, dist, None, None, None, fi, None)
+
     assert lib.difr_gumbel_score(None, fake, fake, None, None, fake, None, None) == NULL
+    assert lib.difr_score_both(None, fake, fake, fake, None, None, fake, fake, None, None, None, fake, None) == NULL
     for bad, want in ((rows(N=-1), SHAPE), (rows(V=0), SHAPE), (rows(ld=15), SHAPE), (rows(S=0), SHAPE),
                       (rows(N=1 << 31), SHAPE), (rows(V=1 << 31, ld=1 << 31), SHAPE), (rows(dtype=2), DTYPE),
                       (rows(temperature=0.0), TEMP), (rows(temperature=-1.0), TEMP),
@@ -91,8 +95,13 @@ def test_argument_validation_needs_no_device(lib):
                       (rows(positions=None), NULL), (rows(logits=0x1001), ALIGN), (rows(dtype=1, logits=0x1002), ALIGN)):
         assert g(bad) == want, want
         assert i(bad) == want, want
+        if want != ALIGN:   # unaligned rows are served by the generic kernels
+            assert both(bad) == want, want
     assert g(rows(), margin=None) == NULL and g(rows(), argmax=None) == NULL and g(rows(), flags=None) == NULL
     assert i(rows(), dist=None) == NULL and i(rows(), flags=None) == NULL
+    for kw in ("margin", "argmax", "fg", "dist", "fi"):
+        assert both(rows(), **{kw: None}) == NULL, kw
+    assert both(rows(N=0)) == OK
     assert i(rows(), sigma=0.0, log_mass=fake) == ARG and i(rows(), eps=-1.0, log_mass=fake) == ARG
     # an empty batch is a successful no-op and needs nothing else
     assert g(rows(N=0, logits=None, seeds=None)) == OK and i(rows(N=0)) == OK

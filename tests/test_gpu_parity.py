@@ -395,6 +395,57 @@ def test_filtered_kernel_equals_unfiltered_bit_for_bit(difr, case):
         say(case, "match rate", float((a["flags"] & 1).float().mean()))
 
 
+@pytest.mark.parametrize("dtype,V,ld,offset,case", [
+    (torch.bfloat16, 20504, 20504, 0, "honest"),      # 10 full rounds + a partial one
+    (torch.bfloat16, 20504, 20504, 0, "mutated"),
+    (torch.bfloat16, 20504, 20504, 0, "sampling"),
+    (torch.bfloat16, 20504, 20504, 0, "invalid"),
+    (torch.bfloat16, 20504, 20504, 0, "small_offset"),
+    (torch.bfloat16, 16384, 16384, 0, "mutated"),     # full rounds only
+    (torch.bfloat16, 2051, 2056, 0, "mutated"),       # ragged last vector
+    (torch.bfloat16, 300, 304, 0, "mutated"),         # less than one round
+    (torch.float32, 4100, 4100, 0, "mutated"),
+    (torch.float32, 5003, 5004, 0, "honest"),
+    (torch.bfloat16, 4099, 4099, 1, "mutated"),       # unaligned rows: the two generic kernels
+])
+def test_score_both_equals_the_two_single_calls(difr, dtype, V, ld, offset, case):
+    """difr_score_both shares one read of the row between the two estimators; every output must equal
+    what difr_gumbel_score and difr_ipt_score return for the same claims, bit for bit."""
+    N = 96
+    g = torch.Generator().manual_seed(1234 + V)
+    store = torch.empty(N * ld + offset + 8, dtype=dtype, device=DEV)
+    x = (torch.randn(N, V, generator=g) * 2.5 + (4.0 if case == "small_offset" else 0.0)).to(dtype)
+    logits = store[offset:offset + N * ld].view(N, ld)
+    logits[:, :V] = x.to(DEV)
+    seeds = torch.tensor([0x1234ABCD00000077, 5, -1], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 3).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    T = 0.7
+    temps = torch.linspace(0.4, 1.6, N).to(DEV) if case == "small_offset" else None
+    cg = difr.gumbel_score(logits, T, seeds, sid, pos, V=V, temperatures=temps)["argmax"]
+    ci = difr.ipt_score(logits, T, seeds, sid, pos, V=V, temperatures=temps, want_token=True)["ipt_token"]
+    if case == "mutated":                      # a third of the claims replaced, independently per estimator
+        r1 = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+        r2 = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+        k = torch.arange(N, device=DEV)
+        cg = torch.where(k % 3 == 1, r1, cg)
+        ci = torch.where(k % 3 == 2, r2, ci)
+    elif case == "invalid":
+        cg = cg.clone(); ci = ci.clone()
+        cg[::5] = -1; ci[1::5] = V; cg[2::5] = V + 3
+    elif case == "sampling":
+        cg = ci = None
+    a = difr.gumbel_score(logits, T, seeds, sid, pos, cg, V=V, temperatures=temps)
+    b = difr.ipt_score(logits, T, seeds, sid, pos, ci, V=V, temperatures=temps, want_interval=True)
+    fa, fb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps)
+    torch.cuda.synchronize()
+    _same_outputs(fa, {k: a[k] for k in fa})
+    _same_outputs(fb, {k: b[k] for k in fb})
+    if case == "honest":
+        assert (fa["flags"] & 1).all()
+        assert int((fb["flags"] & 1).sum()) >= N - 2     # u within rounding of an interval end may fall either way
+
+
 @pytest.mark.parametrize("dtype,V,ld,offset", [(torch.bfloat16, 20504, 20504, 0), (torch.bfloat16, 4099, 4099, 1),
                                                (torch.float32, 4100, 4104, 0), (torch.float32, 3001, 3001, 1)])
 def test_logit_rank_and_classifier(difr, dtype, V, ld, offset):
