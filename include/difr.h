@@ -51,6 +51,7 @@
 #ifndef DIFR_H
 #define DIFR_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -164,6 +165,52 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                     uint8_t *flags_ipt, void *hip_stream);
+
+/*
+ * Fused LM head + scoring: both estimators on logits that are never stored.  The verifier's
+ * prefill ends with the product of each position's final hidden state and the LM-head matrix
+ * [appendix algorithm "sampled token verification via prefill": one forward pass yields the
+ * next-token logits of every position]; here that product runs on the matrix cores tile by
+ * tile and each tile of logits is scored in registers, so the 2 V bytes per token of the
+ * stored-logit path are neither written nor read.
+ *
+ *   x[n][v] = sum_k hidden[n][k] * weight[v][k]      (bf16 inputs, fp32 accumulation; the
+ *             logits are used as accumulated, without rounding to a storage type, no bias)
+ *
+ * hidden  DEVICE [N, ldh] bf16 row-major: final hidden state of each token position (after the
+ *         model's last normalisation); weight  DEVICE [V, ldw] bf16 row-major: one row per
+ *         vocabulary entry.  d % 64 == 0, ldh >= d, ldw >= d, ldh % 8 == ldw % 8 == 0, both bases
+ *         16-byte aligned (else DIFR_ERR_SHAPE / DIFR_ERR_ALIGN).  N, V < 2^31.
+ * claimed_gumbel / claimed_ipt  DEVICE [N] or NULL: the claims scored by Token-DiFR and by
+ *         Token-IPT-DiFR.  The remaining fields are those of difr_rows.
+ * Outputs: exactly those of difr_score_both, with the same optionality and flag bits.  Because
+ *         the fp32 accumulation order of a matrix-core product is not the oracle's, logits carry
+ *         an error of a few 1e-6 relative to sum_k |h_k w_k|; scores inherit it.
+ * workspace  DEVICE scratch of at least difr_lmhead_workspace_bytes(N, V, d) bytes, 8-byte
+ *         aligned, owned by the caller, contents irrelevant before and after the call; calls that
+ *         overlap in time need distinct workspaces.  Too small: DIFR_ERR_SHAPE.
+ * Three kernels are enqueued on hip_stream (claim bound, GEMM + scoring, merge); no sync.
+ */
+typedef struct {
+    const void *hidden;
+    const void *weight;
+    int64_t N, V, d, ldh, ldw;
+    float temperature;
+    const float *temperatures;
+    const uint64_t *seeds;
+    int64_t S;
+    const int32_t *seq_ids;
+    const uint32_t *positions;
+    const int32_t *claimed_gumbel;
+    const int32_t *claimed_ipt;
+} difr_lmhead;
+
+/* Host only, no device needed.  0 for N == 0 or arguments difr_lmhead_score would reject. */
+size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d);
+
+int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
+                      uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                      uint8_t *flags_ipt, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Three-class token classification and per-token exfiltratable information.  [Sec. 7.1 and the

@@ -87,6 +87,15 @@ def _load():
                                      f32p, u64p, i32p, u32p, i32p, C.c_double, C.c_double,
                                      f64p, f64p, f64p, f64p, i32p, f64p, f64p, u8p]
     lib.oracle_ipt_score.restype = C.c_int
+    u16p = C.POINTER(C.c_uint16)
+    lib.oracle_lmhead_row.argtypes = [u16p, u16p, C.c_int64, C.c_int64, C.c_int64, f64p]
+    lib.oracle_lmhead_row.restype = None
+    lib.oracle_lmhead_score.argtypes = ([u16p, C.c_int64, u16p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                         C.c_double, C.POINTER(C.c_float), C.POINTER(C.c_uint64), i32p,
+                                         C.POINTER(C.c_uint32), i32p, i32p, C.c_double, C.c_double]
+                                        + [f64p, i32p, f64p, f64p, f64p, u8p]
+                                        + [f64p, f64p, f64p, f64p, i32p, f64p, f64p, u8p, f64p])
+    lib.oracle_lmhead_score.restype = C.c_int
     lib.oracle_logit_rank_row.argtypes = [f64p, C.c_int64, C.c_int64]
     lib.oracle_logit_rank_row.restype = C.c_int32
     lib.oracle_logit_rank.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, i32p, i32p]
@@ -271,6 +280,49 @@ def ipt_score(logits, V, temperature, seeds, seq_ids, positions, claimed=None, t
     if rc:
         raise MemoryError("oracle_ipt_score")
     return out
+
+
+def lmhead_row(h, W):
+    """Logits of one position: h [d] and W [V, d] as bf16 bit patterns (uint16); returns float64 [V]."""
+    h = np.ascontiguousarray(h, dtype=np.uint16)
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    V, d = W.shape
+    assert h.shape == (d,)
+    x = np.zeros(V)
+    _load().oracle_lmhead_row(_ptr(h, C.c_uint16), _ptr(W, C.c_uint16), V, d, d, _ptr(x, C.c_double))
+    return x
+
+
+def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+                 temperatures=None, sigma=0.01, eps=1e-30, want_logits=False):
+    """Both estimators on logits = hidden @ weight.T (bf16 bit patterns, uint16; [N, d] and [V, d]).
+    Returns (gumbel dict, ipt dict[, logits float64 [N, V]])."""
+    hidden = np.ascontiguousarray(hidden, dtype=np.uint16)
+    weight = np.ascontiguousarray(weight, dtype=np.uint16)
+    N, d = hidden.shape
+    V = weight.shape[0]
+    assert weight.shape[1] == d
+    seeds, seq_ids, positions, cg, cgp, temperatures, tp = _aux(N, seeds, seq_ids, positions, claimed_gumbel,
+                                                                temperatures)
+    ci = None if claimed_ipt is None else np.ascontiguousarray(claimed_ipt, dtype=np.int32)
+    cip = None if ci is None else _ptr(ci, C.c_int32)
+    g = dict(margin=np.zeros(N), argmax=np.zeros(N, np.int32), max_score=np.zeros(N), claimed_score=np.zeros(N),
+             gap2=np.zeros(N), flags=np.zeros(N, np.uint8))
+    i = dict(u=np.zeros(N), cdf_lo=np.zeros(N), cdf_hi=np.zeros(N), dist=np.zeros(N),
+             ipt_token=np.zeros(N, np.int32), log_mass=np.zeros(N), edge=np.zeros(N), flags=np.zeros(N, np.uint8))
+    x = np.zeros((N, V)) if want_logits else None
+    rc = _load().oracle_lmhead_score(
+        _ptr(hidden, C.c_uint16), d, _ptr(weight, C.c_uint16), d, N, V, d, float(temperature), tp,
+        _ptr(seeds, C.c_uint64), _ptr(seq_ids, C.c_int32), _ptr(positions, C.c_uint32), cgp, cip,
+        float(sigma), float(eps),
+        _ptr(g["margin"], C.c_double), _ptr(g["argmax"], C.c_int32), _ptr(g["max_score"], C.c_double),
+        _ptr(g["claimed_score"], C.c_double), _ptr(g["gap2"], C.c_double), _ptr(g["flags"], C.c_uint8),
+        _ptr(i["u"], C.c_double), _ptr(i["cdf_lo"], C.c_double), _ptr(i["cdf_hi"], C.c_double),
+        _ptr(i["dist"], C.c_double), _ptr(i["ipt_token"], C.c_int32), _ptr(i["log_mass"], C.c_double),
+        _ptr(i["edge"], C.c_double), _ptr(i["flags"], C.c_uint8), None if x is None else _ptr(x, C.c_double))
+    if rc:
+        raise MemoryError("oracle_lmhead_score")
+    return (g, i, x) if want_logits else (g, i)
 
 
 def logit_rank_row(x, claimed) -> int:

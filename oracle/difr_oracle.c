@@ -23,6 +23,8 @@
  *                                           for the Gumbel likelihood estimator
  *   - regenerate-and-compare per position . Sec. 5.1 and the appendix algorithm
  *                                           "verification via prefill"
+ *   - logits from the final hidden state .. the Prefill step of the appendix
+ *                                           algorithm "verification via prefill"
  *   - pooling and flagging ................ Sec. 5.2 (threshold rule), Sec. 6.4,
  *                                           appendix "Response to detecting
  *                                           exfiltration attempts" (score, pool, flag)
@@ -51,7 +53,9 @@
  * of the k -> u -> g map and its moments; brute force with exact rationals and
  * multi-precision on tiny vocabularies; library softmax / cumsum / searchsorted;
  * chi-square of sample frequencies; Gumbel max-stability; scipy / mpmath normal
- * CDF.  No function here is "parity unpinned".
+ * CDF; the hidden-state-to-logits step against a library matrix product and
+ * against the stored-logit entry points on inputs whose products are exact.
+ * No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -371,6 +375,64 @@ int oracle_ipt_score(const void *logits, int dtype, int64_t N, int64_t V, int64_
             int64_t t = claimed ? (int64_t)claimed[n] : -1;
             oracle_ipt_row(x, V, T, seeds[s], (uint32_t)s, positions[n], t, sigma, eps, &u[n], &cdf_lo[n],
                            &cdf_hi[n], &dist[n], &tok[n], &log_mass[n], &edge[n], &flags[n]);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Next-token logits of one position from its final hidden state: the last    */
+/* step of the verifier's prefill (appendix algorithm "sampled token          */
+/* verification via prefill": one forward pass yields the logits of every     */
+/* position).  x_v = sum_k h_k * W[v,k], k ascending, every product and sum    */
+/* in double from the exact values of the stored bf16 numbers.  No bias, no    */
+/* rounding of x_v to a storage type.                                          */
+/* ------------------------------------------------------------------------- */
+void oracle_lmhead_row(const uint16_t *h, const uint16_t *W, int64_t V, int64_t d, int64_t ldw, double *x)
+{
+    for (int64_t v = 0; v < V; ++v) {
+        const uint16_t *w = W + (size_t)v * (size_t)ldw;
+        double acc = 0.0;
+        for (int64_t k = 0; k < d; ++k) acc += decode_bf16(h[k]) * decode_bf16(w[k]);
+        x[v] = acc;
+    }
+}
+
+/* Both estimators on logits that are never stored: for each row n the logits  */
+/* come from oracle_lmhead_row(hidden[n], weight), then Token-DiFR with the     */
+/* claims claimed_gumbel and Token-IPT-DiFR with the claims claimed_ipt (either */
+/* may be NULL = sampling).  Outputs as in the two batch entry points above;    */
+/* x_out, if given, receives the logits ([N, V] doubles).                       */
+int oracle_lmhead_score(const uint16_t *hidden, int64_t ldh, const uint16_t *weight, int64_t ldw, int64_t N,
+                        int64_t V, int64_t d, double temperature, const float *temperatures,
+                        const uint64_t *seeds, const int32_t *seq_ids, const uint32_t *positions,
+                        const int32_t *claimed_gumbel, const int32_t *claimed_ipt, double sigma, double eps,
+                        double *margin, int32_t *argmax, double *max_score, double *claimed_score, double *gap2,
+                        uint8_t *flags_gumbel, double *u, double *cdf_lo, double *cdf_hi, double *dist,
+                        int32_t *tok, double *log_mass, double *edge, uint8_t *flags_ipt, double *x_out)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            oracle_lmhead_row(hidden + (size_t)n * (size_t)ldh, weight, V, d, ldw, x);
+            if (x_out) memcpy(x_out + (size_t)n * (size_t)V, x, (size_t)V * sizeof(double));
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t s = seq_ids[n];
+            int64_t tg = claimed_gumbel ? (int64_t)claimed_gumbel[n] : -1;
+            int64_t ti = claimed_ipt ? (int64_t)claimed_ipt[n] : -1;
+            oracle_gumbel_row(x, V, T, seeds[s], (uint32_t)s, positions[n], tg, &margin[n], &argmax[n],
+                              &max_score[n], &claimed_score[n], &gap2[n], &flags_gumbel[n], NULL);
+            oracle_ipt_row(x, V, T, seeds[s], (uint32_t)s, positions[n], ti, sigma, eps, &u[n], &cdf_lo[n],
+                           &cdf_hi[n], &dist[n], &tok[n], &log_mass[n], &edge[n], &flags_ipt[n]);
         }
         free(x);
     }

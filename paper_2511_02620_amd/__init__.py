@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     gumbel_score,
     ipt_score,
     lib_path,
+    lmhead_score,
+    lmhead_workspace_bytes,
     load_library,
     philox4x32_10,
     score_both,

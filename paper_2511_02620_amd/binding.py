@@ -48,7 +48,27 @@ class _Rows(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+class _LmHead(C.Structure):
+    _fields_ = [
+        ("hidden", C.c_void_p),
+        ("weight", C.c_void_p),
+        ("N", C.c_int64),
+        ("V", C.c_int64),
+        ("d", C.c_int64),
+        ("ldh", C.c_int64),
+        ("ldw", C.c_int64),
+        ("temperature", C.c_float),
+        ("temperatures", C.c_void_p),
+        ("seeds", C.c_void_p),
+        ("S", C.c_int64),
+        ("seq_ids", C.c_void_p),
+        ("positions", C.c_void_p),
+        ("claimed_gumbel", C.c_void_p),
+        ("claimed_ipt", C.c_void_p),
+    ]
+
+
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -73,6 +93,10 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
     lib.difr_score_both.restype = C.c_int
+    lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
+    lib.difr_lmhead_workspace_bytes.restype = C.c_size_t
+    lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 11 + [C.c_size_t, vp]
+    lib.difr_lmhead_score.restype = C.c_int
     lib.difr_classify.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_int64, C.c_int64, vp, vp, vp, vp]
     lib.difr_classify.restype = C.c_int
     lib.difr_ipt_score.restype = C.c_int
@@ -226,6 +250,62 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
                                  _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_score_both")
+    return g, i
+
+
+def lmhead_workspace_bytes(N, V, d) -> int:
+    return int(load_library().difr_lmhead_workspace_bytes(int(N), int(V), int(d)))
+
+
+def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+                 temperatures=None, workspace=None):
+    """difr_lmhead_score: both estimators on logits = hidden @ weight.T that are never stored.
+    hidden [N, d], weight [V, d] bf16 on the GPU (unit column stride).  Returns (gumbel dict, ipt dict)."""
+    lib = load_library()
+    for name, t in (("hidden", hidden), ("weight", weight)):
+        if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("%s must be a 2-D bfloat16 GPU tensor with unit column stride" % name)
+    dev = hidden.device
+    N, d = hidden.shape
+    V = weight.shape[0]
+    if weight.shape[1] != d or weight.device != dev:
+        raise ValueError("weight must be [V, d] on the device of hidden")
+    _check(seq_ids, torch.int32, N, "seq_ids", dev)
+    _check(positions, torch.int32, N, "positions", dev)
+    _check(claimed_gumbel, torch.int32, N, "claimed_gumbel", dev)
+    _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
+    _check(temperatures, torch.float32, N, "temperatures", dev)
+    if seeds.device != dev or seeds.dtype != torch.int64 or seeds.dim() != 1 or not seeds.is_contiguous():
+        raise ValueError("seeds must be a contiguous 1-D int64 GPU tensor (uint64 bit patterns)")
+    need = lmhead_workspace_bytes(N, V, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    elif workspace.device != dev or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 tensor on the device of hidden")
+    r = _LmHead()
+    r.hidden, r.weight = hidden.data_ptr(), weight.data_ptr()
+    r.N, r.V, r.d = N, V, d
+    r.ldh = hidden.stride(0) if N > 1 else d
+    r.ldw = weight.stride(0) if V > 1 else d
+    r.temperature = float(temperature)
+    r.temperatures = None if temperatures is None else temperatures.data_ptr()
+    r.seeds, r.S = seeds.data_ptr(), seeds.shape[0]
+    r.seq_ids, r.positions = seq_ids.data_ptr(), positions.data_ptr()
+    r.claimed_gumbel = None if claimed_gumbel is None else claimed_gumbel.data_ptr()
+    r.claimed_ipt = None if claimed_ipt is None else claimed_ipt.data_ptr()
+    f32 = dict(dtype=torch.float32, device=dev)
+    g = dict(margin=torch.empty(N, **f32), argmax=torch.empty(N, dtype=torch.int32, device=dev),
+             max_score=torch.empty(N, **f32), claimed_score=torch.empty(N, **f32),
+             flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    i = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
+             u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    with torch.cuda.device(dev):
+        rc = lib.difr_lmhead_score(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
+                                   _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]), _ptr(i["cdf_lo"]),
+                                   _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]), _ptr(workspace),
+                                   workspace.numel(), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_lmhead_score")
     return g, i
 
 

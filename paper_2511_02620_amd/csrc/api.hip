@@ -10,6 +10,7 @@
 #include "difr_host.hpp"
 #include "gumbel_stream.hpp"
 #include "ipt_stream.hpp"
+#include "lmhead.hpp"
 
 namespace {
 
@@ -63,9 +64,65 @@ int validate_rows(const difr_rows *in, difr::RowBatch *b, bool *aligned)
     return DIFR_OK;
 }
 
+int validate_lmhead(const difr_lmhead *in, difr::LmHeadBatch *b)
+{
+    if (!in) return DIFR_ERR_NULL;
+    if (in->N < 0 || in->V < 0 || in->d < 0 || in->ldh < 0 || in->ldw < 0 || in->S < 0) return DIFR_ERR_SHAPE;
+    if (in->N >= (int64_t)1 << 31 || in->V >= (int64_t)1 << 31 || in->d >= (int64_t)1 << 31) return DIFR_ERR_SHAPE;
+    if (in->N > 0) {
+        if (in->V == 0 || in->d == 0 || in->d % difr::kLmTileK || in->ldh < in->d || in->ldw < in->d || in->ldh % 8 ||
+            in->ldw % 8 || in->S < 1)
+            return DIFR_ERR_SHAPE;
+        if (!in->hidden || !in->weight || !in->seeds || !in->seq_ids || !in->positions) return DIFR_ERR_NULL;
+        if (!in->temperatures && !(in->temperature > 0.0f && isfinite(in->temperature))) return DIFR_ERR_TEMPERATURE;
+        if ((uintptr_t)in->hidden % 16u || (uintptr_t)in->weight % 16u) return DIFR_ERR_ALIGN;
+    }
+    b->hidden = (const uint16_t *)in->hidden;
+    b->weight = (const uint16_t *)in->weight;
+    b->N = in->N;
+    b->V = in->V;
+    b->d = in->d;
+    b->ldh = in->ldh;
+    b->ldw = in->ldw;
+    b->temperature = in->temperature;
+    b->temperatures = in->temperatures;
+    b->seeds = in->seeds;
+    b->S = in->S;
+    b->seq_ids = in->seq_ids;
+    b->positions = in->positions;
+    b->claimed_gumbel = in->claimed_gumbel;
+    b->claimed_ipt = in->claimed_ipt;
+    return DIFR_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d)
+{
+    if (N <= 0 || V <= 0 || d <= 0 || N >= (int64_t)1 << 31 || V >= (int64_t)1 << 31) return 0;
+    return difr::lmhead_workspace_bytes(N, difr::lmhead_plan(N, V).splits);
+}
+
+int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
+                      uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                      uint8_t *flags_ipt, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    difr::LmHeadBatch b;
+    int rc = validate_lmhead(in, &b);
+    if (rc != DIFR_OK) return rc;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt || !workspace) return DIFR_ERR_NULL;
+    const difr::LmHeadPlan plan = difr::lmhead_plan(b.N, b.V);
+    if ((uintptr_t)workspace % 8u) return DIFR_ERR_ALIGN;
+    if (workspace_bytes < difr::lmhead_workspace_bytes(b.N, plan.splits)) return DIFR_ERR_SHAPE;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    const difr::LmHeadWorkspace ws = difr::lmhead_carve(workspace, b.N, plan.splits);
+    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+    return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
 
 int difr_gumbel_score(const difr_rows *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
                       uint8_t *flags, int32_t *logit_rank, void *hip_stream)

@@ -21,6 +21,12 @@ struct IptOutputs;
 // Both estimators in one pass (aligned rows only).
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
                       hipStream_t stream);
+struct LmHeadBatch;
+struct LmHeadWorkspace;
+struct LmHeadPlan;
+// Fused LM head + both estimators: claim bound, GEMM + scoring, merge.
+int launch_lmhead_score(const LmHeadBatch &b, const LmHeadWorkspace &ws, const LmHeadPlan &plan, const GumbelOutputs &og,
+                        const IptOutputs &oi, hipStream_t stream);
 int launch_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t R, int64_t V,
                     const float *log2_admissible, uint8_t *cls, float *bits, hipStream_t stream);
 int launch_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t *seq_offsets, int64_t N,

@@ -1,0 +1,522 @@
+// Fused LM head + scoring: the logits x[n][v] = <hidden[n], weight[v]> (the last step of the
+// verifier's prefill; appendix algorithm "sampled token verification via prefill") are produced
+// tile by tile on the matrix cores and scored in registers by both estimators (Token-DiFR,
+// Sec. 6.3; Token-IPT-DiFR, Sec. 6.2) without ever being written to memory.
+//
+// Work split: a workgroup owns 256 token rows and a contiguous range of 256-entry vocabulary
+// tiles.  Per tile it runs a bf16 MFMA GEMM over the hidden dimension (W tile as the A operand,
+// H tile as the B operand, both staged through LDS in 64-deep slabs, double buffered), so that in
+// the 32x32 accumulator blocks a lane holds 16 vocabulary entries of ONE token, four consecutive
+// entries per register group: exactly the granularity of one Philox4x32 block.  The epilogue
+// then updates, per lane and token, the running best perturbed score and the online softmax sums,
+// and the next tile starts.  Partial results of the vocabulary ranges are merged by a last kernel.
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+#include "gumbel_stream.hpp"
+#include "ipt_stream.hpp"
+#include "lmhead.hpp"
+
+namespace difr {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct TokInfo {
+    PhiloxKey key;
+    uint32_t pos, seq;
+    float inv_T;
+    int32_t tg, ti;  // claims of the two estimators, -1 if absent or out of range
+    bool ok;         // sequence id and temperature usable
+    bool seq_ok;
+};
+
+__device__ __forceinline__ TokInfo load_tok(const LmHeadBatch &b, int64_t n)
+{
+    TokInfo t;
+    const int32_t s = b.seq_ids[n];
+    t.seq_ok = (s >= 0 && (int64_t)s < b.S);
+    const uint64_t seed = t.seq_ok ? b.seeds[s] : 0ull;
+    t.key.k0 = (uint32_t)seed;
+    t.key.k1 = (uint32_t)(seed >> 32);
+    t.seq = (uint32_t)s;
+    t.pos = b.positions[n];
+    const float T = b.temperatures ? b.temperatures[n] : b.temperature;
+    t.ok = t.seq_ok && (T > 0.0f) && (T < __builtin_inff());
+    t.inv_T = t.ok ? 1.0f / T : 1.0f;
+    const int32_t tg = b.claimed_gumbel ? b.claimed_gumbel[n] : -1;
+    const int32_t ti = b.claimed_ipt ? b.claimed_ipt[n] : -1;
+    t.tg = (tg >= 0 && (int64_t)tg < b.V) ? tg : -1;
+    t.ti = (ti >= 0 && (int64_t)ti < b.V) ? ti : -1;
+    return t;
+}
+
+__device__ __forceinline__ uint32_t noise_word_of(const TokInfo &t, uint32_t stream, int32_t v)
+{
+    uint32_t r[4];
+    noise_block(t.key, t.pos, t.seq, stream, (uint32_t)v >> 2, r);
+    return (v & 3) == 0 ? r[0] : (v & 3) == 1 ? r[1] : (v & 3) == 2 ? r[2] : r[3];
+}
+
+// ---------------------------------------------------------------------------------
+// Before the GEMM: a lower bound on each row's best perturbed score, from the Token-DiFR claim.
+// For an honest claim the claimed token IS the row maximum, so almost every other entry can be
+// ruled out by its noise word alone.  The claimed logit is a plain fp32 dot product here; it
+// differs from the matrix-core value of the same logit by accumulation order only, and the bound
+// is lowered by a rigorous estimate of that difference, so it never exceeds the true maximum.
+// One wave per token.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void lmhead_prepare_kernel(LmHeadBatch b, LmHeadWorkspace ws)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t n = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
+    if (n >= b.N) return;  // uniform per wave
+    const TokInfo t = load_tok(b, n);
+    float L0 = -__builtin_inff();
+    if (t.ok && t.tg >= 0) {
+        const uint16_t *h = b.hidden + n * b.ldh;
+        const uint16_t *w = b.weight + (int64_t)t.tg * b.ldw;
+        float dot = 0.0f, mag = 0.0f;
+        for (int64_t c = lane; c < b.d / 8; c += 64) {
+            const uint4 hv = *reinterpret_cast<const uint4 *>(h + 8 * c);
+            const uint4 wv = *reinterpret_cast<const uint4 *>(w + 8 * c);
+            const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w}, ww[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float h0 = __uint_as_float(hw[j] << 16), h1 = __uint_as_float(hw[j] & 0xFFFF0000u);
+                const float w0 = __uint_as_float(ww[j] << 16), w1 = __uint_as_float(ww[j] & 0xFFFF0000u);
+                dot = __fmaf_rn(h0, w0, dot);
+                dot = __fmaf_rn(h1, w1, dot);
+                mag = __fmaf_rn(fabsf(h0), fabsf(w0), mag);
+                mag = __fmaf_rn(fabsf(h1), fabsf(w1), mag);
+            }
+        }
+        dot = wave_sum(dot);
+        mag = wave_sum(mag);
+        const float y = perturbed_score(dot, t.inv_T, noise_word_of(t, kStreamGumbel, t.tg));
+        // any two fp32 summation orders of d products differ by at most ~2 d 2^-24 sum|h w|; twice that here
+        const float slack = 1e-3f + 1e-5f * fabsf(y) + t.inv_T * mag * (float)b.d * 0x1p-22f;
+        L0 = y - slack;
+        if (!(L0 == L0) || !(L0 < __builtin_inff())) L0 = -__builtin_inff();
+    }
+    if (lane == 0) {
+        ws.L0[n] = L0;
+        ws.x_claim_gumbel[n] = __builtin_nanf("");
+        ws.x_claim_ipt[n] = __builtin_nanf("");
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Per-lane, per-token running state of the epilogue.
+// ---------------------------------------------------------------------------------
+struct Slot {
+    float best_y;
+    int32_t best_v;
+    float L;      // lower bound on the row's best score: max(bound from the claim, best seen by this lane)
+    float m;      // largest logit seen by this lane for this token
+    double Z, P;  // sum of 2^((x - m) c) over all entries seen / over those below the IPT claim
+};
+
+// Noise gate: an entry with noise word r < rgate cannot reach L whatever its logit (all logits seen
+// are <= m).  g(r) <= c  <=>  u(r) <= exp(-exp(-c)); the threshold is lowered by 64 cells of the 23-bit
+// uniform, far more than the fp32 error of the two exponentials.  Anything doubtful gives 0 (no skipping).
+__device__ __forceinline__ uint32_t noise_gate(float L, float cap)
+{
+    const float c = L - cap - (0.01f + 1e-5f * (fabsf(L) + fabsf(cap)));
+    const float t = fast_exp2(-c * kLog2e);
+    const float kf = fast_exp2(-t * kLog2e) * 0x1p23f;
+    const uint32_t kg = (kf > 64.0f) ? (uint32_t)kf - 64u : 0u;
+    return kg << 9;
+}
+
+struct BlockCtx {
+    const TokInfo &t;
+    float c;       // log2(e) / T
+    float neg_mc;  // -(m c)
+    float Lgate;   // L minus slack
+    uint32_t rgate;
+    bool live;     // the lane's token row exists (n < N)
+};
+
+__device__ __forceinline__ void refresh_gates(const Slot &s, BlockCtx &k)
+{
+    k.Lgate = s.L - (0.01f + 1e-5f * fabsf(s.L));
+    k.rgate = noise_gate(s.L, s.m * k.t.inv_T);
+}
+
+// Score one 32x32 accumulator block: this lane's 16 entries are the logits of ONE token at
+// vocabulary rows v(r) = vlane + 8 (r / 4) + (r % 4).
+__device__ __forceinline__ void score_block(const f32x16 &acc, Slot &s, BlockCtx &k, int32_t vlane, int32_t V,
+                                            bool ragged, int64_t n, const LmHeadWorkspace &ws)
+{
+    const float ninf = -__builtin_inff();
+    float x[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) x[r] = acc[r];
+    if (ragged) {  // uniform: the tile runs past the end of the vocabulary
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (vlane + 8 * (r >> 2) + (r & 3) >= V) x[r] = ninf;
+    }
+    // ---- Token-IPT-DiFR: online softmax sums ----
+    float bm = max3_raw(x[0], x[1], x[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) bm = max3_raw(bm, x[r], x[r + 1]);
+    bm = fmaxf(bm, x[15]);
+    if (__builtin_amdgcn_ballot_w64(bm > s.m) != 0ull) {
+        asm volatile("" ::: "memory");  // keep this a real, rarely taken branch
+        if (bm > s.m) {
+            const double f = (s.m > ninf) ? (double)fast_exp2((s.m - bm) * k.c) : 0.0;
+            s.Z *= f;
+            s.P *= f;
+            s.m = bm;
+            k.neg_mc = -(bm * k.c);
+            refresh_gates(s, k);  // the logit cap of the noise gate has moved
+        }
+    }
+    float e[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) e[r] = fast_exp2(__fmaf_rn(x[r], k.c, k.neg_mc));
+    if (ragged) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            if (vlane + 8 * (r >> 2) + (r & 3) >= V) e[r] = 0.0f;
+    }
+    const float bs = tree_sum<16>(e);
+    float ps = (vlane + 27 < k.t.ti) ? bs : 0.0f;  // all 16 rows lie below the IPT claim
+    // a claimed token inside this lane's rows: exact prefix, and keep the claimed logits (rare)
+    const bool near = (uint32_t)(k.t.ti - vlane) < 28u || (uint32_t)(k.t.tg - vlane) < 28u;
+    if (__builtin_amdgcn_ballot_w64(near) != 0ull) {
+        asm volatile("" ::: "memory");
+        if (near) {
+            const bool straddle = (uint32_t)(k.t.ti - vlane) < 28u;
+            if (straddle) ps = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int32_t v = vlane + 8 * (r >> 2) + (r & 3);
+                if (straddle && v < k.t.ti) ps += e[r];
+                if (k.live && v == k.t.ti) ws.x_claim_ipt[n] = x[r];
+                if (k.live && v == k.t.tg) ws.x_claim_gumbel[n] = x[r];
+            }
+        }
+    }
+    s.Z += (double)bs;
+    s.P += (double)ps;
+
+    // ---- Token-DiFR: noise for all 16 entries, exact score only where the gates allow ----
+    uint32_t rw[16];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) noise_block(k.t.key, k.t.pos, k.t.seq, kStreamGumbel, (uint32_t)(vlane + 8 * g) >> 2, rw + 4 * g);
+    uint32_t rmax = rw[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) rmax = max(rmax, rw[r]);
+    if (__builtin_amdgcn_ballot_w64(rmax >= k.rgate) != 0ull) {
+        asm volatile("" ::: "memory");
+        if (rmax >= k.rgate) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int32_t v = vlane + 8 * (r >> 2) + (r & 3);
+                if (rw[r] >= k.rgate && !(ragged && v >= V) &&
+                    !(__fmaf_rn(x[r], k.t.inv_T, gumbel_upper_bound(rw[r])) < k.Lgate)) {
+                    const float y = perturbed_score(x[r], k.t.inv_T, rw[r]);
+                    if (y > s.best_y || (y == s.best_y && v < s.best_v)) {
+                        s.best_y = y;
+                        s.best_v = v;
+                    }
+                }
+            }
+            if (s.best_y > s.L) {
+                s.L = s.best_y;
+                refresh_gates(s, k);
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ void merge_softmax(float &m, double &Z, double &P, float om, double oZ, double oP, float c)
+{
+    const float ninf = -__builtin_inff();
+    const float M = fmaxf(m, om);
+    const double f = (m > ninf) ? (double)fast_exp2((m - M) * c) : 0.0;
+    const double of = (om > ninf) ? (double)fast_exp2((om - M) * c) : 0.0;
+    Z = Z * f + oZ * of;
+    P = P * f + oP * of;
+    m = M;
+}
+
+// ---------------------------------------------------------------------------------
+// The GEMM + epilogue kernel.  256 threads = 4 waves in a 2 (vocabulary) x 2 (tokens) arrangement;
+// each wave owns a 128 x 128 sub-tile = 4 x 4 accumulator blocks of 32 x 32.
+// LDS: two stages of [256 rows][64 k] bf16 for each operand; the eight 16-byte chunks of a row are
+// permuted by (row / 2) % 8 so that both the 16-byte slab writes and the fragment reads of 16
+// consecutive rows spread over all banks.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, LmHeadWorkspace ws, LmHeadPlan plan)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_h[2][kLmTileT * kLmTileK];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wv = wave >> 1, wt = wave & 1;  // vocabulary half, token half
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    // Workgroup -> (token block, vocabulary range).  Consecutive workgroup ids go to different XCDs;
+    // remap so that each XCD works on a compact set of token blocks across all ranges and its L2
+    // sees each weight tile and each hidden-state tile from several workgroups at about the same time.
+    const int G = plan.n_tb * plan.splits;
+    int q = blockIdx.x;
+    if (G % 8 == 0) q = (q % 8) * (G / 8) + q / 8;
+    const int tb = q / plan.splits, sp = q % plan.splits;
+    const int vt0 = (int)((int64_t)sp * plan.n_vt / plan.splits), vt1 = (int)((int64_t)(sp + 1) * plan.n_vt / plan.splits);
+    const int64_t n0 = (int64_t)tb * kLmTileT;
+    const int32_t V = (int32_t)b.V;
+    const int nk = (int)(b.d / kLmTileK);
+
+    // slab copy: thread -> chunk (tid % 8) of rows (tid / 8) + 32 p
+    const int crow = tid >> 3, cchunk = tid & 7;
+    const int lds_copy_off = crow * kLmTileK + ((cchunk ^ ((crow >> 1) & 7)) * 8);
+    const uint16_t *hsrc[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t gn = n0 + crow + 32 * p;
+        if (gn > b.N - 1) gn = b.N - 1;
+        hsrc[p] = b.hidden + gn * b.ldh + cchunk * 8;
+    }
+    u32x4 gw[8], gh[8];
+    auto load_slab = [&](int64_t v0, int k0) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            int64_t gv = v0 + crow + 32 * p;
+            if (gv > b.V - 1) gv = b.V - 1;
+            gw[p] = *reinterpret_cast<const u32x4 *>(b.weight + gv * b.ldw + k0 + cchunk * 8);
+            gh[p] = *reinterpret_cast<const u32x4 *>(hsrc[p] + k0);
+        }
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            *reinterpret_cast<u32x4 *>(&lds_w[buf][lds_copy_off + 32 * p * kLmTileK]) = gw[p];
+            *reinterpret_cast<u32x4 *>(&lds_h[buf][lds_copy_off + 32 * p * kLmTileK]) = gh[p];
+        }
+    };
+
+    // fragment reads: lane -> row l32 of a 32-row block, k chunk 2 kk + lh
+    const int sw = (l32 >> 1) & 7;
+    const int a_row_off = (wv * 128 + l32) * kLmTileK;
+    const int b_row_off = (wt * 128 + l32) * kLmTileK;
+
+    // per-lane state of the lane's four tokens
+    Slot slot[4];
+    int64_t tok_n[4];
+    bool tok_live[4];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        int64_t n = n0 + wt * 128 + jb * 32 + l32;
+        tok_live[jb] = n < b.N;
+        if (!tok_live[jb]) n = b.N - 1;
+        tok_n[jb] = n;
+        slot[jb].best_y = -__builtin_inff();
+        slot[jb].best_v = 0x7FFFFFFF;
+        slot[jb].L = ws.L0[n];
+        slot[jb].m = -__builtin_inff();
+        slot[jb].Z = 0.0;
+        slot[jb].P = 0.0;
+    }
+
+    for (int vt = vt0; vt < vt1; ++vt) {
+        const int64_t v0 = (int64_t)vt * kLmTileV;
+        f32x16 acc[4][4];
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ib][jb][r] = 0.0f;
+
+        load_slab(v0, 0);
+        store_slab(0);
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int buf = kt & 1;
+            if (kt + 1 < nk) load_slab(v0, (kt + 1) * kLmTileK);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int coff = ((2 * kk + lh) ^ sw) * 8;
+                bf16x8 af[4], bf[4];
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib)
+                    af[ib] = *reinterpret_cast<const bf16x8 *>(&lds_w[buf][a_row_off + ib * 32 * kLmTileK + coff]);
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb)
+                    bf[jb] = *reinterpret_cast<const bf16x8 *>(&lds_h[buf][b_row_off + jb * 32 * kLmTileK + coff]);
+#pragma unroll
+                for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+                        acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ib], bf[jb], acc[ib][jb], 0, 0, 0);
+            }
+            if (kt + 1 < nk) store_slab(buf ^ 1);
+            __syncthreads();
+        }
+
+        // ---- epilogue: score the 256 x 256 logits of this tile ----
+        const bool ragged = v0 + kLmTileV > b.V;
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const TokInfo t = load_tok(b, tok_n[jb]);
+            BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_live[jb]};
+            k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
+            refresh_gates(slot[jb], k);
+#pragma unroll
+            for (int ib = 0; ib < 4; ++ib) {
+                const int32_t vlane = (int32_t)v0 + wv * 128 + ib * 32 + 4 * lh;
+                score_block(acc[ib][jb], slot[jb], k, vlane, V, ragged, tok_n[jb], ws);
+            }
+        }
+    }
+
+    // ---- merge the four lanes/waves that share a token and write this range's partial ----
+    float *ex_y = reinterpret_cast<float *>(&lds_w[0][0]);  // [2][128] each, in the (now idle) tile memory
+    int32_t *ex_v = reinterpret_cast<int32_t *>(ex_y + 256);
+    float *ex_m = reinterpret_cast<float *>(ex_v + 256);
+    double *ex_Z = reinterpret_cast<double *>(ex_m + 256);
+    double *ex_P = ex_Z + 256;
+    float tok_c[4];
+#pragma unroll
+    for (int jb = 0; jb < 4; ++jb) {
+        Slot &s = slot[jb];
+        tok_c[jb] = load_tok(b, tok_n[jb]).inv_T * kLog2e;
+        const float oy = __shfl_xor(s.best_y, 32, 64);
+        const int32_t ov = __shfl_xor(s.best_v, 32, 64);
+        const float om = __shfl_xor(s.m, 32, 64);
+        const double oZ = __shfl_xor(s.Z, 32, 64), oP = __shfl_xor(s.P, 32, 64);
+        if (lh == 0) {  // rows 0-3 (mod 8) first, then rows 4-7: a fixed order
+            argmax_combine(s.best_y, s.best_v, oy, ov);
+            merge_softmax(s.m, s.Z, s.P, om, oZ, oP, tok_c[jb]);
+        }
+    }
+    __syncthreads();
+    if (wv == 1 && lh == 0) {
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            const int i = wt * 128 + jb * 32 + l32;
+            ex_y[i] = slot[jb].best_y;
+            ex_v[i] = slot[jb].best_v;
+            ex_m[i] = slot[jb].m;
+            ex_Z[i] = slot[jb].Z;
+            ex_P[i] = slot[jb].P;
+        }
+    }
+    __syncthreads();
+    if (wv == 0 && lh == 0) {
+#pragma unroll
+        for (int jb = 0; jb < 4; ++jb) {
+            if (!tok_live[jb]) continue;
+            Slot &s = slot[jb];
+            const int i = wt * 128 + jb * 32 + l32;
+            argmax_combine(s.best_y, s.best_v, ex_y[i], ex_v[i]);
+            merge_softmax(s.m, s.Z, s.P, ex_m[i], ex_Z[i], ex_P[i], tok_c[jb]);
+            const int64_t o = (int64_t)sp * b.N + tok_n[jb];
+            ws.best_y[o] = s.best_y;
+            ws.best_v[o] = s.best_v;
+            ws.m[o] = s.m;
+            ws.Z[o] = s.Z;
+            ws.P[o] = s.P;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Merge the vocabulary ranges of each token (ascending) and form every output.  One thread per token.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, LmHeadWorkspace ws, int splits,
+                                                                 GumbelOutputs og, IptOutputs oi)
+{
+    const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (n >= b.N) return;
+    const float nan = __builtin_nanf("");
+    const float ninf = -__builtin_inff();
+    const TokInfo t = load_tok(b, n);
+    const int32_t tg_raw = b.claimed_gumbel ? b.claimed_gumbel[n] : -1;
+    (void)tg_raw;
+    if (!t.ok) {
+        const uint8_t f = (uint8_t)(t.seq_ok ? kFlagNonfinite : kFlagInvalidClaim);
+        og.margin[n] = nan;
+        og.argmax[n] = -1;
+        if (og.max_score) og.max_score[n] = nan;
+        if (og.claimed_score) og.claimed_score[n] = nan;
+        og.flags[n] = f;
+        oi.dist[n] = nan;
+        if (oi.cdf_lo) oi.cdf_lo[n] = nan;
+        if (oi.cdf_hi) oi.cdf_hi[n] = nan;
+        if (oi.u) oi.u[n] = nan;
+        oi.flags[n] = f;
+        return;
+    }
+    const float c = t.inv_T * kLog2e;
+    float best_y = ninf, m = ninf;
+    int32_t best_v = 0x7FFFFFFF;
+    double Z = 0.0, P = 0.0;
+    for (int sp = 0; sp < splits; ++sp) {
+        const int64_t o = (int64_t)sp * b.N + n;
+        argmax_combine(best_y, best_v, ws.best_y[o], ws.best_v[o]);
+        merge_softmax(m, Z, P, ws.m[o], ws.Z[o], ws.P[o], c);
+    }
+    if (best_v == 0x7FFFFFFF) best_v = 0;
+    const bool ipt_bad = !(Z > 0.0) || !(Z < (double)__builtin_inff()) || !(m < __builtin_inff()) || !(m > ninf);
+    const bool nonfinite = !(Z == Z) || !(Z < (double)__builtin_inff()) || !(m < __builtin_inff());
+
+    // Token-DiFR
+    uint32_t fg = nonfinite ? kFlagNonfinite : 0u;
+    float yt = nan, mg = nan;
+    if (t.tg >= 0) {
+        yt = perturbed_score(ws.x_claim_gumbel[n], t.inv_T, noise_word_of(t, kStreamGumbel, t.tg));
+        mg = best_y - yt;
+        if (best_v == t.tg) fg |= kFlagMatch;
+    } else {
+        fg |= kFlagInvalidClaim;
+    }
+    og.margin[n] = mg;
+    og.argmax[n] = best_v;
+    if (og.max_score) og.max_score[n] = best_y;
+    if (og.claimed_score) og.claimed_score[n] = yt;
+    og.flags[n] = (uint8_t)fg;
+
+    // Token-IPT-DiFR
+    uint32_t r[4];
+    noise_block(t.key, t.pos, t.seq, kStreamIpt, 0u, r);
+    const float u = uniform_from_bits(r[0]);
+    float a = nan, bb = nan, dd = nan;
+    bool match = false;
+    if (t.ti >= 0 && !ipt_bad) {
+        const double et = (double)fast_exp2(__fmaf_rn(ws.x_claim_ipt[n], c, -(m * c)));
+        const double ud = (double)u;
+        const double ad = P / Z, bd = (P + et) / Z;
+        a = (float)ad;
+        bb = (float)bd;
+        dd = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+        match = (ad <= ud) && (ud < bd);
+    }
+    uint32_t fi = 0;
+    if (t.ti < 0) fi |= kFlagInvalidClaim;
+    if (ipt_bad) fi |= kFlagNonfinite;
+    if (match) fi |= kFlagMatch;
+    oi.dist[n] = dd;
+    if (oi.cdf_lo) oi.cdf_lo[n] = a;
+    if (oi.cdf_hi) oi.cdf_hi[n] = bb;
+    if (oi.u) oi.u[n] = u;
+    oi.flags[n] = (uint8_t)fi;
+}
+
+int launch_lmhead_score(const LmHeadBatch &b, const LmHeadWorkspace &ws, const LmHeadPlan &plan, const GumbelOutputs &og,
+                        const IptOutputs &oi, hipStream_t stream)
+{
+    lmhead_prepare_kernel<<<dim3((unsigned)((b.N + kWaves - 1) / kWaves)), dim3(kBlock), 0, stream>>>(b, ws);
+    if (hipGetLastError() != hipSuccess) return 1;
+    lmhead_score_kernel<<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
+    if (hipGetLastError() != hipSuccess) return 1;
+    lmhead_finalize_kernel<<<dim3((unsigned)((b.N + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(b, ws, plan.splits,
+                                                                                                    og, oi);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

@@ -167,8 +167,58 @@ class Workload:
         raise ValueError(self.mutation)
 
 
-# The configurations named in the benchmark spec, in its order (index 4, the fused LM head, has
-# no logits workload: its inputs are hidden states).
+@dataclasses.dataclass(frozen=True)
+class LmHeadWorkload:
+    """Inputs of the fused LM-head path: final hidden states and the LM-head matrix instead of logits.
+
+    hidden [N, d] bf16 ~ N(0, 1); weight [V, d] bf16 ~ N(0, w_sigma^2); the prover's hidden states are
+    the verifier's plus N(0, drift_sigma^2), re-rounded to bf16 (benign numerical drift upstream of
+    the LM head)."""
+    name: str
+    index: int
+    S: int
+    L: int
+    V: int
+    d: int
+    temperature: float
+    w_sigma: float
+    drift_sigma: float
+
+    @property
+    def N(self) -> int:
+        return self.S * self.L
+
+    seeds = Workload.seeds
+    seq_ids = Workload.seq_ids
+    positions = Workload.positions
+    seq_offsets = Workload.seq_offsets
+
+    def _gen(self, device, salt: int):
+        g = torch.Generator(device=device)
+        g.manual_seed(MASTER_SEED + self.index + 10_000 * salt)
+        return g
+
+    def weight(self, device, rows_per_chunk: int = 8192):
+        device = torch.device(device)
+        g = self._gen(device, 1)
+        W = torch.empty(self.V, self.d, dtype=torch.bfloat16, device=device)
+        for r0 in range(0, self.V, rows_per_chunk):
+            r1 = min(self.V, r0 + rows_per_chunk)
+            W[r0:r1] = (torch.randn(r1 - r0, self.d, generator=g, device=device, dtype=torch.float32)
+                        * self.w_sigma).to(torch.bfloat16)
+        return W
+
+    def hidden(self, device):
+        """(verifier, prover) hidden states, both [N, d] bf16 on `device`."""
+        device = torch.device(device)
+        g = self._gen(device, 2)
+        h = torch.randn(self.N, self.d, generator=g, device=device, dtype=torch.float32)
+        drift = torch.randn(self.N, self.d, generator=g, device=device, dtype=torch.float32) * self.drift_sigma
+        return h.to(torch.bfloat16), (h + drift).to(torch.bfloat16)
+
+
+# The configurations named in BASELINE.json, in its order (index 4, the fused LM head, takes
+# hidden states instead of logits: C4_LMHEAD below).
 C1_TINY = Workload("c1_tiny", 1, S=4, L=16, V=1024, dtype=torch.float32, temperature=1.0, profile="gauss",
                    drift_sigma=1e-3, prover_bf16=False, chunk_rows=64, mutation="uniform", mutation_frac=0.10)
 C2_3B = Workload("c2_3b_class", 2, S=32, L=128, V=128256, dtype=torch.bfloat16, temperature=0.7, profile="zipf",
@@ -179,6 +229,9 @@ C3_30B = Workload("c3_30b_moe_class", 3, S=64, L=1024, V=151936, dtype=torch.bfl
 C5_STEGO = Workload("c5_stego_audit", 5, S=256, L=1024, V=151936, dtype=torch.bfloat16, temperature=0.8,
                     profile="zipf", drift_sigma=4e-3, prover_bf16=True, chunk_rows=512, mutation="stego",
                     mutation_frac=0.01, mutation_k=4)
+
+C4_LMHEAD = LmHeadWorkload("c4_fused_lm_head", 4, S=16, L=1024, V=151936, d=4096, temperature=1.0, w_sigma=0.02,
+                           drift_sigma=4e-3)
 
 WORKLOADS = {w.name: w for w in (C1_TINY, C2_3B, C3_30B, C5_STEGO)}
 
