@@ -145,7 +145,7 @@ __device__ __forceinline__ void refresh_gates(const Slot &s, BlockCtx &k)
 
 // Score one 32x32 accumulator block: this lane's 16 entries are the logits of ONE token at
 // vocabulary rows v(r) = vlane + 8 (r / 4) + (r % 4).
-__device__ __forceinline__ void score_block(const f32x16 &acc, Slot &s, BlockCtx &k, int32_t vlane, int32_t V,
+__device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx &k, int32_t vlane, int32_t V,
                                             bool ragged, int64_t n, const LmHeadWorkspace &ws)
 {
     const float ninf = -__builtin_inff();
@@ -248,11 +248,11 @@ __device__ __forceinline__ void merge_softmax(float &m, double &Z, double &P, fl
 // each wave owns a 128 x 128 sub-tile = 4 x 4 accumulator blocks of 32 x 32.
 // LDS: two stages of [256 rows][64 k] bf16 for each operand; the eight 16-byte chunks of a row are
 // permuted by (row / 2) % 8 so that both the 16-byte slab writes and the fragment reads of 16
-// consecutive rows spread over all banks.
+// consecutive rows spread over all 64 banks.
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, LmHeadWorkspace ws, LmHeadPlan plan)
 {
-    __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];  // 32 KB per stage
     __shared__ __attribute__((aligned(16))) uint16_t lds_h[2][kLmTileT * kLmTileK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -271,7 +271,8 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     const int32_t V = (int32_t)b.V;
     const int nk = (int)(b.d / kLmTileK);
 
-    // slab copy: thread -> chunk (tid % 8) of rows (tid / 8) + 32 p
+    // Slab copy (global -> registers -> LDS): a slab is 256 rows x 64 k of each operand, i.e. whole
+    // 128-byte lines; thread -> 16-byte chunk (tid % 8) of rows (tid / 8) + 32 p.
     const int crow = tid >> 3, cchunk = tid & 7;
     const int lds_copy_off = crow * kLmTileK + ((cchunk ^ ((crow >> 1) & 7)) * 8);
     const uint16_t *hsrc[8];
@@ -281,28 +282,35 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         if (gn > b.N - 1) gn = b.N - 1;
         hsrc[p] = b.hidden + gn * b.ldh + cchunk * 8;
     }
-    u32x4 gw[8], gh[8];
-    auto load_slab = [&](int64_t v0, int k0) {
+    auto weight_rows = [&](int vt, const uint16_t *(&src)[8]) {
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
-            int64_t gv = v0 + crow + 32 * p;
+            int64_t gv = (int64_t)vt * kLmTileV + crow + 32 * p;
             if (gv > b.V - 1) gv = b.V - 1;
-            gw[p] = *reinterpret_cast<const u32x4 *>(b.weight + gv * b.ldw + k0 + cchunk * 8);
-            gh[p] = *reinterpret_cast<const u32x4 *>(hsrc[p] + k0);
+            src[p] = b.weight + gv * b.ldw + cchunk * 8;
         }
     };
-    auto store_slab = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            *reinterpret_cast<u32x4 *>(&lds_w[buf][lds_copy_off + 32 * p * kLmTileK]) = gw[p];
-            *reinterpret_cast<u32x4 *>(&lds_h[buf][lds_copy_off + 32 * p * kLmTileK]) = gh[p];
-        }
+    u32x4 GS[16];  // the slab in flight: 8 weight chunks, 8 hidden-state chunks
+    auto store_chunk = [&](int i, int buf) {
+        uint16_t *dst = (i < 8 ? &lds_w[buf][0] : &lds_h[buf][0]) + lds_copy_off + 32 * (i & 7) * kLmTileK;
+        *reinterpret_cast<u32x4 *>(dst) = GS[i];
     };
 
-    // fragment reads: lane -> row l32 of a 32-row block, k chunk 2 kk + lh
+    // fragment reads: lane -> row l32 of a 32-row block, 16-byte k chunk 2 kk + lh (permuted like the copy)
     const int sw = (l32 >> 1) & 7;
     const int a_row_off = (wv * 128 + l32) * kLmTileK;
     const int b_row_off = (wt * 128 + l32) * kLmTileK;
+    struct Frag {
+        bf16x8 a[4], b[4];
+    };
+    // fragment i (0-3: weight blocks, 4-7: hidden-state blocks) of k step kk from LDS stage buf
+    auto read_frag = [&](Frag &f, int i, int buf, int kk) {
+        const int coff = ((2 * kk + lh) ^ sw) * 8;
+        if (i < 4)
+            f.a[i] = *reinterpret_cast<const bf16x8 *>(&lds_w[buf][a_row_off + i * 32 * kLmTileK + coff]);
+        else
+            f.b[i - 4] = *reinterpret_cast<const bf16x8 *>(&lds_h[buf][b_row_off + (i - 4) * 32 * kLmTileK + coff]);
+    };
 
     // per-lane state of the lane's four tokens
     Slot slot[4];
@@ -322,56 +330,93 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         slot[jb].P = 0.0;
     }
 
+    // ---- main loop ----
+    // One wave per SIMD: nothing else hides latency, so copies and fragment reads are interleaved with the
+    // matrix instructions by hand and the order is pinned with scheduling fences.  Per 64-deep slab, four
+    // k steps of 16 MFMAs each:
+    //   step 0: + the 16 global loads of the next slab           + fragment reads for step 1
+    //   step 1:                                                   + fragment reads for step 2
+    //   step 2: + the 16 LDS writes of the next slab (other stage) + fragment reads for step 3
+    //   barrier
+    //   step 3:                                                   + fragment reads for step 0 of the next slab
+    f32x16 acc[4][4];
+    Frag F0, F1;
+    auto kstep = [&](const Frag &cur, Frag &nxt, int buf_next, int kk_next, auto &&extra) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int e0 = 2 * i, e1 = 2 * i + 1;
+            acc[e0 >> 2][e0 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e0 >> 2], cur.b[e0 & 3], acc[e0 >> 2][e0 & 3], 0, 0, 0);
+            extra(e0);
+            acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
+            extra(e1);
+            read_frag(nxt, i, buf_next, kk_next);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    int par = 0;  // LDS stage of the slab being multiplied
+    // one slab; wsrc / k0 say where the NEXT slab comes from
+    auto slab = [&](const uint16_t *const (&wsrc)[8], int k0) {
+        kstep(F0, F1, par, 1, [&](int i) {
+            GS[i] = *reinterpret_cast<const u32x4 *>((i < 8 ? wsrc[i & 7] : hsrc[i & 7]) + k0);
+        });
+        kstep(F1, F0, par, 2, [&](int) {});
+        kstep(F0, F1, par, 3, [&](int i) { store_chunk(i, par ^ 1); });
+        __syncthreads();
+        kstep(F1, F0, par ^ 1, 0, [&](int) {});
+        par ^= 1;
+    };
+
+    const uint16_t *wsrc_cur[8], *wsrc_next[8];
+    weight_rows(vt0, wsrc_cur);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) GS[i] = *reinterpret_cast<const u32x4 *>(i < 8 ? wsrc_cur[i & 7] : hsrc[i & 7]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) store_chunk(i, 0);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) read_frag(F0, i, 0, 0);
+
     for (int vt = vt0; vt < vt1; ++vt) {
         const int64_t v0 = (int64_t)vt * kLmTileV;
-        f32x16 acc[4][4];
+        const f32x16 zero = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb)
+            for (int jb = 0; jb < 4; ++jb) acc[ib][jb] = zero;
+        // after this tile's last slab comes the first slab of the next tile (of this one again if there
+        // is none: a harmless reload that keeps the loop free of special cases)
+        weight_rows(vt + 1 < vt1 ? vt + 1 : vt, wsrc_next);
+        for (int kt = 0; kt + 1 < nk; ++kt) slab(wsrc_cur, (kt + 1) * kLmTileK);
+        slab(wsrc_next, 0);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[ib][jb][r] = 0.0f;
-
-        load_slab(v0, 0);
-        store_slab(0);
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int buf = kt & 1;
-            if (kt + 1 < nk) load_slab(v0, (kt + 1) * kLmTileK);
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int coff = ((2 * kk + lh) ^ sw) * 8;
-                bf16x8 af[4], bf[4];
-#pragma unroll
-                for (int ib = 0; ib < 4; ++ib)
-                    af[ib] = *reinterpret_cast<const bf16x8 *>(&lds_w[buf][a_row_off + ib * 32 * kLmTileK + coff]);
-#pragma unroll
-                for (int jb = 0; jb < 4; ++jb)
-                    bf[jb] = *reinterpret_cast<const bf16x8 *>(&lds_h[buf][b_row_off + jb * 32 * kLmTileK + coff]);
-#pragma unroll
-                for (int ib = 0; ib < 4; ++ib)
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-                        acc[ib][jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ib], bf[jb], acc[ib][jb], 0, 0, 0);
-            }
-            if (kt + 1 < nk) store_slab(buf ^ 1);
-            __syncthreads();
-        }
+        for (int p = 0; p < 8; ++p) wsrc_cur[p] = wsrc_next[p];
 
         // ---- epilogue: score the 256 x 256 logits of this tile ----
         const bool ragged = v0 + kLmTileV > b.V;
-#pragma unroll
-        for (int jb = 0; jb < 4; ++jb) {
+        // (explicit instantiation per block: the accumulator indices must be compile-time constants)
+        auto score_token = [&](auto JB) {
+            constexpr int jb = decltype(JB)::value;
             const TokInfo t = load_tok(b, tok_n[jb]);
             BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_live[jb]};
             k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
             refresh_gates(slot[jb], k);
+            const int32_t vl = (int32_t)v0 + wv * 128 + 4 * lh;
+            score_block(acc[0][jb], slot[jb], k, vl, V, ragged, tok_n[jb], ws);
+            score_block(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_n[jb], ws);
+            score_block(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_n[jb], ws);
+            score_block(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_n[jb], ws);
+        };
+#ifdef LMHEAD_VARIANT_NOEPI
 #pragma unroll
-            for (int ib = 0; ib < 4; ++ib) {
-                const int32_t vlane = (int32_t)v0 + wv * 128 + ib * 32 + 4 * lh;
-                score_block(acc[ib][jb], slot[jb], k, vlane, V, ragged, tok_n[jb], ws);
-            }
-        }
+        for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) slot[jb].best_y = fmaxf(slot[jb].best_y, acc[ib][jb][0] + acc[ib][jb][7]);
+#else
+        score_token(std::integral_constant<int, 0>());
+        score_token(std::integral_constant<int, 1>());
+        score_token(std::integral_constant<int, 2>());
+        score_token(std::integral_constant<int, 3>());
+#endif
     }
 
     // ---- merge the four lanes/waves that share a token and write this range's partial ----
