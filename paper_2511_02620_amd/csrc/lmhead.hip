@@ -282,15 +282,26 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         if (gn > b.N - 1) gn = b.N - 1;
         hsrc[p] = b.hidden + gn * b.ldh + cchunk * 8;
     }
-    auto weight_rows = [&](int vt, const uint16_t *(&src)[8]) {
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            int64_t gv = (int64_t)vt * kLmTileV + crow + 32 * p;
-            if (gv > b.V - 1) gv = b.V - 1;
-            src[p] = b.weight + gv * b.ldw + cchunk * 8;
-        }
+    // load cursor: the next slab to fetch is slab l_kt of vocabulary tile l_vt; once past the end it stays
+    // on the last tile (harmless reloads keep the loop free of special cases)
+    int l_vt = vt0, l_kt = 0;
+    auto advance_cursor = [&]() {
+        const bool wrap = (l_kt + 1 == nk);
+        l_kt = wrap ? 0 : l_kt + 1;
+        l_vt = (wrap && l_vt + 1 < vt1) ? l_vt + 1 : l_vt;
     };
     u32x4 GS[16];  // the slab in flight: 8 weight chunks, 8 hidden-state chunks
+    auto load_chunk = [&](int i) {
+        const uint16_t *src;
+        if (i < 8) {
+            int64_t gv = (int64_t)l_vt * kLmTileV + crow + 32 * i;
+            if (gv > b.V - 1) gv = b.V - 1;
+            src = b.weight + gv * b.ldw + cchunk * 8 + l_kt * kLmTileK;
+        } else {
+            src = hsrc[i & 7] + l_kt * kLmTileK;
+        }
+        GS[i] = *reinterpret_cast<const u32x4 *>(src);
+    };
     auto store_chunk = [&](int i, int buf) {
         uint16_t *dst = (i < 8 ? &lds_w[buf][0] : &lds_h[buf][0]) + lds_copy_off + 32 * (i & 7) * kLmTileK;
         *reinterpret_cast<u32x4 *>(dst) = GS[i];
@@ -334,11 +345,12 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     // One wave per SIMD: nothing else hides latency, so copies and fragment reads are interleaved with the
     // matrix instructions by hand and the order is pinned with scheduling fences.  Per 64-deep slab, four
     // k steps of 16 MFMAs each:
-    //   step 0: + the 16 global loads of the next slab           + fragment reads for step 1
-    //   step 1:                                                   + fragment reads for step 2
+    //   step 0:                                                    + fragment reads for step 1
+    //   step 1:                                                    + fragment reads for step 2
     //   step 2: + the 16 LDS writes of the next slab (other stage) + fragment reads for step 3
     //   barrier
-    //   step 3:                                                   + fragment reads for step 0 of the next slab
+    //   step 3: + the 16 global loads of the slab after the next   + fragment reads for step 0 of the next slab
+    // so a slab's loads are in flight for three k steps before their first use.
     f32x16 acc[4][4];
     Frag F0, F1;
     auto kstep = [&](const Frag &cur, Frag &nxt, int buf_next, int kk_next, auto &&extra) {
@@ -349,32 +361,49 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             extra(e0);
             acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
             extra(e1);
+#ifndef LMHEAD_VARIANT_NOREAD
             read_frag(nxt, i, buf_next, kk_next);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     int par = 0;  // LDS stage of the slab being multiplied
-    // one slab; wsrc / k0 say where the NEXT slab comes from
-    auto slab = [&](const uint16_t *const (&wsrc)[8], int k0) {
-        kstep(F0, F1, par, 1, [&](int i) {
-            GS[i] = *reinterpret_cast<const u32x4 *>((i < 8 ? wsrc[i & 7] : hsrc[i & 7]) + k0);
-        });
-        kstep(F1, F0, par, 2, [&](int) {});
-        kstep(F0, F1, par, 3, [&](int i) { store_chunk(i, par ^ 1); });
+    // chunk i of the slab in registers goes to LDS at MFMA slot 3 i of the slab, and its register is
+    // refilled at once with chunk i of the slab after: every load has a whole slab of time to land and
+    // the loads are spread evenly instead of arriving at the memory pipeline in one burst
+    auto slab = [&]() {
+        auto copy = [&](int slot) {
+#if !defined(LMHEAD_VARIANT_NOSTORE)
+            if (slot % 3 == 0) {
+                store_chunk(slot / 3, par ^ 1);
+#if !defined(LMHEAD_VARIANT_NOLOAD)
+                load_chunk(slot / 3);
+#endif
+            }
+#endif
+        };
+        kstep(F0, F1, par, 1, [&](int e) { copy(e); });
+        kstep(F1, F0, par, 2, [&](int e) { copy(16 + e); });
+        kstep(F0, F1, par, 3, [&](int e) { copy(32 + e); });
+#if !defined(LMHEAD_VARIANT_NOSTORE)
         __syncthreads();
+#endif
         kstep(F1, F0, par ^ 1, 0, [&](int) {});
+        advance_cursor();
         par ^= 1;
     };
 
-    const uint16_t *wsrc_cur[8], *wsrc_next[8];
-    weight_rows(vt0, wsrc_cur);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) GS[i] = *reinterpret_cast<const u32x4 *>(i < 8 ? wsrc_cur[i & 7] : hsrc[i & 7]);
+    for (int i = 0; i < 16; ++i) load_chunk(i);
+    advance_cursor();
 #pragma unroll
     for (int i = 0; i < 16; ++i) store_chunk(i, 0);
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 8; ++i) read_frag(F0, i, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) load_chunk(i);
+    advance_cursor();
 
     for (int vt = vt0; vt < vt1; ++vt) {
         const int64_t v0 = (int64_t)vt * kLmTileV;
@@ -383,13 +412,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
             for (int jb = 0; jb < 4; ++jb) acc[ib][jb] = zero;
-        // after this tile's last slab comes the first slab of the next tile (of this one again if there
-        // is none: a harmless reload that keeps the loop free of special cases)
-        weight_rows(vt + 1 < vt1 ? vt + 1 : vt, wsrc_next);
-        for (int kt = 0; kt + 1 < nk; ++kt) slab(wsrc_cur, (kt + 1) * kLmTileK);
-        slab(wsrc_next, 0);
-#pragma unroll
-        for (int p = 0; p < 8; ++p) wsrc_cur[p] = wsrc_next[p];
+        for (int kt = 0; kt < nk; ++kt) slab();
 
         // ---- epilogue: score the 256 x 256 logits of this tile ----
         const bool ragged = v0 + kLmTileV > b.V;
