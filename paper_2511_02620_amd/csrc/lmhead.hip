@@ -149,9 +149,11 @@ __device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx 
                                             bool ragged, int64_t n, const LmHeadWorkspace &ws)
 {
     const float ninf = -__builtin_inff();
+    // the accumulators live in the accumulation registers; fetch them one by one (left to itself the
+    // register allocator moves whole blocks through scratch memory instead)
     float x[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) x[r] = acc[r];
+    for (int r = 0; r < 16; ++r) asm("v_accvgpr_read_b32 %0, %1" : "=v"(x[r]) : "a"(acc[r]));
     if (ragged) {  // uniform: the tile runs past the end of the vocabulary
 #pragma unroll
         for (int r = 0; r < 16; ++r)
@@ -254,6 +256,9 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];  // 32 KB per stage
     __shared__ __attribute__((aligned(16))) uint16_t lds_h[2][kLmTileT * kLmTileK];
+    // per-token constants of the workgroup's 256 token rows (one wave per SIMD cannot hide a global load
+    // in the epilogue, an LDS read it can): key, position, sequence, 1/T, the two claims
+    __shared__ uint32_t lds_tok[7][kLmTileT];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wv = wave >> 1, wt = wave & 1;  // vocabulary half, token half
@@ -323,16 +328,39 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             f.b[i - 4] = *reinterpret_cast<const bf16x8 *>(&lds_h[buf][b_row_off + (i - 4) * 32 * kLmTileK + coff]);
     };
 
+    {
+        int64_t n = n0 + tid;
+        if (n > b.N - 1) n = b.N - 1;
+        const TokInfo t = load_tok(b, n);
+        lds_tok[0][tid] = t.key.k0;
+        lds_tok[1][tid] = t.key.k1;
+        lds_tok[2][tid] = t.pos;
+        lds_tok[3][tid] = t.seq;
+        lds_tok[4][tid] = __float_as_uint(t.inv_T);
+        lds_tok[5][tid] = (uint32_t)t.tg;
+        lds_tok[6][tid] = (uint32_t)t.ti;
+    }
+    auto tok_from_lds = [&](int i) {
+        TokInfo t;
+        t.key.k0 = lds_tok[0][i];
+        t.key.k1 = lds_tok[1][i];
+        t.pos = lds_tok[2][i];
+        t.seq = lds_tok[3][i];
+        t.inv_T = __uint_as_float(lds_tok[4][i]);
+        t.tg = (int32_t)lds_tok[5][i];
+        t.ti = (int32_t)lds_tok[6][i];
+        t.ok = t.seq_ok = true;  // not used by the epilogue
+        return t;
+    };
+
     // per-lane state of the lane's four tokens
     Slot slot[4];
-    int64_t tok_n[4];
-    bool tok_live[4];
+    const int64_t tok_first = n0 + wt * 128 + l32;  // the lane's tokens are tok_first + 32 jb
+    auto tok_row = [&](int jb) { return tok_first + 32 * jb < b.N ? tok_first + 32 * jb : b.N - 1; };
+    auto tok_is_live = [&](int jb) { return tok_first + 32 * jb < b.N; };
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
-        int64_t n = n0 + wt * 128 + jb * 32 + l32;
-        tok_live[jb] = n < b.N;
-        if (!tok_live[jb]) n = b.N - 1;
-        tok_n[jb] = n;
+        const int64_t n = tok_row(jb);
         slot[jb].best_y = -__builtin_inff();
         slot[jb].best_v = 0x7FFFFFFF;
         slot[jb].L = ws.L0[n];
@@ -345,15 +373,12 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     // One wave per SIMD: nothing else hides latency, so copies and fragment reads are interleaved with the
     // matrix instructions by hand and the order is pinned with scheduling fences.  Per 64-deep slab, four
     // k steps of 16 MFMAs each:
-    //   step 0:                                                    + fragment reads for step 1
-    //   step 1:                                                    + fragment reads for step 2
-    //   step 2: + the 16 LDS writes of the next slab (other stage) + fragment reads for step 3
+    //   steps 0-2: + fragment reads for the next step, + one LDS write and one global load every third MFMA
     //   barrier
-    //   step 3: + the 16 global loads of the slab after the next   + fragment reads for step 0 of the next slab
-    // so a slab's loads are in flight for three k steps before their first use.
+    //   step 3:    + fragment reads for step 0 of the next slab (from the other LDS stage)
     f32x16 acc[4][4];
     Frag F0, F1;
-    auto kstep = [&](const Frag &cur, Frag &nxt, int buf_next, int kk_next, auto &&extra) {
+    auto kstep = [&](const Frag &cur, Frag &nxt, int buf_next, int kk_next, auto READ, auto &&extra) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int e0 = 2 * i, e1 = 2 * i + 1;
@@ -361,34 +386,35 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             extra(e0);
             acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
             extra(e1);
-#ifndef LMHEAD_VARIANT_NOREAD
-            read_frag(nxt, i, buf_next, kk_next);
-#endif
+            if (decltype(READ)::value) read_frag(nxt, i, buf_next, kk_next);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     int par = 0;  // LDS stage of the slab being multiplied
-    // chunk i of the slab in registers goes to LDS at MFMA slot 3 i of the slab, and its register is
+    // Chunk i of the slab in registers goes to LDS at MFMA slot 3 i of the slab, and its register is
     // refilled at once with chunk i of the slab after: every load has a whole slab of time to land and
-    // the loads are spread evenly instead of arriving at the memory pipeline in one burst
-    auto slab = [&]() {
+    // the loads are spread evenly instead of arriving at the memory pipeline in one burst.
+    // Around the epilogue the registers are emptied: the slab they hold is written to its LDS stage
+    // before the epilogue (the stage is idle by then), so the FIRST slab of a tile only refills them,
+    // and the LAST slab of a tile does not read fragments ahead.  The epilogue then has those 96
+    // registers for itself.
+    const std::true_type yes;
+    const std::false_type no;
+    auto slab = [&](auto FIRST, auto LAST) {
         auto copy = [&](int slot) {
-#if !defined(LMHEAD_VARIANT_NOSTORE)
             if (slot % 3 == 0) {
-                store_chunk(slot / 3, par ^ 1);
-#if !defined(LMHEAD_VARIANT_NOLOAD)
+                if (!decltype(FIRST)::value) store_chunk(slot / 3, par ^ 1);
                 load_chunk(slot / 3);
-#endif
             }
-#endif
         };
-        kstep(F0, F1, par, 1, [&](int e) { copy(e); });
-        kstep(F1, F0, par, 2, [&](int e) { copy(16 + e); });
-        kstep(F0, F1, par, 3, [&](int e) { copy(32 + e); });
-#if !defined(LMHEAD_VARIANT_NOSTORE)
+        kstep(F0, F1, par, 1, yes, [&](int e) { copy(e); });
+        kstep(F1, F0, par, 2, yes, [&](int e) { copy(16 + e); });
+        kstep(F0, F1, par, 3, yes, [&](int e) { copy(32 + e); });
         __syncthreads();
-#endif
-        kstep(F1, F0, par ^ 1, 0, [&](int) {});
+        if (decltype(LAST)::value)
+            kstep(F1, F0, par ^ 1, 0, no, [&](int) {});
+        else
+            kstep(F1, F0, par ^ 1, 0, yes, [&](int) {});
         advance_cursor();
         par ^= 1;
     };
@@ -398,12 +424,12 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     advance_cursor();
 #pragma unroll
     for (int i = 0; i < 16; ++i) store_chunk(i, 0);
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 8; ++i) read_frag(F0, i, 0, 0);
 #pragma unroll
     for (int i = 0; i < 16; ++i) load_chunk(i);
     advance_cursor();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) store_chunk(i, 1);
+    __syncthreads();
 
     for (int vt = vt0; vt < vt1; ++vt) {
         const int64_t v0 = (int64_t)vt * kLmTileV;
@@ -412,24 +438,36 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
             for (int jb = 0; jb < 4; ++jb) acc[ib][jb] = zero;
-        for (int kt = 0; kt < nk; ++kt) slab();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) read_frag(F0, i, par, 0);
+        if (nk == 1) {
+            slab(yes, yes);
+        } else {
+            slab(yes, no);
+            for (int kt = 2; kt < nk; ++kt) slab(no, no);
+            slab(no, yes);
+        }
+        // the slab in registers (the next tile's second) goes to its LDS stage now; the first slab's
+        // barrier orders these writes before anyone reads them
+#pragma unroll
+        for (int i = 0; i < 16; ++i) store_chunk(i, par ^ 1);
 
         // ---- epilogue: score the 256 x 256 logits of this tile ----
         const bool ragged = v0 + kLmTileV > b.V;
         // (explicit instantiation per block: the accumulator indices must be compile-time constants)
         auto score_token = [&](auto JB) {
             constexpr int jb = decltype(JB)::value;
-            const TokInfo t = load_tok(b, tok_n[jb]);
-            BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_live[jb]};
+            const TokInfo t = tok_from_lds(wt * 128 + jb * 32 + l32);
+            BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_is_live(jb)};
             k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
             refresh_gates(slot[jb], k);
             const int32_t vl = (int32_t)v0 + wv * 128 + 4 * lh;
-            score_block(acc[0][jb], slot[jb], k, vl, V, ragged, tok_n[jb], ws);
-            score_block(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_n[jb], ws);
-            score_block(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_n[jb], ws);
-            score_block(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_n[jb], ws);
+            score_block(acc[0][jb], slot[jb], k, vl, V, ragged, tok_row(jb), ws);
+            score_block(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_row(jb), ws);
+            score_block(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_row(jb), ws);
+            score_block(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_row(jb), ws);
         };
-#ifdef LMHEAD_VARIANT_NOEPI
+#ifdef LMHEAD_VARIANT_NOEPI  // timing experiments only: the GEMM without the scoring
 #pragma unroll
         for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
@@ -452,7 +490,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
         Slot &s = slot[jb];
-        tok_c[jb] = load_tok(b, tok_n[jb]).inv_T * kLog2e;
+        tok_c[jb] = __uint_as_float(lds_tok[4][wt * 128 + jb * 32 + l32]) * kLog2e;
         const float oy = __shfl_xor(s.best_y, 32, 64);
         const int32_t ov = __shfl_xor(s.best_v, 32, 64);
         const float om = __shfl_xor(s.m, 32, 64);
@@ -478,12 +516,12 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     if (wv == 0 && lh == 0) {
 #pragma unroll
         for (int jb = 0; jb < 4; ++jb) {
-            if (!tok_live[jb]) continue;
+            if (!tok_is_live(jb)) continue;
             Slot &s = slot[jb];
             const int i = wt * 128 + jb * 32 + l32;
             argmax_combine(s.best_y, s.best_v, ex_y[i], ex_v[i]);
             merge_softmax(s.m, s.Z, s.P, ex_m[i], ex_Z[i], ex_P[i], tok_c[jb]);
-            const int64_t o = (int64_t)sp * b.N + tok_n[jb];
+            const int64_t o = (int64_t)sp * b.N + tok_row(jb);
             ws.best_y[o] = s.best_y;
             ws.best_v[o] = s.best_v;
             ws.m[o] = s.m;
