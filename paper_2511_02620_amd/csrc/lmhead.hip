@@ -280,13 +280,17 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     // 128-byte lines; thread -> 16-byte chunk (tid % 8) of rows (tid / 8) + 32 p.
     const int crow = tid >> 3, cchunk = tid & 7;
     const int lds_copy_off = crow * kLmTileK + ((cchunk ^ ((crow >> 1) & 7)) * 8);
-    const uint16_t *hsrc[8];
+    // Addresses are a wave-uniform base (scalar registers, moved by scalar arithmetic) plus a 32-bit
+    // per-lane byte offset that never changes, so a load costs no vector arithmetic.
+    uint32_t hoff[8];  // hidden-state rows: offset from the first row of the token block
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        int64_t gn = n0 + crow + 32 * p;
-        if (gn > b.N - 1) gn = b.N - 1;
-        hsrc[p] = b.hidden + gn * b.ldh + cchunk * 8;
+        int64_t r = crow + 32 * p;
+        if (n0 + r > b.N - 1) r = b.N - 1 - n0;
+        hoff[p] = (uint32_t)(r * b.ldh + cchunk * 8) * 2u;
     }
+    const char *const hbase = reinterpret_cast<const char *>(b.hidden + n0 * b.ldh);
+    const uint32_t wrow_bytes = (uint32_t)b.ldw * 2u;
     // load cursor: the next slab to fetch is slab l_kt of vocabulary tile l_vt; once past the end it stays
     // on the last tile (harmless reloads keep the loop free of special cases)
     int l_vt = vt0, l_kt = 0;
@@ -297,13 +301,16 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     };
     u32x4 GS[16];  // the slab in flight: 8 weight chunks, 8 hidden-state chunks
     auto load_chunk = [&](int i) {
-        const uint16_t *src;
+        const char *src;
         if (i < 8) {
-            int64_t gv = (int64_t)l_vt * kLmTileV + crow + 32 * i;
-            if (gv > b.V - 1) gv = b.V - 1;
-            src = b.weight + gv * b.ldw + cchunk * 8 + l_kt * kLmTileK;
+            // rows past the end of the vocabulary (last tile only) re-read the last row
+            const int64_t tile_v0 = (int64_t)l_vt * kLmTileV;
+            const int32_t last = (int32_t)((b.V - tile_v0 < kLmTileV ? b.V - tile_v0 : kLmTileV) - 1);  // uniform
+            const int32_t r = min(crow + 32 * i, last);
+            const char *wbase = reinterpret_cast<const char *>(b.weight + tile_v0 * b.ldw + l_kt * kLmTileK);
+            src = wbase + ((uint32_t)r * wrow_bytes + (uint32_t)cchunk * 16u);
         } else {
-            src = hsrc[i & 7] + l_kt * kLmTileK;
+            src = hbase + (size_t)l_kt * (kLmTileK * 2) + hoff[i & 7];
         }
         GS[i] = *reinterpret_cast<const u32x4 *>(src);
     };
@@ -386,7 +393,9 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             extra(e0);
             acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
             extra(e1);
+#ifndef LMHEAD_VARIANT_NOREAD
             if (decltype(READ)::value) read_frag(nxt, i, buf_next, kk_next);
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -403,14 +412,20 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     auto slab = [&](auto FIRST, auto LAST) {
         auto copy = [&](int slot) {
             if (slot % 3 == 0) {
+#ifndef LMHEAD_VARIANT_NOSTORE
                 if (!decltype(FIRST)::value) store_chunk(slot / 3, par ^ 1);
+#endif
+#ifndef LMHEAD_VARIANT_NOLOAD
                 load_chunk(slot / 3);
+#endif
             }
         };
         kstep(F0, F1, par, 1, yes, [&](int e) { copy(e); });
         kstep(F1, F0, par, 2, yes, [&](int e) { copy(16 + e); });
         kstep(F0, F1, par, 3, yes, [&](int e) { copy(32 + e); });
+#ifndef LMHEAD_VARIANT_NOBARRIER
         __syncthreads();
+#endif
         if (decltype(LAST)::value)
             kstep(F1, F0, par ^ 1, 0, no, [&](int) {});
         else
