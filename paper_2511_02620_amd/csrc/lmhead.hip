@@ -393,9 +393,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             extra(e0);
             acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
             extra(e1);
-#ifndef LMHEAD_VARIANT_NOREAD
             if (decltype(READ)::value) read_frag(nxt, i, buf_next, kk_next);
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -412,20 +410,14 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     auto slab = [&](auto FIRST, auto LAST) {
         auto copy = [&](int slot) {
             if (slot % 3 == 0) {
-#ifndef LMHEAD_VARIANT_NOSTORE
                 if (!decltype(FIRST)::value) store_chunk(slot / 3, par ^ 1);
-#endif
-#ifndef LMHEAD_VARIANT_NOLOAD
                 load_chunk(slot / 3);
-#endif
             }
         };
         kstep(F0, F1, par, 1, yes, [&](int e) { copy(e); });
         kstep(F1, F0, par, 2, yes, [&](int e) { copy(16 + e); });
         kstep(F0, F1, par, 3, yes, [&](int e) { copy(32 + e); });
-#ifndef LMHEAD_VARIANT_NOBARRIER
         __syncthreads();
-#endif
         if (decltype(LAST)::value)
             kstep(F1, F0, par ^ 1, 0, no, [&](int) {});
         else
@@ -482,17 +474,10 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             score_block(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_row(jb), ws);
             score_block(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_row(jb), ws);
         };
-#ifdef LMHEAD_VARIANT_NOEPI  // timing experiments only: the GEMM without the scoring
-#pragma unroll
-        for (int ib = 0; ib < 4; ++ib)
-#pragma unroll
-            for (int jb = 0; jb < 4; ++jb) slot[jb].best_y = fmaxf(slot[jb].best_y, acc[ib][jb][0] + acc[ib][jb][7]);
-#else
         score_token(std::integral_constant<int, 0>());
         score_token(std::integral_constant<int, 1>());
         score_token(std::integral_constant<int, 2>());
         score_token(std::integral_constant<int, 3>());
-#endif
     }
 
     // ---- merge the four lanes/waves that share a token and write this range's partial ----

@@ -119,6 +119,34 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_classify(fake, fake, 4, 0.0, 8, 100, None, None, None, None) == NULL
     assert lib.difr_classify(fake, fake, 4, float("nan"), 8, 100, None, fake, None, None) == ARG
     assert lib.difr_classify(None, None, 0, 0.0, 8, 100, None, None, None, None) == OK
+    # fused LM head
+    from paper_2511_02620_amd.binding import _LmHead
+
+    def lm(**kw):
+        r = _LmHead()
+        r.hidden, r.weight, r.N, r.V, r.d, r.ldh, r.ldw = fake, fake, 4, 100, 128, 128, 128
+        r.temperature, r.temperatures = 1.0, None
+        r.seeds, r.S, r.seq_ids, r.positions, r.claimed_gumbel, r.claimed_ipt = fake, 1, fake, fake, fake, fake
+        for k, v in kw.items():
+            setattr(r, k, v)
+        return r
+
+    def lms(r, ws=fake, ws_bytes=1 << 20, margin=fake):
+        return lib.difr_lmhead_score(C.byref(r), margin, fake, None, None, fake, fake, None, None, None, fake, ws,
+                                     ws_bytes, None)
+
+    need = lib.difr_lmhead_workspace_bytes(4, 100, 128)
+    assert 0 < need < 1 << 20 and lib.difr_lmhead_workspace_bytes(0, 100, 128) == 0
+    assert lib.difr_lmhead_workspace_bytes(16384, 151936, 4096) < 4 << 20
+    for bad, want in ((lm(N=-1), SHAPE), (lm(V=0), SHAPE), (lm(d=0), SHAPE), (lm(d=96, ldh=96, ldw=96), SHAPE),
+                      (lm(ldh=64), SHAPE), (lm(ldw=132), SHAPE), (lm(S=0), SHAPE), (lm(N=1 << 31), SHAPE),
+                      (lm(temperature=0.0), TEMP), (lm(hidden=None), NULL), (lm(weight=None), NULL),
+                      (lm(seeds=None), NULL), (lm(hidden=0x1008), ALIGN), (lm(weight=0x1004), ALIGN)):
+        assert lms(bad) == want, want
+    assert lms(lm(), ws=None) == NULL and lms(lm(), margin=None) == NULL
+    assert lms(lm(), ws=0x1004) == ALIGN and lms(lm(), ws_bytes=need - 1) == SHAPE
+    assert lms(lm(N=0, hidden=None), ws=None) == OK
+    assert lib.difr_lmhead_score(None, fake, fake, None, None, fake, fake, None, None, None, fake, fake, 64, None) == NULL
     assert lib.difr_debug_noise(C.byref(rows()), 4, 0, fake, None) == SHAPE
     assert lib.difr_debug_gumbel_map(None, 4, fake, None) == NULL
 
