@@ -47,11 +47,11 @@ GUMBEL_ALU_OPS_PER_ENTRY = 11
 IPT_ALU_OPS_PER_ENTRY = 4
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
-# the same counter reads for a plain 4 GiB device copy (profiles/c3_gumbel_ipt_hbm_traffic.md).
+# the same counter reads for a plain 4 GiB device copy (profiles/c3_hbm_traffic.md).
 MEASURED_TRAFFIC = {
     ("difr_gumbel_score", "c3_30b_moe_class"): 1.9936e10,
-    ("difr_ipt_score", "c3_30b_moe_class"): 1.9944e10,
-    ("difr_score_both", "c3_30b_moe_class"): None,
+    ("difr_ipt_score", "c3_30b_moe_class"): 1.9936e10,
+    ("difr_score_both", "c3_30b_moe_class"): 1.9959e10,
 }
 
 
