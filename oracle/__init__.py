@@ -87,6 +87,13 @@ def _load():
                                      f32p, u64p, i32p, u32p, i32p, C.c_double, C.c_double,
                                      f64p, f64p, f64p, f64p, i32p, f64p, f64p, u8p]
     lib.oracle_ipt_score.restype = C.c_int
+    lib.oracle_admissible_count_row.argtypes = [f64p, C.c_int64, C.c_double, C.c_uint64, C.c_uint32, C.c_uint32,
+                                                C.c_double, C.c_double, f64p, i32p, i32p, i32p]
+    lib.oracle_admissible_count_row.restype = None
+    lib.oracle_admissible_count.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                            C.POINTER(C.c_float), C.POINTER(C.c_uint64), i32p, C.POINTER(C.c_uint32),
+                                            C.c_double, C.c_double, i32p, i32p, i32p]
+    lib.oracle_admissible_count.restype = C.c_int
     u16p = C.POINTER(C.c_uint16)
     lib.oracle_lmhead_row.argtypes = [u16p, u16p, C.c_int64, C.c_int64, C.c_int64, f64p]
     lib.oracle_lmhead_row.restype = None
@@ -279,6 +286,34 @@ def ipt_score(logits, V, temperature, seeds, seq_ids, positions, claimed=None, t
                                   _ptr(out["edge"], C.c_double), _ptr(out["flags"], C.c_uint8))
     if rc:
         raise MemoryError("oracle_ipt_score")
+    return out
+
+
+def admissible_count_row(x, T, seed, seq, pos, delta, tol=0.0):
+    """(count, count at delta - tol, count at delta + tol) of { v : max y - y_v <= delta } for one row of doubles."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    y = np.zeros_like(x)
+    c, lo, hi = C.c_int32(), C.c_int32(), C.c_int32()
+    _load().oracle_admissible_count_row(_ptr(x, C.c_double), x.shape[0], float(T), int(seed), int(seq), int(pos),
+                                        float(delta), float(tol), _ptr(y, C.c_double), C.byref(c), C.byref(lo),
+                                        C.byref(hi))
+    return c.value, lo.value, hi.value
+
+
+def admissible_count(logits, V, temperature, seeds, seq_ids, positions, delta, tol=0.0, temperatures=None):
+    """Admissible-set size per row: dict(count, count_lo, count_hi) of int32 [N]."""
+    a, dtype, ld = _logits_view(logits)
+    N = a.shape[0]
+    assert a.shape[1] >= V
+    seeds, seq_ids, positions, _, _, temperatures, tp = _aux(N, seeds, seq_ids, positions, None, temperatures)
+    out = dict(count=np.zeros(N, np.int32), count_lo=np.zeros(N, np.int32), count_hi=np.zeros(N, np.int32))
+    rc = _load().oracle_admissible_count(a.ctypes.data, dtype, N, int(V), ld, float(temperature), tp,
+                                         _ptr(seeds, C.c_uint64), _ptr(seq_ids, C.c_int32),
+                                         _ptr(positions, C.c_uint32), float(delta), float(tol),
+                                         _ptr(out["count"], C.c_int32), _ptr(out["count_lo"], C.c_int32),
+                                         _ptr(out["count_hi"], C.c_int32))
+    if rc:
+        raise MemoryError("oracle_admissible_count")
     return out
 
 

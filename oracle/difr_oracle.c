@@ -23,6 +23,9 @@
  *                                           for the Gumbel likelihood estimator
  *   - regenerate-and-compare per position . Sec. 5.1 and the appendix algorithm
  *                                           "verification via prefill"
+ *   - admissible set size ................. Sec. 7 (A_t(tau), log2 |A_t| bits per
+ *                                           accepted token), appendix "Threshold
+ *                                           selection and FPR-information trade-off"
  *   - logits from the final hidden state .. the Prefill step of the appendix
  *                                           algorithm "verification via prefill"
  *   - pooling and flagging ................ Sec. 5.2 (threshold rule), Sec. 6.4,
@@ -53,7 +56,8 @@
  * of the k -> u -> g map and its moments; brute force with exact rationals and
  * multi-precision on tiny vocabularies; library softmax / cumsum / searchsorted;
  * chi-square of sample frequencies; Gumbel max-stability; scipy / mpmath normal
- * CDF; the hidden-state-to-logits step against a library matrix product and
+ * CDF; the admissible-set count against explicit sorting and its geometric law;
+ * the hidden-state-to-logits step against a library matrix product and
  * against the stored-logit entry points on inputs whose products are exact.
  * No function here is "parity unpinned".
  */
@@ -375,6 +379,63 @@ int oracle_ipt_score(const void *logits, int dtype, int64_t N, int64_t V, int64_
             int64_t t = claimed ? (int64_t)claimed[n] : -1;
             oracle_ipt_row(x, V, T, seeds[s], (uint32_t)s, positions[n], t, sigma, eps, &u[n], &cdf_lo[n],
                            &cdf_hi[n], &dist[n], &tok[n], &log_mass[n], &edge[n], &flags[n]);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Size of the admissible set of one position (Sec. 7: A_t(tau) = the tokens   */
+/* the verifier would accept; an accepted token carries at most log2 |A_t|     */
+/* bits).  With the Token-DiFR margin as the score, a token v is accepted when */
+/* its margin  max_w y_w - y_v  is at most delta:                              */
+/*   count = #{ v : max_w y_w - y_v <= delta }.                                */
+/* The same count at delta - tol and delta + tol brackets what an evaluation   */
+/* in lower precision may return.  y must hold V doubles of scratch.           */
+/* ------------------------------------------------------------------------- */
+void oracle_admissible_count_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
+                                 double delta, double tol, double *y, int32_t *count, int32_t *count_lo,
+                                 int32_t *count_hi)
+{
+    double margin, max_score, claimed_score, gap2;
+    int32_t argmax;
+    uint8_t flags;
+    oracle_gumbel_row(x, V, T, seed, seq, pos, -1, &margin, &argmax, &max_score, &claimed_score, &gap2, &flags, y);
+    int32_t c = 0, lo = 0, hi = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        double m = max_score - y[v];
+        if (m <= delta) ++c;
+        if (m <= delta - tol) ++lo;
+        if (m <= delta + tol) ++hi;
+    }
+    *count = c;
+    *count_lo = lo;
+    *count_hi = hi;
+}
+
+int oracle_admissible_count(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, double temperature,
+                            const float *temperatures, const uint64_t *seeds, const int32_t *seq_ids,
+                            const uint32_t *positions, double delta, double tol, int32_t *count, int32_t *count_lo,
+                            int32_t *count_hi)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * 2 * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t s = seq_ids[n];
+            oracle_admissible_count_row(x, V, T, seeds[s], (uint32_t)s, positions[n], delta, tol, x + V, &count[n],
+                                        &count_lo[n], &count_hi[n]);
         }
         free(x);
     }
