@@ -45,6 +45,7 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 GUMBEL_ALU_OPS_PER_ENTRY = 11
 # ... and of the softmax statistics of the IPT estimator: scale-and-shift, exponential, sum, running maximum.
 IPT_ALU_OPS_PER_ENTRY = 4
+ADMISSIBLE_DELTA = 2.5         # margin threshold of the admissible-set count timed next to the step
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 4 GiB device copy (profiles/c3_hbm_traffic.md).
@@ -314,8 +315,9 @@ def main():
         reps = max(1, min(args.steps, 5))
         t_g = time_alone(lambda: difr.gumbel_score(*row_args, data["claims_g"]), reps)
         t_i = time_alone(lambda: difr.ipt_score(*row_args, data["claims_i"]), reps)
+        t_a = time_alone(lambda: difr.admissible_count(*row_args, out[0]["max_score"], ADMISSIBLE_DELTA), reps)
     else:
-        t_b = None
+        t_b = t_a = None
         t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
@@ -378,7 +380,10 @@ def main():
                                           "hbm_gbs": round(gbs_g, 1), "frac_of_peak": round(gbs_g / HBM_PEAK_GBS, 4)},
                     "difr_ipt_score": {"ms": round(t_i, 4), "tokens_per_s": round(wl.N / (t_i * 1e-3), 1),
                                        "hbm_gbs": round(gbs_i, 1), "frac_of_peak": round(gbs_i / HBM_PEAK_GBS, 4)},
-                    "difr_seq_reduce_x2": {"ms": round(t_r, 4)}},
+                    "difr_seq_reduce_x2": {"ms": round(t_r, 4)},
+                    "difr_admissible_count": None if t_a is None else
+                    {"ms": round(t_a, 4), "delta": ADMISSIBLE_DELTA, "tokens_per_s": round(wl.N / (t_a * 1e-3), 1),
+                     "hbm_gbs": round(wl.N * (wl.V * esz + 24) / (t_a * 1e-3) / 1e9, 1)}},
         "match_rate": {"gumbel": round(match_g, 5), "ipt": round(match_i, 5)},
     }
     if args.cpu_rows > 0:

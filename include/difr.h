@@ -167,6 +167,23 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                     uint8_t *flags_ipt, void *hip_stream);
 
 /*
+ * Size of each row's admissible set.  [Sec. 7, "admissible set" A_t(tau) = { i : FSSL_t(i) >= tau }: an accepted
+ * token carries at most log2 |A_t(tau)| bits, a sequence at most the sum; appendix "Threshold selection and
+ * FPR-information trade-off".]  With the Token-DiFR margin as the score (suspiciousness, accepted when small):
+ *     count[n] = #{ v in [0,V) : max_score[n] - y_v <= delta },   y_v = x_v / T + g_v  as in difr_gumbel_score,
+ * i.e. the number of tokens that would have been scored margin <= delta had they been claimed at this position.
+ * max_score  DEVICE [N]: the `max_score` output of difr_gumbel_score (or difr_score_both) for the same rows; the
+ *            comparison is made in fp32, exactly as difr_gumbel_score forms margins, so the claimed token is
+ *            counted if and only if its margin is <= delta.  delta >= 0, finite (else DIFR_ERR_ARGUMENT).
+ * count      DEVICE [N] int32; log2_count DEVICE [N] fp32 or NULL (the per-token bit bound; it is the
+ *            log2_admissible input of difr_classify).  A row with a NaN or infinite max_score, a bad sequence id
+ *            or temperature gets count 0 and log2_count NaN.  in->claimed is not used.
+ * One more pass over the logits (the row maximum has to be known first).
+ */
+int difr_admissible_count(const difr_rows *in, const float *max_score, float delta, int32_t *count, float *log2_count,
+                          void *hip_stream);
+
+/*
  * Fused LM head + scoring: both estimators on logits that are never stored.  The verifier's
  * prefill ends with the product of each position's final hidden state and the LM-head matrix
  * [appendix algorithm "sampled token verification via prefill": one forward pass yields the

@@ -7,6 +7,7 @@ return torch tensors.  There is no CPU fallback; if the library is missing the i
 of :mod:`paper_2511_02620_amd.binding` fails loudly.
 """
 from .binding import (  # noqa: F401
+    admissible_count,
     DifrError,
     FLAG_INVALID_CLAIM,
     FLAG_MATCH,

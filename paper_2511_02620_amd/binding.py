@@ -68,7 +68,7 @@ class _LmHead(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -93,6 +93,8 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
     lib.difr_score_both.restype = C.c_int
+    lib.difr_admissible_count.argtypes = [C.POINTER(_Rows), vp, C.c_float, vp, vp, vp]
+    lib.difr_admissible_count.restype = C.c_int
     lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
     lib.difr_lmhead_workspace_bytes.restype = C.c_size_t
     lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 11 + [C.c_size_t, vp]
@@ -251,6 +253,23 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if rc:
         raise DifrError(rc, "difr_score_both")
     return g, i
+
+
+def admissible_count(logits, temperature, seeds, seq_ids, positions, max_score, delta, temperatures=None, V=None,
+                     want_log2=True):
+    """difr_admissible_count: size of { v : max_score - y_v <= delta } per row (max_score from gumbel_score)."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, None, temperatures)
+    _check(max_score, torch.float32, N, "max_score", dev)
+    out = dict(count=torch.empty(N, dtype=torch.int32, device=dev))
+    if want_log2:
+        out["log2_count"] = torch.empty(N, dtype=torch.float32, device=dev)
+    with torch.cuda.device(dev):
+        rc = lib.difr_admissible_count(C.byref(r), _ptr(max_score), float(delta), _ptr(out["count"]),
+                                       _ptr(out.get("log2_count")), _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_admissible_count")
+    return out
 
 
 def lmhead_workspace_bytes(N, V, d) -> int:

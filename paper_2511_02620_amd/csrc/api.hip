@@ -189,6 +189,22 @@ int difr_seq_reduce(const float *scores, const uint8_t *row_flags, const int64_t
                : DIFR_OK;
 }
 
+int difr_admissible_count(const difr_rows *in, const float *max_score, float delta, int32_t *count, float *log2_count,
+                          void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (!(delta >= 0.0f) || !isfinite(delta)) return DIFR_ERR_ARGUMENT;
+    if (b.N == 0) return DIFR_OK;
+    if (!max_score || !count) return DIFR_ERR_NULL;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    return difr::launch_admissible_count(b, aligned, max_score, delta, count, log2_count, (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                     uint8_t *flags_ipt, void *hip_stream)

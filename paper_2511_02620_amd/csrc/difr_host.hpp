@@ -16,6 +16,9 @@ int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *m
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags,
                      int32_t *logit_rank, hipStream_t stream);
+// Size of each row's admissible set { v : max_score - y_v <= delta } (max_score from launch_gumbel_score).
+int launch_admissible_count(const RowBatch &b, bool aligned, const float *max_score, float delta, int32_t *count,
+                            float *log2_count, hipStream_t stream);
 struct GumbelOutputs;
 struct IptOutputs;
 // Both estimators in one pass (aligned rows only).

@@ -162,6 +162,90 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
     g.finish(row, o, lds_y, lds_i, lds_rank);
 }
 
+// Size of the admissible set of each row (Sec. 7: A_t(tau) = tokens whose score passes the threshold; here
+// the score is the margin, so A_t = { v : max_score - y_v <= delta }).  Second pass over the row with the
+// row maximum known: the same exact pre-filter with the fixed bound M - delta, and a count instead of an
+// argmax.  Any alignment is accepted; unaligned rows evaluate every entry.
+template <int DT, bool ALIGNED>
+__global__ __launch_bounds__(kBlock) void admissible_count_kernel(RowBatch b, const float *__restrict__ max_score,
+                                                                  float delta, int32_t *__restrict__ count,
+                                                                  float *__restrict__ log2_count)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ float lds_L[kWaves];
+    __shared__ int32_t lds_c[kWaves];
+    const int64_t row = blockIdx.x;
+    RowInfo ri = load_row_info(b, row);
+    ri.claimed = -1;
+    const int tid = threadIdx.x;
+    const float M = max_score[row];
+    const float nan = __builtin_nanf("");
+    if (!ri.seq_ok || !ri.temp_ok || !(M == M) || !(fabsf(M) < __builtin_inff())) {  // uniform over the workgroup
+        if (tid == 0) {
+            count[row] = 0;
+            if (log2_count) log2_count[row] = nan;
+        }
+        return;
+    }
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const int64_t V = b.V;
+    int32_t c = 0;
+    if (ALIGNED) {
+        GumbelStream<DT, false, true> g(ri, x_row, V, lds_L);
+        __syncthreads();
+        g.arm_count(M, delta);
+        __syncthreads();
+        const int64_t nvec = V / E;
+        const int n_main = (int)(nvec / kBlock);
+        int round = 0;
+        auto run_rounds = [&](auto mode_tag) {  // the bound never moves, so neither does the gate mode
+            constexpr int MODE = decltype(mode_tag)::value;
+            u32x4 q_next = load_round(x_row, round);
+            while (round < n_main) {
+                const u32x4 q = q_next;
+                if (round + 1 < n_main) q_next = load_round(x_row, round + 1);
+                g.template process<MODE>(q, round, true);
+                ++round;
+            }
+        };
+        if (n_main > 0) {
+            if (g.gate.mode == 0)
+                run_rounds(std::integral_constant<int, 0>());
+            else if (g.gate.mode == 1)
+                run_rounds(std::integral_constant<int, 1>());
+            else
+                run_rounds(std::integral_constant<int, 2>());
+        }
+        if ((int64_t)n_main * kBlock < nvec) {
+            const bool active = (int64_t)n_main * kBlock + tid < nvec;
+            u32x4 q = u32x4{0u, 0u, 0u, 0u};
+            if (active) q = load_round(x_row, n_main);
+            g.process_any(q, n_main, active);
+        }
+        g.tail();
+        c = (int32_t)g.count;
+    } else {
+        const float inv_T = 1.0f / ri.T;
+        for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
+            float x[E];
+            load_elems<DT, false>(x_row, base, V, x);
+#pragma unroll
+            for (int q = 0; q < E / 4; ++q) {
+                uint32_t r[4];
+                noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)((base >> 2) + q), r);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c += (int32_t)(M - perturbed_score(x[4 * q + j], inv_T, r[j]) <= delta);
+            }
+        }
+    }
+    c = block_sum_i32(c, lds_c);
+    if (tid == 0) {
+        count[row] = c;
+        if (log2_count) log2_count[row] = c > 0 ? __log2f((float)c) : nan;
+    }
+}
+
 // Raw noise words of one row, through the same device code as the scoring kernels.
 __global__ __launch_bounds__(kBlock) void debug_noise_kernel(RowBatch b, int64_t row, uint32_t stream,
                                                              uint32_t *__restrict__ bits)
@@ -215,6 +299,24 @@ int launch_gumbel_score(const RowBatch &b, bool aligned, bool filtered, float *m
             gumbel_score_kernel<1, false><<<grid, block, 0, stream>>>(DIFR_ARGS);
     }
 #undef DIFR_ARGS
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_admissible_count(const RowBatch &b, bool aligned, const float *max_score, float delta, int32_t *count,
+                            float *log2_count, hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    if (b.dtype == 0) {
+        if (aligned)
+            admissible_count_kernel<0, true><<<grid, block, 0, stream>>>(b, max_score, delta, count, log2_count);
+        else
+            admissible_count_kernel<0, false><<<grid, block, 0, stream>>>(b, max_score, delta, count, log2_count);
+    } else {
+        if (aligned)
+            admissible_count_kernel<1, true><<<grid, block, 0, stream>>>(b, max_score, delta, count, log2_count);
+        else
+            admissible_count_kernel<1, false><<<grid, block, 0, stream>>>(b, max_score, delta, count, log2_count);
+    }
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

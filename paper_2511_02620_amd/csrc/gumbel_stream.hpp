@@ -123,7 +123,11 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 // For bf16 the count works on the raw bit patterns, two per dword, without unpacking: for a claimed
 // logit >= +0 "x > x_t" is "bits > bits(x_t)" as signed 16-bit, for a negative one it is
 // "bits < bits(x_t)" as unsigned 16-bit (a claimed -0 is treated as +0).
-template <int DT, bool RANK>
+//
+// COUNT: instead of tracking the best score, count the entries whose score is within `delta` of a
+// maximum that is already known (the admissible set of Sec. 7: tokens the verifier would accept).
+// The same gates apply with the fixed bound M - delta; nothing ever raises it.
+template <int DT, bool RANK, bool COUNT = false>
 struct GumbelStream {
     typedef typename Elem<DT>::type elt_t;
     static constexpr int E = Elem<DT>::kPerVec;
@@ -146,6 +150,9 @@ struct GumbelStream {
     float best_y;
     int32_t best_v;
     uint32_t bad, above;
+    // COUNT mode
+    float count_M, count_delta;
+    uint32_t count;
 
     // Computes the claimed token's score with the same function the stream uses (the first lower
     // bound) and publishes it.  The caller must __syncthreads() before the first process().
@@ -177,6 +184,20 @@ struct GumbelStream {
         // second term never changes, the first is scalar, and the sum cannot wrap (counter < 2^29).
         lane_prod = (uint64_t)kPhiloxM0 * (uint32_t)(tid * (E / 4));
         asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
+        count_M = count_delta = 0.0f;
+        count = 0;
+    }
+
+    // COUNT mode: fix the bound at M - delta.  Call after the constructor's publication has been
+    // separated by a __syncthreads(); the caller synchronises again before the first process().
+    __device__ __forceinline__ void arm_count(float M, float delta)
+    {
+        count_M = M;
+        count_delta = delta;
+        float Lc = M - delta;
+        if (!(Lc == Lc)) Lc = -__builtin_inff();
+        gate = make_gate(Lc, T);
+        if ((tid & 63) == 0) lds_L[wave] = gate.L;
     }
 
     // Exact evaluation of one entry (same arithmetic as the unfiltered kernel), ties to the lowest index.
@@ -184,6 +205,10 @@ struct GumbelStream {
     {
         const float y = perturbed_score(xv, inv_T, rv);
         bad |= (uint32_t)!(xv < __builtin_inff());
+        if (COUNT) {
+            count += (uint32_t)(count_M - y <= count_delta);  // the margin of entry v, in the kernel's precision
+            return;
+        }
         if (y > best_y || (y == best_y && v < best_v)) {
             best_y = y;
             best_v = v;

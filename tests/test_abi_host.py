@@ -119,6 +119,13 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_classify(fake, fake, 4, 0.0, 8, 100, None, None, None, None) == NULL
     assert lib.difr_classify(fake, fake, 4, float("nan"), 8, 100, None, fake, None, None) == ARG
     assert lib.difr_classify(None, None, 0, 0.0, 8, 100, None, None, None, None) == OK
+    # admissible-set size
+    assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(-1.0), fake, None, None) == ARG
+    assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(float("nan")), fake, None, None) == ARG
+    assert lib.difr_admissible_count(C.byref(rows()), None, C.c_float(1.0), fake, None, None) == NULL
+    assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(1.0), None, None, None) == NULL
+    assert lib.difr_admissible_count(C.byref(rows(V=0)), fake, C.c_float(1.0), fake, None, None) == SHAPE
+    assert lib.difr_admissible_count(C.byref(rows(N=0)), None, C.c_float(1.0), None, None, None) == OK
     # fused LM head
     from paper_2511_02620_amd.binding import _LmHead
 

@@ -145,6 +145,19 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     st_i = parity.compare_ipt({k: v[sel] for k, v in i.items()}, oi, host, wl.V, (f32(T), hs, hsid, hpos), 0.01)
     say(wl.name, "T=%g" % T, "gumbel", st_g)
     say(wl.name, "T=%g" % T, "ipt", st_i)
+    # admissible-set size on every row; the oracle's count on the sampled rows (an fp32 threshold decision:
+    # the GPU's count must lie between the oracle's counts at delta -/+ 2e-5)
+    a1 = difr.admissible_count(logits, T, seeds, sid, pos, g["max_score"], 1.0)
+    a2 = difr.admissible_count(logits, T, seeds, sid, pos, g["max_score"], 2.5)
+    torch.cuda.synchronize()
+    assert (a1["count"] >= 1).all() and (a1["count"] <= a2["count"]).all()
+    oa = oracle.admissible_count(host, wl.V, f32(T), hs, hsid, hpos, 2.5, tol=2e-5)
+    ca = a2["count"][sel].cpu().numpy()
+    assert (ca >= oa["count_lo"]).all() and (ca <= oa["count_hi"]).all()
+    sure = oa["count_lo"] == oa["count_hi"]
+    assert (ca[sure] == oa["count"][sure]).all()
+    say(wl.name, "T=%g" % T, "admissible set at delta 2.5: mean size %.2f over all rows, %d near-threshold sampled rows"
+        % (float(a2["count"].float().mean()), int((~sure).sum())))
     return g, i, sg, si, og, oi, st_g, st_i
 
 
