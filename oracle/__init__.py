@@ -87,6 +87,11 @@ def _load():
                                      f32p, u64p, i32p, u32p, i32p, C.c_double, C.c_double,
                                      f64p, f64p, f64p, f64p, i32p, f64p, f64p, u8p]
     lib.oracle_ipt_score.restype = C.c_int
+    lib.oracle_likelihood.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                      C.POINTER(C.c_float), C.POINTER(C.c_uint64), i32p, C.POINTER(C.c_uint32), i32p,
+                                      C.c_int64, C.c_double, C.c_int64, C.c_double, f64p, C.c_int64,
+                                      f64p, f64p, f64p, i32p, f64p, f64p]
+    lib.oracle_likelihood.restype = C.c_int
     lib.oracle_admissible_count_row.argtypes = [f64p, C.c_int64, C.c_double, C.c_uint64, C.c_uint32, C.c_uint32,
                                                 C.c_double, C.c_double, f64p, i32p, i32p, i32p]
     lib.oracle_admissible_count_row.restype = None
@@ -286,6 +291,31 @@ def ipt_score(logits, V, temperature, seeds, seq_ids, positions, claimed=None, t
                                   _ptr(out["edge"], C.c_double), _ptr(out["flags"], C.c_uint8))
     if rc:
         raise MemoryError("oracle_ipt_score")
+    return out
+
+
+def likelihood(logits, V, temperature, seeds, seq_ids, positions, claimed, top_k, top_p, s, sigma, z,
+               temperatures=None):
+    """Token-DiFR likelihood estimate per row.  z: the standard normal draws (float64 [M]).
+    Returns dict(pi, log_pi, tau, active [N, s], gap_s, gap_p)."""
+    a, dtype, ld = _logits_view(logits)
+    N = a.shape[0]
+    assert a.shape[1] >= V
+    seeds, seq_ids, positions, claimed, cp, temperatures, tp = _aux(N, seeds, seq_ids, positions, claimed,
+                                                                    temperatures)
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    s = int(s)
+    out = dict(pi=np.zeros(N), log_pi=np.zeros(N), tau=np.zeros(N), active=np.full((N, max(s, 1)), -1, np.int32),
+               gap_s=np.zeros(N), gap_p=np.zeros(N))
+    rc = _load().oracle_likelihood(a.ctypes.data, dtype, N, int(V), ld, float(temperature), tp,
+                                   _ptr(seeds, C.c_uint64), _ptr(seq_ids, C.c_int32), _ptr(positions, C.c_uint32),
+                                   cp, int(top_k), float(top_p), s, float(sigma), _ptr(z, C.c_double), z.shape[0],
+                                   _ptr(out["pi"], C.c_double), _ptr(out["log_pi"], C.c_double),
+                                   _ptr(out["tau"], C.c_double), _ptr(out["active"], C.c_int32),
+                                   _ptr(out["gap_s"], C.c_double), _ptr(out["gap_p"], C.c_double))
+    if rc:
+        raise MemoryError("oracle_likelihood")
+    out["active"] = out["active"][:, :s]
     return out
 
 

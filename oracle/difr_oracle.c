@@ -23,6 +23,9 @@
  *                                           for the Gumbel likelihood estimator
  *   - regenerate-and-compare per position . Sec. 5.1 and the appendix algorithm
  *                                           "verification via prefill"
+ *   - Token-DiFR likelihood estimate ...... Sec. 6.3, appendix algorithm of the
+ *                                           Gumbel-max FSSL estimator (active set,
+ *                                           filter threshold, A, B, noise average)
  *   - admissible set size ................. Sec. 7 (A_t(tau), log2 |A_t| bits per
  *                                           accepted token), appendix "Threshold
  *                                           selection and FPR-information trade-off"
@@ -56,7 +59,9 @@
  * of the k -> u -> g map and its moments; brute force with exact rationals and
  * multi-precision on tiny vocabularies; library softmax / cumsum / searchsorted;
  * chi-square of sample frequencies; Gumbel max-stability; scipy / mpmath normal
- * CDF; the admissible-set count against explicit sorting and its geometric law;
+ * CDF; the likelihood estimate against closed forms (no competitor, one competitor),
+ * a direct simulation of the noisy race it describes, explicit Python sorting for the
+ * active set and the filter threshold; the admissible-set count against explicit sorting and its geometric law;
  * the hidden-state-to-logits step against a library matrix product and
  * against the stored-logit entry points on inputs whose products are exact.
  * No function here is "parity unpinned".
@@ -436,6 +441,176 @@ int oracle_admissible_count(const void *logits, int dtype, int64_t N, int64_t V,
             int32_t s = seq_ids[n];
             oracle_admissible_count_row(x, V, T, seeds[s], (uint32_t)s, positions[n], delta, tol, x + V, &count[n],
                                         &count_lo[n], &count_hi[n]);
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-DiFR likelihood estimate of the claimed token (Sec. 6.3 and the        */
+/* appendix algorithm of the Gumbel-max FSSL estimator), in the algorithm's     */
+/* order and notation, Gaussian noise N(0, sigma^2) on every logit:             */
+/*   1. G_i for every token (as everywhere in this file).                       */
+/*   2. S = the s tokens with the largest l_i + T G_i, the claimed token left   */
+/*      out (a factor for i = t* would compare t* with itself); ties to the     */
+/*      lower index.                                                            */
+/*   3. tau = the smallest logit the sampler's filter keeps: top-k first (the   */
+/*      k largest logits), then top-p on the distribution renormalised over     */
+/*      those k (the shortest prefix, in descending logit order, whose          */
+/*      softmax(l/T) mass reaches p).  k <= 0: no top-k; p >= 1: no top-p;      */
+/*      neither: tau = -inf.  With k <= 0 the nucleus is taken over the whole   */
+/*      vocabulary.                                                             */
+/*   4. A_i = l_t* - l_i + T (G_t* - G_i),  B_i = tau - l_i   for i in S.       */
+/*   5. pi = (1/M) sum_j [l_t* + x_j > tau] prod_{i in S} Phi(max(x_j + A_i,    */
+/*      B_i) / sigma),  x_j = sigma z_j, with the M standard normal draws z_j   */
+/*      supplied by the caller (the algorithm samples them; drawing them is     */
+/*      not part of what is checked here).                                      */
+/* Outputs: pi, ln pi (-inf if pi = 0), tau, the set S (s indices, -1 padded,   */
+/* in rank order) and two gaps for the tests' near-tie rule: gap_s = distance   */
+/* between the last member of S and the best token left out, gap_p = distance   */
+/* of the nucleus' cumulative mass from p at the two prefixes around the cut.   */
+/* claimed outside [0,V): pi = NaN.                                             */
+/* ------------------------------------------------------------------------- */
+static double normal_cdf(double z) { return 0.5 * erfc(-z / M_SQRT2); }
+
+typedef struct {
+    double key;
+    int64_t idx;
+} keyed;
+
+static int keyed_desc(const void *a, const void *b)
+{
+    const keyed *p = (const keyed *)a, *q = (const keyed *)b;
+    if (p->key > q->key) return -1;
+    if (p->key < q->key) return 1;
+    return p->idx < q->idx ? -1 : (p->idx > q->idx ? 1 : 0);
+}
+
+int oracle_likelihood_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
+                          int64_t claimed, int64_t top_k, double top_p, int64_t s, double sigma, const double *z,
+                          int64_t M, double *pi, double *log_pi, double *tau_out, int32_t *S_out, double *gap_s,
+                          double *gap_p)
+{
+    keyed *a = (keyed *)malloc((size_t)(V > 0 ? V : 1) * sizeof(keyed));
+    double *g = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+    if (!a || !g) {
+        free(a);
+        free(g);
+        return 1;
+    }
+    /* 1. noise */
+    for (int64_t v = 0; v < V; ++v)
+        g[v] = oracle_uniform_to_gumbel(oracle_bits_to_uniform(oracle_noise_word(seed, seq, pos, ORACLE_STREAM_GUMBEL, (uint64_t)v)));
+    const int valid = claimed >= 0 && claimed < V;
+    /* 3. filter threshold (does not depend on the claim) */
+    double tau = -INFINITY;
+    *gap_p = INFINITY;
+    if (top_k > 0 || top_p < 1.0) {
+        for (int64_t v = 0; v < V; ++v) {
+            a[v].key = x[v];
+            a[v].idx = v;
+        }
+        qsort(a, (size_t)V, sizeof(keyed), keyed_desc);
+        int64_t kept = (top_k > 0 && top_k < V) ? top_k : V;
+        if (top_p < 1.0) {
+            double Z = 0.0;
+            for (int64_t r = 0; r < kept; ++r) Z += exp((a[r].key - a[0].key) / T);
+            double cum = 0.0;
+            int64_t cut = kept;
+            for (int64_t r = 0; r < kept; ++r) {
+                double before = cum;
+                cum += exp((a[r].key - a[0].key) / T) / Z;
+                if (cum >= top_p) {
+                    cut = r + 1;
+                    *gap_p = fmin(fabs(cum - top_p), fabs(top_p - before));
+                    break;
+                }
+            }
+            kept = cut;
+        }
+        tau = a[kept - 1].key;
+    }
+    *tau_out = tau;
+    for (int64_t j = 0; j < s; ++j) S_out[j] = -1;
+    *gap_s = INFINITY;
+    if (!valid) {
+        *pi = NAN;
+        *log_pi = NAN;
+        free(a);
+        free(g);
+        return 0;
+    }
+    /* 2. active set */
+    int64_t n = 0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (v == claimed) continue;
+        a[n].key = x[v] + T * g[v];
+        a[n].idx = v;
+        ++n;
+    }
+    qsort(a, (size_t)n, sizeof(keyed), keyed_desc);
+    const int64_t ns = s < n ? s : n;
+    if (ns > 0 && ns < n) *gap_s = (a[ns - 1].key - a[ns].key) / T; /* in units of l/T + G */
+    /* 4. */
+    double *A = (double *)malloc((size_t)(ns > 0 ? ns : 1) * 2 * sizeof(double)), *B = A + (ns > 0 ? ns : 1);
+    if (!A) {
+        free(a);
+        free(g);
+        return 1;
+    }
+    for (int64_t j = 0; j < ns; ++j) {
+        const int64_t i = a[j].idx;
+        S_out[j] = (int32_t)i;
+        A[j] = x[claimed] - x[i] + T * (g[claimed] - g[i]);
+        B[j] = tau - x[i];
+    }
+    /* 5. */
+    double acc = 0.0;
+    for (int64_t j = 0; j < M; ++j) {
+        const double xj = sigma * z[j];
+        if (x[claimed] + xj > tau) {
+            double prod = 1.0;
+            for (int64_t i = 0; i < ns; ++i) prod *= normal_cdf(fmax(xj + A[i], B[i]) / sigma);
+            acc += prod;
+        }
+    }
+    *pi = M > 0 ? acc / (double)M : NAN;
+    *log_pi = log(*pi);
+    free(A);
+    free(a);
+    free(g);
+    return 0;
+}
+
+int oracle_likelihood(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, double temperature,
+                      const float *temperatures, const uint64_t *seeds, const int32_t *seq_ids,
+                      const uint32_t *positions, const int32_t *claimed, int64_t top_k, double top_p, int64_t s,
+                      double sigma, const double *z, int64_t M, double *pi, double *log_pi, double *tau,
+                      int32_t *S_out, double *gap_s, double *gap_p)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t sq = seq_ids[n];
+            int64_t t = claimed ? (int64_t)claimed[n] : -1;
+            if (oracle_likelihood_row(x, V, T, seeds[sq], (uint32_t)sq, positions[n], t, top_k, top_p, s, sigma, z, M,
+                                      &pi[n], &log_pi[n], &tau[n], S_out + (size_t)n * (size_t)(s > 0 ? s : 0),
+                                      &gap_s[n], &gap_p[n])) {
+#pragma omp atomic write
+                failed = 1;
+            }
         }
         free(x);
     }
