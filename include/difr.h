@@ -167,6 +167,38 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                     uint8_t *flags_ipt, void *hip_stream);
 
 /*
+ * Token-DiFR likelihood estimate of the claimed token.  [Sec. 6.3; appendix algorithm of the Gumbel-max FSSL
+ * estimator.]  Per row, with G the regenerated Gumbel noise and Gaussian noise N(0, sigma^2) on every logit:
+ *   S     = the s tokens with the largest x_i + T G_i, the claimed token t left out (ties to the lower index);
+ *   tau   = the smallest logit the sampler's filter keeps: top_k largest logits, then top_p on the distribution
+ *           renormalised over those (shortest prefix in descending logit order whose softmax(x/T) mass reaches
+ *           top_p).  top_k = 0: no top-k; top_p >= 1: no top-p; neither: tau = -inf.  top_p < 1 needs top_k > 0
+ *           here (DIFR_ERR_UNSUPPORTED otherwise: a nucleus over the whole vocabulary is not built);
+ *   A_i   = x_t - x_i + T (G_t - G_i),  B_i = tau - x_i   for i in S;
+ *   pi    = (1/M) sum_j [x_t + sigma z_j > tau] prod_{i in S} Phi(max(sigma z_j + A_i, B_i) / sigma).
+ * p->z  DEVICE [M] fp32 standard normal draws, supplied by the caller and shared by all rows (the algorithm
+ *       samples them; how is the caller's business: pseudo-random, stratified quantiles, a quadrature rule).
+ * Limits: 0 <= s <= 256, 0 <= top_k <= 256, M >= 1, sigma > 0, top_p > 0 (else DIFR_ERR_ARGUMENT); rows must
+ *       be 16-byte aligned (DIFR_ERR_ALIGN).
+ * Outputs (DEVICE): pi [N] fp32; log_pi [N] fp32 or NULL (natural log, -inf if pi = 0; this is the FSSL score
+ *       the paper thresholds); tau [N] fp32 or NULL; active [N, s] int32 or NULL (S in rank order, -1 padded);
+ *       flags [N] (DIFR_FLAG_INVALID_CLAIM: pi NaN; DIFR_FLAG_NONFINITE).  Which tokens are in S is decided on
+ *       fp32 scores; A_i, B_i and the average are then formed in fp64 / fp32 from exact logits and fp64 noise.
+ * One pass over the logits.
+ */
+typedef struct {
+    int32_t top_k;
+    float top_p;
+    int32_t s;
+    float sigma;
+    int32_t M;
+    const float *z;
+} difr_likelihood_params;
+
+int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p, float *pi, float *log_pi, float *tau,
+                           int32_t *active, uint8_t *flags, void *hip_stream);
+
+/*
  * Size of each row's admissible set.  [Sec. 7, "admissible set" A_t(tau) = { i : FSSL_t(i) >= tau }: an accepted
  * token carries at most log2 |A_t(tau)| bits, a sequence at most the sum; appendix "Threshold selection and
  * FPR-information trade-off".]  With the Token-DiFR margin as the score (suspiciousness, accepted when small):

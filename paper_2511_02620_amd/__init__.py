@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     classify,
     debug_gumbel_map,
     debug_noise,
+    gumbel_likelihood,
     gumbel_score,
     ipt_score,
     lib_path,

@@ -68,7 +68,12 @@ class _LmHead(C.Structure):
     ]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+class _LikelihoodParams(C.Structure):
+    _fields_ = [("top_k", C.c_int32), ("top_p", C.c_float), ("s", C.c_int32), ("sigma", C.c_float),
+                ("M", C.c_int32), ("z", C.c_void_p)]
+
+
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_gumbel_likelihood", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -93,6 +98,8 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
     lib.difr_score_both.restype = C.c_int
+    lib.difr_gumbel_likelihood.argtypes = [C.POINTER(_Rows), C.POINTER(_LikelihoodParams), vp, vp, vp, vp, vp, vp]
+    lib.difr_gumbel_likelihood.restype = C.c_int
     lib.difr_admissible_count.argtypes = [C.POINTER(_Rows), vp, C.c_float, vp, vp, vp]
     lib.difr_admissible_count.restype = C.c_int
     lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
@@ -253,6 +260,28 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if rc:
         raise DifrError(rc, "difr_score_both")
     return g, i
+
+
+def gumbel_likelihood(logits, temperature, seeds, seq_ids, positions, claimed, z, top_k=0, top_p=1.0, s=16, sigma=1.0,
+                      temperatures=None, V=None, want_active=False):
+    """difr_gumbel_likelihood.  z: fp32 [M] standard normal draws on the GPU.  Returns a dict of device tensors."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
+    if z.device != dev or z.dtype != torch.float32 or z.dim() != 1 or not z.is_contiguous():
+        raise ValueError("z must be a contiguous 1-D float32 tensor on the device of logits")
+    p = _LikelihoodParams(int(top_k), float(top_p), int(s), float(sigma), z.shape[0], z.data_ptr())
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(pi=torch.empty(N, **f32), log_pi=torch.empty(N, **f32), tau=torch.empty(N, **f32),
+               flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_active:
+        out["active"] = torch.empty(N, max(int(s), 1), dtype=torch.int32, device=dev)[:, :int(s)].contiguous()
+    with torch.cuda.device(dev):
+        rc = lib.difr_gumbel_likelihood(C.byref(r), C.byref(p), _ptr(out["pi"]), _ptr(out["log_pi"]), _ptr(out["tau"]),
+                                        _ptr(out.get("active")) if int(s) > 0 else None, _ptr(out["flags"]),
+                                        _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_gumbel_likelihood")
+    return out
 
 
 def admissible_count(logits, temperature, seeds, seq_ids, positions, max_score, delta, temperatures=None, V=None,

@@ -205,6 +205,26 @@ int difr_admissible_count(const difr_rows *in, const float *max_score, float del
                : DIFR_OK;
 }
 
+int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p, float *pi, float *log_pi, float *tau,
+                           int32_t *active, uint8_t *flags, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (!p) return DIFR_ERR_NULL;
+    if (p->s < 0 || p->s > 256 || p->top_k < 0 || p->top_k > 256 || p->M < 1) return DIFR_ERR_ARGUMENT;
+    if (!(p->sigma > 0.0f) || !isfinite(p->sigma) || !(p->top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
+    if (p->top_k == 0 && p->top_p < 1.0f) return DIFR_ERR_UNSUPPORTED;
+    if (b.N == 0) return DIFR_OK;
+    if (!pi || !flags || !p->z) return DIFR_ERR_NULL;
+    if (!aligned) return DIFR_ERR_ALIGN;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z};
+    const difr::LikelihoodOutputs lo{pi, log_pi, tau, active, flags};
+    return difr::launch_likelihood(b, lp, lo, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
+
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                     uint8_t *flags_ipt, void *hip_stream)

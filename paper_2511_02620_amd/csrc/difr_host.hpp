@@ -24,6 +24,21 @@ struct IptOutputs;
 // Both estimators in one pass (aligned rows only).
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
                       hipStream_t stream);
+// Token-DiFR likelihood estimate (aligned rows only).
+struct LikelihoodParams {
+    int32_t top_k;   // 0 = no top-k
+    float top_p;     // >= 1 = no top-p
+    int32_t s;       // active-set size, 0 .. 256
+    float sigma;     // standard deviation of the Gaussian logit noise
+    int32_t M;       // number of draws
+    const float *z;  // DEVICE [M] standard normal draws
+};
+struct LikelihoodOutputs {
+    float *pi, *log_pi, *tau;
+    int32_t *active;  // [N, s] or null
+    uint8_t *flags;
+};
+int launch_likelihood(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o, hipStream_t stream);
 struct LmHeadBatch;
 struct LmHeadWorkspace;
 struct LmHeadPlan;

@@ -6,6 +6,7 @@
 #include <type_traits>
 
 #include "difr_device.hpp"
+#include "topn.hpp"
 
 namespace difr {
 
@@ -127,7 +128,10 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 // COUNT: instead of tracking the best score, count the entries whose score is within `delta` of a
 // maximum that is already known (the admissible set of Sec. 7: tokens the verifier would accept).
 // The same gates apply with the fixed bound M - delta; nothing ever raises it.
-template <int DT, bool RANK, bool COUNT = false>
+//
+// TOPN: instead of tracking the best score, push every score that may belong to the n largest of the
+// row (the claimed token left out) into a TopN buffer; the gates use the buffer's threshold as the bound.
+template <int DT, bool RANK, bool COUNT = false, bool TOPN = false>
 struct GumbelStream {
     typedef typename Elem<DT>::type elt_t;
     static constexpr int E = Elem<DT>::kPerVec;
@@ -153,6 +157,8 @@ struct GumbelStream {
     // COUNT mode
     float count_M, count_delta;
     uint32_t count;
+    // TOPN mode
+    TopN *top;
 
     // Computes the claimed token's score with the same function the stream uses (the first lower
     // bound) and publishes it.  The caller must __syncthreads() before the first process().
@@ -186,6 +192,21 @@ struct GumbelStream {
         asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
         count_M = count_delta = 0.0f;
         count = 0;
+        top = nullptr;
+    }
+
+    // TOPN mode: scores go to `top_`; the bound is its threshold (call retarget() whenever that moves).
+    // Same synchronisation rules as arm_count().
+    __device__ __forceinline__ void arm_topn(TopN *top_)
+    {
+        top = top_;
+        retarget();
+    }
+    __device__ __forceinline__ void retarget()
+    {
+        const float bound = top->theta == 0ull ? -__builtin_inff() : (top->theta == ~0ull ? 3.0e38f : top_key(top->theta));
+        gate = make_gate(bound, T);
+        if ((tid & 63) == 0) lds_L[wave] = gate.L;
     }
 
     // COUNT mode: fix the bound at M - delta.  Call after the constructor's publication has been
@@ -207,6 +228,10 @@ struct GumbelStream {
         bad |= (uint32_t)!(xv < __builtin_inff());
         if (COUNT) {
             count += (uint32_t)(count_M - y <= count_delta);  // the margin of entry v, in the kernel's precision
+            return;
+        }
+        if (TOPN) {
+            if (y == y && v != t) top->push(top_composite(y, v));
             return;
         }
         if (y > best_y || (y == best_y && v < best_v)) {

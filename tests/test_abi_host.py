@@ -119,6 +119,23 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_classify(fake, fake, 4, 0.0, 8, 100, None, None, None, None) == NULL
     assert lib.difr_classify(fake, fake, 4, float("nan"), 8, 100, None, fake, None, None) == ARG
     assert lib.difr_classify(None, None, 0, 0.0, 8, 100, None, None, None, None) == OK
+    # likelihood estimate
+    from paper_2511_02620_amd.binding import _LikelihoodParams
+
+    def lik(r=None, pi=fake, fl=fake, **kw):
+        prm = dict(top_k=50, top_p=0.95, s=16, sigma=0.5, M=64, z=fake)
+        prm.update(kw)
+        p = _LikelihoodParams(prm["top_k"], prm["top_p"], prm["s"], prm["sigma"], prm["M"], prm["z"])
+        return lib.difr_gumbel_likelihood(C.byref(r or rows()), C.byref(p), pi, None, None, None, fl, None)
+
+    for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0),
+               dict(sigma=float("nan")), dict(top_p=0.0)):
+        assert lik(**kw) == ARG, kw
+    assert lik(top_k=0, top_p=0.9) == 7                      # DIFR_ERR_UNSUPPORTED: nucleus over the whole vocabulary
+    assert lik(z=None) == NULL and lik(pi=None) == NULL and lik(fl=None) == NULL
+    assert lik(rows(V=0)) == SHAPE and lik(rows(N=0), pi=None, fl=None, z=None) == OK
+    assert lik(rows(V=15, ld=15)) == ALIGN                   # rows not 16-byte aligned
+    assert lib.difr_gumbel_likelihood(C.byref(rows()), None, fake, None, None, None, fake, None) == NULL
     # admissible-set size
     assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(-1.0), fake, None, None) == ARG
     assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(float("nan")), fake, None, None) == ARG
