@@ -46,6 +46,7 @@ GUMBEL_ALU_OPS_PER_ENTRY = 11
 # ... and of the softmax statistics of the IPT estimator: scale-and-shift, exponential, sum, running maximum.
 IPT_ALU_OPS_PER_ENTRY = 4
 ADMISSIBLE_DELTA = 2.5         # margin threshold of the admissible-set count timed next to the step
+LIKELIHOOD = {"top_k": 50, "top_p": 0.95, "s": 16, "sigma": 0.3, "M": 256}   # likelihood estimate timed next to it
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 4 GiB device copy (profiles/c3_hbm_traffic.md).
@@ -316,8 +317,12 @@ def main():
         t_g = time_alone(lambda: difr.gumbel_score(*row_args, data["claims_g"]), reps)
         t_i = time_alone(lambda: difr.ipt_score(*row_args, data["claims_i"]), reps)
         t_a = time_alone(lambda: difr.admissible_count(*row_args, out[0]["max_score"], ADMISSIBLE_DELTA), reps)
+        zl = torch.randn(LIKELIHOOD["M"], generator=torch.Generator().manual_seed(5)).to(dev)
+        t_l = time_alone(lambda: difr.gumbel_likelihood(*row_args, data["claims_g"], zl, top_k=LIKELIHOOD["top_k"],
+                                                        top_p=LIKELIHOOD["top_p"], s=LIKELIHOOD["s"],
+                                                        sigma=LIKELIHOOD["sigma"]), reps)
     else:
-        t_b = t_a = None
+        t_b = t_a = t_l = None
         t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
@@ -383,7 +388,10 @@ def main():
                     "difr_seq_reduce_x2": {"ms": round(t_r, 4)},
                     "difr_admissible_count": None if t_a is None else
                     {"ms": round(t_a, 4), "delta": ADMISSIBLE_DELTA, "tokens_per_s": round(wl.N / (t_a * 1e-3), 1),
-                     "hbm_gbs": round(wl.N * (wl.V * esz + 24) / (t_a * 1e-3) / 1e9, 1)}},
+                     "hbm_gbs": round(wl.N * (wl.V * esz + 24) / (t_a * 1e-3) / 1e9, 1)},
+                    "difr_gumbel_likelihood": None if t_l is None else
+                    dict(LIKELIHOOD, ms=round(t_l, 4), tokens_per_s=round(wl.N / (t_l * 1e-3), 1),
+                         hbm_gbs=round(wl.N * (wl.V * esz + 24) / (t_l * 1e-3) / 1e9, 1))},
         "match_rate": {"gumbel": round(match_g, 5), "ipt": round(match_i, 5)},
     }
     if args.cpu_rows > 0:

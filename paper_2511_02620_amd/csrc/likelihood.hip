@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     __shared__ uint64_t buf_y[kTopCap];
     __shared__ uint64_t buf_x[kTopCap];
     __shared__ TopScratch scratch;
-    __shared__ int32_t cnt_y, cnt_x;
+    __shared__ int32_t cnt_y, cnt_x, snap_y, snap_x;
     __shared__ float lds_L[kWaves];
     __shared__ double lds_d[kWaves];
     __shared__ double sA[kTopMaxN], sB[kTopMaxN];
@@ -68,45 +68,125 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     TopN top_y, top_x;
     top_y.init(buf_y, &cnt_y, valid ? p.s : 0);
     top_x.init(buf_x, &cnt_x, p.top_k);
-    if (tid == 0) s_bad = 0;
+    if (tid == 0) {
+        s_bad = 0;
+        snap_y = snap_x = 0;
+    }
     GumbelStream<DT, false, false, true> g(ri, x_row, V, lds_L);
     __syncthreads();
     g.arm_topn(&top_y);
     __syncthreads();
     uint32_t bad = 0;
 
-    // raw-logit candidates of one vector
+    // raw-logit candidates of one vector.  First a test of the whole vector against the selection's threshold
+    // (bf16: packed 16-bit min / max on the raw bit patterns, as in the Gumbel gates; a NaN with the sign bit
+    // clear passes it and is flagged below, one with the sign bit set counts as -inf), then the 64-bit
+    // composite only for the entries that pass.
+    float x_floor = -__builtin_inff();
+    uint32_t x_floor16 = cap_bits(x_floor, true);
+    bool x_floor_pos = false;
+    auto set_x_floor = [&](float f) {
+        x_floor = f;
+        x_floor_pos = f > 0.0f;
+        x_floor16 = cap_bits(f, !x_floor_pos);
+    };
     auto push_logits = [&](u32x4 q, int64_t v0, bool active) {
-        if (!active) return;
-        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+        bool hit;
+        if (DT == 0) {
+            if (x_floor_pos) {
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                hit = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)x_floor16;
+            } else {
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                hit = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)x_floor16;
+            }
+        } else {
+            hit = !(__uint_as_float(q.x) < x_floor) || !(__uint_as_float(q.y) < x_floor) ||
+                  !(__uint_as_float(q.z) < x_floor) || !(__uint_as_float(q.w) < x_floor);
+        }
+        hit = hit && active;
+        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+            if (hit) {
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int j = 0; j < E; ++j) {
-            const uint32_t w = qw[DT == 0 ? j >> 1 : j];
-            const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
-            bad |= (uint32_t)!(xv < __builtin_inff());
-            if (xv == xv) top_x.push(top_composite(xv, (int32_t)(v0 + j)));
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+                    bad |= (uint32_t)!(xv < __builtin_inff());
+                    if (xv >= x_floor) top_x.push(top_composite(xv, (int32_t)(v0 + j)));
+                }
+            }
         }
     };
-    // after the pushes of a round: compact whichever buffer is half full
+    // compaction of whichever buffer has reached its trigger (uniform decisions through the barrier
+    // reduction, which returns a truth value: one call per buffer)
     auto settle = [&]() {
-        // (the barrier reduction returns a truth value, not the OR of the bits: one call per buffer)
         if (__syncthreads_or((int)top_y.full)) {
-            if (top_y.compact(scratch)) g.retarget();
+            if (top_y.compact(scratch, true)) g.retarget();
         }
-        if (p.top_k > 0 && __syncthreads_or((int)top_x.full)) top_x.compact(scratch);
+        if (p.top_k > 0 && __syncthreads_or((int)top_x.full)) {
+            top_x.compact(scratch, true);
+            set_x_floor(top_key(top_x.theta));
+        }
     };
 
     const int64_t nvec = V / E;
     const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);
-    for (int round = 0; round < n_rounds; ++round) {
+    auto fetch = [&](int round) {
+        u32x4 q = u32x4{0u, 0u, 0u, 0u};
+        if ((int64_t)round * kBlock + tid < nvec) q = load_round(x_row, round);
+        return q;
+    };
+    auto do_round = [&](u32x4 q, int round) {
         const int64_t vec = (int64_t)round * kBlock + tid;
         const bool active = vec < nvec;
-        u32x4 q = u32x4{0u, 0u, 0u, 0u};
-        if (active) q = load_round(x_row, round);
         g.process_any(q, round, active);
         if (p.top_k > 0) push_logits(q, vec * E, active);
-        settle();
+    };
+    // Epochs: the first round alone (every entry is a candidate while there is no threshold: exactly the
+    // quota), then eight rounds at a time without a barrier.
+    int round = 0;
+    while (round < n_rounds) {
+        const int r_end = min(n_rounds, round + (round == 0 ? 1 : 8));
+        top_y.new_epoch(kTopQuota);
+        top_x.new_epoch(kTopQuota);
+        u32x4 q_next = fetch(round);
+        for (int r = round; r < r_end; ++r) {
+            const u32x4 q = q_next;
+            if (r + 1 < r_end) q_next = fetch(r + 1);  // keep one vector in flight
+            do_round(q, r);
+        }
+        if (__syncthreads_or((int)(top_y.over || top_x.over))) {
+            // some thread had more candidates than its quota (data in ascending order, for instance):
+            // forget the epoch and repeat it round by round, compacting whenever a trigger is reached
+            if (tid == 0) {
+                cnt_y = snap_y;
+                cnt_x = snap_x;
+            }
+            top_y.new_epoch(0x7FFFFFFF);
+            top_x.new_epoch(0x7FFFFFFF);
+            top_y.full = top_x.full = false;
+            __syncthreads();
+            for (int r = round; r < r_end; ++r) {
+                do_round(fetch(r), r);
+                settle();
+            }
+        } else {
+            settle();
+        }
+        if (tid == 0) {
+            snap_y = cnt_y;
+            snap_x = cnt_x;
+        }
+        __syncthreads();
+        round = r_end;
     }
+    top_y.new_epoch(kTopQuota);  // the tail: at most one entry per thread
+    top_x.new_epoch(kTopQuota);
     // ragged tail: V % E entries, one lane each
     g.tail();
     {
@@ -114,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         if (v < V && p.top_k > 0) {
             const float xv = Elem<DT>::to_float(x_row[v]);
             bad |= (uint32_t)!(xv < __builtin_inff());
-            if (xv == xv) top_x.push(top_composite(xv, (int32_t)v));
+            if (xv >= x_floor) top_x.push(top_composite(xv, (int32_t)v));
         }
     }
     if (bad) s_bad = 1;
@@ -167,12 +247,12 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     // average over the supplied draws
     double acc = 0.0;
     if (valid) {
-        const double sigma = (double)p.sigma;
+        const double sigma = (double)p.sigma, inv_sigma = 1.0 / sigma;
         for (int j = tid; j < p.M; j += kBlock) {
             const double xj = sigma * (double)p.z[j];
             if (xt + xj > tau) {
                 float prod = 1.0f;
-                for (int i = 0; i < ns; ++i) prod *= normal_cdf_f32((float)(fmax(xj + sA[i], sB[i]) / sigma));
+                for (int i = 0; i < ns; ++i) prod *= normal_cdf_f32((float)(fmax(xj + sA[i], sB[i]) * inv_sigma));
                 acc += (double)prod;
             }
         }

@@ -3,21 +3,30 @@
 // Candidates are pushed into an LDS buffer as 64-bit composites (order-preserving image of the float
 // key in the high word, complemented index in the low word: a larger composite is a larger key or,
 // for equal keys, a smaller index, so all composites of a row are distinct).  Only composites above the
-// current threshold are pushed.  When the buffer is half full the workgroup finds the n-th largest
-// composite with a radix select (8 passes of 8 bits over the buffer), makes it the new threshold and
-// keeps exactly the n entries at or above it.  A round of the row stream pushes at most 2048 entries
-// (256 lanes x 8), so with 4096 slots and a check after every round the buffer never overflows, whatever
-// the order of the data; nothing that belongs to the final top n is ever dropped, because the threshold
-// is always the n-th largest of what has been seen and only grows.
+// current threshold are pushed.  A compaction finds a lower bound of the n-th largest composite with a
+// radix select over the buffer, makes it the new threshold and keeps the entries at or above it.  In the
+// stream the select stops after the top 16 bits of the key (2 passes of 8 bits: the n-th largest key at
+// bf16 resolution, a handful of entries too many survive) unless more than kTopKeep entries share them;
+// all 8 passes, down to the exact n-th composite, run at the end of the row.  Nothing that belongs to the
+// final top n is ever dropped: the threshold is a lower bound of the n-th largest of what has been seen.
+//
+// Capacity.  The caller works in epochs of a few stream rounds without any barrier.  Within an epoch a
+// thread may push at most kTopQuota entries; one that needs more raises `over` instead, and the caller
+// rewinds the epoch (resets the counter to its value at the epoch's start) and repeats it round by round
+// with a compaction check after every round.  An epoch starts with fewer than kTopTrigger entries, so
+// the buffer never holds more than kTopTrigger + 256 * kTopQuota = kTopCap entries either way (a round
+// is at most 8 entries per thread), whatever the order of the data.
 #pragma once
 
 #include "difr_device.hpp"
 
 namespace difr {
 
-constexpr int kTopCap = 4096;      // slots per buffer
-constexpr int kTopTrigger = 2048;  // compact when this many slots are used
+constexpr int kTopQuota = 8;       // pushes per thread and epoch
+constexpr int kTopTrigger = 512;   // a compaction is due at the latest when this many slots are used
+constexpr int kTopCap = kTopTrigger + 256 * kTopQuota;  // slots per buffer
 constexpr int kTopMaxN = 256;      // largest n supported
+constexpr int kTopKeep = 256;      // a coarse compaction may leave up to this many entries
 
 // float -> uint32 such that a < b  <=>  image(a) < image(b)  (-0 < +0; NaNs must be kept out by the caller)
 __device__ __forceinline__ uint32_t float_order_bits(float f)
@@ -41,7 +50,7 @@ struct TopScratch {
     int32_t hist[256];
     int32_t wave_sum[kWaves];
     int32_t sel_bin, sel_need, kept;
-    uint64_t tmp[kTopMaxN];
+    uint64_t tmp[kTopKeep];
 };
 
 struct TopN {
@@ -49,8 +58,12 @@ struct TopN {
     int32_t *count;  // in LDS
     int n;
     uint64_t theta;  // wave-uniform copy of the threshold: only composites above it are pushed
+    int trigger;     // fill level at which the next compaction is due: max(n, 64) pushes after the last one, so
+                     // that the threshold, which is also the bound of the stream's gates, stays fresh
     bool full;       // this thread's push took the buffer to the compaction trigger (combine over the workgroup
                      // with __syncthreads_or: reading the counter instead would race with the next round's pushes)
+    int quota;       // pushes this thread may still make in the current epoch
+    bool over;       // this thread had a candidate beyond its quota: the epoch must be repeated
 
     __device__ __forceinline__ void init(uint64_t *buf_, int32_t *count_, int n_)
     {
@@ -58,23 +71,39 @@ struct TopN {
         count = count_;
         n = n_;
         theta = n_ > 0 ? 0ull : ~0ull;  // nothing wanted: nothing is ever pushed
+        trigger = n_ > 64 ? n_ : 64;
         full = false;
+        quota = kTopQuota;
+        over = false;
         if (threadIdx.x == 0) *count = 0;
+    }
+
+    __device__ __forceinline__ void new_epoch(int quota_)
+    {
+        quota = quota_;
+        over = false;
     }
 
     __device__ __forceinline__ void push(uint64_t c)
     {
         if (c > theta) {
+            if (quota <= 0) {
+                over = true;
+                return;
+            }
+            --quota;
             const int32_t i = atomicAdd(count, 1);
             if (i < kTopCap) buf[i] = c;  // always true by construction (see the header comment)
-            if (i >= kTopTrigger - 1) full = true;
+            if (i >= trigger - 1) full = true;
         }
     }
 
-    // All 256 threads, after a __syncthreads() that follows the pushes.  If the buffer holds more than n
-    // entries, reduce it to the n largest and raise the threshold to the smallest of them.  Returns true if
-    // the threshold moved.  Ends with a __syncthreads().
-    __device__ bool compact(TopScratch &s)
+    // All 256 threads, after a barrier that follows the pushes.  If the buffer holds more than n entries,
+    // raise the threshold to a lower bound of the n-th largest composite and keep only the entries at or
+    // above it: exactly the n largest (coarse = false), or at most kTopKeep of them chosen at the
+    // resolution of the top 16 key bits (coarse = true).  Returns true if the threshold moved.  Ends with
+    // a __syncthreads().
+    __device__ bool compact(TopScratch &s, bool coarse = false)
     {
         const int tid = threadIdx.x;
         const int cnt = min(*count, kTopCap);
@@ -87,12 +116,15 @@ struct TopN {
             return true;
         }
         if (cnt <= n) {
+            trigger = min(kTopTrigger, cnt + (n > 64 ? n : 64));
             __syncthreads();
             return false;
         }
         uint64_t prefix = 0ull, mask = 0ull;
-        int need = n;
+        int need = n;        // rank of the wanted composite among the entries that match the prefix
+        int at_or_above = cnt;  // entries at or above the prefix found so far (unset low bits zero)
         for (int pass = 7; pass >= 0; --pass) {
+            if (coarse && pass < 6 && at_or_above <= kTopKeep) break;
             const int shift = 8 * pass;
             s.hist[tid] = 0;
             __syncthreads();
@@ -101,7 +133,7 @@ struct TopN {
                 if ((c & mask) == prefix) atomicAdd(&s.hist[(int)((c >> shift) & 255ull)], 1);
             }
             __syncthreads();
-            // suffix sums over the 256 bins: thread b gets the number of entries in bins >= b
+            // suffix sums over the 256 bins: thread b gets the number of matching entries in bins >= b
             int v = s.hist[tid];
             const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
@@ -112,60 +144,55 @@ struct TopN {
             if (lane == 0) s.wave_sum[wave] = v;
             __syncthreads();
             for (int w = wave + 1; w < kWaves; ++w) v += s.wave_sum[w];
-            const int above = v - s.hist[tid];  // entries in bins > tid
+            const int above = v - s.hist[tid];  // matching entries in bins > tid
             if (above < need && v >= need) {    // exactly one thread
                 s.sel_bin = tid;
                 s.sel_need = need - above;
+                s.kept = (n - need) + v;
             }
             __syncthreads();
             prefix |= (uint64_t)s.sel_bin << shift;
             mask |= 255ull << shift;
             need = s.sel_need;
+            at_or_above = s.kept;
             __syncthreads();
         }
-        // prefix is now the n-th largest composite; keep the n entries at or above it
+        // gather the survivors (at_or_above <= kTopKeep of them) and move them to the front
         if (tid == 0) s.kept = 0;
         __syncthreads();
         for (int i = tid; i < cnt; i += kBlock) {
             const uint64_t c = buf[i];
             if (c >= prefix) {
                 const int j = atomicAdd(&s.kept, 1);
-                if (j < kTopMaxN) s.tmp[j] = c;
+                if (j < kTopKeep) s.tmp[j] = c;
             }
         }
         __syncthreads();
-        if (tid < n) buf[tid] = s.tmp[tid];
-        if (tid == 0) *count = n;
+        for (int i = tid; i < at_or_above; i += kBlock) buf[i] = s.tmp[i];
+        if (tid == 0) *count = at_or_above;
         theta = prefix;
+        trigger = min(kTopTrigger, at_or_above + (n > 64 ? n : 64));
         __syncthreads();
         return true;
     }
 
-    // All 256 threads: final compaction, then sort the survivors in descending order into buf[0 .. m),
-    // m = min(n, entries seen); returns m.  Bitonic network over 256 slots (empty slots hold 0, which sorts last).
+    // All 256 threads: reduce to exactly the n largest, then order them.  Afterwards buf[0 .. m) holds them in
+    // descending order, m = min(n, entries seen); returns m.  Each survivor finds its rank by counting the
+    // survivors above it (m <= 256 broadcast reads, no barriers).
     __device__ int finish_sorted(TopScratch &s)
     {
         const int tid = threadIdx.x;
         __syncthreads();
-        compact(s);
+        compact(s, false);
         const int m = min(min(*count, kTopCap), n);
-        uint64_t mine = tid < m ? buf[tid] : 0ull;
-        __syncthreads();
-        s.tmp[tid] = mine;
-        __syncthreads();
-        for (int k = 2; k <= kTopMaxN; k <<= 1) {
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                const int partner = tid ^ j;
-                const uint64_t a = s.tmp[tid], b = s.tmp[partner];
-                const bool descending = (tid & k) == 0;
-                const bool keep_larger = (tid < partner) == descending;
-                const uint64_t mine2 = keep_larger ? (a > b ? a : b) : (a > b ? b : a);
-                __syncthreads();
-                s.tmp[tid] = mine2;
-                __syncthreads();
-            }
+        if (tid < m) {
+            const uint64_t mine = buf[tid];
+            int rank = 0;
+            for (int i = 0; i < m; ++i) rank += (int)(buf[i] > mine);
+            s.tmp[rank] = mine;
         }
-        buf[tid] = s.tmp[tid];
+        __syncthreads();
+        if (tid < m) buf[tid] = s.tmp[tid];
         __syncthreads();
         return m;
     }

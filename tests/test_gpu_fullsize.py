@@ -158,6 +158,26 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     assert (ca[sure] == oa["count"][sure]).all()
     say(wl.name, "T=%g" % T, "admissible set at delta 2.5: mean size %.2f over all rows, %d near-threshold sampled rows"
         % (float(a2["count"].float().mean()), int((~sure).sum())))
+    # Token-DiFR likelihood estimate with the paper's generation policy (top-k 50, top-p 0.95) on every row;
+    # the oracle on the first 384 sampled rows (it sorts the whole vocabulary twice per row)
+    z = torch.randn(256, generator=torch.Generator().manual_seed(5), dtype=torch.float32)
+    lk = difr.gumbel_likelihood(logits, T, seeds, sid, pos, cg, z.to(DEV), top_k=50, top_p=0.95, s=16, sigma=0.3,
+                                want_active=True)
+    torch.cuda.synchronize()
+    pi_all = lk["pi"]
+    assert ((pi_all >= 0) & (pi_all <= 1)).all() and (lk["flags"] == 0).all()
+    sub = sample_rows[:384]
+    ssel = torch.tensor(sub, dtype=torch.int64, device=DEV)
+    ol = oracle.likelihood(host[:384], wl.V, f32(T), hs, hsid[:384], hpos[:384], cg[ssel].cpu().numpy(), 50,
+                           float(f32(0.95)), 16, float(f32(0.3)), z.double().numpy())
+    assert np.array_equal(lk["tau"][ssel].cpu().numpy(), ol["tau"].astype(np.float32))
+    diff = (lk["active"][ssel].cpu().numpy() != ol["active"]).any(axis=1)
+    excused = diff & (ol["gap_s"] < 1e-5)
+    assert not (diff & ~excused).any()
+    perr = np.where(excused, 0.0, np.abs(lk["pi"][ssel].cpu().numpy().astype(np.float64) - ol["pi"]))
+    assert perr.max() <= 1e-4
+    say(wl.name, "T=%g" % T, "likelihood: mean pi %.4f over all rows, worst error %.3g on %d oracle rows, %d excused"
+        % (float(pi_all.mean()), perr.max(), len(sub), int(excused.sum())))
     return g, i, sg, si, og, oi, st_g, st_i
 
 
