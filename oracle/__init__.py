@@ -87,6 +87,11 @@ def _load():
                                      f32p, u64p, i32p, u32p, i32p, C.c_double, C.c_double,
                                      f64p, f64p, f64p, f64p, i32p, f64p, f64p, u8p]
     lib.oracle_ipt_score.restype = C.c_int
+    lib.oracle_ipt_filtered_score.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                              C.POINTER(C.c_float), C.POINTER(C.c_uint64), i32p,
+                                              C.POINTER(C.c_uint32), i32p, C.c_int64, C.c_double, C.c_double,
+                                              C.c_double, f64p, f64p, f64p, f64p, i32p, f64p, f64p, i32p, f64p, u8p]
+    lib.oracle_ipt_filtered_score.restype = C.c_int
     lib.oracle_likelihood.argtypes = [C.c_void_p, C.c_int, C.c_int64, C.c_int64, C.c_int64, C.c_double,
                                       C.POINTER(C.c_float), C.POINTER(C.c_uint64), i32p, C.POINTER(C.c_uint32), i32p,
                                       C.c_int64, C.c_double, C.c_int64, C.c_double, f64p, C.c_int64,
@@ -291,6 +296,30 @@ def ipt_score(logits, V, temperature, seeds, seq_ids, positions, claimed=None, t
                                   _ptr(out["edge"], C.c_double), _ptr(out["flags"], C.c_uint8))
     if rc:
         raise MemoryError("oracle_ipt_score")
+    return out
+
+
+def ipt_filtered_score(logits, V, temperature, seeds, seq_ids, positions, claimed, top_k, top_p, temperatures=None,
+                       sigma=0.01, eps=1e-30):
+    """Token-IPT-DiFR on the distribution the filtering sampler used (top-k, then top-p renormalised)."""
+    a, dtype, ld = _logits_view(logits)
+    N = a.shape[0]
+    assert a.shape[1] >= V
+    seeds, seq_ids, positions, claimed, cp, temperatures, tp = _aux(N, seeds, seq_ids, positions, claimed,
+                                                                    temperatures)
+    out = dict(u=np.zeros(N), cdf_lo=np.zeros(N), cdf_hi=np.zeros(N), dist=np.zeros(N),
+               ipt_token=np.zeros(N, np.int32), log_mass=np.zeros(N), edge=np.zeros(N), kept=np.zeros(N, np.int32),
+               gap_p=np.zeros(N), flags=np.zeros(N, np.uint8))
+    rc = _load().oracle_ipt_filtered_score(a.ctypes.data, dtype, N, int(V), ld, float(temperature), tp,
+                                           _ptr(seeds, C.c_uint64), _ptr(seq_ids, C.c_int32),
+                                           _ptr(positions, C.c_uint32), cp, int(top_k), float(top_p), float(sigma),
+                                           float(eps), _ptr(out["u"], C.c_double), _ptr(out["cdf_lo"], C.c_double),
+                                           _ptr(out["cdf_hi"], C.c_double), _ptr(out["dist"], C.c_double),
+                                           _ptr(out["ipt_token"], C.c_int32), _ptr(out["log_mass"], C.c_double),
+                                           _ptr(out["edge"], C.c_double), _ptr(out["kept"], C.c_int32),
+                                           _ptr(out["gap_p"], C.c_double), _ptr(out["flags"], C.c_uint8))
+    if rc:
+        raise MemoryError("oracle_ipt_filtered_score")
     return out
 
 

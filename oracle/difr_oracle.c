@@ -26,6 +26,8 @@
  *   - Token-DiFR likelihood estimate ...... Sec. 6.3, appendix algorithm of the
  *                                           Gumbel-max FSSL estimator (active set,
  *                                           filter threshold, A, B, noise average)
+ *   - Token-IPT-DiFR under the sampler's     Sec. 3.2 (filter policy), Sec. 6.2, appendix
+ *     top-k / top-p filter .................  "convolved Gaussian score"
  *   - admissible set size ................. Sec. 7 (A_t(tau), log2 |A_t| bits per
  *                                           accepted token), appendix "Threshold
  *                                           selection and FPR-information trade-off"
@@ -487,6 +489,38 @@ static int keyed_desc(const void *a, const void *b)
     return p->idx < q->idx ? -1 : (p->idx > q->idx ? 1 : 0);
 }
 
+/* The sampler's filter (Sec. 3.2 "temperature / top-k / nucleus policy"; the experiments use k = 50,     */
+/* p = 0.95): tokens ranked by logit, descending, ties to the lower index; top-k keeps the first k;        */
+/* top-p then keeps the shortest prefix of those whose softmax(l/T) mass, renormalised over the k, reaches */
+/* p.  Fills order[0..V) with the ranking and returns the length of the kept prefix (>= 1).  gap_p: how    */
+/* close the cumulative mass came to p on either side of the cut (for the tests' near-tie rule).           */
+static int64_t filter_prefix(const double *x, int64_t V, double T, int64_t top_k, double top_p, keyed *order,
+                             double *gap_p)
+{
+    for (int64_t v = 0; v < V; ++v) {
+        order[v].key = x[v];
+        order[v].idx = v;
+    }
+    qsort(order, (size_t)V, sizeof(keyed), keyed_desc);
+    int64_t kept = (top_k > 0 && top_k < V) ? top_k : V;
+    *gap_p = INFINITY;
+    if (top_p < 1.0) {
+        double Z = 0.0;
+        for (int64_t r = 0; r < kept; ++r) Z += exp((order[r].key - order[0].key) / T);
+        double cum = 0.0;
+        for (int64_t r = 0; r < kept; ++r) {
+            double before = cum;
+            cum += exp((order[r].key - order[0].key) / T) / Z;
+            if (cum >= top_p) {
+                *gap_p = fmin(fabs(cum - top_p), fabs(top_p - before));
+                kept = r + 1;
+                break;
+            }
+        }
+    }
+    return kept;
+}
+
 int oracle_likelihood_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
                           int64_t claimed, int64_t top_k, double top_p, int64_t s, double sigma, const double *z,
                           int64_t M, double *pi, double *log_pi, double *tau_out, int32_t *S_out, double *gap_s,
@@ -507,28 +541,7 @@ int oracle_likelihood_row(const double *x, int64_t V, double T, uint64_t seed, u
     double tau = -INFINITY;
     *gap_p = INFINITY;
     if (top_k > 0 || top_p < 1.0) {
-        for (int64_t v = 0; v < V; ++v) {
-            a[v].key = x[v];
-            a[v].idx = v;
-        }
-        qsort(a, (size_t)V, sizeof(keyed), keyed_desc);
-        int64_t kept = (top_k > 0 && top_k < V) ? top_k : V;
-        if (top_p < 1.0) {
-            double Z = 0.0;
-            for (int64_t r = 0; r < kept; ++r) Z += exp((a[r].key - a[0].key) / T);
-            double cum = 0.0;
-            int64_t cut = kept;
-            for (int64_t r = 0; r < kept; ++r) {
-                double before = cum;
-                cum += exp((a[r].key - a[0].key) / T) / Z;
-                if (cum >= top_p) {
-                    cut = r + 1;
-                    *gap_p = fmin(fabs(cum - top_p), fabs(top_p - before));
-                    break;
-                }
-            }
-            kept = cut;
-        }
+        int64_t kept = filter_prefix(x, V, T, top_k, top_p, a, gap_p);
         tau = a[kept - 1].key;
     }
     *tau_out = tau;
@@ -608,6 +621,115 @@ int oracle_likelihood(const void *logits, int dtype, int64_t N, int64_t V, int64
             if (oracle_likelihood_row(x, V, T, seeds[sq], (uint32_t)sq, positions[n], t, top_k, top_p, s, sigma, z, M,
                                       &pi[n], &log_pi[n], &tau[n], S_out + (size_t)n * (size_t)(s > 0 ? s : 0),
                                       &gap_s[n], &gap_p[n])) {
+#pragma omp atomic write
+                failed = 1;
+            }
+        }
+        free(x);
+    }
+    return failed;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-IPT-DiFR when the sampler filters (Sec. 3.2 IPT sampler applied to the  */
+/* filtered, renormalised distribution; appendix "convolved Gaussian score":     */
+/* "token probabilities p" are the probabilities the sampler actually used).     */
+/*   K = the kept prefix of filter_prefix();  p'_v = exp(x_v/T) / sum_K for      */
+/*   v in K, 0 otherwise;  Fbar over ascending vocabulary index;  a, b, d, match */
+/*   and the sampler's token as in oracle_ipt_row.  A claimed token outside K    */
+/*   has an empty interval a = b (never a match, d = |u - a|).                   */
+/* kept_out: |K|.  top_k <= 0 and top_p >= 1: identical to oracle_ipt_row.       */
+/* ------------------------------------------------------------------------- */
+int oracle_ipt_filtered_row(const double *x, int64_t V, double T, uint64_t seed, uint32_t seq, uint32_t pos,
+                            int64_t claimed, int64_t top_k, double top_p, double sigma, double eps, double *u_out,
+                            double *a_out, double *b_out, double *dist, int32_t *tok, double *log_mass, double *edge,
+                            int32_t *kept_out, double *gap_p, uint8_t *flags)
+{
+    keyed *order = (keyed *)malloc((size_t)(V > 0 ? V : 1) * sizeof(keyed));
+    unsigned char *in_K = (unsigned char *)calloc((size_t)(V > 0 ? V : 1), 1);
+    if (!order || !in_K) {
+        free(order);
+        free(in_K);
+        return 1;
+    }
+    const int64_t kept = filter_prefix(x, V, T, top_k, top_p, order, gap_p);
+    for (int64_t r = 0; r < kept; ++r) in_K[order[r].idx] = 1;
+    const double top = order[0].key;
+    free(order);
+    uint32_t r = oracle_noise_word(seed, seq, pos, ORACLE_STREAM_IPT, 0);
+    double u = oracle_bits_to_uniform(r);
+    int nonfinite = 0;
+    double Z = 0.0;
+    for (int64_t v = 0; v < V; ++v) {
+        if (isnan(x[v]) || x[v] == INFINITY) nonfinite = 1;
+        if (in_K[v]) Z += exp((x[v] - top) / T);
+    }
+    int valid = (claimed >= 0 && claimed < V);
+    double c = 0.0, a = NAN, b = NAN;
+    int64_t first = -1, last_kept = -1;
+    for (int64_t v = 0; v < V; ++v) {
+        double e = in_K[v] ? exp((x[v] - top) / T) : 0.0;
+        if (valid && v == claimed) {
+            a = c / Z;
+            b = a + e / Z;
+        }
+        c += e;
+        if (in_K[v]) last_kept = v;
+        if (first < 0 && in_K[v] && c / Z > u) first = v;
+    }
+    if (first < 0) first = last_kept;
+    free(in_K);
+    uint8_t f = 0;
+    if (!valid) {
+        f |= ORACLE_FLAG_INVALID_CLAIM;
+        *dist = NAN;
+        *edge = NAN;
+        *log_mass = NAN;
+    } else {
+        double d = 0.0;
+        if (a - u > d) d = a - u;
+        if (u - b > d) d = u - b;
+        *dist = d;
+        if (a <= u && u < b) f |= ORACLE_FLAG_MATCH;
+        *edge = fmin(fabs(u - a), fabs(u - b));
+        *log_mass = oracle_gaussian_log_mass(a, b, u, sigma, eps);
+    }
+    if (nonfinite) f |= ORACLE_FLAG_NONFINITE;
+    *u_out = u;
+    *a_out = a;
+    *b_out = b;
+    *tok = (int32_t)first;
+    *kept_out = (int32_t)kept;
+    *flags = f;
+    return 0;
+}
+
+int oracle_ipt_filtered_score(const void *logits, int dtype, int64_t N, int64_t V, int64_t ld, double temperature,
+                              const float *temperatures, const uint64_t *seeds, const int32_t *seq_ids,
+                              const uint32_t *positions, const int32_t *claimed, int64_t top_k, double top_p,
+                              double sigma, double eps, double *u, double *cdf_lo, double *cdf_hi, double *dist,
+                              int32_t *tok, double *log_mass, double *edge, int32_t *kept, double *gap_p,
+                              uint8_t *flags)
+{
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc((size_t)(V > 0 ? V : 1) * sizeof(double));
+        if (!x) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t n = 0; n < N; ++n) {
+            if (!x) continue;
+            const char *row = (const char *)logits + (size_t)n * (size_t)ld * elt_size(dtype);
+            oracle_decode_row(row, dtype, V, x);
+            double T = temperatures ? (double)temperatures[n] : temperature;
+            int32_t s = seq_ids[n];
+            int64_t t = claimed ? (int64_t)claimed[n] : -1;
+            if (oracle_ipt_filtered_row(x, V, T, seeds[s], (uint32_t)s, positions[n], t, top_k, top_p, sigma, eps,
+                                        &u[n], &cdf_lo[n], &cdf_hi[n], &dist[n], &tok[n], &log_mass[n], &edge[n],
+                                        &kept[n], &gap_p[n], &flags[n])) {
 #pragma omp atomic write
                 failed = 1;
             }

@@ -1,0 +1,89 @@
+"""Pins of the oracle's Token-IPT-DiFR under the sampler's top-k / top-p filter.
+
+Independent of the code under test: an explicit numpy implementation of the filter and of the CDF over
+the kept tokens, the special case "no filter" (must reproduce the unfiltered, separately pinned function
+bit for bit), the tiling property (for any u exactly one kept token matches), chi-square of the sampler's
+tokens against the renormalised probabilities, and a claimed token outside the kept set."""
+import numpy as np
+from scipy.stats import chi2
+
+import oracle
+
+
+def explicit(x, T, k, p):
+    """(kept indices in rank order, renormalised probabilities over the vocabulary)"""
+    order = np.lexsort((np.arange(len(x)), -x))                   # logit descending, index ascending
+    kept = order[:k] if 0 < k < len(x) else order
+    if p < 1.0:
+        w = np.exp((x[kept] - x[kept[0]]) / T)
+        cum = np.cumsum(w / w.sum())
+        kept = kept[:int(np.searchsorted(cum, p, side="left")) + 1]
+    prob = np.zeros(len(x))
+    w = np.exp((x[kept] - x[kept[0]]) / T)
+    prob[kept] = w / w.sum()
+    return kept, prob
+
+
+def batch(x, T, claims, k, p, seeds=(12345,), positions=None):
+    N, V = x.shape
+    seeds = np.array(seeds, dtype=np.uint64)
+    sid = np.zeros(N, np.int32)
+    pos = np.arange(N, dtype=np.uint32) if positions is None else positions
+    return oracle.ipt_filtered_score(x.astype(np.float32), V, T, seeds, sid, pos, claims, k, p), seeds, sid, pos
+
+
+def test_interval_matches_explicit_filter_and_cumsum():
+    rng = np.random.default_rng(31)
+    N, V = 30, 97
+    x = np.round(rng.standard_normal((N, V)) * 2, 1).astype(np.float32).astype(np.float64)   # coarse: ties
+    claims = rng.integers(0, V, size=N).astype(np.int32)
+    for k, p in ((10, 1.0), (50, 0.95), (0, 0.7), (5, 0.5), (200, 1.0)):
+        r, *_ = batch(x, 0.8, claims, k, p)
+        for n in range(N):
+            kept, prob = explicit(x[n], 0.8, k, p)
+            F = np.concatenate(([0.0], np.cumsum(prob)))
+            t = claims[n]
+            assert r["kept"][n] == len(kept)
+            assert abs(r["cdf_lo"][n] - F[t]) < 1e-12 and abs(r["cdf_hi"][n] - F[t + 1]) < 1e-12
+            u = r["u"][n]
+            assert abs(r["dist"][n] - max(F[t] - u, u - F[t + 1], 0.0)) < 1e-12
+            assert bool(r["flags"][n] & 1) == (F[t] <= u < F[t + 1])
+            if t not in kept:
+                assert r["cdf_lo"][n] == r["cdf_hi"][n] and not (r["flags"][n] & 1)
+            # the sampler's token: the kept token whose interval holds u
+            want = int(np.searchsorted(F[1:], u, side="right"))
+            while prob[want] == 0.0:
+                want += 1
+            assert r["ipt_token"][n] == want and prob[r["ipt_token"][n]] > 0
+
+
+def test_no_filter_is_the_unfiltered_estimator():
+    rng = np.random.default_rng(32)
+    N, V = 25, 300
+    x = (rng.standard_normal((N, V)) * 2).astype(np.float32)
+    claims = rng.integers(0, V, size=N).astype(np.int32)
+    r, seeds, sid, pos = batch(x.astype(np.float64), 1.1, claims, 0, 1.0)
+    r0 = oracle.ipt_score(x, V, 1.1, seeds, sid, pos, claims)
+    for key in ("u", "ipt_token", "flags"):
+        assert np.array_equal(r[key], r0[key]), key
+    for key in ("cdf_lo", "cdf_hi", "dist"):       # the two normalise by a different reference (top logit vs max x/T): rounding only
+        assert np.abs(r[key] - r0[key]).max() < 1e-14, key
+    assert (r["kept"] == V).all()
+
+
+def test_filtered_sampler_follows_the_renormalised_distribution():
+    rng = np.random.default_rng(33)
+    V, k, p, T = 12, 6, 0.9, 1.0
+    x1 = rng.standard_normal(V) * 1.5
+    kept, prob = explicit(x1.astype(np.float32).astype(np.float64), T, k, p)
+    N = 60000
+    x = np.tile(x1, (N, 1))
+    r, *_ = batch(x, T, None, k, p, positions=np.arange(N, dtype=np.uint32))
+    counts = np.bincount(r["ipt_token"], minlength=V).astype(np.float64)
+    assert counts[prob == 0].sum() == 0
+    live = prob > 0
+    stat = ((counts[live] - N * prob[live]) ** 2 / (N * prob[live])).sum()
+    assert stat < chi2.ppf(1 - 1e-4, int(live.sum()) - 1), stat
+    # an honest claim (the sampler's own token) always matches with distance 0
+    r2, *_ = batch(x[:500], T, r["ipt_token"][:500].astype(np.int32), k, p, positions=np.arange(500, dtype=np.uint32))
+    assert (r2["flags"] & 1).all() and (r2["dist"] == 0).all()
