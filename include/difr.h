@@ -167,6 +167,23 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                     uint8_t *flags_ipt, void *hip_stream);
 
 /*
+ * Token-IPT-DiFR on the distribution a filtering sampler used.  [Sec. 3.2: the IPT sampler applied under the
+ * generation policy's top-k / top-p filter; Sec. 6.2 and the appendix "convolved Gaussian score", whose input p is
+ * the probabilities the sampler actually used.]  The kept set K is a prefix of the tokens ranked by logit (ties to
+ * the lower index): the first top_k, cut to the shortest prefix whose softmax(x/T) mass, renormalised over those
+ * top_k, reaches top_p (top_p >= 1: no cut).  Inside K probabilities are renormalised, the CDF runs in ascending
+ * vocabulary index, and everything else is as in difr_ipt_score: interval [a, b) of the claimed token, distance d,
+ * MATCH, the sampler's own token, optional Gaussian log-mass.  A claimed token outside K has the empty interval
+ * a = b (never a match; d = |u - a|).
+ * 1 <= top_k <= 256 (0: DIFR_ERR_UNSUPPORTED - without a filter call difr_ipt_score; a nucleus over the whole
+ * vocabulary is not built); top_p > 0; rows 16-byte aligned (DIFR_ERR_ALIGN).  Outputs as difr_ipt_score (all
+ * optional ones may be NULL) plus kept [N] int32 or NULL = |K|.  One pass over the logits.
+ */
+int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, float *dist, float *cdf_lo, float *cdf_hi,
+                            float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass, int32_t *kept,
+                            uint8_t *flags, void *hip_stream);
+
+/*
  * Token-DiFR likelihood estimate of the claimed token.  [Sec. 6.3; appendix algorithm of the Gumbel-max FSSL
  * estimator.]  Per row, with G the regenerated Gumbel noise and Gaussian noise N(0, sigma^2) on every logit:
  *   S     = the s tokens with the largest x_i + T G_i, the claimed token t left out (ties to the lower index);

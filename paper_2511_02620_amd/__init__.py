@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     gumbel_likelihood,
     gumbel_score,
     ipt_score,
+    ipt_score_filtered,
     lib_path,
     lmhead_score,
     lmhead_workspace_bytes,

@@ -73,7 +73,7 @@ class _LikelihoodParams(C.Structure):
                 ("M", C.c_int32), ("z", C.c_void_p)]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_gumbel_likelihood", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -98,6 +98,9 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
     lib.difr_score_both.restype = C.c_int
+    lib.difr_ipt_score_filtered.argtypes = [C.POINTER(_Rows), C.c_int32, C.c_float, vp, vp, vp, vp, vp, C.c_double,
+                                            C.c_double, vp, vp, vp, vp]
+    lib.difr_ipt_score_filtered.restype = C.c_int
     lib.difr_gumbel_likelihood.argtypes = [C.POINTER(_Rows), C.POINTER(_LikelihoodParams), vp, vp, vp, vp, vp, vp]
     lib.difr_gumbel_likelihood.restype = C.c_int
     lib.difr_admissible_count.argtypes = [C.POINTER(_Rows), vp, C.c_float, vp, vp, vp]
@@ -260,6 +263,29 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if rc:
         raise DifrError(rc, "difr_score_both")
     return g, i
+
+
+def ipt_score_filtered(logits, temperature, seeds, seq_ids, positions, claimed=None, top_k=50, top_p=1.0,
+                       temperatures=None, V=None, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30):
+    """difr_ipt_score_filtered.  Returns a dict of device tensors (dist, cdf_lo, cdf_hi, u, kept, flags, ...)."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed, temperatures)
+    f32 = dict(dtype=torch.float32, device=dev)
+    out = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
+               u=torch.empty(N, **f32), kept=torch.empty(N, dtype=torch.int32, device=dev),
+               flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_token:
+        out["ipt_token"] = torch.empty(N, dtype=torch.int32, device=dev)
+    if want_log_mass:
+        out["log_mass"] = torch.empty(N, **f32)
+    with torch.cuda.device(dev):
+        rc = lib.difr_ipt_score_filtered(C.byref(r), int(top_k), float(top_p), _ptr(out["dist"]), _ptr(out["cdf_lo"]),
+                                         _ptr(out["cdf_hi"]), _ptr(out["u"]), _ptr(out.get("ipt_token")), float(sigma),
+                                         float(eps), _ptr(out.get("log_mass")), _ptr(out["kept"]), _ptr(out["flags"]),
+                                         _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_ipt_score_filtered")
+    return out
 
 
 def gumbel_likelihood(logits, temperature, seeds, seq_ids, positions, claimed, z, top_k=0, top_p=1.0, s=16, sigma=1.0,

@@ -205,6 +205,25 @@ int difr_admissible_count(const difr_rows *in, const float *max_score, float del
                : DIFR_OK;
 }
 
+int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, float *dist, float *cdf_lo, float *cdf_hi,
+                            float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass, int32_t *kept,
+                            uint8_t *flags, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (top_k < 0 || top_k > 256 || !(top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
+    if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
+    if (top_k == 0) return DIFR_ERR_UNSUPPORTED;  // no top-k: use difr_ipt_score (no filter) - a nucleus over the whole vocabulary is not built
+    if (b.N == 0) return DIFR_OK;
+    if (!dist || !flags) return DIFR_ERR_NULL;
+    if (!aligned) return DIFR_ERR_ALIGN;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    const difr::IptOutputs o{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags, nullptr};
+    return difr::launch_ipt_filtered(b, top_k, top_p, o, kept, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
+
 int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p, float *pi, float *log_pi, float *tau,
                            int32_t *active, uint8_t *flags, void *hip_stream)
 {

@@ -1,0 +1,177 @@
+// Token-IPT-DiFR on the distribution a filtering sampler used (Sec. 3.2: IPT sampler under the generation
+// policy's top-k / top-p filter; Sec. 6.2 and the appendix "convolved Gaussian score" with p = those
+// probabilities).  The kept set K is a prefix of the tokens ranked by logit (ties to the lower index):
+// the first top_k, cut further to the shortest prefix whose softmax(x / T) mass, renormalised over the
+// top_k, reaches top_p.  Inside K the probabilities are renormalised and the CDF runs in ascending
+// vocabulary index; a claimed token outside K has an empty interval.
+//
+// One workgroup per row, one pass over the logits that keeps the top_k largest (logit_top.hpp); no noise
+// is generated per entry, so the pass runs at streaming speed.  Everything else works on <= 256 tokens in fp64.
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+#include "gumbel_stream.hpp"
+#include "ipt_stream.hpp"
+#include "logit_top.hpp"
+#include "topn.hpp"
+
+namespace difr {
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int top_k, float top_p, IptOutputs o,
+                                                              int32_t *__restrict__ kept_out)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    __shared__ uint64_t buf_x[kTopCap];
+    __shared__ TopScratch scratch;
+    __shared__ int32_t cnt_x, snap_x, s_bad, s_kept, s_tok;
+    __shared__ double lds_d[kWaves];
+    __shared__ double s_e[kTopMaxN];     // unnormalised probabilities of K in ascending vocabulary index
+    __shared__ int32_t s_idx[kTopMaxN];  // and those indices
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    const int tid = threadIdx.x;
+    if (ipt_row_rejected(ri, row, o)) {
+        if (kept_out && tid == 0) kept_out[row] = 0;
+        return;
+    }
+    const float nan = __builtin_nanf("");
+    const int64_t V = b.V;
+    const int64_t t = ri.claimed;
+    const bool valid = t >= 0 && t < V;
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+
+    LogitTop<DT> lx;
+    lx.init(buf_x, &cnt_x, top_k);
+    if (tid == 0) {
+        s_bad = 0;
+        snap_x = 0;
+        s_tok = -1;
+    }
+    __syncthreads();
+    auto settle = [&]() {
+        if (__syncthreads_or((int)lx.top.full)) {
+            if (lx.top.compact(scratch, true)) lx.retarget();
+        }
+    };
+    const int64_t nvec = V / E;
+    const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);
+    auto fetch = [&](int round) {
+        u32x4 q = u32x4{0u, 0u, 0u, 0u};
+        if ((int64_t)round * kBlock + tid < nvec) q = load_round(x_row, round);
+        return q;
+    };
+    auto do_round = [&](u32x4 q, int round) {
+        const int64_t vec = (int64_t)round * kBlock + tid;
+        lx.push_vector(q, vec * E, vec < nvec);
+    };
+    // epochs without barriers, as in the likelihood kernel: the first round alone, then eight at a time, with a
+    // rewind and a round-by-round repeat if some thread had more candidates than its quota
+    int round = 0;
+    while (round < n_rounds) {
+        const int r_end = min(n_rounds, round + (round == 0 ? 1 : 8));
+        lx.top.new_epoch(kTopQuota);
+        u32x4 q_next = fetch(round);
+        for (int r = round; r < r_end; ++r) {
+            const u32x4 q = q_next;
+            if (r + 1 < r_end) q_next = fetch(r + 1);
+            do_round(q, r);
+        }
+        if (__syncthreads_or((int)lx.top.over)) {
+            if (tid == 0) cnt_x = snap_x;
+            lx.top.new_epoch(0x7FFFFFFF);
+            lx.top.full = false;
+            __syncthreads();
+            for (int r = round; r < r_end; ++r) {
+                do_round(fetch(r), r);
+                settle();
+            }
+        } else {
+            settle();
+        }
+        if (tid == 0) snap_x = cnt_x;
+        __syncthreads();
+        round = r_end;
+    }
+    lx.top.new_epoch(kTopQuota);
+    {
+        const int64_t v = nvec * E + tid;  // ragged tail: V % E entries
+        if (v < V) lx.push_entry(Elem<DT>::to_float(x_row[v]), (int32_t)v);
+    }
+    if (lx.bad) s_bad = 1;
+    const int nk = lx.top.finish_sorted(scratch);  // buf_x[0 .. nk): the top_k logits in rank order
+    if (tid == 0) s_kept = filter_prefix_length(buf_x, nk, (double)ri.T, top_p);
+    __syncthreads();
+    const int kc = s_kept;
+
+    // K in ascending vocabulary index: each member finds its place by counting the members with a smaller index
+    const double x0 = kc > 0 ? (double)top_key(buf_x[0]) : 0.0;
+    if (tid < kc) {
+        const int32_t mine = top_index(buf_x[tid]);
+        int place = 0;
+        for (int r = 0; r < kc; ++r) place += (int)(top_index(buf_x[r]) < mine);
+        s_idx[place] = mine;
+        s_e[place] = exp(((double)top_key(buf_x[tid]) - x0) / (double)ri.T);
+    }
+    __syncthreads();
+    const double e = tid < kc ? s_e[tid] : 0.0;
+    const int32_t idx = tid < kc ? s_idx[tid] : 0x7FFFFFFF;
+    double Z;
+    const double incl = block_inclusive_scan(e, lds_d, Z);  // CDF numerators in index order
+
+    uint32_t r4[4];
+    noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r4);
+    const float u = uniform_from_bits(r4[0]);
+    const double ud = (double)u;
+    const bool bad = s_bad != 0 || !(Z > 0.0) || !(Z < (double)__builtin_inff());
+
+    // the sampler's token: the first member whose cumulative mass exceeds u (the last member if rounding leaves none)
+    if (tid < kc && !bad) {
+        const double before = incl - e;
+        if (incl / Z > ud && !(before / Z > ud)) s_tok = idx;
+    }
+    // the claimed token's interval
+    const double below = block_sum_f64((tid < kc && (int64_t)idx < t) ? e : 0.0, lds_d);
+    const double own = block_sum_f64((tid < kc && (int64_t)idx == t) ? e : 0.0, lds_d);
+    __syncthreads();
+    if (tid == 0) {
+        float a = nan, bb = nan, d = nan;
+        double ad = 0.0, bd = 0.0;
+        bool match = false;
+        if (valid && !bad) {
+            ad = below / Z;
+            bd = ad + own / Z;
+            a = (float)ad;
+            bb = (float)bd;
+            d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+            match = (ad <= ud) && (ud < bd);
+        }
+        uint32_t f = 0;
+        if (!valid) f |= kFlagInvalidClaim;
+        if (bad) f |= kFlagNonfinite;
+        if (match) f |= kFlagMatch;
+        int32_t tok = s_tok;
+        if (tok < 0 && kc > 0) tok = s_idx[kc - 1];
+        o.dist[row] = d;
+        if (o.cdf_lo) o.cdf_lo[row] = a;
+        if (o.cdf_hi) o.cdf_hi[row] = bb;
+        if (o.u) o.u[row] = u;
+        if (o.ipt_token) o.ipt_token[row] = bad ? -1 : tok;
+        if (o.log_mass) o.log_mass[row] = (valid && !bad) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
+        if (kept_out) kept_out[row] = kc;
+        o.flags[row] = (uint8_t)f;
+    }
+}
+
+int launch_ipt_filtered(const RowBatch &b, int top_k, float top_p, const IptOutputs &o, int32_t *kept, hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    if (b.dtype == 0)
+        ipt_filtered_kernel<0><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+    else
+        ipt_filtered_kernel<1><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

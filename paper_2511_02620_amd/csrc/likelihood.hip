@@ -12,6 +12,7 @@
 #include "difr_host.hpp"
 #include "gumbel_stream.hpp"
 #include "ipt_stream.hpp"
+#include "logit_top.hpp"
 #include "topn.hpp"
 
 namespace difr {
@@ -65,9 +66,11 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     }
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
 
-    TopN top_y, top_x;
+    TopN top_y;
+    LogitTop<DT> lx;
+    TopN &top_x = lx.top;
     top_y.init(buf_y, &cnt_y, valid ? p.s : 0);
-    top_x.init(buf_x, &cnt_x, p.top_k);
+    lx.init(buf_x, &cnt_x, p.top_k);
     if (tid == 0) {
         s_bad = 0;
         snap_y = snap_x = 0;
@@ -76,52 +79,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     __syncthreads();
     g.arm_topn(&top_y);
     __syncthreads();
-    uint32_t bad = 0;
 
-    // raw-logit candidates of one vector.  First a test of the whole vector against the selection's threshold
-    // (bf16: packed 16-bit min / max on the raw bit patterns, as in the Gumbel gates; a NaN with the sign bit
-    // clear passes it and is flagged below, one with the sign bit set counts as -inf), then the 64-bit
-    // composite only for the entries that pass.
-    float x_floor = -__builtin_inff();
-    uint32_t x_floor16 = cap_bits(x_floor, true);
-    bool x_floor_pos = false;
-    auto set_x_floor = [&](float f) {
-        x_floor = f;
-        x_floor_pos = f > 0.0f;
-        x_floor16 = cap_bits(f, !x_floor_pos);
-    };
-    auto push_logits = [&](u32x4 q, int64_t v0, bool active) {
-        bool hit;
-        if (DT == 0) {
-            if (x_floor_pos) {
-                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
-                m = __builtin_elementwise_max(m, as_i16x2(q.z));
-                m = __builtin_elementwise_max(m, as_i16x2(q.w));
-                hit = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)x_floor16;
-            } else {
-                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
-                m = __builtin_elementwise_min(m, as_u16x2(q.z));
-                m = __builtin_elementwise_min(m, as_u16x2(q.w));
-                hit = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)x_floor16;
-            }
-        } else {
-            hit = !(__uint_as_float(q.x) < x_floor) || !(__uint_as_float(q.y) < x_floor) ||
-                  !(__uint_as_float(q.z) < x_floor) || !(__uint_as_float(q.w) < x_floor);
-        }
-        hit = hit && active;
-        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
-            if (hit) {
-                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
-                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
-                    bad |= (uint32_t)!(xv < __builtin_inff());
-                    if (xv >= x_floor) top_x.push(top_composite(xv, (int32_t)(v0 + j)));
-                }
-            }
-        }
-    };
     // compaction of whichever buffer has reached its trigger (uniform decisions through the barrier
     // reduction, which returns a truth value: one call per buffer)
     auto settle = [&]() {
@@ -129,8 +87,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
             if (top_y.compact(scratch, true)) g.retarget();
         }
         if (p.top_k > 0 && __syncthreads_or((int)top_x.full)) {
-            top_x.compact(scratch, true);
-            set_x_floor(top_key(top_x.theta));
+            if (top_x.compact(scratch, true)) lx.retarget();
         }
     };
 
@@ -145,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         const int64_t vec = (int64_t)round * kBlock + tid;
         const bool active = vec < nvec;
         g.process_any(q, round, active);
-        if (p.top_k > 0) push_logits(q, vec * E, active);
+        if (p.top_k > 0) lx.push_vector(q, vec * E, active);
     };
     // Epochs: the first round alone (every entry is a candidate while there is no threshold: exactly the
     // quota), then eight rounds at a time without a barrier.
@@ -191,37 +148,16 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     g.tail();
     {
         const int64_t v = nvec * E + tid;
-        if (v < V && p.top_k > 0) {
-            const float xv = Elem<DT>::to_float(x_row[v]);
-            bad |= (uint32_t)!(xv < __builtin_inff());
-            if (xv >= x_floor) top_x.push(top_composite(xv, (int32_t)v));
-        }
+        if (v < V && p.top_k > 0) lx.push_entry(Elem<DT>::to_float(x_row[v]), (int32_t)v);
     }
-    if (bad) s_bad = 1;
+    if (lx.bad) s_bad = 1;
     const int ns = top_y.finish_sorted(scratch);   // buf_y[0 .. ns): S in rank order
     const int nk = top_x.finish_sorted(scratch);   // buf_x[0 .. nk): the k largest logits, descending
 
     // filter threshold: top-k first, then top-p on the distribution renormalised over those k (fp64, one thread)
     if (tid == 0) {
         double tau = -(double)__builtin_inff();
-        if (p.top_k > 0 && nk > 0) {
-            int kept = nk;
-            if (p.top_p < 1.0f) {
-                const double x0 = (double)top_key(buf_x[0]);
-                const double T = (double)ri.T;
-                double Z = 0.0;
-                for (int r = 0; r < nk; ++r) Z += exp(((double)top_key(buf_x[r]) - x0) / T);
-                double cum = 0.0;
-                for (int r = 0; r < nk; ++r) {
-                    cum += exp(((double)top_key(buf_x[r]) - x0) / T) / Z;
-                    if (cum >= (double)p.top_p) {
-                        kept = r + 1;
-                        break;
-                    }
-                }
-            }
-            tau = (double)top_key(buf_x[kept - 1]);
-        }
+        if (p.top_k > 0 && nk > 0) tau = (double)top_key(buf_x[filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p) - 1]);
         s_tau = tau;
     }
     __syncthreads();

@@ -1,0 +1,95 @@
+// Streaming selection of the k largest raw logits of a row (the sampler's top-k set; Sec. 3.2 filter
+// policy), on top of topn.hpp: a cheap test of a whole 16-byte vector against the selection's threshold
+// first, the 64-bit composite only for the entries that pass.
+#pragma once
+
+#include "gumbel_stream.hpp"
+#include "topn.hpp"
+
+namespace difr {
+
+template <int DT>
+struct LogitTop {
+    static constexpr int E = Elem<DT>::kPerVec;
+    TopN top;
+    float floor;       // no logit below this can still belong to the k largest (wave-uniform)
+    uint32_t floor16;  // its bf16 bit pattern, rounded so that the packed test never misses an entry
+    bool floor_pos;
+    uint32_t bad;      // a NaN (sign bit clear) or +inf logit was seen
+
+    __device__ __forceinline__ void init(uint64_t *buf, int32_t *count, int k)
+    {
+        top.init(buf, count, k);
+        bad = 0;
+        set_floor(-__builtin_inff());
+    }
+    __device__ __forceinline__ void set_floor(float f)
+    {
+        floor = f;
+        floor_pos = f > 0.0f;
+        floor16 = cap_bits(f, !floor_pos);
+    }
+    // call after a compaction of `top`
+    __device__ __forceinline__ void retarget() { set_floor(top.theta == 0ull ? -__builtin_inff() : top_key(top.theta)); }
+
+    __device__ __forceinline__ void push_entry(float xv, int32_t v)
+    {
+        bad |= (uint32_t)!(xv < __builtin_inff());
+        if (xv >= floor) top.push(top_composite(xv, v));
+    }
+
+    // One 16-byte vector (entries v0 .. v0 + E - 1).  bf16: packed 16-bit min / max on the raw bit patterns, as
+    // in the Gumbel gates; a NaN with the sign bit clear passes the test and is flagged, one with the sign bit
+    // set counts as -inf.
+    __device__ __forceinline__ void push_vector(u32x4 q, int64_t v0, bool active)
+    {
+        bool hit;
+        if (DT == 0) {
+            if (floor_pos) {
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                hit = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)floor16;
+            } else {
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                hit = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)floor16;
+            }
+        } else {
+            hit = !(__uint_as_float(q.x) < floor) || !(__uint_as_float(q.y) < floor) ||
+                  !(__uint_as_float(q.z) < floor) || !(__uint_as_float(q.w) < floor);
+        }
+        hit = hit && active;
+        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+            if (hit) {
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+                    push_entry(xv, (int32_t)(v0 + j));
+                }
+            }
+        }
+    }
+};
+
+// The filter's kept prefix from the k largest logits in rank order (buf[0 .. nk), descending): top-k is the whole
+// list, top-p cuts it to the shortest prefix whose softmax(x / T) mass, renormalised over the list, reaches
+// top_p.  fp64, meant for one thread.  Returns the prefix length (>= 1 if nk >= 1).
+__device__ __forceinline__ int filter_prefix_length(const uint64_t *buf, int nk, double T, float top_p)
+{
+    if (nk <= 0 || !(top_p < 1.0f)) return nk;
+    const double x0 = (double)top_key(buf[0]);
+    double Z = 0.0;
+    for (int r = 0; r < nk; ++r) Z += exp(((double)top_key(buf[r]) - x0) / T);
+    double cum = 0.0;
+    for (int r = 0; r < nk; ++r) {
+        cum += exp(((double)top_key(buf[r]) - x0) / T) / Z;
+        if (cum >= (double)top_p) return r + 1;
+    }
+    return nk;
+}
+
+}  // namespace difr

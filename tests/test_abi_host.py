@@ -119,6 +119,14 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_classify(fake, fake, 4, 0.0, 8, 100, None, None, None, None) == NULL
     assert lib.difr_classify(fake, fake, 4, float("nan"), 8, 100, None, fake, None, None) == ARG
     assert lib.difr_classify(None, None, 0, 0.0, 8, 100, None, None, None, None) == OK
+    # filtered IPT
+    def iptf(r=None, k=50, p=0.95, dist=fake, fl=fake, sigma=0.01, lm=None):
+        return lib.difr_ipt_score_filtered(C.byref(r or rows()), k, p, dist, None, None, None, None, sigma,
+                                           1e-30, lm, None, fl, None)
+
+    assert iptf(k=-1) == ARG and iptf(k=257) == ARG and iptf(p=0.0) == ARG and iptf(sigma=0.0, lm=fake) == ARG
+    assert iptf(k=0) == 7 and iptf(dist=None) == NULL and iptf(fl=None) == NULL
+    assert iptf(rows(V=15, ld=15)) == ALIGN and iptf(rows(N=0), dist=None, fl=None) == OK
     # likelihood estimate
     from paper_2511_02620_amd.binding import _LikelihoodParams
 
