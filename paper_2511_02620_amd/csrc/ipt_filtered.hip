@@ -72,12 +72,14 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     while (round < n_rounds) {
         const int r_end = min(n_rounds, round + (round == 0 ? 1 : 8));
         lx.top.new_epoch(kTopQuota);
-        u32x4 q_next = fetch(round);
-        for (int r = round; r < r_end; ++r) {
-            const u32x4 q = q_next;
-            if (r + 1 < r_end) q_next = fetch(r + 1);
-            do_round(q, r);
-        }
+        // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
+        // nothing else would hide the load latency (fetch() of a round past the end returns zeros without a load)
+        u32x4 qv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (round + i < r_end) do_round(qv[i], round + i);
         if (__syncthreads_or((int)lx.top.over)) {
             if (tid == 0) cnt_x = snap_x;
             lx.top.new_epoch(0x7FFFFFFF);

@@ -176,6 +176,15 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     assert not (diff & ~excused).any()
     perr = np.where(excused, 0.0, np.abs(lk["pi"][ssel].cpu().numpy().astype(np.float64) - ol["pi"]))
     assert perr.max() <= 1e-4
+    # Token-IPT-DiFR under the same filter, every row; the oracle on the same 384 rows
+    fi = difr.ipt_score_filtered(logits, T, seeds, sid, pos, ci, top_k=50, top_p=0.95)
+    torch.cuda.synchronize()
+    assert ((fi["dist"] >= 0) & (fi["dist"] < 1)).all() and (fi["flags"] & 6 == 0).all() and (fi["kept"] >= 1).all()
+    ofi = oracle.ipt_filtered_score(host[:384], wl.V, f32(T), hs, hsid[:384], hpos[:384], ci[ssel].cpu().numpy(), 50,
+                                    float(f32(0.95)))
+    assert np.array_equal(fi["kept"][ssel].cpu().numpy(), ofi["kept"])
+    st_f = parity.compare_ipt({k: v[ssel] for k, v in fi.items() if k != "kept"}, ofi)
+    say(wl.name, "T=%g" % T, "filtered ipt:", st_f, "mean kept %.1f" % float(fi["kept"].float().mean()))
     say(wl.name, "T=%g" % T, "likelihood: mean pi %.4f over all rows, worst error %.3g on %d oracle rows, %d excused"
         % (float(pi_all.mean()), perr.max(), len(sub), int(excused.sum())))
     return g, i, sg, si, og, oi, st_g, st_i
