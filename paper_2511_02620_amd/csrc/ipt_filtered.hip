@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     constexpr int E = Elem<DT>::kPerVec;
     __shared__ uint64_t buf_x[kTopCap];
     __shared__ TopScratch scratch;
-    __shared__ int32_t cnt_x, snap_x, s_bad, s_kept, s_tok;
+    __shared__ int32_t cnt_x, snap_x, s_bad, s_tok;
     __shared__ double lds_d[kWaves];
     __shared__ double s_e[kTopMaxN];     // unnormalised probabilities of K in ascending vocabulary index
     __shared__ int32_t s_idx[kTopMaxN];  // and those indices
@@ -103,9 +103,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     }
     if (lx.bad) s_bad = 1;
     const int nk = lx.top.finish_sorted(scratch);  // buf_x[0 .. nk): the top_k logits in rank order
-    if (tid == 0) s_kept = filter_prefix_length(buf_x, nk, (double)ri.T, top_p);
-    __syncthreads();
-    const int kc = s_kept;
+    const int kc = filter_prefix_length(buf_x, nk, (double)ri.T, top_p, scratch);
 
     // K in ascending vocabulary index: each member finds its place by counting the members with a smaller index
     const double x0 = kc > 0 ? (double)top_key(buf_x[0]) : 0.0;

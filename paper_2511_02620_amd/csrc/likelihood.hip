@@ -43,7 +43,6 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     __shared__ float lds_L[kWaves];
     __shared__ double lds_d[kWaves];
     __shared__ double sA[kTopMaxN], sB[kTopMaxN];
-    __shared__ double s_tau;
     __shared__ int32_t s_bad;
 
     const int64_t row = blockIdx.x;
@@ -154,14 +153,9 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     const int ns = top_y.finish_sorted(scratch);   // buf_y[0 .. ns): S in rank order
     const int nk = top_x.finish_sorted(scratch);   // buf_x[0 .. nk): the k largest logits, descending
 
-    // filter threshold: top-k first, then top-p on the distribution renormalised over those k (fp64, one thread)
-    if (tid == 0) {
-        double tau = -(double)__builtin_inff();
-        if (p.top_k > 0 && nk > 0) tau = (double)top_key(buf_x[filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p) - 1]);
-        s_tau = tau;
-    }
-    __syncthreads();
-    const double tau = s_tau;
+    // filter threshold: top-k first, then top-p on the distribution renormalised over those k (fp64)
+    double tau = -(double)__builtin_inff();
+    if (p.top_k > 0 && nk > 0) tau = (double)top_key(buf_x[filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p, scratch) - 1]);
     double xt = 0.0, gt = 0.0;
     if (valid) {
         xt = (double)Elem<DT>::to_float(x_row[t]);

@@ -77,19 +77,34 @@ struct LogitTop {
 
 // The filter's kept prefix from the k largest logits in rank order (buf[0 .. nk), descending): top-k is the whole
 // list, top-p cuts it to the shortest prefix whose softmax(x / T) mass, renormalised over the list, reaches
-// top_p.  fp64, meant for one thread.  Returns the prefix length (>= 1 if nk >= 1).
-__device__ __forceinline__ int filter_prefix_length(const uint64_t *buf, int nk, double T, float top_p)
+// top_p.  All 256 threads call it (nk <= kTopMaxN, `s` idle): the exponentials are taken in parallel, one per
+// thread, and one thread then adds them up in rank order in fp64.  Returns the prefix length (>= 1 if nk >= 1) to
+// every thread; ends with a __syncthreads().
+__device__ __forceinline__ int filter_prefix_length(const uint64_t *buf, int nk, double T, float top_p, TopScratch &s)
 {
     if (nk <= 0 || !(top_p < 1.0f)) return nk;
-    const double x0 = (double)top_key(buf[0]);
-    double Z = 0.0;
-    for (int r = 0; r < nk; ++r) Z += exp(((double)top_key(buf[r]) - x0) / T);
-    double cum = 0.0;
-    for (int r = 0; r < nk; ++r) {
-        cum += exp(((double)top_key(buf[r]) - x0) / T) / Z;
-        if (cum >= (double)top_p) return r + 1;
+    const int tid = threadIdx.x;
+    double *e = reinterpret_cast<double *>(s.tmp);
+    if (tid < nk) e[tid] = exp(((double)top_key(buf[tid]) - (double)top_key(buf[0])) / T);
+    __syncthreads();
+    if (tid == 0) {
+        double Z = 0.0;
+        for (int r = 0; r < nk; ++r) Z += e[r];
+        double cum = 0.0;
+        int kept = nk;
+        for (int r = 0; r < nk; ++r) {
+            cum += e[r] / Z;
+            if (cum >= (double)top_p) {
+                kept = r + 1;
+                break;
+            }
+        }
+        s.kept = kept;
     }
-    return nk;
+    __syncthreads();
+    const int kept = s.kept;
+    __syncthreads();
+    return kept;
 }
 
 }  // namespace difr

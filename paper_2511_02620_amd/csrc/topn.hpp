@@ -125,6 +125,7 @@ struct TopN {
         int at_or_above = cnt;  // entries at or above the prefix found so far (unset low bits zero)
         for (int pass = 7; pass >= 0; --pass) {
             if (coarse && pass < 6 && at_or_above <= kTopKeep) break;
+            if (at_or_above == n) break;  // the prefix already separates exactly n entries from the rest
             const int shift = 8 * pass;
             s.hist[tid] = 0;
             __syncthreads();
