@@ -10,6 +10,9 @@
 // entries per register group: exactly the granularity of one Philox4x32 block.  The epilogue
 // then updates, per lane and token, the running best perturbed score and the online softmax sums,
 // and the next tile starts.  Partial results of the vocabulary ranges are merged by a last kernel.
+#include <type_traits>
+#include <utility>
+
 #include "difr_device.hpp"
 #include "difr_host.hpp"
 #include "gumbel_stream.hpp"
@@ -20,6 +23,31 @@ namespace difr {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// When the 16 copies of a slab are issued: copy c goes out after matrix instruction kCopySlot[c] of the 48
+// issued in the fourth k step of one slab and the first two of the next.  Spaced out because the memory
+// pipeline accepts a 1 KB copy only every so often, and a wave whose copy is not accepted cannot issue its
+// next matrix instruction either (measured: all 16 in one k step cost 11% of the kernel's time).
+__host__ __device__ constexpr int copy_at_slot(int n)
+{
+    constexpr int kCopySlot[16] = {0, 3, 5, 8, 10, 13, 15, 18, 20, 23, 25, 28, 30, 33, 35, 38};
+    for (int c = 0; c < 16; ++c)
+        if (kCopySlot[c] == n) return c;
+    return -1;
+}
+
+// f(integral_constant<int, 0>()), ..., f(integral_constant<int, N - 1>()): a loop whose index is a compile-time
+// constant in the body (register numbers and instruction immediates depend on it)
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>()), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>(), f);
+}
 
 struct TokInfo {
     PhiloxKey key;
@@ -276,10 +304,13 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     const int32_t V = (int32_t)b.V;
     const int nk = (int)(b.d / kLmTileK);
 
-    // Slab copy (global -> registers -> LDS): a slab is 256 rows x 64 k of each operand, i.e. whole
-    // 128-byte lines; thread -> 16-byte chunk (tid % 8) of rows (tid / 8) + 32 p.
-    const int crow = tid >> 3, cchunk = tid & 7;
-    const int lds_copy_off = crow * kLmTileK + ((cchunk ^ ((crow >> 1) & 7)) * 8);
+    // Slab copy, global memory straight into LDS (no registers in between): a slab is 256 rows x 64 k of
+    // each operand, i.e. whole 128-byte lines.  One wave-wide 16-byte-per-lane load fills 1 KB of LDS in
+    // lane order = 8 rows; lane i lands in 16-byte position i % 8 of row i / 8, so it fetches the k chunk
+    // that the permutation of the LDS layout puts there.  Thread -> rows (tid / 8) + 32 p, p = 0 .. 7.
+    const int crow = tid >> 3;
+    const int cchunk = (tid & 7) ^ ((crow >> 1) & 7);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     // Addresses are a wave-uniform base (scalar registers, moved by scalar arithmetic) plus a 32-bit
     // per-lane byte offset that never changes, so a load costs no vector arithmetic.
     uint32_t hoff[8];  // hidden-state rows: offset from the first row of the token block
@@ -291,32 +322,50 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     }
     const char *const hbase = reinterpret_cast<const char *>(b.hidden + n0 * b.ldh);
     const uint32_t wrow_bytes = (uint32_t)b.ldw * 2u;
+    uint32_t woff[8];  // weight rows: offset from the first row of the vocabulary tile
+    // rows past the end of the vocabulary (last tile only) re-read the last row
+    auto set_woff = [&](int vt) {
+        const int64_t tile_v0 = (int64_t)vt * kLmTileV;
+        const int32_t last = (int32_t)((b.V - tile_v0 < kLmTileV ? b.V - tile_v0 : kLmTileV) - 1);  // uniform
+#pragma unroll
+        for (int p = 0; p < 8; ++p) woff[p] = (uint32_t)min(crow + 32 * p, last) * wrow_bytes + (uint32_t)cchunk * 16u;
+    };
+    set_woff(vt0);
     // load cursor: the next slab to fetch is slab l_kt of vocabulary tile l_vt; once past the end it stays
     // on the last tile (harmless reloads keep the loop free of special cases)
     int l_vt = vt0, l_kt = 0;
     auto advance_cursor = [&]() {
         const bool wrap = (l_kt + 1 == nk);
         l_kt = wrap ? 0 : l_kt + 1;
-        l_vt = (wrap && l_vt + 1 < vt1) ? l_vt + 1 : l_vt;
-    };
-    u32x4 GS[16];  // the slab in flight: 8 weight chunks, 8 hidden-state chunks
-    auto load_chunk = [&](int i) {
-        const char *src;
-        if (i < 8) {
-            // rows past the end of the vocabulary (last tile only) re-read the last row
-            const int64_t tile_v0 = (int64_t)l_vt * kLmTileV;
-            const int32_t last = (int32_t)((b.V - tile_v0 < kLmTileV ? b.V - tile_v0 : kLmTileV) - 1);  // uniform
-            const int32_t r = min(crow + 32 * i, last);
-            const char *wbase = reinterpret_cast<const char *>(b.weight + tile_v0 * b.ldw + l_kt * kLmTileK);
-            src = wbase + ((uint32_t)r * wrow_bytes + (uint32_t)cchunk * 16u);
-        } else {
-            src = hbase + (size_t)l_kt * (kLmTileK * 2) + hoff[i & 7];
+        if (wrap && l_vt + 1 < vt1) {
+            ++l_vt;
+            if ((int64_t)(l_vt + 1) * kLmTileV > b.V) set_woff(l_vt);  // the ragged tile, at most once
         }
-        GS[i] = *reinterpret_cast<const u32x4 *>(src);
     };
-    auto store_chunk = [&](int i, int buf) {
-        uint16_t *dst = (i < 8 ? &lds_w[buf][0] : &lds_h[buf][0]) + lds_copy_off + 32 * (i & 7) * kLmTileK;
-        *reinterpret_cast<u32x4 *>(dst) = GS[i];
+    // Chunk i (0-7: weight rows, 8-15: hidden-state rows) of the cursor's slab -> LDS stage buf.
+    // The register M0 carries the LDS address of lane 0; lane i writes 16 i bytes further on.  Written as
+    // assembly for two reasons: the compiler would make every later LDS read wait for the copies in flight (it
+    // cannot tell the stages apart; the waits are placed by hand, see copies_landed), and a wave that runs
+    // alone on its SIMD can issue only a handful of instructions between two matrix instructions, so a copy
+    // must cost no address arithmetic: scalar base, invariant lane offset, M0 = stage base + constant.
+    auto copy_chunk = [&](auto I, int buf) {
+        constexpr int i = decltype(I)::value;
+        const char *sbase = i < 8 ? reinterpret_cast<const char *>(b.weight + (int64_t)l_vt * kLmTileV * b.ldw + l_kt * kLmTileK)
+                                  : hbase + (size_t)l_kt * (kLmTileK * 2);
+        const uint32_t voff = i < 8 ? woff[i & 7] : hoff[i & 7];
+        const uint16_t *stage = (i < 8 ? &lds_w[buf][0] : &lds_h[buf][0]) + 8 * wave_u * kLmTileK;
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)stage;
+        asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                     :
+                     : "s"(sbase), "v"(voff), "s"(lds_base), "n"(32 * (i & 7) * kLmTileK * 2)
+                     : "memory", "m0", "scc");
+    };
+    // every copy this wave has issued has landed in LDS, and every LDS read it has issued is complete
+    auto copies_landed = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     };
 
     // fragment reads: lane -> row l32 of a 32-row block, 16-byte k chunk 2 kk + lh (permuted like the copy)
@@ -380,62 +429,59 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     // One wave per SIMD: nothing else hides latency, so copies and fragment reads are interleaved with the
     // matrix instructions by hand and the order is pinned with scheduling fences.  Per 64-deep slab, four
     // k steps of 16 MFMAs each:
-    //   steps 0-2: + fragment reads for the next step, + one LDS write and one global load every third MFMA
-    //   barrier
-    //   step 3:    + fragment reads for step 0 of the next slab (from the other LDS stage)
+    //   steps 0-1: + fragment reads for the next step, + the rest of the copies of the next slab
+    //   step 2:    + fragment reads for step 3
+    //   wait for this wave's copies, barrier
+    //   step 3:    + fragment reads for step 0 of the next slab (from the other LDS stage), + the first copies
+    //              of the slab after that into the stage just released
     f32x16 acc[4][4];
     Frag F0, F1;
     auto kstep = [&](const Frag &cur, Frag &nxt, int buf_next, int kk_next, auto READ, auto &&extra) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int e0 = 2 * i, e1 = 2 * i + 1;
+        static_for<8>([&](auto I) {
+            constexpr int i = decltype(I)::value, e0 = 2 * i, e1 = 2 * i + 1;
             acc[e0 >> 2][e0 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e0 >> 2], cur.b[e0 & 3], acc[e0 >> 2][e0 & 3], 0, 0, 0);
-            extra(e0);
+            extra(std::integral_constant<int, e0>());
             acc[e1 >> 2][e1 & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.a[e1 >> 2], cur.b[e1 & 3], acc[e1 >> 2][e1 & 3], 0, 0, 0);
-            extra(e1);
+            extra(std::integral_constant<int, e1>());
             if (decltype(READ)::value) read_frag(nxt, i, buf_next, kk_next);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     };
     int par = 0;  // LDS stage of the slab being multiplied
-    // Chunk i of the slab in registers goes to LDS at MFMA slot 3 i of the slab, and its register is
-    // refilled at once with chunk i of the slab after: every load has a whole slab of time to land and
-    // the loads are spread evenly instead of arriving at the memory pipeline in one burst.
-    // Around the epilogue the registers are emptied: the slab they hold is written to its LDS stage
-    // before the epilogue (the stage is idle by then), so the FIRST slab of a tile only refills them,
-    // and the LAST slab of a tile does not read fragments ahead.  The epilogue then has those 96
-    // registers for itself.
+    // Two LDS stages.  The stage of slab g is last read during its third k step (fragments are read one
+    // step ahead), so after the barrier that follows that step it is free until the same barrier of slab
+    // g + 1, and the 16 copies of slab g + 2 are issued into it during the fourth step of slab g and the
+    // first two of slab g + 1 (copy_at_slot).  Each wave waits for its own copies before the barrier of
+    // slab g + 1; the last of them has had a whole k step to land by then.  The LAST slab of a tile does
+    // not read fragments ahead, so the epilogue has those 64 registers for itself.
     const std::true_type yes;
     const std::false_type no;
-    auto slab = [&](auto FIRST, auto LAST) {
-        auto copy = [&](int slot) {
-            if (slot % 3 == 0) {
-                if (!decltype(FIRST)::value) store_chunk(slot / 3, par ^ 1);
-                load_chunk(slot / 3);
-            }
+    // the copy (if any) that goes out at slot E of phase PH (0: fourth k step, 1 and 2: first and second of the next slab)
+    auto cp = [&](auto PH, int buf) {
+        return [&, buf](auto E) {
+            constexpr int c = copy_at_slot(16 * decltype(PH)::value + decltype(E)::value);
+            if constexpr (c >= 0) copy_chunk(std::integral_constant<int, c>(), buf);
         };
-        kstep(F0, F1, par, 1, yes, [&](int e) { copy(e); });
-        kstep(F1, F0, par, 2, yes, [&](int e) { copy(16 + e); });
-        kstep(F0, F1, par, 3, yes, [&](int e) { copy(32 + e); });
-        __syncthreads();
-        if (decltype(LAST)::value)
-            kstep(F1, F0, par ^ 1, 0, no, [&](int) {});
-        else
-            kstep(F1, F0, par ^ 1, 0, yes, [&](int) {});
+    };
+    auto slab = [&](auto LAST) {
+        kstep(F0, F1, par, 1, yes, cp(std::integral_constant<int, 1>(), par ^ 1));
+        kstep(F1, F0, par, 2, yes, cp(std::integral_constant<int, 2>(), par ^ 1));
         advance_cursor();
+        kstep(F0, F1, par, 3, yes, [&](auto) {});
+        copies_landed();
+        barrier();
+        if (decltype(LAST)::value)
+            kstep(F1, F0, par ^ 1, 0, no, cp(std::integral_constant<int, 0>(), par));
+        else
+            kstep(F1, F0, par ^ 1, 0, yes, cp(std::integral_constant<int, 0>(), par));
         par ^= 1;
     };
 
-#pragma unroll
-    for (int i = 0; i < 16; ++i) load_chunk(i);
+    // prologue: slab 0 whole, and of slab 1 what the fourth k step of a slab before it would have issued
+    static_for<16>([&](auto I) { copy_chunk(I, 0); });
     advance_cursor();
-#pragma unroll
-    for (int i = 0; i < 16; ++i) store_chunk(i, 0);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) load_chunk(i);
-    advance_cursor();
-#pragma unroll
-    for (int i = 0; i < 16; ++i) store_chunk(i, 1);
+    static_for<16>([&](auto E) { cp(std::integral_constant<int, 0>(), 1)(E); });
+    copies_landed();
     __syncthreads();
 
     for (int vt = vt0; vt < vt1; ++vt) {
@@ -447,17 +493,8 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             for (int jb = 0; jb < 4; ++jb) acc[ib][jb] = zero;
 #pragma unroll
         for (int i = 0; i < 8; ++i) read_frag(F0, i, par, 0);
-        if (nk == 1) {
-            slab(yes, yes);
-        } else {
-            slab(yes, no);
-            for (int kt = 2; kt < nk; ++kt) slab(no, no);
-            slab(no, yes);
-        }
-        // the slab in registers (the next tile's second) goes to its LDS stage now; the first slab's
-        // barrier orders these writes before anyone reads them
-#pragma unroll
-        for (int i = 0; i < 16; ++i) store_chunk(i, par ^ 1);
+        for (int kt = 1; kt < nk; ++kt) slab(no);
+        slab(yes);
 
         // ---- epilogue: score the 256 x 256 logits of this tile ----
         const bool ragged = v0 + kLmTileV > b.V;
@@ -500,6 +537,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             merge_softmax(s.m, s.Z, s.P, om, oZ, oP, tok_c[jb]);
         }
     }
+    copies_landed();  // the tile memory is reused below: nothing may still be on its way into it
     __syncthreads();
     if (wv == 1 && lh == 0) {
 #pragma unroll
