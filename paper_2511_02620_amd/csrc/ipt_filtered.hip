@@ -70,15 +70,15 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     // rewind and a round-by-round repeat if some thread had more candidates than its quota
     int round = 0;
     while (round < n_rounds) {
-        const int r_end = min(n_rounds, round + (round == 0 ? 1 : 8));
+        const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));
         lx.top.new_epoch(kTopQuota);
         // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
         // nothing else would hide the load latency (fetch() of a round past the end returns zeros without a load)
-        u32x4 qv[8];
+        u32x4 qv[kTopEpoch];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
+        for (int i = 0; i < kTopEpoch; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+        for (int i = 0; i < kTopEpoch; ++i)
             if (round + i < r_end) do_round(qv[i], round + i);
         if (__syncthreads_or((int)lx.top.over)) {
             if (tid == 0) cnt_x = snap_x;

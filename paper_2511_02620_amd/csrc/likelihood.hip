@@ -107,15 +107,17 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     // quota), then eight rounds at a time without a barrier.
     int round = 0;
     while (round < n_rounds) {
-        const int r_end = min(n_rounds, round + (round == 0 ? 1 : 8));
+        const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));
         top_y.new_epoch(kTopQuota);
         top_x.new_epoch(kTopQuota);
-        u32x4 q_next = fetch(round);
-        for (int r = round; r < r_end; ++r) {
-            const u32x4 q = q_next;
-            if (r + 1 < r_end) q_next = fetch(r + 1);  // keep one vector in flight
-            do_round(q, r);
-        }
+        // all vectors of the epoch are requested before the first is used: three workgroups per CU (the LDS
+        // buffers) cannot hide the load latency otherwise, and the registers are there
+        u32x4 qv[kTopEpoch];
+#pragma unroll
+        for (int i = 0; i < kTopEpoch; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < kTopEpoch; ++i)
+            if (round + i < r_end) do_round(qv[i], round + i);
         if (__syncthreads_or((int)(top_y.over || top_x.over))) {
             // some thread had more candidates than its quota (data in ascending order, for instance):
             // forget the epoch and repeat it round by round, compacting whenever a trigger is reached

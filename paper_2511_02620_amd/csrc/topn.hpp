@@ -22,6 +22,8 @@
 
 namespace difr {
 
+constexpr int kTopEpoch = 8;       // stream rounds per epoch (measured: 4 and 16 are both slower)
+constexpr int kTopFresh = 16;      // a compaction is due after max(n, kTopFresh) pushes
 constexpr int kTopQuota = 8;       // pushes per thread and epoch
 constexpr int kTopTrigger = 512;   // a compaction is due at the latest when this many slots are used
 constexpr int kTopCap = kTopTrigger + 256 * kTopQuota;  // slots per buffer
@@ -58,7 +60,7 @@ struct TopN {
     int32_t *count;  // in LDS
     int n;
     uint64_t theta;  // wave-uniform copy of the threshold: only composites above it are pushed
-    int trigger;     // fill level at which the next compaction is due: max(n, 64) pushes after the last one, so
+    int trigger;     // fill level at which the next compaction is due: max(n, kTopFresh) pushes after the last one, so
                      // that the threshold, which is also the bound of the stream's gates, stays fresh
     bool full;       // this thread's push took the buffer to the compaction trigger (combine over the workgroup
                      // with __syncthreads_or: reading the counter instead would race with the next round's pushes)
@@ -71,7 +73,7 @@ struct TopN {
         count = count_;
         n = n_;
         theta = n_ > 0 ? 0ull : ~0ull;  // nothing wanted: nothing is ever pushed
-        trigger = n_ > 64 ? n_ : 64;
+        trigger = n_ > kTopFresh ? n_ : kTopFresh;
         full = false;
         quota = kTopQuota;
         over = false;
@@ -116,7 +118,7 @@ struct TopN {
             return true;
         }
         if (cnt <= n) {
-            trigger = min(kTopTrigger, cnt + (n > 64 ? n : 64));
+            trigger = min(kTopTrigger, cnt + (n > kTopFresh ? n : kTopFresh));
             __syncthreads();
             return false;
         }
@@ -172,7 +174,7 @@ struct TopN {
         for (int i = tid; i < at_or_above; i += kBlock) buf[i] = s.tmp[i];
         if (tid == 0) *count = at_or_above;
         theta = prefix;
-        trigger = min(kTopTrigger, at_or_above + (n > 64 ? n : 64));
+        trigger = min(kTopTrigger, at_or_above + (n > kTopFresh ? n : kTopFresh));
         __syncthreads();
         return true;
     }
