@@ -49,8 +49,9 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    build()
-    lib = C.CDLL(_LIB)
+    # DIFR_ORACLE_LIB: a test hook.  tests/test_oracle_pins_have_teeth.py points it at deliberately broken
+    # builds of the oracle to show that the pins notice; nothing else sets it.
+    lib = C.CDLL(os.environ.get("DIFR_ORACLE_LIB") or build())
     u32p, u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)
     i32p, i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
     f32p, f64p, u8p = C.POINTER(C.c_float), C.POINTER(C.c_double), C.POINTER(C.c_uint8)
