@@ -158,7 +158,6 @@ struct GumbelStream {
     float count_M, count_delta;
     uint32_t count;
     // TOPN mode
-    TopN *top;
 
     // Computes the claimed token's score with the same function the stream uses (the first lower
     // bound) and publishes it.  The caller must __syncthreads() before the first process().
@@ -192,19 +191,14 @@ struct GumbelStream {
         asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
         count_M = count_delta = 0.0f;
         count = 0;
-        top = nullptr;
     }
 
-    // TOPN mode: scores go to `top_`; the bound is its threshold (call retarget() whenever that moves).
-    // Same synchronisation rules as arm_count().
-    __device__ __forceinline__ void arm_topn(TopN *top_)
+    // TOPN mode: scores go to the selection handed to process() / tail() (by pointer argument, never stored:
+    // the selection must stay in registers); the bound is its threshold (call retarget() whenever that
+    // moves).  Same synchronisation rules as arm_count().
+    __device__ __forceinline__ void retarget(const TopN &top)
     {
-        top = top_;
-        retarget();
-    }
-    __device__ __forceinline__ void retarget()
-    {
-        const float bound = top->theta == 0ull ? -__builtin_inff() : (top->theta == ~0ull ? 3.0e38f : top_key(top->theta));
+        const float bound = top.theta == 0ull ? -__builtin_inff() : (top.theta == ~0ull ? 3.0e38f : top_key(top.theta));
         gate = make_gate(bound, T);
         if ((tid & 63) == 0) lds_L[wave] = gate.L;
     }
@@ -222,7 +216,7 @@ struct GumbelStream {
     }
 
     // Exact evaluation of one entry (same arithmetic as the unfiltered kernel), ties to the lowest index.
-    __device__ __forceinline__ void evaluate(float xv, uint32_t rv, int32_t v)
+    __device__ __forceinline__ void evaluate(float xv, uint32_t rv, int32_t v, TopN *top = nullptr)
     {
         const float y = perturbed_score(xv, inv_T, rv);
         bad |= (uint32_t)!(xv < __builtin_inff());
@@ -241,9 +235,9 @@ struct GumbelStream {
     }
 
     // Entry-level test: can this entry still reach the lower bound?
-    __device__ __forceinline__ void consider(float xv, uint32_t rv, int32_t v)
+    __device__ __forceinline__ void consider(float xv, uint32_t rv, int32_t v, TopN *top = nullptr)
     {
-        if (!(__fmaf_rn(xv, inv_T, gumbel_upper_bound(rv)) < gate.Lgate)) evaluate(xv, rv, v);
+        if (!(__fmaf_rn(xv, inv_T, gumbel_upper_bound(rv)) < gate.Lgate)) evaluate(xv, rv, v, top);
     }
 
     __device__ __forceinline__ void count_above(u32x4 q, bool active)
@@ -279,7 +273,7 @@ struct GumbelStream {
     // One 16-byte vector per lane; `round` is the vector round (vector index = round * 256 + tid).
     // MODE is the gate's mode, fixed per instantiation so that the loop body carries no mode branches.
     template <int MODE>
-    __device__ __forceinline__ void process(u32x4 q, int round, bool active)
+    __device__ __forceinline__ void process(u32x4 q, int round, bool active, TopN *top = nullptr)
     {
         const uint64_t round_prod = (uint64_t)kPhiloxM0 * (uint32_t)(round * kBlock * (E / 4));
         const uint64_t p0 = round_prod + lane_prod;
@@ -333,7 +327,7 @@ struct GumbelStream {
                     const uint32_t w = qw[DT == 0 ? j >> 1 : j];
                     const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
                                              : __uint_as_float(w);
-                    if (r[j] >= kGateLo || !(xv < gate.xcap_lo)) consider(xv, r[j], v0 + j);
+                    if (r[j] >= kGateLo || !(xv < gate.xcap_lo)) consider(xv, r[j], v0 + j, top);
                 }
             }
             // a better score raises the lower bound for this wave; other waves pick it up from LDS
@@ -347,14 +341,14 @@ struct GumbelStream {
     }
 
     // process() for whatever mode the gate is in right now (used outside the hot loop)
-    __device__ __forceinline__ void process_any(u32x4 q, int round, bool active)
+    __device__ __forceinline__ void process_any(u32x4 q, int round, bool active, TopN *top = nullptr)
     {
         if (gate.mode == 0)
-            process<0>(q, round, active);
+            process<0>(q, round, active, top);
         else if (gate.mode == 1)
-            process<1>(q, round, active);
+            process<1>(q, round, active, top);
         else
-            process<2>(q, round, active);
+            process<2>(q, round, active, top);
     }
 
     // pick up a bound another wave has raised
@@ -365,14 +359,14 @@ struct GumbelStream {
     }
 
     // the ragged tail: V % E entries, one lane each, evaluated exactly
-    __device__ __forceinline__ void tail()
+    __device__ __forceinline__ void tail(TopN *top = nullptr)
     {
         const int64_t v = (V / E) * E + tid;
         if (v < V) {
             uint32_t r[4];
             noise_block(ri.key, ri.pos, ri.seq, kStreamGumbel, (uint32_t)(v >> 2), r);
             const uint32_t rv = (v & 3) == 0 ? r[0] : (v & 3) == 1 ? r[1] : (v & 3) == 2 ? r[2] : r[3];
-            evaluate(Elem<DT>::to_float(x_row[v]), rv, (int32_t)v);
+            evaluate(Elem<DT>::to_float(x_row[v]), rv, (int32_t)v, top);
         }
         if (RANK)
             above += __builtin_popcountll(

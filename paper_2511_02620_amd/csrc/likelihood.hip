@@ -65,6 +65,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     }
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
 
+    GumbelStream<DT, false, false, true> g(ri, x_row, V, lds_L);
     TopN top_y;
     LogitTop<DT> lx;
     TopN &top_x = lx.top;
@@ -74,16 +75,15 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         s_bad = 0;
         snap_y = snap_x = 0;
     }
-    GumbelStream<DT, false, false, true> g(ri, x_row, V, lds_L);
     __syncthreads();
-    g.arm_topn(&top_y);
+    g.retarget(top_y);
     __syncthreads();
 
     // compaction of whichever buffer has reached its trigger (uniform decisions through the barrier
     // reduction, which returns a truth value: one call per buffer)
-    auto settle = [&]() {
+    auto settle = [&]() __attribute__((always_inline)) {
         if (__syncthreads_or((int)top_y.full)) {
-            if (top_y.compact(scratch, true)) g.retarget();
+            if (top_y.compact(scratch, true)) g.retarget(top_y);
         }
         if (p.top_k > 0 && __syncthreads_or((int)top_x.full)) {
             if (top_x.compact(scratch, true)) lx.retarget();
@@ -91,33 +91,46 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     };
 
     const int64_t nvec = V / E;
-    const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);
-    auto fetch = [&](int round) {
-        u32x4 q = u32x4{0u, 0u, 0u, 0u};
-        if ((int64_t)round * kBlock + tid < nvec) q = load_round(x_row, round);
-        return q;
-    };
-    auto do_round = [&](u32x4 q, int round) {
+    const int n_main = (int)(nvec / kBlock);                       // rounds in which every lane has a vector
+    const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);      // plus a last, partly filled one
+    // one round, any gate mode, lanes past the end of the row idle (the partly filled round, and repeats)
+    auto do_round = [&](int round) __attribute__((always_inline)) {
         const int64_t vec = (int64_t)round * kBlock + tid;
         const bool active = vec < nvec;
-        g.process_any(q, round, active);
+        u32x4 q = u32x4{0u, 0u, 0u, 0u};
+        if (active) q = load_round(x_row, round);
+        g.process_any(q, round, active, &top_y);
         if (p.top_k > 0) lx.push_vector(q, vec * E, active);
     };
+    // full rounds [r0, r1) with the loop body instantiated for the gate's mode (it can only change at a
+    // compaction, i.e. between epochs): one copy of the Philox + gate code per mode instead of one per
+    // mode and unrolled round, which did not fit the instruction cache
+    auto run_rounds = [&](auto mode_tag, int r0, int r1) __attribute__((always_inline)) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        u32x4 q_next = load_round(x_row, r0);
+#pragma nounroll
+        for (int r = r0; r < r1; ++r) {
+            const u32x4 q = q_next;
+            if (r + 1 < r1) q_next = load_round(x_row, r + 1);  // keep one vector in flight
+            g.template process<MODE>(q, r, true, &top_y);
+            if (p.top_k > 0) lx.push_vector(q, ((int64_t)r * kBlock + tid) * E, true);
+        }
+    };
     // Epochs: the first round alone (every entry is a candidate while there is no threshold: exactly the
-    // quota), then eight rounds at a time without a barrier.
+    // quota), then kTopEpoch rounds at a time without a barrier; the partly filled round is an epoch of its own.
     int round = 0;
     while (round < n_rounds) {
-        const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));
+        const int r_end = round < n_main ? min(n_main, round + (round == 0 ? 1 : kTopEpoch)) : n_rounds;
         top_y.new_epoch(kTopQuota);
         top_x.new_epoch(kTopQuota);
-        // all vectors of the epoch are requested before the first is used: three workgroups per CU (the LDS
-        // buffers) cannot hide the load latency otherwise, and the registers are there
-        u32x4 qv[kTopEpoch];
-#pragma unroll
-        for (int i = 0; i < kTopEpoch; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int i = 0; i < kTopEpoch; ++i)
-            if (round + i < r_end) do_round(qv[i], round + i);
+        if (round >= n_main)
+            do_round(round);
+        else if (g.gate.mode == 0)
+            run_rounds(std::integral_constant<int, 0>(), round, r_end);
+        else if (g.gate.mode == 1)
+            run_rounds(std::integral_constant<int, 1>(), round, r_end);
+        else
+            run_rounds(std::integral_constant<int, 2>(), round, r_end);
         if (__syncthreads_or((int)(top_y.over || top_x.over))) {
             // some thread had more candidates than its quota (data in ascending order, for instance):
             // forget the epoch and repeat it round by round, compacting whenever a trigger is reached
@@ -130,7 +143,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
             top_y.full = top_x.full = false;
             __syncthreads();
             for (int r = round; r < r_end; ++r) {
-                do_round(fetch(r), r);
+                do_round(r);
                 settle();
             }
         } else {
@@ -146,7 +159,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     top_y.new_epoch(kTopQuota);  // the tail: at most one entry per thread
     top_x.new_epoch(kTopQuota);
     // ragged tail: V % E entries, one lane each
-    g.tail();
+    g.tail(&top_y);
     {
         const int64_t v = nvec * E + tid;
         if (v < V && p.top_k > 0) lx.push_entry(Elem<DT>::to_float(x_row[v]), (int32_t)v);

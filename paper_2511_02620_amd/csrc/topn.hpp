@@ -105,7 +105,7 @@ struct TopN {
     // above it: exactly the n largest (coarse = false), or at most kTopKeep of them chosen at the
     // resolution of the top 16 key bits (coarse = true).  Returns true if the threshold moved.  Ends with
     // a __syncthreads().
-    __device__ bool compact(TopScratch &s, bool coarse = false)
+    __device__ __forceinline__ bool compact(TopScratch &s, bool coarse = false)
     {
         const int tid = threadIdx.x;
         const int cnt = min(*count, kTopCap);
@@ -182,7 +182,7 @@ struct TopN {
     // All 256 threads: reduce to exactly the n largest, then order them.  Afterwards buf[0 .. m) holds them in
     // descending order, m = min(n, entries seen); returns m.  Each survivor finds its rank by counting the
     // survivors above it (m <= 256 broadcast reads, no barriers).
-    __device__ int finish_sorted(TopScratch &s)
+    __device__ __forceinline__ int finish_sorted(TopScratch &s)
     {
         const int tid = threadIdx.x;
         __syncthreads();
