@@ -355,10 +355,15 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         const uint32_t voff = i < 8 ? woff[i & 7] : hoff[i & 7];
         const uint16_t *stage = (i < 8 ? &lds_w[buf][0] : &lds_h[buf][0]) + 8 * wave_u * kLmTileK;
         const uint32_t lds_base = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void *)stage;
+        // (M0 is set and consumed inside the one statement and declared clobbered; the compiler's remark that
+        // it is a reserved register does not apply to that use)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
         asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
                      :
                      : "s"(sbase), "v"(voff), "s"(lds_base), "n"(32 * (i & 7) * kLmTileK * 2)
                      : "memory", "m0", "scc");
+#pragma clang diagnostic pop
     };
     // every copy this wave has issued has landed in LDS, and every LDS read it has issued is complete
     auto copies_landed = [&]() { asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory"); };
