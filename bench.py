@@ -115,9 +115,19 @@ def cpu_baseline(wl, data, sample_rows):
     oracle.seq_reduce(og["margin"], og["flags"], off, 0.05)
     oracle.seq_reduce(oi["dist"], oi["flags"], off, 0.05)
     dt = time.time() - t0
-    return {"value": n / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+    # the same on one thread, on a sixteenth of the sample (reported beside it, not part of `value`)
+    cores = oracle.num_threads()
+    n1 = max(1, n // 16)
+    oracle.set_num_threads(1)
+    t0 = time.time()
+    oracle.gumbel_score(host[:n1], wl.V, T, seeds, sid[:n1], pos[:n1], cg[:n1])
+    oracle.ipt_score(host[:n1], wl.V, T, seeds, sid[:n1], pos[:n1], ci[:n1])
+    dt1 = time.time() - t0
+    oracle.set_num_threads(cores)
+    return {"value": n / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": "first %d rows (%d whole sequences) of the same batch, both estimators + pooling, %.1f s"
-                      % (n, S, dt)}
+                      % (n, S, dt),
+            "one_thread": {"value": n1 / dt1, "sample": "first %d rows, %.1f s" % (n1, dt1)}}
 
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak, published

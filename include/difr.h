@@ -246,7 +246,7 @@ int difr_admissible_count(const difr_rows *in, const float *max_score, float del
  * hidden  DEVICE [N, ldh] bf16 row-major: final hidden state of each token position (after the
  *         model's last normalisation); weight  DEVICE [V, ldw] bf16 row-major: one row per
  *         vocabulary entry.  d % 64 == 0, ldh >= d, ldw >= d, ldh % 8 == ldw % 8 == 0, both bases
- *         16-byte aligned (else DIFR_ERR_SHAPE / DIFR_ERR_ALIGN).  N, V < 2^31.
+ *         16-byte aligned (else DIFR_ERR_SHAPE / DIFR_ERR_ALIGN).  N, V < 2^31; ldh, ldw < 2^23.
  * claimed_gumbel / claimed_ipt  DEVICE [N] or NULL: the claims scored by Token-DiFR and by
  *         Token-IPT-DiFR.  The remaining fields are those of difr_rows.
  * Outputs: exactly those of difr_score_both, with the same optionality and flag bits.  Because

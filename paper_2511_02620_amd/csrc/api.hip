@@ -69,6 +69,8 @@ int validate_lmhead(const difr_lmhead *in, difr::LmHeadBatch *b)
     if (!in) return DIFR_ERR_NULL;
     if (in->N < 0 || in->V < 0 || in->d < 0 || in->ldh < 0 || in->ldw < 0 || in->S < 0) return DIFR_ERR_SHAPE;
     if (in->N >= (int64_t)1 << 31 || in->V >= (int64_t)1 << 31 || in->d >= (int64_t)1 << 31) return DIFR_ERR_SHAPE;
+    // the kernel addresses the 256 rows of a tile with 32-bit byte offsets from the tile's first row
+    if (in->ldh >= (int64_t)1 << 23 || in->ldw >= (int64_t)1 << 23) return DIFR_ERR_SHAPE;
     if (in->N > 0) {
         if (in->V == 0 || in->d == 0 || in->d % difr::kLmTileK || in->ldh < in->d || in->ldw < in->d || in->ldh % 8 ||
             in->ldw % 8 || in->S < 1)

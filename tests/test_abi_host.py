@@ -172,6 +172,7 @@ def test_argument_validation_needs_no_device(lib):
     assert lib.difr_lmhead_workspace_bytes(16384, 151936, 4096) < 4 << 20
     for bad, want in ((lm(N=-1), SHAPE), (lm(V=0), SHAPE), (lm(d=0), SHAPE), (lm(d=96, ldh=96, ldw=96), SHAPE),
                       (lm(ldh=64), SHAPE), (lm(ldw=132), SHAPE), (lm(S=0), SHAPE), (lm(N=1 << 31), SHAPE),
+                      (lm(ldh=1 << 23), SHAPE), (lm(ldw=1 << 23), SHAPE),
                       (lm(temperature=0.0), TEMP), (lm(hidden=None), NULL), (lm(weight=None), NULL),
                       (lm(seeds=None), NULL), (lm(hidden=0x1008), ALIGN), (lm(weight=0x1004), ALIGN)):
         assert lms(bad) == want, want
