@@ -327,6 +327,8 @@ def main():
         t_g = time_alone(lambda: difr.gumbel_score(*row_args, data["claims_g"]), reps)
         t_i = time_alone(lambda: difr.ipt_score(*row_args, data["claims_i"]), reps)
         t_a = time_alone(lambda: difr.admissible_count(*row_args, out[0]["max_score"], ADMISSIBLE_DELTA), reps)
+        t_ba = time_alone(lambda: difr.score_both_admissible(*row_args, ADMISSIBLE_DELTA, data["claims_g"],
+                                                             data["claims_i"]), reps)
         t_f = time_alone(lambda: difr.ipt_score_filtered(*row_args, data["claims_i"], top_k=LIKELIHOOD["top_k"],
                                                          top_p=LIKELIHOOD["top_p"]), reps)
         zl = torch.randn(LIKELIHOOD["M"], generator=torch.Generator().manual_seed(5)).to(dev)
@@ -334,7 +336,7 @@ def main():
                                                         top_p=LIKELIHOOD["top_p"], s=LIKELIHOOD["s"],
                                                         sigma=LIKELIHOOD["sigma"]), reps)
     else:
-        t_b = t_a = t_l = t_f = None
+        t_b = t_a = t_l = t_f = t_ba = None
         t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
@@ -401,6 +403,9 @@ def main():
                     "difr_admissible_count": None if t_a is None else
                     {"ms": round(t_a, 4), "delta": ADMISSIBLE_DELTA, "tokens_per_s": round(wl.N / (t_a * 1e-3), 1),
                      "hbm_gbs": round(wl.N * (wl.V * esz + 24) / (t_a * 1e-3) / 1e9, 1)},
+                    "difr_score_both_admissible": None if t_ba is None else
+                    {"ms": round(t_ba, 4), "delta": ADMISSIBLE_DELTA, "tokens_per_s": round(wl.N / (t_ba * 1e-3), 1),
+                     "hbm_gbs": round(wl.N * (per_row_b + 8) / (t_ba * 1e-3) / 1e9, 1)},
                     "difr_ipt_score_filtered": None if t_f is None else
                     {"ms": round(t_f, 4), "top_k": LIKELIHOOD["top_k"], "top_p": LIKELIHOOD["top_p"],
                      "tokens_per_s": round(wl.N / (t_f * 1e-3), 1),

@@ -233,6 +233,25 @@ int difr_admissible_count(const difr_rows *in, const float *max_score, float del
                           void *hip_stream);
 
 /*
+ * difr_score_both and the admissible-set size in ONE pass over the logits.  [Sec. 7: the score decides whether
+ * a token is accepted, log2 |A_t| bounds what an accepted token can carry; a verifier wants both per position.]
+ * The row maximum is only known at the end of the pass, so every score that may lie within delta of it is kept
+ * in a short on-chip list while the running lower bound of the maximum rises, and the list is counted against
+ * the true maximum after the row: count[n] is exactly what difr_admissible_count returns for max_score[n] and
+ * the same delta.  If a row has more candidates than the list holds (a very large delta, or a row whose
+ * bound stays far below its maximum for long), count[n] = -1 and log2_count[n] = NaN: call
+ * difr_admissible_count for those rows.  With honest claims (the bound starts at the maximum) and delta up
+ * to about 5 this does not happen.
+ * delta >= 0, finite (else DIFR_ERR_ARGUMENT); rows must be 16-byte aligned (DIFR_ERR_ALIGN).
+ * count DEVICE [N] int32 (required); log2_count DEVICE [N] fp32 or NULL.  All other arguments and outputs as
+ * in difr_score_both, bit-identical to it.
+ */
+int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, float delta, float *margin,
+                               int32_t *argmax, float *max_score, float *claimed_score, uint8_t *flags_gumbel,
+                               float *dist, float *cdf_lo, float *cdf_hi, float *u, uint8_t *flags_ipt, int32_t *count,
+                               float *log2_count, void *hip_stream);
+
+/*
  * Fused LM head + scoring: both estimators on logits that are never stored.  The verifier's
  * prefill ends with the product of each position's final hidden state and the LM-head matrix
  * [appendix algorithm "sampled token verification via prefill": one forward pass yields the

@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     load_library,
     philox4x32_10,
     score_both,
+    score_both_admissible,
     seq_reduce,
     version,
 )

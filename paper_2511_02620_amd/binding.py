@@ -73,7 +73,7 @@ class _LikelihoodParams(C.Structure):
                 ("M", C.c_int32), ("z", C.c_void_p)]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -98,6 +98,8 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
     lib.difr_score_both.restype = C.c_int
+    lib.difr_score_both_admissible.argtypes = [C.POINTER(_Rows), vp, C.c_float] + [vp] * 13
+    lib.difr_score_both_admissible.restype = C.c_int
     lib.difr_ipt_score_filtered.argtypes = [C.POINTER(_Rows), C.c_int32, C.c_float, vp, vp, vp, vp, vp, C.c_double,
                                             C.c_double, vp, vp, vp, vp]
     lib.difr_ipt_score_filtered.restype = C.c_int
@@ -263,6 +265,31 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if rc:
         raise DifrError(rc, "difr_score_both")
     return g, i
+
+
+def score_both_admissible(logits, temperature, seeds, seq_ids, positions, delta, claimed_gumbel=None, claimed_ipt=None,
+                          temperatures=None, V=None):
+    """difr_score_both_admissible: both estimators and the admissible-set size in one pass.
+    Returns (gumbel dict, ipt dict, admissible dict with count [-1 = undetermined] and log2_count)."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
+    _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    g = dict(margin=torch.empty(N, **f32), argmax=torch.empty(N, dtype=torch.int32, device=dev),
+             max_score=torch.empty(N, **f32), claimed_score=torch.empty(N, **f32),
+             flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    i = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
+             u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    a = dict(count=torch.empty(N, dtype=torch.int32, device=dev), log2_count=torch.empty(N, **f32))
+    with torch.cuda.device(dev):
+        rc = lib.difr_score_both_admissible(C.byref(r), _ptr(claimed_ipt), float(delta), _ptr(g["margin"]),
+                                            _ptr(g["argmax"]), _ptr(g["max_score"]), _ptr(g["claimed_score"]),
+                                            _ptr(g["flags"]), _ptr(i["dist"]), _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]),
+                                            _ptr(i["u"]), _ptr(i["flags"]), _ptr(a["count"]), _ptr(a["log2_count"]),
+                                            _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_score_both_admissible")
+    return g, i, a
 
 
 def ipt_score_filtered(logits, temperature, seeds, seq_ids, positions, claimed=None, top_k=50, top_p=1.0,

@@ -274,6 +274,27 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                : DIFR_OK;
 }
 
+int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, float delta, float *margin,
+                               int32_t *argmax, float *max_score, float *claimed_score, uint8_t *flags_gumbel,
+                               float *dist, float *cdf_lo, float *cdf_hi, float *u, uint8_t *flags_ipt, int32_t *count,
+                               float *log2_count, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (!(delta >= 0.0f) || !isfinite(delta)) return DIFR_ERR_ARGUMENT;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt || !count) return DIFR_ERR_NULL;
+    if (!aligned) return DIFR_ERR_ALIGN;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+    return difr::launch_score_both_admissible(b, claimed_ipt, og, oi, delta, count, log2_count, (hipStream_t)hip_stream)
+               ? DIFR_ERR_LAUNCH
+               : DIFR_OK;
+}
+
 int difr_classify(const float *scores, const int32_t *ranks, int64_t N, float tau, int64_t rank_cutoff, int64_t V,
                   const float *log2_admissible, uint8_t *cls, float *bits, void *hip_stream)
 {

@@ -24,6 +24,8 @@ struct IptOutputs;
 // Both estimators in one pass (aligned rows only).
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
                       hipStream_t stream);
+int launch_score_both_admissible(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og,
+                                 const IptOutputs &oi, float delta, int32_t *count, float *log2_count, hipStream_t stream);
 // Token-DiFR likelihood estimate (aligned rows only).
 struct LikelihoodParams {
     int32_t top_k;   // 0 = no top-k

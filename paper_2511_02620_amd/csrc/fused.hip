@@ -2,6 +2,9 @@
 // share the 16-byte vector each lane has just loaded, so the logits are read from HBM once for
 // the two scores.  The two row streams are the ones the single-estimator kernels use
 // (gumbel_stream.hpp, ipt_stream.hpp); outputs are bit-identical to theirs.
+//
+// ADM: the same pass also returns the size of the row's admissible set { v : max y - y_v <= delta } (Sec. 7),
+// the count difr_admissible_count makes in a second pass once the maximum is known.
 #include "difr_device.hpp"
 #include "difr_host.hpp"
 #include "gumbel_stream.hpp"
@@ -9,9 +12,15 @@
 
 namespace difr {
 
-template <int DT>
+struct AdmissibleOutputs {
+    float delta;
+    int32_t *count;     // [N]; -1: not determined in one pass
+    float *log2_count;  // [N] or null
+};
+
+template <int DT, bool ADM>
 __global__ __launch_bounds__(kBlock) void score_both_kernel(RowBatch b, const int32_t *__restrict__ claimed_ipt,
-                                                            GumbelOutputs og, IptOutputs oi)
+                                                            GumbelOutputs og, IptOutputs oi, AdmissibleOutputs oa)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
@@ -22,6 +31,9 @@ __global__ __launch_bounds__(kBlock) void score_both_kernel(RowBatch b, const in
     __shared__ float lds_f[kWaves];
     __shared__ double lds_d[kWaves];
     __shared__ int32_t lds_tok;
+    __shared__ float adm_lists[ADM ? kWaves * kAdmCap : 1];
+    __shared__ int32_t adm_fills[kWaves];
+    __shared__ int32_t lds_c[kWaves];
 
     const int64_t row = blockIdx.x;
     const RowInfo ri = load_row_info(b, row);
@@ -30,15 +42,23 @@ __global__ __launch_bounds__(kBlock) void score_both_kernel(RowBatch b, const in
     if (!ri.seq_ok || !ri.temp_ok) {  // uniform over the workgroup
         gumbel_row_rejected(ri, row, og);
         ipt_row_rejected(ri_ipt, row, oi);
+        if (ADM && threadIdx.x == 0) {
+            oa.count[row] = 0;
+            if (oa.log2_count) oa.log2_count[row] = __builtin_nanf("");
+        }
         return;
     }
     const int tid = threadIdx.x;
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
     const int64_t V = b.V;
 
-    GumbelStream<DT, false> g(ri, x_row, V, lds_L);
+    GumbelStream<DT, false, false, false, ADM> g(ri, x_row, V, lds_L);
     IptStream<DT> s(ri_ipt, x_row, V, false);
     __syncthreads();
+    if (ADM) {
+        g.arm_admissible(oa.delta, adm_lists, adm_fills);
+        __syncthreads();
+    }
 
     const int64_t nvec = V / E;                                      // complete vectors
     const int64_t nvec_total = (V + E - 1) / E;                      // the last vector may be partial
@@ -93,6 +113,15 @@ __global__ __launch_bounds__(kBlock) void score_both_kernel(RowBatch b, const in
     }
     g.tail();
     g.finish(row, og, lds_y, lds_i, lds_rank);
+    if (ADM) {
+        const float M = g.best_y;  // the row maximum, in every thread
+        int32_t c = g.adm_count(lds_c);
+        if (!(M == M) || !(fabsf(M) < __builtin_inff())) c = 0;  // as difr_admissible_count: no finite maximum
+        if (tid == 0) {
+            oa.count[row] = c;
+            if (oa.log2_count) oa.log2_count[row] = c > 0 ? __log2f((float)c) : __builtin_nanf("");
+        }
+    }
     ipt_finish<DT, true>(b, ri_ipt, row, x_row, s.c, s.m, s.Z, s.P, s.mP, 0, oi, lds_f, lds_d, &lds_tok);
 }
 
@@ -100,10 +129,23 @@ int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const Gumbe
                       hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
+    const AdmissibleOutputs none{0.0f, nullptr, nullptr};
     if (b.dtype == 0)
-        score_both_kernel<0><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi);
+        score_both_kernel<0, false><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, none);
     else
-        score_both_kernel<1><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi);
+        score_both_kernel<1, false><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, none);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_score_both_admissible(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og,
+                                 const IptOutputs &oi, float delta, int32_t *count, float *log2_count, hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    const AdmissibleOutputs oa{delta, count, log2_count};
+    if (b.dtype == 0)
+        score_both_kernel<0, true><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, oa);
+    else
+        score_both_kernel<1, true><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, oa);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -76,14 +76,17 @@ struct Gate {
     int mode;         // 0: both caps <= 0 (unsigned min test); 1: both > 0 (signed max test); 2: hi > 0 >= lo
 };
 
-__device__ __forceinline__ Gate make_gate(float L, float T)
+// `reach`: how far below L a score may lie and still matter (0 for the argmax; delta when the entries within
+// delta of the row maximum are wanted as well).  All tests are made against L - reach.
+__device__ __forceinline__ Gate make_gate(float L, float T, float reach = 0.0f)
 {
     Gate g;
     L = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, L)));
-    const float slack = 0.01f + 1e-5f * fabsf(L);
+    const float Lr = L - reach;
+    const float slack = 0.01f + 1e-5f * fabsf(Lr);
     g.L = L;
-    g.Lgate = L - slack;
-    float hi = (L - kGumbelLo - slack) * T, lo = (L - kGumbelHi - slack) * T;
+    g.Lgate = Lr - slack;
+    float hi = (Lr - kGumbelLo - slack) * T, lo = (Lr - kGumbelHi - slack) * T;
     if (!(hi == hi)) hi = -__builtin_inff();  // L = +-inf arithmetic: gate everything in
     if (!(lo == lo)) lo = -__builtin_inff();
     g.xcap_hi = hi;
@@ -131,7 +134,17 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 //
 // TOPN: instead of tracking the best score, push every score that may belong to the n largest of the
 // row (the claimed token left out) into a TopN buffer; the gates use the buffer's threshold as the bound.
-template <int DT, bool RANK, bool COUNT = false, bool TOPN = false>
+//
+// ADM: the argmax as usual and, in the same pass, the size of the admissible set { v : max y - y_v <= delta }
+// although the maximum is only known at the end.  The gates test against L - delta instead of L (L = the
+// running lower bound of the maximum), every score evaluated that may lie within delta of the final maximum
+// is kept in a per-wave LDS list, and the list is counted against the true maximum after the row.  Since
+// L <= max y at all times, nothing within delta of the maximum is ever skipped or dropped.  A wave prunes
+// its own list against its current L - delta whenever it is half full (wave-synchronous, no barrier); if
+// pruning cannot get it below half, the row is reported as undetermined (count -1) rather than risk a miss.
+constexpr int kAdmCap = 1024;  // list entries per wave
+
+template <int DT, bool RANK, bool COUNT = false, bool TOPN = false, bool ADM = false>
 struct GumbelStream {
     typedef typename Elem<DT>::type elt_t;
     static constexpr int E = Elem<DT>::kPerVec;
@@ -157,6 +170,11 @@ struct GumbelStream {
     // COUNT mode
     float count_M, count_delta;
     uint32_t count;
+    // ADM mode
+    float adm_delta;    // 0 in every other mode
+    float *adm_list;    // this wave's kAdmCap floats in LDS
+    int32_t *adm_fill;  // this wave's fill counter in LDS
+    uint32_t adm_over;  // the list could not be kept below half: the count is not to be trusted
     // TOPN mode
 
     // Computes the claimed token's score with the same function the stream uses (the first lower
@@ -191,6 +209,21 @@ struct GumbelStream {
         asm volatile("" : "+v"(lane_prod));  // keep it a loop-invariant register pair
         count_M = count_delta = 0.0f;
         count = 0;
+        adm_delta = 0.0f;
+        adm_list = nullptr;
+        adm_fill = nullptr;
+        adm_over = 0;
+    }
+
+    // ADM mode: lists = kWaves * kAdmCap floats, fills = kWaves counters, both in LDS.  Call after the
+    // constructor's publication has been separated by a __syncthreads(); synchronise again before process().
+    __device__ __forceinline__ void arm_admissible(float delta, float *lists, int32_t *fills)
+    {
+        adm_delta = delta;
+        adm_list = lists + wave * kAdmCap;
+        adm_fill = fills + wave;
+        if ((tid & 63) == 0) *adm_fill = 0;
+        gate = make_gate(gate.L, T, adm_delta);
     }
 
     // TOPN mode: scores go to the selection handed to process() / tail() (by pointer argument, never stored:
@@ -232,6 +265,56 @@ struct GumbelStream {
             best_y = y;
             best_v = v;
         }
+        if (ADM) {
+            if (!(y < gate.Lgate)) {  // may lie within delta of the final maximum
+                const int32_t i = atomicAdd(adm_fill, 1);
+                if (i < kAdmCap)
+                    adm_list[i] = y;
+                else
+                    adm_over = 1;
+            }
+        }
+    }
+
+    // ADM mode, whole wave (call from wave-uniform code): drop what the current bound has ruled out once the
+    // list is half full.  A call of process() adds at most 512 entries, so a list that starts below half
+    // cannot overflow.
+    __device__ __forceinline__ void adm_prune()
+    {
+        const int lane = tid & 63;
+        const int32_t fill = __builtin_amdgcn_readfirstlane(*adm_fill);
+        if (fill <= kAdmCap / 2) return;
+        const int32_t c = min(fill, kAdmCap);
+        int32_t out = 0;
+        for (int32_t base = 0; base < c; base += 64) {
+            const bool have = base + lane < c;
+            const float y = have ? adm_list[base + lane] : 0.0f;
+            const bool keep = have && !(y < gate.Lgate);
+            const uint64_t m = __builtin_amdgcn_ballot_w64(keep);
+            const int32_t pos = out + (int32_t)__builtin_popcountll(m & ((1ull << lane) - 1ull));
+            if (keep) adm_list[pos] = y;  // pos <= base + lane: nothing unread is overwritten
+            out += (int32_t)__builtin_popcountll(m);
+        }
+        if (lane == 0) *adm_fill = out;
+        if (out > kAdmCap / 2) adm_over = 1;
+    }
+
+    // ADM mode, all 256 threads, after finish() (best_y is then the row maximum in every thread): the number
+    // of listed scores within delta of it, by the expression that forms margins; -1 if undetermined.
+    __device__ __forceinline__ int32_t adm_count(int32_t *lds_c)
+    {
+        const int lane = tid & 63;
+        const int32_t c = min(__builtin_amdgcn_readfirstlane(*adm_fill), kAdmCap);
+        int32_t n = 0;
+        for (int32_t base = 0; base < c; base += 64) {
+            const bool in = base + lane < c && (best_y - adm_list[base + lane < c ? base + lane : 0] <= adm_delta);
+            n += (int32_t)__builtin_popcountll(__builtin_amdgcn_ballot_w64(in));
+        }
+        const int any_over = __syncthreads_or((int)adm_over);
+        if (lane == 0) lds_c[wave] = n;
+        __syncthreads();
+        n = lds_c[0] + lds_c[1] + lds_c[2] + lds_c[3];
+        return any_over ? -1 : n;
     }
 
     // Entry-level test: can this entry still reach the lower bound?
@@ -334,9 +417,10 @@ struct GumbelStream {
             if (__builtin_amdgcn_ballot_w64(best_y > gate.L) != 0ull) {
                 float L = fmaxf(wave_max(best_y), gate.L);
                 L = fmaxf(fmaxf(L, lds_L[0]), fmaxf(lds_L[1], fmaxf(lds_L[2], lds_L[3])));
-                gate = make_gate(L, T);
+                gate = make_gate(L, T, ADM ? adm_delta : 0.0f);
                 if ((tid & 63) == 0) lds_L[wave] = gate.L;
             }
+            if (ADM) adm_prune();
         }
     }
 
@@ -355,7 +439,7 @@ struct GumbelStream {
     __device__ __forceinline__ void pickup()
     {
         const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
-        if (L > gate.L) gate = make_gate(L, T);
+        if (L > gate.L) gate = make_gate(L, T, ADM ? adm_delta : 0.0f);
     }
 
     // the ragged tail: V % E entries, one lane each, evaluated exactly

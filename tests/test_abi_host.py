@@ -144,6 +144,14 @@ def test_argument_validation_needs_no_device(lib):
     assert lik(rows(V=0)) == SHAPE and lik(rows(N=0), pi=None, fl=None, z=None) == OK
     assert lik(rows(V=15, ld=15)) == ALIGN                   # rows not 16-byte aligned
     assert lib.difr_gumbel_likelihood(C.byref(rows()), None, fake, None, None, None, fake, None) == NULL
+    # both estimators + admissible-set size in one pass
+    def sba(r=None, delta=1.0, margin=fake, count=fake):
+        return lib.difr_score_both_admissible(C.byref(r or rows()), None, C.c_float(delta), margin, fake, None, None, fake,
+                                              fake, None, None, None, fake, count, None, None)
+
+    assert sba(delta=-1.0) == ARG and sba(delta=float("inf")) == ARG and sba(delta=float("nan")) == ARG
+    assert sba(margin=None) == NULL and sba(count=None) == NULL
+    assert sba(rows(V=15, ld=15)) == ALIGN and sba(rows(V=0)) == SHAPE and sba(rows(N=0), margin=None, count=None) == OK
     # admissible-set size
     assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(-1.0), fake, None, None) == ARG
     assert lib.difr_admissible_count(C.byref(rows()), fake, C.c_float(float("nan")), fake, None, None) == ARG

@@ -158,6 +158,15 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     assert (ca[sure] == oa["count"][sure]).all()
     say(wl.name, "T=%g" % T, "admissible set at delta 2.5: mean size %.2f over all rows, %d near-threshold sampled rows"
         % (float(a2["count"].float().mean()), int((~sure).sum())))
+    # the same count from the one-pass call, with both scores: every row determined and equal to the two-pass count
+    g1, i1, a3 = difr.score_both_admissible(logits, T, seeds, sid, pos, 2.5, cg, ci)
+    torch.cuda.synchronize()
+    assert torch.equal(a3["count"], a2["count"]), int((a3["count"] != a2["count"]).sum())
+    for k in g1:
+        assert torch.equal(torch.nan_to_num(g1[k].float(), nan=-7.0), torch.nan_to_num(g[k].float(), nan=-7.0)), k
+    for k in i1:
+        ref = i[k] & 0xF7 if k == "flags" else i[k]      # the honest-token search of difr_ipt_score sets SLOW_PATH
+        assert torch.equal(torch.nan_to_num(i1[k].float(), nan=-7.0), torch.nan_to_num(ref.float(), nan=-7.0)), k
     # Token-DiFR likelihood estimate with the paper's generation policy (top-k 50, top-p 0.95) on every row;
     # the oracle on the first 384 sampled rows (it sorts the whole vocabulary twice per row)
     z = torch.randn(256, generator=torch.Generator().manual_seed(5), dtype=torch.float32)
