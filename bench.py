@@ -54,6 +54,9 @@ MEASURED_TRAFFIC = {
     ("difr_gumbel_score", "c3_30b_moe_class"): 1.9936e10,
     ("difr_ipt_score", "c3_30b_moe_class"): 1.9936e10,
     ("difr_score_both", "c3_30b_moe_class"): 1.9959e10,
+    # what the L2 fetched from the fabric (Infinity Cache and HBM together; the counter cannot tell them apart):
+    # every operand tile is wanted again by other workgroups after it has left the 4 MB L2 of its XCD
+    ("difr_lmhead_score", "c4_fused_lm_head"): 3.0296e10,
 }
 
 
@@ -163,6 +166,13 @@ def bench_lmhead(args, difr, W, dev):
             ev[2].record()
         return g, i, sg, si
 
+    if args.copy_probe:   # a plain copy of known size, to scale the profiler's byte counters
+        src = torch.empty(1 << 30, dtype=torch.int32, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -205,7 +215,9 @@ def bench_lmhead(args, difr, W, dev):
         "config": {"workload": wl.name, "N": wl.N, "V": wl.V, "d": wl.d, "temperature": wl.temperature,
                    "step": "difr_lmhead_score + 2x difr_seq_reduce over the whole batch"},
         "roofline": {"bound": "mfma", "achieved": round(tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(("difr_lmhead_score", wl.name)),
+                     "algorithmic_bytes_per_launch": 2.0 * (wl.V * wl.d + wl.N * wl.d),
                      "kernel": "difr_lmhead_score", "kernel_ms": round(t_l, 4), "algorithmic_flops_per_launch": flop},
         "kernels": {"difr_lmhead_score": {"ms": round(t_l, 4), "tokens_per_s": round(wl.N / (t_l * 1e-3), 1)},
                     "difr_seq_reduce_x2": {"ms": round(t_r, 4)},
