@@ -112,3 +112,44 @@ def test_extreme_temperatures(difr, T):
     near = og["gap2"] < 1e-6 * np.maximum(1.0, np.abs(og["max_score"]))
     assert ((gq["argmax"].cpu().numpy() == og["argmax"]) | near).all()
     parity.compare_ipt(iq, oi, tie_rel=1e-6)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_alignments_and_temperatures(difr, case):
+    """Seeded random draws of everything a caller can vary at once: row count, vocabulary size (round
+    boundaries +/- a few entries included), row stride, element type, a base offset that breaks the 16-byte
+    alignment in a third of the cases, shared or per-row temperatures, number of sequences, honest / random /
+    out-of-range claims.  Every row goes through the oracle."""
+    rng = np.random.default_rng(4200 + case)
+    dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+    per_vec = 8 if dtype == torch.bfloat16 else 4
+    base_v = int(rng.choice([per_vec * 256, per_vec * 256 * 3, 5000, 12000, 333]))
+    V = max(1, base_v + int(rng.integers(-9, 10)))
+    N = int(rng.integers(1, 70))
+    pad = int(rng.integers(0, 3)) * per_vec
+    aligned = rng.random() > 0.33
+    ld = ((V + per_vec - 1) // per_vec) * per_vec + pad if aligned else V + int(rng.integers(0, 3))
+    offset = 0 if aligned else int(rng.integers(1, per_vec))
+    g = torch.Generator().manual_seed(9000 + case)
+    store = torch.full((N * ld + offset + 16,), float("nan"), dtype=dtype, device=DEV)
+    logits = store[offset:offset + N * ld].view(N, ld)
+    logits[:, :V] = (torch.randn(N, V, generator=g) * float(rng.uniform(0.5, 4.0))).to(dtype).to(DEV)
+    S = int(rng.integers(1, 5))
+    seeds = torch.from_numpy(rng.integers(-(1 << 63), (1 << 63) - 1, size=S, dtype=np.int64)).to(DEV)
+    sid = torch.from_numpy(rng.integers(0, S, size=N).astype(np.int32)).to(DEV)
+    pos = torch.from_numpy(rng.integers(0, 1 << 20, size=N).astype(np.int32)).to(DEV)
+    T = float(rng.uniform(0.3, 1.8))
+    temps = None
+    if rng.random() < 0.4:
+        temps = torch.from_numpy(rng.uniform(0.3, 1.8, size=N).astype(np.float32)).to(DEV)
+    cg = difr.gumbel_score(logits, T, seeds, sid, pos, None, V=V, temperatures=temps)["argmax"]
+    ci = difr.ipt_score(logits, T, seeds, sid, pos, None, V=V, temperatures=temps, want_token=True)["ipt_token"]
+    rnd = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    k = torch.arange(N, device=DEV)
+    cg = torch.where(k % 4 == 1, rnd, cg)
+    ci = torch.where(k % 4 == 2, rnd, ci)
+    if N > 5:
+        cg[5] = V            # out of range: INVALID_CLAIM on that row only
+        ci[3] = -1
+    sg, si, was_aligned = _run_all(difr, logits, V, T, seeds, sid, pos, cg, ci, temps=temps)
+    assert was_aligned == aligned
