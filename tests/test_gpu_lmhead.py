@@ -95,6 +95,36 @@ def test_lmhead_every_row(difr, S, L, V, d, mode):
             assert torch.equal(torch.nan_to_num(a[key].float(), nan=-7.0), torch.nan_to_num(b[key].float(), nan=-7.0)), key
 
 
+def test_lmhead_padded_strides_and_many_vocabulary_ranges(difr):
+    """Few token rows and a long vocabulary: one token block, so the plan cuts the vocabulary into as many ranges
+    as it has tiles (79 partial results per token to merge); both operands are views into wider buffers (row
+    strides larger than d) whose padding holds NaNs."""
+    wl = _case(1, 64, 20000, 128, T=0.9)
+    Wm0, (Hv0, Hp0) = wl.weight(DEV), wl.hidden(DEV)
+    Wbig = torch.full((wl.V, wl.d + 24), float("nan"), dtype=torch.bfloat16, device=DEV)
+    Hbig = torch.full((wl.N, wl.d + 8), float("nan"), dtype=torch.bfloat16, device=DEV)
+    Wbig[:, :wl.d] = Wm0
+    Hbig[:, :wl.d] = Hv0
+    Wm, Hv = Wbig[:, :wl.d], Hbig[:, :wl.d]
+    assert Wm.stride(0) == wl.d + 24 and Hv.stride(0) == wl.d + 8
+    seeds, sid, pos = wl.seeds().to(DEV), wl.seq_ids().to(DEV), wl.positions().to(DEV)
+    cg = difr.lmhead_score(Hp0, Wm0, wl.temperature, seeds, sid, pos, None, None)[0]["argmax"].clone()
+    gen = torch.Generator().manual_seed(3)
+    ci = torch.randint(0, wl.V, (wl.N,), generator=gen, dtype=torch.int32).to(DEV)
+    cg[::5] = ci[::5]
+    g, i = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci)
+    g_ref, i_ref = difr.lmhead_score(Hv0, Wm0, wl.temperature, seeds, sid, pos, cg, ci)
+    torch.cuda.synchronize()
+    for a, b in ((g, g_ref), (i, i_ref)):      # the strides change nothing
+        for key in a:
+            assert torch.equal(torch.nan_to_num(a[key].float(), nan=-7.0), torch.nan_to_num(b[key].float(), nan=-7.0)), key
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    og, oi = oracle.lmhead_score(bits(Hv), bits(Wm), np.float32(wl.temperature), hs, hsid, hpos, cg.cpu().numpy(),
+                                 ci.cpu().numpy())
+    say("  strided / 79 ranges: gumbel", parity.compare_gumbel(g, og, tie_rel=TIE), "ipt", parity.compare_ipt(i, oi, tie_rel=TIE))
+    assert not (g["flags"] & 4).any() and not (i["flags"] & 4).any()      # the NaN padding was never read
+
+
 def test_lmhead_honest_claim_on_identical_inputs_has_margin_zero(difr):
     """A claim sampled by the same kernel from the same hidden states is the row maximum again:
     margin exactly 0 and MATCH, whatever the accumulation order of the matrix cores is."""
