@@ -134,14 +134,21 @@ __global__ __launch_bounds__(kBlock) void gumbel_score_filtered_kernel(RowBatch 
     int round = 0;
     auto run_rounds = [&](auto mode_tag) {
         constexpr int MODE = decltype(mode_tag)::value;
-        u32x4 q_next = load_round(x_row, round);
-        while (round < n_main) {
-            const u32x4 q = q_next;
-            if (round + 1 < n_main) q_next = load_round(x_row, round + 1);  // keep one vector in flight
+        // one round; returns false when the loop must be left (end reached, or the gate changed mode)
+        auto body = [&](const u32x4 &q) {
             g.template process<MODE>(q, round, true);
             ++round;
             if ((round & 15) == 0) g.pickup();
-            if (g.gate.mode != MODE) break;
+            return round < n_main && g.gate.mode == MODE;
+        };
+        // one vector is kept in flight; two copies of the body, so that the vector being loaded and the one
+        // being used swap roles instead of being copied from register to register every round
+        u32x4 qa = load_round(x_row, round), qb = qa;
+        while (true) {
+            if (round + 1 < n_main) qb = load_round(x_row, round + 1);
+            if (!body(qa)) break;
+            if (round + 1 < n_main) qa = load_round(x_row, round + 1);
+            if (!body(qb)) break;
         }
     };
     while (round < n_main) {
