@@ -226,7 +226,7 @@ __device__ __forceinline__ bool ipt_row_rejected(const RowInfo &ri, int64_t row,
     return true;
 }
 
-// Online softmax statistics per thread: m = running maximum logit, Z = sum of 2^((x - m) c).  Each
+// Online softmax statistics per thread: m = the lane's reference logit (see terms()), Z = sum of 2^((x - m) c).  Each
 // vector's terms are summed as an fp32 tree and the vector sums are accumulated in fp64, so the CDF
 // values are good to fp32 rounding.  (P, mP) is the same sum restricted to v < t.  Vector rounds
 // that lie wholly below the claimed token, wholly above it, and are full need no per-entry test:
@@ -255,7 +255,7 @@ struct IptStream {
         valid = (t >= 0 && t < V);
         xt = valid ? Elem<DT>::to_float(x_row[t]) : __builtin_nanf("");
         m = -__builtin_inff();
-        neg_mc = 0.0f;
+        neg_mc = __builtin_inff();  // no reference yet: see terms()
         mP = -__builtin_inff();
         Z = 0.0;
         P = 0.0;
@@ -278,27 +278,39 @@ struct IptStream {
         }
     }
 
-    // exponentials of one vector relative to the (possibly raised) running maximum
-    __device__ __forceinline__ void terms(const float x[E], float e[E])
+    // Exponentials of one vector relative to the lane's reference point m.  The reference is the maximum of the
+    // first vector the lane met and moves only when it has to: the sum of the eight terms is needed anyway,
+    // and as long as it stays below 2^64 no term has overflowed (an entry more than 64 / c above m, or a lane
+    // that has no reference yet -- neg_mc = +inf makes every term inf or NaN -- sends the sum over the limit).
+    // Nothing is lost by a reference below the running maximum: fp32 terms keep their relative precision at any
+    // scale, the sums are fp64, and every lane's sum is rescaled to the row's common reference at the end.
+    // Returns the sum of the terms.
+    __device__ __forceinline__ float terms(const float x[E], float e[E])
     {
-        float m8;
-        if (E == 8)
-            m8 = max3_raw(max3_raw(x[0], x[1], x[2]), max3_raw(x[3], x[4], x[5]), max3_raw(x[6 % E], x[7 % E], x[7 % E]));
-        else
-            m8 = max3_raw(max3_raw(x[0], x[1], x[2]), x[3], x[3]);
-        // Rebase the running sum when a lane meets a new maximum (m = -inf: Z is still 0 and stays 0).
-        // After the first few vectors no lane does, so the test is one compare and a scalar branch.
-        if (__builtin_amdgcn_ballot_w64(m8 > m) != 0ull) {
-            asm volatile("" ::: "memory");  // keep this a real branch: the body must not be speculated
-            if (m8 > m) {
-                Z *= (double)fast_exp2((m - m8) * c);
-                m = m8;
-                neg_mc = -(m8 * c);
-            }
-        }
-        // while only masked entries have been seen neg_mc is 0, so the exponent stays -inf, not NaN
 #pragma unroll
         for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, neg_mc));
+        float sum = tree_sum<E>(e);
+        if (__builtin_amdgcn_ballot_w64(!(sum <= 0x1p64f)) != 0ull) {
+            asm volatile("" ::: "memory");  // keep this a real, rarely taken branch
+            if (!(sum <= 0x1p64f)) {
+                float m8;
+                if (E == 8)
+                    m8 = max3_raw(max3_raw(x[0], x[1], x[2]), max3_raw(x[3], x[4], x[5]), max3_raw(x[6 % E], x[7 % E], x[7 % E]));
+                else
+                    m8 = max3_raw(max3_raw(x[0], x[1], x[2]), x[3], x[3]);
+                if (m8 > m) {  // (m = -inf: Z is still 0 and stays 0)
+                    Z *= (double)fast_exp2((m - m8) * c);
+                    m = m8;
+                    neg_mc = -(m8 * c);
+                }
+                // a lane that has met only masked entries keeps m = -inf; its terms are 2^(-inf + 0) = 0
+                const float shift = (m > -__builtin_inff()) ? neg_mc : 0.0f;
+#pragma unroll
+                for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, shift));
+                sum = tree_sum<E>(e);
+            }
+        }
+        return sum;
     }
 
     // a full round: every lane holds a complete vector, no index tests
@@ -312,8 +324,7 @@ struct IptStream {
             for (int j = 0; j < E; ++j) n += __builtin_popcountll(__builtin_amdgcn_ballot_w64(x[j] > xt));
             above += n;
         }
-        terms(x, e);
-        Z += (double)tree_sum<E>(e);
+        Z += (double)terms(x, e);
     }
 
     // everything seen so far lies below the claimed token
@@ -340,7 +351,7 @@ struct IptStream {
                 for (int j = 0; j < E; ++j) n += (uint32_t)(x[j] > xt);
                 lane_above += n;
             }
-            terms(x, e);
+            const float sum = terms(x, e);
             if (prefix_open) {
                 float pre = 0.0f;
 #pragma unroll
@@ -349,7 +360,7 @@ struct IptStream {
                 P = Z + (double)pre;
                 mP = m;
             }
-            Z += (double)tree_sum<E>(e);
+            Z += (double)sum;
         } else if (prefix_open) {
             P = Z;
             mP = m;
