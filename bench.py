@@ -43,8 +43,9 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # the entry against the running maximum.  The two logarithms and the fma of entries that provably
 # cannot reach the maximum are not counted: the exact pre-filter removes them.
 GUMBEL_ALU_OPS_PER_ENTRY = 11
-# ... and of the softmax statistics of the IPT estimator: scale-and-shift, exponential, sum, running maximum.
-IPT_ALU_OPS_PER_ENTRY = 4
+# ... and of the softmax statistics of the IPT estimator: scale-and-shift, exponential, sum (no running maximum:
+# the kernel's reference point moves only when a term would overflow).
+IPT_ALU_OPS_PER_ENTRY = 3
 ADMISSIBLE_DELTA = 2.5         # margin threshold of the admissible-set count timed next to the step
 LIKELIHOOD = {"top_k": 50, "top_p": 0.95, "s": 16, "sigma": 0.3, "M": 256}   # likelihood estimate timed next to it
 
