@@ -344,12 +344,14 @@ def main():
                                                              data["claims_i"]), reps)
         t_f = time_alone(lambda: difr.ipt_score_filtered(*row_args, data["claims_i"], top_k=LIKELIHOOD["top_k"],
                                                          top_p=LIKELIHOOD["top_p"]), reps)
+        t_n = time_alone(lambda: difr.ipt_score_filtered(*row_args, data["claims_i"], top_k=0, top_p=LIKELIHOOD["top_p"]),
+                         min(reps, 2))
         zl = torch.randn(LIKELIHOOD["M"], generator=torch.Generator().manual_seed(5)).to(dev)
         t_l = time_alone(lambda: difr.gumbel_likelihood(*row_args, data["claims_g"], zl, top_k=LIKELIHOOD["top_k"],
                                                         top_p=LIKELIHOOD["top_p"], s=LIKELIHOOD["s"],
                                                         sigma=LIKELIHOOD["sigma"]), reps)
     else:
-        t_b = t_a = t_l = t_f = t_ba = None
+        t_b = t_a = t_l = t_f = t_ba = t_n = None
         t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
@@ -423,6 +425,9 @@ def main():
                     {"ms": round(t_f, 4), "top_k": LIKELIHOOD["top_k"], "top_p": LIKELIHOOD["top_p"],
                      "tokens_per_s": round(wl.N / (t_f * 1e-3), 1),
                      "hbm_gbs": round(wl.N * (wl.V * esz + 33) / (t_f * 1e-3) / 1e9, 1)},
+                    "difr_ipt_score_filtered_nucleus": None if t_n is None else
+                    {"ms": round(t_n, 4), "top_k": 0, "top_p": LIKELIHOOD["top_p"],
+                     "tokens_per_s": round(wl.N / (t_n * 1e-3), 1)},
                     "difr_gumbel_likelihood": None if t_l is None else
                     dict(LIKELIHOOD, ms=round(t_l, 4), tokens_per_s=round(wl.N / (t_l * 1e-3), 1),
                          hbm_gbs=round(wl.N * (wl.V * esz + 24) / (t_l * 1e-3) / 1e9, 1))},

@@ -175,9 +175,15 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
  * vocabulary index, and everything else is as in difr_ipt_score: interval [a, b) of the claimed token, distance d,
  * MATCH, the sampler's own token, optional Gaussian log-mass.  A claimed token outside K has the empty interval
  * a = b (never a match; d = |u - a|).
- * 1 <= top_k <= 256 (0: DIFR_ERR_UNSUPPORTED - without a filter call difr_ipt_score; a nucleus over the whole
- * vocabulary is not built); top_p > 0; rows 16-byte aligned (DIFR_ERR_ALIGN).  Outputs as difr_ipt_score (all
+ * 1 <= top_k <= 256; top_p > 0; rows 16-byte aligned (DIFR_ERR_ALIGN).  Outputs as difr_ipt_score (all
  * optional ones may be NULL) plus kept [N] int32 or NULL = |K|.  One pass over the logits.
+ * top_k = 0 with top_p < 1 is the bare nucleus filter: the prefix is taken over the WHOLE vocabulary and may hold
+ * tens of thousands of tokens.  The library then searches for the last (logit, index) pair inside K with a radix
+ * search on the logit keys weighted by probability mass: four to six passes over the row instead of one.  The
+ * marginal tokens of such a nucleus have probabilities around 1e-6, the accuracy of the fp32 exponentials the mass
+ * is summed from, so kept[n] may differ from an evaluation in double by those few tokens; a, b and d keep the 1e-4
+ * contract.  ipt_token is not offered on this path (DIFR_ERR_UNSUPPORTED), nor is top_k = 0 with top_p >= 1 (no
+ * filter at all: call difr_ipt_score).
  */
 int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, float *dist, float *cdf_lo, float *cdf_hi,
                             float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass, int32_t *kept,
@@ -196,7 +202,9 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
  * p->z  DEVICE [M] fp32 standard normal draws, supplied by the caller and shared by all rows (the algorithm
  *       samples them; how is the caller's business: pseudo-random, stratified quantiles, a quadrature rule).
  * Limits: 0 <= s <= 256, 0 <= top_k <= 256, M >= 1, sigma > 0, top_p > 0 (else DIFR_ERR_ARGUMENT); rows must
- *       be 16-byte aligned (DIFR_ERR_ALIGN).
+ *       be 16-byte aligned (DIFR_ERR_ALIGN).  top_k = 0 with top_p < 1 (a nucleus over the whole vocabulary)
+ *       runs the search described at difr_ipt_score_filtered first; it leaves the threshold in `tau`, which is
+ *       then a required output (DIFR_ERR_UNSUPPORTED if NULL).
  * Outputs (DEVICE): pi [N] fp32; log_pi [N] fp32 or NULL (natural log, -inf if pi = 0; this is the FSSL score
  *       the paper thresholds); tau [N] fp32 or NULL; active [N, s] int32 or NULL (S in rank order, -1 padded);
  *       flags [N] (DIFR_FLAG_INVALID_CLAIM: pi NaN; DIFR_FLAG_NONFINITE).  Which tokens are in S is decided on

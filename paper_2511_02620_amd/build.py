@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdifr.so")
-SOURCES = ["api.hip", "gumbel.hip", "ipt.hip", "fused.hip", "likelihood.hip", "ipt_filtered.hip", "lmhead.hip", "reduce.hip"]
+SOURCES = ["api.hip", "gumbel.hip", "ipt.hip", "fused.hip", "likelihood.hip", "ipt_filtered.hip", "nucleus.hip", "lmhead.hip", "reduce.hip"]
 
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall",

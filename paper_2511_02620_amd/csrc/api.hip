@@ -217,12 +217,15 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
     if (rc != DIFR_OK) return rc;
     if (top_k < 0 || top_k > 256 || !(top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
     if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
-    if (top_k == 0) return DIFR_ERR_UNSUPPORTED;  // no top-k: use difr_ipt_score (no filter) - a nucleus over the whole vocabulary is not built
+    // no top-k: a nucleus over the whole vocabulary (without top-p either there is no filter: difr_ipt_score);
+    // the sampler's own token is not offered on that path
+    if (top_k == 0 && (!(top_p < 1.0f) || ipt_token)) return DIFR_ERR_UNSUPPORTED;
     if (b.N == 0) return DIFR_OK;
     if (!dist || !flags) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
     if ((rc = check_device()) != DIFR_OK) return rc;
     const difr::IptOutputs o{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags, nullptr};
+    if (top_k == 0) return difr::launch_ipt_nucleus(b, top_p, o, kept, nullptr, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
     return difr::launch_ipt_filtered(b, top_k, top_p, o, kept, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 
@@ -236,12 +239,19 @@ int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p,
     if (!p) return DIFR_ERR_NULL;
     if (p->s < 0 || p->s > 256 || p->top_k < 0 || p->top_k > 256 || p->M < 1) return DIFR_ERR_ARGUMENT;
     if (!(p->sigma > 0.0f) || !isfinite(p->sigma) || !(p->top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
-    if (p->top_k == 0 && p->top_p < 1.0f) return DIFR_ERR_UNSUPPORTED;
+    // a nucleus over the whole vocabulary is found by a kernel of its own, which leaves the threshold in the
+    // caller's tau array for the estimator to pick up: that output is then required
+    const bool nucleus = p->top_k == 0 && p->top_p < 1.0f;
+    if (nucleus && !tau) return DIFR_ERR_UNSUPPORTED;
     if (b.N == 0) return DIFR_OK;
     if (!pi || !flags || !p->z) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z};
+    if (nucleus) {
+        const difr::IptOutputs none{nullptr, nullptr, nullptr, nullptr, nullptr, 0.0, 0.0, nullptr, nullptr, nullptr};
+        if (difr::launch_ipt_nucleus(b, p->top_p, none, nullptr, tau, (hipStream_t)hip_stream)) return DIFR_ERR_LAUNCH;
+    }
+    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z, nucleus ? tau : nullptr};
     const difr::LikelihoodOutputs lo{pi, log_pi, tau, active, flags};
     return difr::launch_likelihood(b, lp, lo, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }

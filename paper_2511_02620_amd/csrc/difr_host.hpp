@@ -22,6 +22,7 @@ int launch_admissible_count(const RowBatch &b, bool aligned, const float *max_sc
 struct GumbelOutputs;
 struct IptOutputs;
 // Both estimators in one pass (aligned rows only).
+int launch_ipt_nucleus(const RowBatch &b, float top_p, const IptOutputs &o, int32_t *kept, float *tau, hipStream_t stream);
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
                       hipStream_t stream);
 int launch_score_both_admissible(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og,
@@ -34,6 +35,7 @@ struct LikelihoodParams {
     float sigma;     // standard deviation of the Gaussian logit noise
     int32_t M;       // number of draws
     const float *z;  // DEVICE [M] standard normal draws
+    const float *tau_in;  // DEVICE [N] filter threshold found beforehand (nucleus over the whole vocabulary), or null
 };
 struct LikelihoodOutputs {
     float *pi, *log_pi, *tau;

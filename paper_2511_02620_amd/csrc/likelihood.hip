@@ -171,6 +171,7 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     // filter threshold: top-k first, then top-p on the distribution renormalised over those k (fp64)
     double tau = -(double)__builtin_inff();
     if (p.top_k > 0 && nk > 0) tau = (double)top_key(buf_x[filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p, scratch) - 1]);
+    if (p.tau_in) tau = (double)p.tau_in[row];  // found beforehand by the nucleus kernel (NaN if it could not: pi becomes NaN)
     double xt = 0.0, gt = 0.0;
     if (valid) {
         xt = (double)Elem<DT>::to_float(x_row[t]);

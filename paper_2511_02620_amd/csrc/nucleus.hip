@@ -1,0 +1,379 @@
+// The nucleus (top-p) filter over the WHOLE vocabulary, and Token-IPT-DiFR on the distribution it leaves
+// (Sec. 3.2: the sampler's filter policy and the IPT sampler; Sec. 6.2; appendix "convolved Gaussian
+// score").  K is the shortest prefix of the tokens ranked by logit (ties to the lower index) whose
+// softmax(x / T) mass reaches top_p.  With no top-k in front of it K can hold tens of thousands of tokens,
+// so it is not collected: the kernel finds the CUT, the last (logit, index) pair that still belongs to K,
+// and membership of any token is one comparison against it.
+//
+// One workgroup per row, several passes over the row (it is read from HBM again each time):
+//   A    the row maximum M (the exponent reference) and a NaN / +inf check;
+//   B*   a radix search for the cut, four key bits per pass: every thread adds the mass 2^((x - M) c) and
+//        the count of its entries to 16 private LDS bins (no atomics, no conflicts), the bins are combined
+//        in a fixed order in fp64, and the bin in which the cumulative mass from the top reaches
+//        top_p * Z becomes the bracket for the next pass; Z is the total of the first pass;
+//   C    once the bracket holds at most kNucCap entries they are gathered as 64-bit composites (topn.hpp),
+//        sorted, and walked in rank order with an fp64 scan until the mass is reached: that entry is the cut.
+//        The same pass sums what lies above the bracket and below the claimed token's index.
+// Masses are fp32 terms accumulated per thread in fp32 and combined in fp64; whether a token whose
+// probability is 1e-6 still falls inside K is decided with a relative accuracy of about 1e-6 of the total
+// mass, which is the accuracy of the fp32 exponentials themselves.
+#include "difr_device.hpp"
+#include "difr_host.hpp"
+#include "ipt_stream.hpp"
+#include "topn.hpp"
+
+namespace difr {
+
+constexpr int kNucBins = 16;    // 4 key bits per pass
+constexpr int kNucCap = 2048;   // entries gathered and sorted at the end
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float top_p, IptOutputs o,
+                                                             int32_t *__restrict__ kept_out, float *__restrict__ tau_out)
+{
+    typedef typename Elem<DT>::type elt_t;
+    constexpr int E = Elem<DT>::kPerVec;
+    constexpr int kMinShift = DT == 0 ? 16 : 0;  // bf16 keys carry nothing below bit 16
+    // bins [bin][thread] (mass, then count) during the search; the gather buffer afterwards
+    __shared__ __attribute__((aligned(16))) unsigned char raw[2 * kNucBins * kBlock * 4];
+    __shared__ double part_m[16][kNucBins];
+    __shared__ int32_t part_c[16][kNucBins];
+    __shared__ double bin_m[kNucBins];
+    __shared__ int32_t bin_c[kNucBins];
+    __shared__ float lds_f[kWaves];
+    __shared__ double lds_d[kWaves];
+    __shared__ int32_t lds_i[kWaves];
+    __shared__ int32_t s_fill;
+    __shared__ float s_xtau;
+    __shared__ double s_mass_in;
+    __shared__ uint64_t s_cut;
+    static_assert(sizeof(raw) >= kNucCap * sizeof(uint64_t), "gather buffer must fit the bin memory");
+    float *mass = reinterpret_cast<float *>(raw);
+    int32_t *cnt = reinterpret_cast<int32_t *>(raw) + kNucBins * kBlock;
+    uint64_t *buf = reinterpret_cast<uint64_t *>(raw);
+
+    const int64_t row = blockIdx.x;
+    const RowInfo ri = load_row_info(b, row);
+    const int tid = threadIdx.x;
+    const float nan = __builtin_nanf("");
+    const float ninf = -__builtin_inff();
+    const bool want_ipt = o.dist != nullptr;
+    auto give_up = [&](uint32_t flag, int32_t kept) {  // uniform over the workgroup
+        if (tid == 0) {
+            if (want_ipt) {
+                o.dist[row] = nan;
+                if (o.cdf_lo) o.cdf_lo[row] = nan;
+                if (o.cdf_hi) o.cdf_hi[row] = nan;
+                if (o.u) o.u[row] = nan;
+                if (o.log_mass) o.log_mass[row] = nan;
+                o.flags[row] = (uint8_t)flag;
+            }
+            if (kept_out) kept_out[row] = kept;
+            if (tau_out) tau_out[row] = nan;
+        }
+    };
+    if (!ri.seq_ok || !ri.temp_ok) {
+        give_up(ri.seq_ok ? kFlagNonfinite : kFlagInvalidClaim, 0);
+        return;
+    }
+    const int64_t V = b.V;
+    const int64_t t = ri.claimed;
+    const bool valid = t >= 0 && t < V;
+    const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
+    const float c = kLog2e / ri.T;
+
+    // One pass over the row: f(x, base) for every 16-byte vector of this thread (entries past the end of the row
+    // read as -inf), with the next vector already requested while the current one is worked on.
+    const int64_t nvec = (V + E - 1) / E;
+    auto fetch = [&](int64_t vec) { return *reinterpret_cast<const ipt_u32x4 *>(x_row + vec * E); };
+    auto for_each_vector = [&](auto &&f) {
+        int64_t vec = tid;
+        ipt_u32x4 q_next = ipt_u32x4{0u, 0u, 0u, 0u};
+        if (vec < nvec) q_next = fetch(vec);
+        while (vec < nvec) {
+            const ipt_u32x4 q = q_next;
+            const int64_t next = vec + kBlock;
+            if (next < nvec) q_next = fetch(next);
+            float x[E];
+            IptStream<DT>::unpack(q, x);
+            const int64_t base = vec * E;
+            if (base + E > V) {
+#pragma unroll
+                for (int j = 0; j < E; ++j)
+                    if (base + j >= V) x[j] = ninf;
+            }
+            f(x, base);
+            vec = next;
+        }
+    };
+
+    // ---- pass A: the row maximum ----
+    float M = ninf;
+    uint32_t bad = 0;
+    for_each_vector([&](const float (&x)[E], int64_t) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            bad |= (uint32_t)!(x[j] < __builtin_inff());  // NaN or +inf
+            M = fmaxf(M, x[j]);
+        }
+    });
+    M = block_max(M, lds_f);
+    if (__syncthreads_or((int)bad) || !(M > ninf)) {  // undefined distribution (or every entry masked)
+        give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
+        return;
+    }
+    const float neg_Mc = -(M * c);
+
+    // ---- passes B: radix search for the bracket that holds the cut ----
+    uint32_t prefix = 0;  // the key bits above `shift` of every entry in the bracket
+    int shift = 32;
+    double mass_above = 0.0, target = 0.0;
+    int64_t cnt_above = 0;
+    int32_t bracket = 0;
+    while (true) {
+        shift -= 4;
+#pragma unroll
+        for (int k = 0; k < kNucBins; ++k) {
+            mass[k * kBlock + tid] = 0.0f;
+            cnt[k * kBlock + tid] = 0;
+        }
+        const bool first = shift == 28;
+        for_each_vector([&](const float (&x)[E], int64_t base) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const uint32_t key = float_order_bits(x[j]);
+                const bool inside = base + j < V && (first || (key >> (shift + 4)) == prefix);
+                if (inside) {
+                    const int k = (int)((key >> shift) & 15u);
+                    mass[k * kBlock + tid] += fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+                    cnt[k * kBlock + tid] += 1;
+                }
+            }
+        });
+        __syncthreads();
+        {  // 256 threads x 16 bins -> 16 bins, in a fixed order, fp64
+            const int k = tid & 15, grp = tid >> 4;
+            double sm = 0.0;
+            int32_t sc = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                sm += (double)mass[k * kBlock + grp * 16 + i];
+                sc += cnt[k * kBlock + grp * 16 + i];
+            }
+            part_m[grp][k] = sm;
+            part_c[grp][k] = sc;
+        }
+        __syncthreads();
+        if (tid < kNucBins) {
+            double sm = 0.0;
+            int32_t sc = 0;
+#pragma unroll
+            for (int grp = 0; grp < 16; ++grp) {
+                sm += part_m[grp][tid];
+                sc += part_c[grp][tid];
+            }
+            bin_m[tid] = sm;
+            bin_c[tid] = sc;
+        }
+        __syncthreads();
+        if (first) {
+            double Z = 0.0;
+            for (int k = 0; k < kNucBins; ++k) Z += bin_m[k];
+            target = (double)top_p * Z;
+        }
+        // from the top: the first bin in which the cumulative mass reaches the target (every thread walks
+        // the same 16 values in the same order)
+        int sel = 0;
+        for (int k = kNucBins - 1; k >= 0; --k) {
+            if (mass_above + bin_m[k] >= target || k == 0) {
+                sel = k;
+                break;
+            }
+            mass_above += bin_m[k];
+            cnt_above += bin_c[k];
+        }
+        bracket = bin_c[sel];
+        prefix = (prefix << 4) | (uint32_t)sel;
+        __syncthreads();  // the bins are cleared or reused next
+        if (bracket <= kNucCap || shift == kMinShift) break;
+    }
+    // More entries in the bracket than the sorter holds can only mean that the search has run out of key bits:
+    // the bracket is ONE logit value, shared by thousands of tokens.  Then no sorting is needed: the ties enter
+    // K in index order, each with the same mass, and how many of them do is a division.
+    const bool many_ties = bracket > kNucCap;
+
+    // ---- pass C: gather the bracket (or count the ties below the claimed token), and sum what lies above the
+    //      bracket and below the claimed token's index ----
+    if (tid == 0) s_fill = 0;
+    __syncthreads();
+    double below_above = 0.0;  // mass of entries above the bracket with index < t
+    int32_t ties_below = 0;    // many_ties: bracket entries with index < t
+    for_each_vector([&](const float (&x)[E], int64_t base) {
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            if (base + j >= V) continue;
+            const uint32_t hi = float_order_bits(x[j]) >> shift;
+            if (hi == prefix) {
+                if (many_ties) {
+                    ties_below += (int32_t)(base + j < t);
+                    s_xtau = x[j];  // the same value from every thread that writes it
+                } else {
+                    const int32_t i = atomicAdd(&s_fill, 1);
+                    if (i < kNucCap) buf[i] = top_composite(x[j], (int32_t)(base + j));
+                }
+            } else if (hi > prefix && base + j < t) {
+                below_above += (double)fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+            }
+        }
+    });
+    __syncthreads();
+
+    double Zk, below;     // mass of K; mass of the members of K below the claimed token's index
+    int64_t kept;
+    float tau_val;
+    uint64_t cut = 0ull;  // sorted path: the last member of K in rank order
+    int64_t n_tie = 0;    // tie path: how many of the ties belong to K
+    int32_t tb = 0;       //           and how many ties lie below the claimed token's index
+    if (many_ties) {
+        tau_val = s_xtau;
+        const double e_tau = (double)fast_exp2(__fmaf_rn(tau_val, c, neg_Mc));
+        n_tie = e_tau > 0.0 ? (int64_t)ceil((target - mass_above) / e_tau) : (int64_t)bracket;
+        n_tie = n_tie < 1 ? 1 : (n_tie > (int64_t)bracket ? (int64_t)bracket : n_tie);
+        tb = block_sum_i32(ties_below, lds_i);
+        below = block_sum_f64(below_above, lds_d) + e_tau * (double)((int64_t)tb < n_tie ? (int64_t)tb : n_tie);
+        Zk = mass_above + e_tau * (double)n_tie;
+        kept = cnt_above + n_tie;
+    } else {
+        const int n = min(s_fill, kNucCap);
+        int P = 256;
+        while (P < n) P <<= 1;
+        for (int i = n + tid; i < P; i += kBlock) buf[i] = 0ull;  // below every real composite
+        __syncthreads();
+        // bitonic sort, descending: rank order (larger logit first, then the smaller index)
+        for (int k = 2; k <= P; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int i = tid; i < P; i += kBlock) {
+                    const int l = i ^ j;
+                    if (l > i) {
+                        const uint64_t a = buf[i], bb = buf[l];
+                        const bool desc = (i & k) == 0;
+                        if (desc ? (a < bb) : (a > bb)) {
+                            buf[i] = bb;
+                            buf[l] = a;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+        // walk the sorted bracket: thread `tid` owns positions [tid * per, tid * per + per)
+        const int per = P / kBlock;
+        auto term = [&](int q) {  // mass of the thread's q-th position (0 past the end)
+            const int i = tid * per + q;
+            return (q < per && i < n) ? (double)fast_exp2(__fmaf_rn(top_key(buf[i]), c, neg_Mc)) : 0.0;
+        };
+        double run = 0.0;
+#pragma unroll
+        for (int q = 0; q < kNucCap / kBlock; ++q) run += term(q);
+        double total;
+        const double before = block_inclusive_scan(run, lds_d, total) - run;
+        // the first position at which the cumulative mass reaches the target: in the thread, then over the workgroup
+        int32_t my_pos = 0x7FFFFFFF;
+        double my_mass = 0.0, acc = before;
+#pragma unroll
+        for (int q = 0; q < kNucCap / kBlock; ++q) {
+            acc += term(q);
+            if (q < per && tid * per + q < n && my_pos == 0x7FFFFFFF && mass_above + acc >= target) {
+                my_pos = tid * per + q;
+                my_mass = acc;
+            }
+        }
+        int32_t pos = my_pos;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) pos = min(pos, __shfl_xor(pos, off, 64));
+        if ((tid & 63) == 0) lds_i[tid >> 6] = pos;
+        __syncthreads();
+        pos = min(min(lds_i[0], lds_i[1]), min(lds_i[2], lds_i[3]));
+        if (pos == 0x7FFFFFFF) {  // rounding left the target just out of reach: the whole bracket
+            pos = n - 1;
+            if (n > 0 && pos >= tid * per && pos < tid * per + per) {
+                s_mass_in = before + run;
+                s_cut = buf[pos];
+            }
+        } else if (pos == my_pos) {
+            s_mass_in = my_mass;
+            s_cut = buf[pos];
+        }
+        if (n == 0 && tid == 0) {  // cannot happen for top_p > 0 (the selected bin is never empty); be safe
+            s_mass_in = 0.0;
+            s_cut = ~0ull;
+        }
+        __syncthreads();
+        cut = s_cut;
+        Zk = mass_above + s_mass_in;
+        // included bracket entries below the claimed token's index
+        double mine_below = 0.0;
+#pragma unroll
+        for (int q = 0; q < kNucCap / kBlock; ++q) {
+            const int i = tid * per + q;
+            if (q < per && i <= pos && i < n && (int64_t)top_index(buf[i]) < t) mine_below += term(q);
+        }
+        below = block_sum_f64(below_above + mine_below, lds_d);
+        kept = cnt_above + (int64_t)(n > 0 ? pos + 1 : 0);
+        tau_val = n > 0 ? top_key(cut) : nan;
+    }
+
+    if (tid == 0) {
+        if (kept_out) kept_out[row] = (int32_t)kept;
+        if (tau_out) tau_out[row] = tau_val;
+        if (want_ipt) {
+            uint32_t r[4];
+            noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r);
+            const float u = uniform_from_bits(r[0]);
+            const double ud = (double)u;
+            float a = nan, bb = nan, d = nan;
+            double ad = 0.0, bd = 0.0;
+            bool match = false;
+            const bool ok = Zk > 0.0 && Zk < (double)__builtin_inff();
+            if (valid && ok) {
+                const float xt = Elem<DT>::to_float(x_row[t]);
+                bool in_K;
+                if (many_ties) {
+                    const uint32_t hi = float_order_bits(xt) >> shift;
+                    in_K = hi > prefix || (hi == prefix && (int64_t)tb < n_tie);
+                } else {
+                    in_K = top_composite(xt, (int32_t)t) >= cut;
+                }
+                const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Mc)) : 0.0;
+                ad = below / Zk;
+                bd = ad + own / Zk;
+                a = (float)ad;
+                bb = (float)bd;
+                d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+                match = (ad <= ud) && (ud < bd);
+            }
+            uint32_t f = 0;
+            if (!valid) f |= kFlagInvalidClaim;
+            if (!ok) f |= kFlagNonfinite;
+            if (match) f |= kFlagMatch;
+            o.dist[row] = d;
+            if (o.cdf_lo) o.cdf_lo[row] = a;
+            if (o.cdf_hi) o.cdf_hi[row] = bb;
+            if (o.u) o.u[row] = u;
+            if (o.log_mass) o.log_mass[row] = (valid && ok) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
+            o.flags[row] = (uint8_t)f;
+        }
+    }
+}
+
+int launch_ipt_nucleus(const RowBatch &b, float top_p, const IptOutputs &o, int32_t *kept, float *tau, hipStream_t stream)
+{
+    const dim3 grid((unsigned)b.N), block(kBlock);
+    if (b.dtype == 0)
+        ipt_nucleus_kernel<0><<<grid, block, 0, stream>>>(b, top_p, o, kept, tau);
+    else
+        ipt_nucleus_kernel<1><<<grid, block, 0, stream>>>(b, top_p, o, kept, tau);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // namespace difr

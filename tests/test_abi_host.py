@@ -125,7 +125,11 @@ def test_argument_validation_needs_no_device(lib):
                                            1e-30, lm, None, fl, None)
 
     assert iptf(k=-1) == ARG and iptf(k=257) == ARG and iptf(p=0.0) == ARG and iptf(sigma=0.0, lm=fake) == ARG
-    assert iptf(k=0) == 7 and iptf(dist=None) == NULL and iptf(fl=None) == NULL
+    assert iptf(k=0, p=1.0) == 7                              # DIFR_ERR_UNSUPPORTED: no filter at all is difr_ipt_score
+    assert lib.difr_ipt_score_filtered(C.byref(rows()), 0, 0.9, fake, None, None, None, fake, 0.01, 1e-30, None, None,
+                                       fake, None) == 7       # the sampler's token is not offered with a bare nucleus
+    assert iptf(rows(V=15, ld=15), k=0, p=0.9) == ALIGN and iptf(rows(N=0), k=0, p=0.9, dist=None, fl=None) == OK
+    assert iptf(dist=None) == NULL and iptf(fl=None) == NULL
     assert iptf(rows(V=15, ld=15)) == ALIGN and iptf(rows(N=0), dist=None, fl=None) == OK
     # likelihood estimate
     from paper_2511_02620_amd.binding import _LikelihoodParams
@@ -139,7 +143,7 @@ def test_argument_validation_needs_no_device(lib):
     for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0),
                dict(sigma=float("nan")), dict(top_p=0.0)):
         assert lik(**kw) == ARG, kw
-    assert lik(top_k=0, top_p=0.9) == 7                      # DIFR_ERR_UNSUPPORTED: nucleus over the whole vocabulary
+    assert lik(top_k=0, top_p=0.9) == 7                      # DIFR_ERR_UNSUPPORTED without the tau output (it carries the nucleus' threshold)
     assert lik(z=None) == NULL and lik(pi=None) == NULL and lik(fl=None) == NULL
     assert lik(rows(V=0)) == SHAPE and lik(rows(N=0), pi=None, fl=None, z=None) == OK
     assert lik(rows(V=15, ld=15)) == ALIGN                   # rows not 16-byte aligned

@@ -194,6 +194,20 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     assert np.array_equal(fi["kept"][ssel].cpu().numpy(), ofi["kept"])
     st_f = parity.compare_ipt({k: v[ssel] for k, v in fi.items() if k != "kept"}, ofi)
     say(wl.name, "T=%g" % T, "filtered ipt:", st_f, "mean kept %.1f" % float(fi["kept"].float().mean()))
+    # the bare nucleus (no top-k): every row, the oracle on the first 128 sampled rows at top_p and top_p -/+ 2e-6
+    # (the kept-set size of a nucleus of tens of thousands of tokens is decided by fp32 masses)
+    nu = difr.ipt_score_filtered(logits, T, seeds, sid, pos, ci, top_k=0, top_p=0.9)
+    torch.cuda.synchronize()
+    assert (nu["kept"] >= 1).all() and (nu["flags"] & 6 == 0).all()
+    nsel = ssel[:128]
+    onu = [oracle.ipt_filtered_score(host[:128], wl.V, f32(T), hs, hsid[:128], hpos[:128], ci[nsel].cpu().numpy(), 0,
+                                     float(f32(0.9)) + dp) for dp in (0.0, -2e-6, 2e-6)]
+    kn = nu["kept"][nsel].cpu().numpy()
+    assert (kn >= onu[1]["kept"]).all() and (kn <= onu[2]["kept"]).all()
+    for name in ("cdf_lo", "cdf_hi", "dist"):
+        assert np.abs(nu[name][nsel].cpu().numpy().astype(np.float64) - onu[0][name]).max() <= 1e-4, name
+    say(wl.name, "T=%g" % T, "nucleus 0.9: mean kept %.0f over all rows; %d of 128 oracle rows with the same size"
+        % (float(nu["kept"].float().mean()), int((kn == onu[0]["kept"]).sum())))
     say(wl.name, "T=%g" % T, "likelihood: mean pi %.4f over all rows, worst error %.3g on %d oracle rows, %d excused"
         % (float(pi_all.mean()), perr.max(), len(sub), int(excused.sum())))
     return g, i, sg, si, og, oi, st_g, st_i

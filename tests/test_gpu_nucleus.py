@@ -1,0 +1,144 @@
+"""GPU parity of the nucleus over the whole vocabulary (difr_ipt_score_filtered with top_k = 0, and the filter
+threshold difr_gumbel_likelihood uses with top_k = 0) against the oracle.
+
+Whether the marginal token of a nucleus of thousands of tokens is still inside is decided by a cumulative mass
+that the GPU forms from fp32 exponentials (relative accuracy ~1e-7 each) and the oracle in double.  The
+kept-set size must therefore lie between the oracle's sizes at top_p -/+ 2e-6 (and equal the oracle's wherever
+those two agree); interval ends and the distance must agree within 1e-4 absolute (the contract of the
+unfiltered estimator), which the mass of the few tokens in doubt (< 1e-5) does not touch."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import parity
+from paper_2511_02620_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+EPS_P = 2e-6
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def difr():
+    import paper_2511_02620_amd as m
+    m.load_library()
+    return m
+
+
+def _oracle(host, V, T, seeds, sid, pos, claims, p, temps):
+    return oracle.ipt_filtered_score(host, V, np.float32(T), parity.seeds_u64(seeds), sid.cpu().numpy(),
+                                     parity.positions_u32(pos), None if claims is None else claims.cpu().numpy(), 0,
+                                     float(p), temperatures=None if temps is None else temps.cpu().numpy(), sigma=0.02)
+
+
+def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
+    out = difr.ipt_score_filtered(logits, T, seeds, sid, pos, claims, top_k=0, top_p=p, temperatures=temps, V=V,
+                                  want_log_mass=True, sigma=0.02)
+    torch.cuda.synchronize()
+    host = parity.to_host_logits(logits)
+    p32 = float(np.float32(p))
+    ref = _oracle(host, V, T, seeds, sid, pos, claims, p32, temps)
+    lo = _oracle(host, V, T, seeds, sid, pos, claims, p32 - EPS_P, temps)["kept"]
+    hi = _oracle(host, V, T, seeds, sid, pos, claims, p32 + EPS_P, temps)["kept"]
+    kept = out["kept"].cpu().numpy()
+    assert (kept >= 0).all(), "undetermined rows"
+    assert (kept >= lo).all() and (kept <= hi).all(), np.nonzero((kept < lo) | (kept > hi))[0][:10]
+    sure = lo == hi
+    assert (kept[sure] == ref["kept"][sure]).all()
+    # rows whose kept set is the oracle's: the full comparison (log-mass included).  Rows in doubt differ from the
+    # oracle by the marginal token(s): interval ends and distance within the 1e-4 contract, nothing finer.
+    idx = torch.from_numpy(np.nonzero(sure)[0]).to(DEV)
+    st = parity.compare_ipt({k2: v[idx] for k2, v in out.items() if k2 != "kept"},
+                            {k2: v[sure] for k2, v in ref.items()}, log_mass_sigma=0.02)
+    for name in ("cdf_lo", "cdf_hi", "dist"):
+        g_, r_ = out[name].cpu().numpy().astype(np.float64)[~sure], ref[name][~sure]
+        both_nan = np.isnan(g_) & np.isnan(r_)
+        assert (both_nan | (np.abs(g_ - r_) <= 1e-4)).all(), name
+    st["mean_kept"] = float(kept.mean())
+    st["rows_in_doubt"] = int((~sure).sum())
+    return st, out
+
+
+@pytest.mark.parametrize("dtype,V,p,kind", [
+    (torch.bfloat16, 20504, 0.95, "normal"),       # thousands of tokens in the nucleus, many equal bf16 logits
+    (torch.bfloat16, 20504, 0.5, "normal"),
+    (torch.bfloat16, 20504, 0.9, "peaked"),        # a handful of tokens
+    (torch.bfloat16, 2051, 0.99, "normal"),        # ragged last vector
+    (torch.bfloat16, 300, 0.7, "normal"),          # a single, partly filled round
+    (torch.float32, 5003, 0.9, "normal"),          # fp32 keys: more search passes
+    (torch.float32, 5003, 0.95, "coarse"),         # fp32 storage, few distinct values: long runs of ties at the cut
+    (torch.bfloat16, 16384, 0.8, "masked"),        # half of the vocabulary at -inf
+    (torch.bfloat16, 40000, 0.9, "coarse"),        # thousands of tokens share the logit at the cut: no sorting, a division
+    (torch.float32, 40000, 0.6, "coarse"),
+])
+def test_nucleus_every_row(difr, dtype, V, p, kind):
+    N = 48
+    g = torch.Generator().manual_seed(31 + V + int(p * 100))
+    ld = ((V + 7) // 8) * 8
+    logits = torch.full((N, ld), float("nan"), dtype=dtype, device=DEV)
+    x = torch.randn(N, V, generator=g) * (6.0 if kind == "peaked" else 2.0)
+    if kind == "coarse":
+        x = torch.round(x * 2) / 2
+    if kind == "masked":
+        x[:, ::2] = float("-inf")
+    logits[:, :V] = x.to(dtype).to(DEV)
+    seeds = torch.tensor([11, 1 << 50], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    T = 0.9
+    # claims: the top token, a random token (mostly outside a small nucleus), an out-of-range one
+    claims = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    top = logits[:, :V].float().argmax(dim=1).to(torch.int32)
+    claims = torch.where(torch.arange(N, device=DEV) % 3 == 0, top, claims)
+    claims[5] = V
+    st, out = _compare(difr, logits, V, T, seeds, sid, pos, claims, p)
+    say("nucleus", dtype, V, p, kind, st)
+    assert not (out["flags"] & 4).any()
+
+
+def test_nucleus_zipf_rows_and_per_row_temperatures(difr):
+    """C2-class rows (V = 128256, Zipf profile): flat distributions whose 0.95-nucleus holds tens of thousands of
+    tokens; per-row temperatures."""
+    wl = W.scaled(W.C2_3B, S=2, L=24, chunk_rows=48)
+    ver, prov = wl.logits_chunk(0, DEV)
+    seeds, sid, pos = wl.seeds().to(DEV), wl.seq_ids().to(DEV), wl.positions().to(DEV)
+    temps = torch.linspace(0.4, 1.2, wl.N, device=DEV)
+    claims = difr.ipt_score(prov, 1.0, seeds, sid, pos, None, temperatures=temps, want_token=True, want_interval=False)["ipt_token"]
+    for p in (0.9, 0.95):
+        st, out = _compare(difr, ver, wl.V, 1.0, seeds, sid, pos, claims, p, temps=temps)
+        say("nucleus C2 rows p", p, st)
+
+
+def test_likelihood_with_a_whole_vocabulary_nucleus(difr):
+    """top_k = 0, top_p < 1 in difr_gumbel_likelihood: tau is the smallest logit of the nucleus; it must be the
+    oracle's at top_p, or lie between the oracle's at top_p -/+ 2e-6; pi must then agree wherever tau does."""
+    N, V = 40, 20504
+    g = torch.Generator().manual_seed(77)
+    logits = (torch.randn(N, V, generator=g) * 2.0).to(torch.bfloat16).to(DEV)
+    seeds = torch.tensor([5], dtype=torch.int64).to(DEV)
+    sid = torch.zeros(N, dtype=torch.int32, device=DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    cg = difr.gumbel_score(logits, 0.8, seeds, sid, pos, None, want_scores=False)["argmax"]
+    z = torch.randn(128, generator=g, dtype=torch.float32)
+    out = difr.gumbel_likelihood(logits, 0.8, seeds, sid, pos, cg, z.to(DEV), top_k=0, top_p=0.9, s=8, sigma=0.4)
+    torch.cuda.synchronize()
+    host = parity.to_host_logits(logits)
+    args = (host, V, np.float32(0.8), parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos), cg.cpu().numpy())
+    p32 = float(np.float32(0.9))
+    ref = oracle.likelihood(*args, 0, p32, 8, 0.4, z.numpy().astype(np.float64))
+    lo = oracle.likelihood(*args, 0, p32 + EPS_P, 8, 0.4, z.numpy().astype(np.float64))["tau"]   # more mass: lower threshold
+    hi = oracle.likelihood(*args, 0, p32 - EPS_P, 8, 0.4, z.numpy().astype(np.float64))["tau"]
+    tau = out["tau"].cpu().numpy().astype(np.float64)
+    assert (tau >= lo).all() and (tau <= hi).all()
+    same = tau == ref["tau"]
+    assert same.mean() > 0.8
+    pi = out["pi"].cpu().numpy().astype(np.float64)
+    assert np.abs(pi[same] - ref["pi"][same]).max() < 1e-4
+    say("likelihood with nucleus: tau equal on %d of %d rows, pi err %.2e" % (same.sum(), N, np.abs(pi[same] - ref["pi"][same]).max()))
