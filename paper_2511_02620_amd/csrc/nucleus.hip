@@ -34,12 +34,10 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
     constexpr int kMinShift = DT == 0 ? 16 : 0;  // bf16 keys carry nothing below bit 16
-    // bins [bin][thread] (mass, then count) during the search; the gather buffer afterwards
-    __shared__ __attribute__((aligned(16))) unsigned char raw[2 * kNucBins * kBlock * 4];
+    // mass bins [bin][thread] during the search; the gather buffer afterwards
+    __shared__ __attribute__((aligned(16))) unsigned char raw[kNucBins * kBlock * 4];
     __shared__ double part_m[16][kNucBins];
-    __shared__ int32_t part_c[16][kNucBins];
     __shared__ double bin_m[kNucBins];
-    __shared__ int32_t bin_c[kNucBins];
     __shared__ float lds_f[kWaves];
     __shared__ double lds_d[kWaves];
     __shared__ int32_t lds_i[kWaves];
@@ -49,7 +47,6 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     __shared__ uint64_t s_cut;
     static_assert(sizeof(raw) >= kNucCap * sizeof(uint64_t), "gather buffer must fit the bin memory");
     float *mass = reinterpret_cast<float *>(raw);
-    int32_t *cnt = reinterpret_cast<int32_t *>(raw) + kNucBins * kBlock;
     uint64_t *buf = reinterpret_cast<uint64_t *>(raw);
 
     const int64_t row = blockIdx.x;
@@ -128,52 +125,34 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     uint32_t prefix = 0;  // the key bits above `shift` of every entry in the bracket
     int shift = 32;
     double mass_above = 0.0, target = 0.0;
-    int64_t cnt_above = 0;
-    int32_t bracket = 0;
+    bool single_value = false;  // the search ran out of key bits: the bracket is one logit value
     while (true) {
         shift -= 4;
 #pragma unroll
-        for (int k = 0; k < kNucBins; ++k) {
-            mass[k * kBlock + tid] = 0.0f;
-            cnt[k * kBlock + tid] = 0;
-        }
+        for (int k = 0; k < kNucBins; ++k) mass[k * kBlock + tid] = 0.0f;
         const bool first = shift == 28;
         for_each_vector([&](const float (&x)[E], int64_t base) {
 #pragma unroll
             for (int j = 0; j < E; ++j) {
                 const uint32_t key = float_order_bits(x[j]);
                 const bool inside = base + j < V && (first || (key >> (shift + 4)) == prefix);
-                if (inside) {
-                    const int k = (int)((key >> shift) & 15u);
-                    mass[k * kBlock + tid] += fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
-                    cnt[k * kBlock + tid] += 1;
-                }
+                if (inside) mass[(int)((key >> shift) & 15u) * kBlock + tid] += fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
             }
         });
         __syncthreads();
         {  // 256 threads x 16 bins -> 16 bins, in a fixed order, fp64
             const int k = tid & 15, grp = tid >> 4;
             double sm = 0.0;
-            int32_t sc = 0;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                sm += (double)mass[k * kBlock + grp * 16 + i];
-                sc += cnt[k * kBlock + grp * 16 + i];
-            }
+            for (int i = 0; i < 16; ++i) sm += (double)mass[k * kBlock + grp * 16 + i];
             part_m[grp][k] = sm;
-            part_c[grp][k] = sc;
         }
         __syncthreads();
         if (tid < kNucBins) {
             double sm = 0.0;
-            int32_t sc = 0;
 #pragma unroll
-            for (int grp = 0; grp < 16; ++grp) {
-                sm += part_m[grp][tid];
-                sc += part_c[grp][tid];
-            }
+            for (int grp = 0; grp < 16; ++grp) sm += part_m[grp][tid];
             bin_m[tid] = sm;
-            bin_c[tid] = sc;
         }
         __syncthreads();
         if (first) {
@@ -190,24 +169,33 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
                 break;
             }
             mass_above += bin_m[k];
-            cnt_above += bin_c[k];
         }
-        bracket = bin_c[sel];
+        const double bracket_mass = bin_m[sel];
         prefix = (prefix << 4) | (uint32_t)sel;
         __syncthreads();  // the bins are cleared or reused next
-        if (bracket <= kNucCap || shift == kMinShift) break;
+        if (shift == kMinShift) {
+            single_value = true;
+            break;
+        }
+        // No counts are kept.  Every entry of the bracket weighs at least as much as the bracket's smallest
+        // key would, so mass / that weight bounds the number of entries from above; once the bound fits the
+        // sorter the search can stop.  (A bracket whose lower edge is not a finite number gives no bound.)
+        const float x_lo = float_from_order_bits(prefix << shift);
+        const double e_lo = (double)fast_exp2(__fmaf_rn(x_lo, c, neg_Mc));
+        if (e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48)) break;
     }
-    // More entries in the bracket than the sorter holds can only mean that the search has run out of key bits:
-    // the bracket is ONE logit value, shared by thousands of tokens.  Then no sorting is needed: the ties enter
-    // K in index order, each with the same mass, and how many of them do is a division.
-    const bool many_ties = bracket > kNucCap;
+    // A single logit value shared by the whole bracket (possibly thousands of tokens) needs no sorting: the ties
+    // enter K in index order, each with the same mass, and how many of them do is a division.
+    const bool many_ties = single_value;
 
     // ---- pass C: gather the bracket (or count the ties below the claimed token), and sum what lies above the
     //      bracket and below the claimed token's index ----
     if (tid == 0) s_fill = 0;
     __syncthreads();
     double below_above = 0.0;  // mass of entries above the bracket with index < t
-    int32_t ties_below = 0;    // many_ties: bracket entries with index < t
+    int32_t ties_below = 0;    // many_ties: bracket entries with index < t ...
+    int32_t ties = 0;          // ... and all of them
+    int32_t n_above = 0;       // entries above the bracket
     for_each_vector([&](const float (&x)[E], int64_t base) {
 #pragma unroll
         for (int j = 0; j < E; ++j) {
@@ -215,18 +203,21 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             const uint32_t hi = float_order_bits(x[j]) >> shift;
             if (hi == prefix) {
                 if (many_ties) {
+                    ties += 1;
                     ties_below += (int32_t)(base + j < t);
                     s_xtau = x[j];  // the same value from every thread that writes it
                 } else {
                     const int32_t i = atomicAdd(&s_fill, 1);
                     if (i < kNucCap) buf[i] = top_composite(x[j], (int32_t)(base + j));
                 }
-            } else if (hi > prefix && base + j < t) {
-                below_above += (double)fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+            } else if (hi > prefix) {
+                n_above += 1;
+                if (base + j < t) below_above += (double)fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
             }
         }
     });
     __syncthreads();
+    const int64_t cnt_above = (int64_t)block_sum_i32(n_above, lds_i);
 
     double Zk, below;     // mass of K; mass of the members of K below the claimed token's index
     int64_t kept;
@@ -237,8 +228,9 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     if (many_ties) {
         tau_val = s_xtau;
         const double e_tau = (double)fast_exp2(__fmaf_rn(tau_val, c, neg_Mc));
-        n_tie = e_tau > 0.0 ? (int64_t)ceil((target - mass_above) / e_tau) : (int64_t)bracket;
-        n_tie = n_tie < 1 ? 1 : (n_tie > (int64_t)bracket ? (int64_t)bracket : n_tie);
+        const int64_t bracket = (int64_t)block_sum_i32(ties, lds_i);
+        n_tie = e_tau > 0.0 ? (int64_t)ceil((target - mass_above) / e_tau) : bracket;
+        n_tie = n_tie < 1 ? 1 : (n_tie > bracket ? bracket : n_tie);
         tb = block_sum_i32(ties_below, lds_i);
         below = block_sum_f64(below_above, lds_d) + e_tau * (double)((int64_t)tb < n_tie ? (int64_t)tb : n_tie);
         Zk = mass_above + e_tau * (double)n_tie;
