@@ -7,13 +7,16 @@
 //
 // One workgroup per row, several passes over the row (it is read from HBM again each time):
 //   A    the row maximum M (the exponent reference) and a NaN / +inf check;
-//   B*   a radix search for the cut, four key bits per pass: every thread adds the mass 2^((x - M) c) and
-//        the count of its entries to 16 private LDS bins (no atomics, no conflicts), the bins are combined
-//        in a fixed order in fp64, and the bin in which the cumulative mass from the top reaches
-//        top_p * Z becomes the bracket for the next pass; Z is the total of the first pass;
-//   C    once the bracket holds at most kNucCap entries they are gathered as 64-bit composites (topn.hpp),
-//        sorted, and walked in rank order with an fp64 scan until the mass is reached: that entry is the cut.
-//        The same pass sums what lies above the bracket and below the claimed token's index.
+//   B*   a radix search for the cut, four key bits per pass: every thread adds the mass 2^((x - M) c) of its
+//        entries to 16 private LDS bins (no atomics, no conflicts), the bins are combined in a fixed order in
+//        fp64, and the bin in which the cumulative mass from the top reaches top_p * Z becomes the bracket for
+//        the next pass; Z is the total of the first pass.  The search stops when the bracket provably holds
+//        at most kNucCap entries (its mass divided by the weight of its smallest key bounds their number), or
+//        when the key bits are used up and the bracket is a single logit value;
+//   C    the bracket is gathered as 64-bit composites (topn.hpp), sorted, and walked in rank order with an fp64
+//        scan until the mass is reached: that entry is the cut.  A single-value bracket needs no sorting: the
+//        ties enter K in index order with equal mass, so their number is a division.  The same pass sums what
+//        lies above the bracket and below the claimed token's index.
 // Masses are fp32 terms accumulated per thread in fp32 and combined in fp64; whether a token whose
 // probability is 1e-6 still falls inside K is decided with a relative accuracy of about 1e-6 of the total
 // mass, which is the accuracy of the fp32 exponentials themselves.
