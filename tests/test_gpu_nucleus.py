@@ -142,3 +142,30 @@ def test_likelihood_with_a_whole_vocabulary_nucleus(difr):
     pi = out["pi"].cpu().numpy().astype(np.float64)
     assert np.abs(pi[same] - ref["pi"][same]).max() < 1e-4
     say("likelihood with nucleus: tau equal on %d of %d rows, pi err %.2e" % (same.sum(), N, np.abs(pi[same] - ref["pi"][same]).max()))
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_nucleus_random_shapes(difr, case):
+    """Seeded random vocabulary sizes (round boundaries +/- a few entries), element types, spreads of the logits,
+    temperatures (shared or per row) and top_p values; every row against the oracle."""
+    rng = np.random.default_rng(7700 + case)
+    dtype = torch.bfloat16 if rng.random() < 0.6 else torch.float32
+    per_vec = 8 if dtype == torch.bfloat16 else 4
+    V = max(2, int(rng.choice([per_vec * 256, per_vec * 256 * 2, 3000, 9000, 150])) + int(rng.integers(-5, 6)))
+    ld = ((V + per_vec - 1) // per_vec) * per_vec + int(rng.integers(0, 2)) * per_vec
+    N = int(rng.integers(1, 40))
+    g = torch.Generator().manual_seed(100 + case)
+    logits = torch.full((N, ld), float("nan"), dtype=dtype, device=DEV)
+    logits[:, :V] = (torch.randn(N, V, generator=g) * float(rng.uniform(0.3, 5.0)) + float(rng.uniform(-20, 20))).to(dtype).to(DEV)
+    S = int(rng.integers(1, 4))
+    seeds = torch.from_numpy(rng.integers(-(1 << 63), (1 << 63) - 1, size=S, dtype=np.int64)).to(DEV)
+    sid = torch.from_numpy(rng.integers(0, S, size=N).astype(np.int32)).to(DEV)
+    pos = torch.from_numpy(rng.integers(0, 1 << 20, size=N).astype(np.int32)).to(DEV)
+    T = float(rng.uniform(0.2, 1.6))
+    temps = torch.from_numpy(rng.uniform(0.2, 1.6, size=N).astype(np.float32)).to(DEV) if rng.random() < 0.4 else None
+    p = float(rng.choice([0.1, 0.5, 0.8, 0.9, 0.95, 0.99, 0.999]))
+    claims = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    top = logits[:, :V].float().argmax(dim=1).to(torch.int32)
+    claims = torch.where(torch.arange(N, device=DEV) % 2 == 0, top, claims)
+    st, out = _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=temps)
+    say("nucleus random", case, dtype, V, "p", p, st)
