@@ -68,6 +68,12 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     };
     // epochs without barriers, as in the likelihood kernel: the first round alone, then eight at a time, with a
     // rewind and a round-by-round repeat if some thread had more candidates than its quota
+    // priming run of the first round (topn.hpp): a threshold before anything is pushed
+    if (n_rounds > 0) {
+        lx.top.begin_prime();
+        do_round(fetch(0), 0);
+        if (lx.top.end_prime(scratch)) lx.retarget();
+    }
     int round = 0;
     while (round < n_rounds) {
         const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));

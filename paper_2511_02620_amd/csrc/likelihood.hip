@@ -118,6 +118,14 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     };
     // Epochs: the first round alone (every entry is a candidate while there is no threshold: exactly the
     // quota), then kTopEpoch rounds at a time without a barrier; the partly filled round is an epoch of its own.
+    // priming run of the first round (topn.hpp): thresholds for both selections before anything is pushed
+    if (n_rounds > 0) {
+        top_y.begin_prime();
+        top_x.begin_prime();
+        do_round(0);
+        if (top_y.end_prime(scratch)) g.retarget(top_y);
+        if (top_x.end_prime(scratch)) lx.retarget();
+    }
     int round = 0;
     while (round < n_rounds) {
         const int r_end = round < n_main ? min(n_main, round + (round == 0 ? 1 : kTopEpoch)) : n_rounds;

@@ -52,6 +52,7 @@ struct TopScratch {
     int32_t hist[256];
     int32_t wave_sum[kWaves];
     int32_t sel_bin, sel_need, kept;
+    uint64_t sel64;
     uint64_t tmp[kTopKeep];
 };
 
@@ -66,6 +67,8 @@ struct TopN {
                      // with __syncthreads_or: reading the counter instead would race with the next round's pushes)
     int quota;       // pushes this thread may still make in the current epoch
     bool over;       // this thread had a candidate beyond its quota: the epoch must be repeated
+    bool priming;    // see begin_prime()
+    uint64_t prime_best;
 
     __device__ __forceinline__ void init(uint64_t *buf_, int32_t *count_, int n_)
     {
@@ -77,6 +80,8 @@ struct TopN {
         full = false;
         quota = kTopQuota;
         over = false;
+        priming = false;
+        prime_best = 0ull;
         if (threadIdx.x == 0) *count = 0;
     }
 
@@ -86,8 +91,43 @@ struct TopN {
         over = false;
     }
 
+    // Priming.  While there is no threshold every entry of the first round is a candidate: 2048 pushes through
+    // one counter and a compaction over all of them.  Instead the first round is run twice: the first time each
+    // thread only remembers its best candidate; the n-th largest of those 256 is a valid lower bound of the
+    // n-th largest overall (they are real entries), it becomes the threshold, and the second, ordinary run of
+    // the round pushes only what lies above it.
+    __device__ __forceinline__ void begin_prime()
+    {
+        priming = true;
+        prime_best = 0ull;
+    }
+    // All 256 threads, after the priming run of the round; ends with a __syncthreads().  Returns true if a
+    // threshold was found (the caller re-targets its gates either way and runs the round again).
+    __device__ __forceinline__ bool end_prime(TopScratch &s)
+    {
+        priming = false;
+        if (prime_best != 0ull) {
+            const int32_t i = atomicAdd(count, 1);
+            buf[i] = prime_best;  // at most one per thread
+        }
+        __syncthreads();
+        const bool moved = compact(s, false);
+        // the primed entries are dropped (they come again with the round itself); the n-th largest of them must
+        // pass the push test then, so the threshold is put just below it
+        if (threadIdx.x == 0) *count = 0;
+        if (moved) theta -= 1ull;
+        trigger = min(kTopTrigger, n > kTopFresh ? n : kTopFresh);
+        full = false;
+        __syncthreads();
+        return moved;
+    }
+
     __device__ __forceinline__ void push(uint64_t c)
     {
+        if (priming) {
+            if (c > theta && c > prime_best) prime_best = c;
+            return;
+        }
         if (c > theta) {
             if (quota <= 0) {
                 over = true;
@@ -121,6 +161,28 @@ struct TopN {
             trigger = min(kTopTrigger, cnt + (n > kTopFresh ? n : kTopFresh));
             __syncthreads();
             return false;
+        }
+        if (cnt <= 2 * kBlock) {
+            // Few entries: every entry finds its rank by counting the entries above it (one broadcast read serves
+            // both entries of a thread), the n best move to the front in rank order and the n-th of them is the new,
+            // exact threshold.  Three barriers instead of the dozen of the radix select below.
+            uint64_t mine0 = tid < cnt ? buf[tid] : 0ull, mine1 = tid + kBlock < cnt ? buf[tid + kBlock] : 0ull;
+            int r0 = 0, r1 = 0;
+            for (int i = 0; i < cnt; ++i) {
+                const uint64_t c = buf[i];
+                r0 += (int)(c > mine0);
+                r1 += (int)(c > mine1);
+            }
+            if (tid < cnt && r0 == n - 1) s.sel64 = mine0;
+            if (tid + kBlock < cnt && r1 == n - 1) s.sel64 = mine1;
+            __syncthreads();
+            if (tid < cnt && r0 < n) buf[r0] = mine0;
+            if (tid + kBlock < cnt && r1 < n) buf[r1] = mine1;
+            if (tid == 0) *count = n;
+            theta = s.sel64;
+            trigger = min(kTopTrigger, n + (n > kTopFresh ? n : kTopFresh));
+            __syncthreads();
+            return true;
         }
         uint64_t prefix = 0ull, mask = 0ull;
         int need = n;        // rank of the wanted composite among the entries that match the prefix
