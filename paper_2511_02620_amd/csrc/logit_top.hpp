@@ -64,11 +64,21 @@ struct LogitTop {
         if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
             if (hit) {
                 const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+                if (DT == 0) {
+                    // +inf or a NaN with the sign bit clear: the largest pattern, as signed 16-bit, is >= 0x7F80
+                    i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                    bad |= (uint32_t)((m.x > m.y ? m.x : m.y) >= (int16_t)0x7F80);
 #pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
-                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
-                    push_entry(xv, (int32_t)(v0 + j));
+                    for (int j = 0; j < E; ++j) {
+                        const uint32_t w = qw[j >> 1];
+                        const float xv = __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
+                        if (xv >= floor) top.push(top_composite(xv, (int32_t)(v0 + j)));
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) push_entry(__uint_as_float(qw[j]), (int32_t)(v0 + j));
                 }
             }
         }
