@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     const float nan = __builtin_nanf("");
     const float ninf = -__builtin_inff();
     const bool want_ipt = o.dist != nullptr;
-    auto give_up = [&](uint32_t flag, int32_t kept) {  // uniform over the workgroup
+    auto give_up = [&](uint32_t flag, int32_t kept) __attribute__((always_inline)) {  // uniform over the workgroup
         if (tid == 0) {
             if (want_ipt) {
                 o.dist[row] = nan;
@@ -82,49 +82,96 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
     const float c = kLog2e / ri.T;
 
-    // One pass over the row: f(x, base) for every 16-byte vector of this thread (entries past the end of the row
-    // read as -inf), with the next vector already requested while the current one is worked on.
-    const int64_t nvec = (V + E - 1) / E;
-    auto fetch = [&](int64_t vec) { return *reinterpret_cast<const ipt_u32x4 *>(x_row + vec * E); };
-    auto for_each_vector = [&](auto &&f) {
-        int64_t vec = tid;
+    // One pass over the row: f(q, base) for every 16-byte vector of this thread, with the next vector already
+    // requested while the current one is worked on.  Entries past the end of the row read as -inf.
+    const int32_t nvec = (int32_t)((V + E - 1) / E);  // V < 2^31
+    const uint32_t V32 = (uint32_t)V;
+    auto fetch = [&](int32_t vec) { return *reinterpret_cast<const ipt_u32x4 *>(x_row + (size_t)vec * E); };
+    auto for_each_vector = [&](auto &&f) __attribute__((always_inline)) {
+        int32_t vec = tid;
         ipt_u32x4 q_next = ipt_u32x4{0u, 0u, 0u, 0u};
         if (vec < nvec) q_next = fetch(vec);
         while (vec < nvec) {
-            const ipt_u32x4 q = q_next;
-            const int64_t next = vec + kBlock;
+            ipt_u32x4 q = q_next;
+            const int32_t next = vec + kBlock;
             if (next < nvec) q_next = fetch(next);
-            float x[E];
-            IptStream<DT>::unpack(q, x);
-            const int64_t base = vec * E;
-            if (base + E > V) {
+            const uint32_t base = (uint32_t)vec * E;
+            if (base + E > V32) {  // the last vector of a ragged row
+                uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                for (int j = 0; j < E; ++j)
-                    if (base + j >= V) x[j] = ninf;
+                for (int j = 0; j < E; ++j) {
+                    if (base + j < V32) continue;
+                    if (DT == 0)
+                        w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[j >> 1] & 0xFFFF0000u) | 0x0000FF80u);
+                    else
+                        w[j] = 0xFF800000u;
+                }
+                q = ipt_u32x4{w[0], w[1], w[2], w[3]};
             }
-            f(x, base);
+            f(q, base);
             vec = next;
         }
     };
-
-    // ---- pass A: the row maximum ----
-    float M = ninf;
-    uint32_t bad = 0;
-    for_each_vector([&](const float (&x)[E], int64_t) {
+    // Order keys of a vector at the resolution the storage type has.  bf16: two 16-bit keys per dword (the top
+    // halves of float_order_bits of the two entries), formed on the packed patterns; fp32: one 32-bit key each.
+    // field(kw, j, lo, width): bits [lo, lo + width) of entry j's 32-bit key (lo >= 16 for bf16).
+    auto keys_of = [&](const ipt_u32x4 &q, uint32_t (&kw)[4]) __attribute__((always_inline)) {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-        for (int j = 0; j < E; ++j) {
-            bad |= (uint32_t)!(x[j] < __builtin_inff());  // NaN or +inf
-            M = fmaxf(M, x[j]);
+        for (int i = 0; i < 4; ++i) {
+            if (DT == 0) {
+                typedef int16_t i16x2_t __attribute__((ext_vector_type(2)));
+                const i16x2_t sg = __builtin_bit_cast(i16x2_t, w[i]) >> 15;  // 0xFFFF where the sign bit is set
+                kw[i] = w[i] ^ (__builtin_bit_cast(uint32_t, sg) | 0x80008000u);
+            } else {
+                kw[i] = float_order_bits(__uint_as_float(w[i]));
+            }
         }
-    });
-    M = block_max(M, lds_f);
-    if (__syncthreads_or((int)bad) || !(M > ninf)) {  // undefined distribution (or every entry masked)
-        give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
-        return;
+    };
+    // bits [lo, lo + 4) of entry j's 32-bit key, and everything from bit `lo` up (lo >= 16 for bf16)
+    auto nibble = [&](const uint32_t (&kw)[4], int j, int lo) __attribute__((always_inline)) {
+        if (DT == 0) return __builtin_amdgcn_ubfe(kw[j >> 1], (uint32_t)((j & 1) * 16 + lo - 16), 4u);
+        return __builtin_amdgcn_ubfe(kw[j], (uint32_t)lo, 4u);
+    };
+    auto top_bits = [&](const uint32_t (&kw)[4], int j, int lo) __attribute__((always_inline)) {
+        if (DT == 0) return __builtin_amdgcn_ubfe(kw[j >> 1], (uint32_t)((j & 1) * 16 + lo - 16), (uint32_t)(32 - lo));
+        return kw[j] >> lo;
+    };
+    auto value_of = [&](const ipt_u32x4 &q, int j) __attribute__((always_inline)) {
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+        if (DT == 0) return __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+        return __uint_as_float(w[j]);
+    };
+
+    // ---- the exponent reference R: the largest entry of the first 256 vectors.  Any finite reference serves
+    //      (fp32 terms keep their relative precision at every scale, the sums are fp64); the row maximum M itself
+    //      comes out of the first search pass, and that pass is repeated with R = M in the rare case that M lies so
+    //      far above R that terms could overflow.  A first round without a usable value takes a pass for M. ----
+    float R = ninf;
+    if (tid < nvec) {
+        const ipt_u32x4 q = fetch(tid);
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+            if ((uint32_t)(tid * E + j) < V32) R = fmaxf(R, value_of(q, j));
     }
-    const float neg_Mc = -(M * c);
+    R = block_max(R, lds_f);
+    if (!(R > ninf && R < __builtin_inff())) {  // uniform
+        float m = ninf;
+        for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) m = fmaxf(m, value_of(q, j));  // NaNs drop out; the first pass finds them
+        });
+        R = block_max(m, lds_f);
+        if (!(R > ninf && R < __builtin_inff())) {  // every entry masked, or a +inf
+            give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
+            return;
+        }
+    }
+    float neg_Rc = -(R * c);
 
     // ---- passes B: radix search for the bracket that holds the cut ----
+    constexpr uint32_t kKeyPosInf = DT == 0 ? 0xFF80u : 0xFF800000u;  // keys >= this: +inf or a NaN, sign clear
+    constexpr uint32_t kKeyNegInf = DT == 0 ? 0x007Fu : 0x007FFFFFu;  // keys < this: a NaN with the sign bit set
     uint32_t prefix = 0;  // the key bits above `shift` of every entry in the bracket
     int shift = 32;
     double mass_above = 0.0, target = 0.0;
@@ -134,14 +181,56 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
 #pragma unroll
         for (int k = 0; k < kNucBins; ++k) mass[k * kBlock + tid] = 0.0f;
         const bool first = shift == 28;
-        for_each_vector([&](const float (&x)[E], int64_t base) {
+        // a thread's bins are its own: plain read-modify-write (LDS float atomics run many times slower here)
+        auto add_mass = [&](uint32_t bin, float e) __attribute__((always_inline)) { mass[(int)bin * kBlock + tid] += e; };
+        if (first) {
+            // largest and smallest key met (bf16: of the even and of the odd entries, packed)
+            typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+            uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+            for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
+                uint32_t kw[4];
+                keys_of(q, kw);
 #pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const uint32_t key = float_order_bits(x[j]);
-                const bool inside = base + j < V && (first || (key >> (shift + 4)) == prefix);
-                if (inside) mass[(int)((key >> shift) & 15u) * kBlock + tid] += fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+                for (int i = 0; i < 4; ++i) {
+                    if (DT == 0) {
+                        kmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, kmax), __builtin_bit_cast(u16x2_t, kw[i])));
+                        kmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, kmin), __builtin_bit_cast(u16x2_t, kw[i])));
+                    } else {
+                        kmax = max(kmax, kw[i]);
+                        kmin = min(kmin, kw[i]);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < E; ++j) add_mass(nibble(kw, j, 28), fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
+            });
+            if (DT == 0) {
+                kmax = max(kmax & 0xFFFFu, kmax >> 16);
+                kmin = min(kmin & 0xFFFFu, kmin >> 16);
             }
-        });
+            // NaN or +inf anywhere: no distribution
+            if (__syncthreads_or((int)(kmax >= kKeyPosInf || kmin < kKeyNegInf))) {
+                give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
+                return;
+            }
+            const uint32_t kmax32 = DT == 0 ? ((kmax << 16) | ((kmax & 0x8000u) ? 0u : 0xFFFFu)) : kmax;
+            const float M = block_max(tid < nvec ? float_from_order_bits(kmax32) : ninf, lds_f);
+            if ((M - R) * c > 96.0f) {  // uniform; terms up to 2^96 and more: start again from M
+                R = M;
+                neg_Rc = -(R * c);
+                shift = 32;
+                continue;
+            }
+        } else {
+            for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
+                uint32_t kw[4];
+                keys_of(q, kw);
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    if (top_bits(kw, j, shift + 4) == prefix)
+                        add_mass(nibble(kw, j, shift), fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
+                }
+            });
+        }
         __syncthreads();
         {  // 256 threads x 16 bins -> 16 bins, in a fixed order, fp64
             const int k = tid & 15, grp = tid >> 4;
@@ -184,7 +273,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         // key would, so mass / that weight bounds the number of entries from above; once the bound fits the
         // sorter the search can stop.  (A bracket whose lower edge is not a finite number gives no bound.)
         const float x_lo = float_from_order_bits(prefix << shift);
-        const double e_lo = (double)fast_exp2(__fmaf_rn(x_lo, c, neg_Mc));
+        const double e_lo = (double)fast_exp2(__fmaf_rn(x_lo, c, neg_Rc));
         if (e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48)) break;
     }
     // A single logit value shared by the whole bracket (possibly thousands of tokens) needs no sorting: the ties
@@ -199,25 +288,30 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     int32_t ties_below = 0;    // many_ties: bracket entries with index < t ...
     int32_t ties = 0;          // ... and all of them
     int32_t n_above = 0;       // entries above the bracket
-    for_each_vector([&](const float (&x)[E], int64_t base) {
+    const uint32_t t32 = valid ? (uint32_t)t : 0u;  // an invalid claim has nothing below it (its outputs are NaN anyway)
+    for_each_vector([&](const ipt_u32x4 &q, uint32_t base) {
+        uint32_t kw[4];
+        keys_of(q, kw);
+        float below_vec = 0.0f;
 #pragma unroll
         for (int j = 0; j < E; ++j) {
-            if (base + j >= V) continue;
-            const uint32_t hi = float_order_bits(x[j]) >> shift;
+            if (base + E > V32 && base + j >= V32) continue;  // (false for every vector but a ragged last one)
+            const uint32_t hi = top_bits(kw, j, shift);
             if (hi == prefix) {
                 if (many_ties) {
                     ties += 1;
-                    ties_below += (int32_t)(base + j < t);
-                    s_xtau = x[j];  // the same value from every thread that writes it
+                    ties_below += (int32_t)(base + j < t32);
+                    s_xtau = value_of(q, j);  // the same value from every thread that writes it
                 } else {
                     const int32_t i = atomicAdd(&s_fill, 1);
-                    if (i < kNucCap) buf[i] = top_composite(x[j], (int32_t)(base + j));
+                    if (i < kNucCap) buf[i] = top_composite(value_of(q, j), (int32_t)(base + j));
                 }
             } else if (hi > prefix) {
                 n_above += 1;
-                if (base + j < t) below_above += (double)fast_exp2(__fmaf_rn(x[j], c, neg_Mc));
+                if (base + j < t32) below_vec += fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
             }
         }
+        below_above += (double)below_vec;
     });
     __syncthreads();
     const int64_t cnt_above = (int64_t)block_sum_i32(n_above, lds_i);
@@ -230,7 +324,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     int32_t tb = 0;       //           and how many ties lie below the claimed token's index
     if (many_ties) {
         tau_val = s_xtau;
-        const double e_tau = (double)fast_exp2(__fmaf_rn(tau_val, c, neg_Mc));
+        const double e_tau = (double)fast_exp2(__fmaf_rn(tau_val, c, neg_Rc));
         const int64_t bracket = (int64_t)block_sum_i32(ties, lds_i);
         n_tie = e_tau > 0.0 ? (int64_t)ceil((target - mass_above) / e_tau) : bracket;
         n_tie = n_tie < 1 ? 1 : (n_tie > bracket ? bracket : n_tie);
@@ -265,7 +359,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         const int per = P / kBlock;
         auto term = [&](int q) {  // mass of the thread's q-th position (0 past the end)
             const int i = tid * per + q;
-            return (q < per && i < n) ? (double)fast_exp2(__fmaf_rn(top_key(buf[i]), c, neg_Mc)) : 0.0;
+            return (q < per && i < n) ? (double)fast_exp2(__fmaf_rn(top_key(buf[i]), c, neg_Rc)) : 0.0;
         };
         double run = 0.0;
 #pragma unroll
@@ -339,7 +433,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
                 } else {
                     in_K = top_composite(xt, (int32_t)t) >= cut;
                 }
-                const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Mc)) : 0.0;
+                const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Rc)) : 0.0;
                 ad = below / Zk;
                 bd = ad + own / Zk;
                 a = (float)ad;
