@@ -5,18 +5,28 @@
 // so it is not collected: the kernel finds the CUT, the last (logit, index) pair that still belongs to K,
 // and membership of any token is one comparison against it.
 //
-// One workgroup per row, several passes over the row (it is read from HBM again each time):
-//   A    the row maximum M (the exponent reference) and a NaN / +inf check;
-//   B*   a radix search for the cut, four key bits per pass: every thread adds the mass 2^((x - M) c) of its
-//        entries to 16 private LDS bins (no atomics, no conflicts), the bins are combined in a fixed order in
-//        fp64, and the bin in which the cumulative mass from the top reaches top_p * Z becomes the bracket for
-//        the next pass; Z is the total of the first pass.  The search stops when the bracket provably holds
-//        at most kNucCap entries (its mass divided by the weight of its smallest key bounds their number), or
-//        when the key bits are used up and the bracket is a single logit value;
+// One workgroup per row, several passes over the row (it is read from HBM again each time).  Throughout, a
+// token's KEY is the order-preserving integer image of its logit at the storage type's resolution (16 bits for
+// bf16, formed on the packed patterns), and a bracket is a range of keys [klo, khi].
+//   0    a look at the first 256 vectors: their largest entry R (the exponent reference for every mass
+//        2^((x - R) c): any finite reference serves) and their smallest finite one;
+//   B1   every thread adds the mass of its entries to 16 private LDS bins (no atomics, no conflicts) that divide
+//        the span of LOGIT VALUES seen in step 0 evenly, values outside falling into the end bins; the same pass
+//        finds the smallest and largest key of the row (NaN / +inf check, the maximum M).  The bins are combined
+//        in a fixed order in fp64, their total Z fixes the target top_p * Z, and the bin in which the cumulative
+//        mass from the top reaches it becomes the bracket: bin1 is monotone in the logit, so its first key is
+//        found by bisection.  (If M lies so far above R that terms could overflow, the pass is repeated with
+//        R = M.)
+//   B2.. the bracket's key range is divided evenly into at most 16 bins and searched in the same way, until it
+//        is a single key - one logit value - or provably holds at most kNucCap entries (its mass divided by the
+//        weight of its smallest key bounds their number).  Typically one or two passes;
 //   C    the bracket is gathered as 64-bit composites (topn.hpp), sorted, and walked in rank order with an fp64
 //        scan until the mass is reached: that entry is the cut.  A single-value bracket needs no sorting: the
 //        ties enter K in index order with equal mass, so their number is a division.  The same pass sums what
 //        lies above the bracket and below the claimed token's index.
+// Why the first bins are laid over logit values and not over the leading key bits: the mass is spread over
+// logit values, while key bits spend most of their range on exponents near zero - a search by key digits takes
+// three passes in which nine entries in ten are still inside the bracket.
 // Masses are fp32 terms accumulated per thread in fp32 and combined in fp64; whether a token whose
 // probability is 1e-6 still falls inside K is decided with a relative accuracy of about 1e-6 of the total
 // mass, which is the accuracy of the fp32 exponentials themselves.
@@ -36,7 +46,6 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
-    constexpr int kMinShift = DT == 0 ? 16 : 0;  // bf16 keys carry nothing below bit 16
     // mass bins [bin][thread] during the search; the gather buffer afterwards
     __shared__ __attribute__((aligned(16))) unsigned char raw[kNucBins * kBlock * 4];
     __shared__ double part_m[16][kNucBins];
@@ -128,111 +137,90 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             }
         }
     };
-    // bits [lo, lo + 4) of entry j's 32-bit key, and everything from bit `lo` up (lo >= 16 for bf16)
-    auto nibble = [&](const uint32_t (&kw)[4], int j, int lo) __attribute__((always_inline)) {
-        if (DT == 0) return __builtin_amdgcn_ubfe(kw[j >> 1], (uint32_t)((j & 1) * 16 + lo - 16), 4u);
-        return __builtin_amdgcn_ubfe(kw[j], (uint32_t)lo, 4u);
-    };
-    auto top_bits = [&](const uint32_t (&kw)[4], int j, int lo) __attribute__((always_inline)) {
-        if (DT == 0) return __builtin_amdgcn_ubfe(kw[j >> 1], (uint32_t)((j & 1) * 16 + lo - 16), (uint32_t)(32 - lo));
-        return kw[j] >> lo;
-    };
     auto value_of = [&](const ipt_u32x4 &q, int j) __attribute__((always_inline)) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
         if (DT == 0) return __uint_as_float((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
         return __uint_as_float(w[j]);
     };
 
-    // ---- the exponent reference R: the largest entry of the first 256 vectors.  Any finite reference serves
-    //      (fp32 terms keep their relative precision at every scale, the sums are fp64); the row maximum M itself
-    //      comes out of the first search pass, and that pass is repeated with R = M in the rare case that M lies so
-    //      far above R that terms could overflow.  A first round without a usable value takes a pass for M. ----
-    float R = ninf;
-    if (tid < nvec) {
-        const ipt_u32x4 q = fetch(tid);
+    // ---- a look at the first 256 vectors: their largest entry R and their smallest finite one.  R is the exponent
+    //      reference: any finite reference serves (fp32 terms keep their relative precision at every scale, the sums
+    //      are fp64); the row maximum M itself comes out of the first search pass, and that pass is repeated with
+    //      R = M in the rare case that M lies so far above R that terms could overflow.  The two together tell the
+    //      first search pass where to put its bins.  A first round without a usable value takes a pass of its own. ----
+    float R = ninf, lo_s = __builtin_inff();
+    auto look = [&](const ipt_u32x4 &q) __attribute__((always_inline)) {
 #pragma unroll
-        for (int j = 0; j < E; ++j)
-            if ((uint32_t)(tid * E + j) < V32) R = fmaxf(R, value_of(q, j));
+        for (int j = 0; j < E; ++j) {
+            const float v = value_of(q, j);
+            R = fmaxf(R, v);  // NaNs drop out; the first search pass finds them
+            if (v > ninf) lo_s = fminf(lo_s, v);
+        }
+    };
+    if (tid < nvec) {
+        ipt_u32x4 q = fetch(tid);
+        if ((uint32_t)(tid * E + E) > V32) {  // a row shorter than one round: the ragged vector
+            uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                if ((uint32_t)(tid * E + j) < V32) continue;
+                if (DT == 0)
+                    w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[j >> 1] & 0xFFFF0000u) | 0x0000FF80u);
+                else
+                    w[j] = 0xFF800000u;
+            }
+            q = ipt_u32x4{w[0], w[1], w[2], w[3]};
+        }
+        look(q);
     }
     R = block_max(R, lds_f);
     if (!(R > ninf && R < __builtin_inff())) {  // uniform
-        float m = ninf;
-        for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
-#pragma unroll
-            for (int j = 0; j < E; ++j) m = fmaxf(m, value_of(q, j));  // NaNs drop out; the first pass finds them
-        });
-        R = block_max(m, lds_f);
+        R = ninf;
+        lo_s = __builtin_inff();
+        for_each_vector([&](const ipt_u32x4 &q, uint32_t) { look(q); });
+        R = block_max(R, lds_f);
         if (!(R > ninf && R < __builtin_inff())) {  // every entry masked, or a +inf
             give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
             return;
         }
     }
+    lo_s = -block_max(-lo_s, lds_f);  // finite and <= R, since R is
     float neg_Rc = -(R * c);
 
-    // ---- passes B: radix search for the bracket that holds the cut ----
+    // ---- passes B: search for the bracket [klo, khi] of keys that holds the cut ----
+    // Keys are the order-preserving images of the logits at the storage type's resolution (16 bits for bf16).
     constexpr uint32_t kKeyPosInf = DT == 0 ? 0xFF80u : 0xFF800000u;  // keys >= this: +inf or a NaN, sign clear
     constexpr uint32_t kKeyNegInf = DT == 0 ? 0x007Fu : 0x007FFFFFu;  // keys < this: a NaN with the sign bit set
-    uint32_t prefix = 0;  // the key bits above `shift` of every entry in the bracket
-    int shift = 32;
-    double mass_above = 0.0, target = 0.0;
-    bool single_value = false;  // the search ran out of key bits: the bracket is one logit value
-    while (true) {
-        shift -= 4;
+    auto value_of_key = [&](uint32_t k) __attribute__((always_inline)) {
+        return float_from_order_bits(DT == 0 ? ((k << 16) | ((k & 0x8000u) ? 0u : 0xFFFFu)) : k);
+    };
+    auto key_of = [&](const uint32_t (&kw)[4], int j) __attribute__((always_inline)) {
+        if (DT == 0) return (j & 1) ? (kw[j >> 1] >> 16) : (kw[j >> 1] & 0xFFFFu);
+        return kw[j];
+    };
+    // block-wide maximum / minimum of a key
+    auto block_max_key = [&](uint32_t k) __attribute__((always_inline)) {
+        uint32_t m = k;
 #pragma unroll
-        for (int k = 0; k < kNucBins; ++k) mass[k * kBlock + tid] = 0.0f;
-        const bool first = shift == 28;
-        // a thread's bins are its own: plain read-modify-write (LDS float atomics run many times slower here)
-        auto add_mass = [&](uint32_t bin, float e) __attribute__((always_inline)) { mass[(int)bin * kBlock + tid] += e; };
-        if (first) {
-            // largest and smallest key met (bf16: of the even and of the odd entries, packed)
-            typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
-            uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
-            for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
-                uint32_t kw[4];
-                keys_of(q, kw);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (DT == 0) {
-                        kmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, kmax), __builtin_bit_cast(u16x2_t, kw[i])));
-                        kmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, kmin), __builtin_bit_cast(u16x2_t, kw[i])));
-                    } else {
-                        kmax = max(kmax, kw[i]);
-                        kmin = min(kmin, kw[i]);
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < E; ++j) add_mass(nibble(kw, j, 28), fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
-            });
-            if (DT == 0) {
-                kmax = max(kmax & 0xFFFFu, kmax >> 16);
-                kmin = min(kmin & 0xFFFFu, kmin >> 16);
-            }
-            // NaN or +inf anywhere: no distribution
-            if (__syncthreads_or((int)(kmax >= kKeyPosInf || kmin < kKeyNegInf))) {
-                give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
-                return;
-            }
-            const uint32_t kmax32 = DT == 0 ? ((kmax << 16) | ((kmax & 0x8000u) ? 0u : 0xFFFFu)) : kmax;
-            const float M = block_max(tid < nvec ? float_from_order_bits(kmax32) : ninf, lds_f);
-            if ((M - R) * c > 96.0f) {  // uniform; terms up to 2^96 and more: start again from M
-                R = M;
-                neg_Rc = -(R * c);
-                shift = 32;
-                continue;
-            }
-        } else {
-            for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
-                uint32_t kw[4];
-                keys_of(q, kw);
-#pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    if (top_bits(kw, j, shift + 4) == prefix)
-                        add_mass(nibble(kw, j, shift), fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
-                }
-            });
-        }
+        for (int off = 32; off >= 1; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
         __syncthreads();
-        {  // 256 threads x 16 bins -> 16 bins, in a fixed order, fp64
+        if ((tid & 63) == 0) lds_i[tid >> 6] = (int32_t)m;
+        __syncthreads();
+        return max(max((uint32_t)lds_i[0], (uint32_t)lds_i[1]), max((uint32_t)lds_i[2], (uint32_t)lds_i[3]));
+    };
+    auto block_min_key = [&](uint32_t k) __attribute__((always_inline)) {
+        uint32_t m = k;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) m = min(m, (uint32_t)__shfl_xor((int)m, off, 64));
+        __syncthreads();
+        if ((tid & 63) == 0) lds_i[tid >> 6] = (int32_t)m;
+        __syncthreads();
+        return min(min((uint32_t)lds_i[0], (uint32_t)lds_i[1]), min((uint32_t)lds_i[2], (uint32_t)lds_i[3]));
+    };
+    // the 256 x 16 per-thread bins -> bin_m[16], in a fixed order, fp64; ends with a barrier
+    auto combine_bins = [&]() __attribute__((always_inline)) {
+        __syncthreads();
+        {
             const int k = tid & 15, grp = tid >> 4;
             double sm = 0.0;
 #pragma unroll
@@ -247,13 +235,17 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             bin_m[tid] = sm;
         }
         __syncthreads();
-        if (first) {
-            double Z = 0.0;
-            for (int k = 0; k < kNucBins; ++k) Z += bin_m[k];
-            target = (double)top_p * Z;
-        }
-        // from the top: the first bin in which the cumulative mass reaches the target (every thread walks
-        // the same 16 values in the same order)
+    };
+    // a thread's bins are its own: plain read-modify-write (LDS float atomics run many times slower here)
+    auto add_mass = [&](uint32_t bin, float e) __attribute__((always_inline)) { mass[(int)bin * kBlock + tid] += e; };
+    auto clear_bins = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kNucBins; ++k) mass[k * kBlock + tid] = 0.0f;
+    };
+    double mass_above = 0.0, target = 0.0;
+    // from the top: the first bin in which the cumulative mass reaches the target (every thread walks the same 16
+    // values in the same order); what lies above it is added to mass_above
+    auto select_bin = [&]() __attribute__((always_inline)) {
         int sel = 0;
         for (int k = kNucBins - 1; k >= 0; --k) {
             if (mass_above + bin_m[k] >= target || k == 0) {
@@ -262,19 +254,119 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             }
             mass_above += bin_m[k];
         }
-        const double bracket_mass = bin_m[sel];
-        prefix = (prefix << 4) | (uint32_t)sel;
-        __syncthreads();  // the bins are cleared or reused next
-        if (shift == kMinShift) {
+        return sel;
+    };
+
+    // First pass: every entry counts (the total mass Z fixes the target), and the 16 bins divide the span of
+    // LOGIT VALUES seen in the first round evenly - the mass is spread over logit values, not over key bits, which
+    // spend most of their range on exponents near zero.  bin1 is monotone in the logit, so each bin is a range of
+    // keys; values outside the span seen in the first round fall into the end bins.
+    uint32_t klo, khi;
+    double bracket_mass;  // mass of the entries with keys in [klo, khi]
+    while (true) {
+        float sc = (R > lo_s) ? 16.0f / (R - lo_s) : 0.0f;
+        if (!(sc < 1.0e30f)) sc = 0.0f;  // a span too small to divide: one bin
+        const float off = -(lo_s * sc);
+        auto bin1 = [&](float x) __attribute__((always_inline)) {  // (clamped before the conversion: always in range)
+            return sc > 0.0f ? (uint32_t)(int)__builtin_amdgcn_fmed3f(__fmaf_rn(x, sc, off), 0.0f, 15.0f) : 0u;
+        };
+        clear_bins();
+        // largest and smallest key met (bf16: of the even and of the odd entries, packed)
+        typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+        uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+        for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
+            uint32_t kw[4];
+            keys_of(q, kw);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (DT == 0) {
+                    kmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, kmax), __builtin_bit_cast(u16x2_t, kw[i])));
+                    kmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, kmin), __builtin_bit_cast(u16x2_t, kw[i])));
+                } else {
+                    kmax = max(kmax, kw[i]);
+                    kmin = min(kmin, kw[i]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const float x = value_of(q, j);
+                add_mass(bin1(x), fast_exp2(__fmaf_rn(x, c, neg_Rc)));
+            }
+        });
+        if (DT == 0) {
+            kmax = max(kmax & 0xFFFFu, kmax >> 16);
+            kmin = min(kmin & 0xFFFFu, kmin >> 16);
+        }
+        kmax = block_max_key(kmax);  // (a thread without a vector still holds the neutral values)
+        kmin = block_min_key(kmin);
+        if (kmax >= kKeyPosInf || kmin < kKeyNegInf) {  // uniform: NaN or +inf somewhere, no distribution
+            give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
+            return;
+        }
+        const float M = value_of_key(kmax);
+        if ((M - R) * c > 96.0f) {  // uniform; terms of 2^96 and more: start again from M
+            R = M;
+            neg_Rc = -(R * c);
+            continue;
+        }
+        combine_bins();
+        double Z = 0.0;
+        for (int k = 0; k < kNucBins; ++k) Z += bin_m[k];
+        target = (double)top_p * Z;
+        const uint32_t sel = (uint32_t)select_bin();
+        // the keys of bin `sel`: bin1 is monotone over the keys from -inf to the largest finite one, so the first
+        // key of a bin is found by bisection (every thread runs the same search)
+        auto first_key_of_bin = [&](uint32_t b) __attribute__((always_inline)) {  // smallest key k with bin1 >= b
+            uint32_t a = kKeyNegInf, z = kKeyPosInf;                              // answer in [a, z]
+            while (a < z) {
+                const uint32_t mid = a + ((z - a) >> 1);
+                if (bin1(value_of_key(mid)) >= b)
+                    z = mid;
+                else
+                    a = mid + 1;
+            }
+            return a;
+        };
+        klo = sel == 0 ? kKeyNegInf : first_key_of_bin(sel);
+        khi = sel == 15 ? kKeyPosInf - 1u : first_key_of_bin(sel + 1u) - 1u;
+        klo = max(klo, kmin);
+        khi = min(khi, kmax);
+        bracket_mass = bin_m[sel];  // clipping to [kmin, kmax] removes no entry
+        __syncthreads();            // the bins are cleared or reused next
+        break;
+    }
+    // Further passes: the bracket's key range divided evenly into at most 16 bins, until it is a single key (one
+    // logit value) or provably small enough to sort.  No counts are kept: every entry of the bracket weighs at
+    // least as much as the bracket's smallest key would, so mass / that weight bounds the number of entries.
+    bool single_value = false;
+    while (true) {
+        if (khi <= klo) {  // (khi < klo cannot happen: the selected bin holds mass)
+            khi = klo;
             single_value = true;
             break;
         }
-        // No counts are kept.  Every entry of the bracket weighs at least as much as the bracket's smallest
-        // key would, so mass / that weight bounds the number of entries from above; once the bound fits the
-        // sorter the search can stop.  (A bracket whose lower edge is not a finite number gives no bound.)
-        const float x_lo = float_from_order_bits(prefix << shift);
-        const double e_lo = (double)fast_exp2(__fmaf_rn(x_lo, c, neg_Rc));
-        if (e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48)) break;
+        {  // (a bracket whose lower edge is -inf gives no bound)
+            const double e_lo = (double)fast_exp2(__fmaf_rn(value_of_key(klo), c, neg_Rc));
+            if (e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48)) break;
+        }
+        const uint32_t span = khi - klo;
+        const int sh = max(0, 28 - (int)__builtin_clz(span));  // span >> sh <= 15
+        clear_bins();
+        for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
+            uint32_t kw[4];
+            keys_of(q, kw);
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const uint32_t d = key_of(kw, j) - klo;
+                if (d <= span) add_mass(d >> sh, fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
+            }
+        });
+        combine_bins();
+        const uint32_t sel = (uint32_t)select_bin();
+        bracket_mass = bin_m[sel];
+        klo = klo + (sel << sh);
+        khi = min(khi, klo + ((1u << sh) - 1u));
+        __syncthreads();  // the bins are cleared or reused next
     }
     // A single logit value shared by the whole bracket (possibly thousands of tokens) needs no sorting: the ties
     // enter K in index order, each with the same mass, and how many of them do is a division.
@@ -288,6 +380,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     int32_t ties_below = 0;    // many_ties: bracket entries with index < t ...
     int32_t ties = 0;          // ... and all of them
     int32_t n_above = 0;       // entries above the bracket
+    const uint32_t span_c = khi - klo;
     const uint32_t t32 = valid ? (uint32_t)t : 0u;  // an invalid claim has nothing below it (its outputs are NaN anyway)
     for_each_vector([&](const ipt_u32x4 &q, uint32_t base) {
         uint32_t kw[4];
@@ -296,8 +389,8 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
 #pragma unroll
         for (int j = 0; j < E; ++j) {
             if (base + E > V32 && base + j >= V32) continue;  // (false for every vector but a ragged last one)
-            const uint32_t hi = top_bits(kw, j, shift);
-            if (hi == prefix) {
+            const uint32_t key = key_of(kw, j);
+            if (key - klo <= span_c) {
                 if (many_ties) {
                     ties += 1;
                     ties_below += (int32_t)(base + j < t32);
@@ -306,7 +399,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
                     const int32_t i = atomicAdd(&s_fill, 1);
                     if (i < kNucCap) buf[i] = top_composite(value_of(q, j), (int32_t)(base + j));
                 }
-            } else if (hi > prefix) {
+            } else if (key > khi) {
                 n_above += 1;
                 if (base + j < t32) below_vec += fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
             }
@@ -428,8 +521,8 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
                 const float xt = Elem<DT>::to_float(x_row[t]);
                 bool in_K;
                 if (many_ties) {
-                    const uint32_t hi = float_order_bits(xt) >> shift;
-                    in_K = hi > prefix || (hi == prefix && (int64_t)tb < n_tie);
+                    const uint32_t kt = float_order_bits(xt) >> (DT == 0 ? 16 : 0);
+                    in_K = kt > khi || (kt == klo && (int64_t)tb < n_tie);
                 } else {
                     in_K = top_composite(xt, (int32_t)t) >= cut;
                 }

@@ -54,9 +54,11 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
     assert (kept[sure] == ref["kept"][sure]).all()
     # rows whose kept set is the oracle's: the full comparison (log-mass included).  Rows in doubt differ from the
     # oracle by the marginal token(s): interval ends and distance within the 1e-4 contract, nothing finer.
-    idx = torch.from_numpy(np.nonzero(sure)[0]).to(DEV)
-    st = parity.compare_ipt({k2: v[idx] for k2, v in out.items() if k2 != "kept"},
-                            {k2: v[sure] for k2, v in ref.items()}, log_mass_sigma=0.02)
+    st = {}
+    if sure.any():
+        idx = torch.from_numpy(np.nonzero(sure)[0]).to(DEV)
+        st = parity.compare_ipt({k2: v[idx] for k2, v in out.items() if k2 != "kept"},
+                                {k2: v[sure] for k2, v in ref.items()}, log_mass_sigma=0.02)
     for name in ("cdf_lo", "cdf_hi", "dist"):
         g_, r_ = out[name].cpu().numpy().astype(np.float64)[~sure], ref[name][~sure]
         both_nan = np.isnan(g_) & np.isnan(r_)
@@ -101,6 +103,52 @@ def test_nucleus_every_row(difr, dtype, V, p, kind):
     st, out = _compare(difr, logits, V, T, seeds, sid, pos, claims, p)
     say("nucleus", dtype, V, p, kind, st)
     assert not (out["flags"] & 4).any()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("layout", ["ascending", "descending", "head_masked", "constant", "two_values",
+                                    "tiny_head_span", "far_below_head", "huge_tail"])
+def test_nucleus_first_round_unlike_the_row(difr, dtype, layout):
+    """The search lays its first bins over the values met in the first 2048 (bf16) or 1024 (fp32) entries and takes
+    its exponent reference from them; rows whose beginning says nothing about the rest - or something misleading -
+    must come out the same: sorted either way, a masked beginning, one or two distinct values, a beginning whose
+    values span next to nothing, a maximum so far above the beginning that the pass has to start again, and a
+    beginning of outliers far above a flat rest."""
+    N, V = 24, 9000
+    g = torch.Generator().manual_seed(77 + len(layout) + (dtype == torch.float32))
+    x = torch.randn(N, V, generator=g) * 2.0
+    T = 0.9
+    if layout == "ascending":
+        x = x.sort(dim=1).values
+    elif layout == "descending":
+        x = x.sort(dim=1, descending=True).values
+    elif layout == "head_masked":
+        x[:, :2300] = float("-inf")
+    elif layout == "constant":
+        x[:] = -1.25
+    elif layout == "two_values":
+        x = torch.where(torch.rand(N, V, generator=g) < 0.01, torch.tensor(3.0), torch.tensor(-2.0))
+    elif layout == "tiny_head_span":
+        x[:, :2300] = 1.0
+        x[:, 7] = 1.0 + 2.0 ** -7       # the next bf16 (and an fp32) value above 1
+    elif layout == "far_below_head":
+        x[:, :2300] -= 120.0             # (M - R) c is far beyond what an fp32 term can hold
+    elif layout == "huge_tail":
+        x = x * 0.05 - 30.0
+        x[:, :64] = torch.randn(N, 64, generator=g) + 5.0
+    ld = ((V + 7) // 8) * 8
+    logits = torch.full((N, ld), float("nan"), dtype=dtype, device=DEV)
+    logits[:, :V] = x.to(dtype).to(DEV)
+    seeds = torch.tensor([3, 1 << 40], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    claims = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    top = logits[:, :V].float().argmax(dim=1).to(torch.int32)
+    claims = torch.where(torch.arange(N, device=DEV) % 2 == 0, top, claims)
+    for p in (0.3, 0.9, 0.99):
+        st, out = _compare(difr, logits, V, T, seeds, sid, pos, claims, p)
+        say("nucleus layout", layout, dtype, p, st)
+        assert not (out["flags"] & 4).any()
 
 
 def test_nucleus_zipf_rows_and_per_row_temperatures(difr):
