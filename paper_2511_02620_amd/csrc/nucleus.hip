@@ -265,10 +265,10 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     double bracket_mass;  // mass of the entries with keys in [klo, khi]
     while (true) {
         float sc = (R > lo_s) ? 16.0f / (R - lo_s) : 0.0f;
-        if (!(sc < 1.0e30f)) sc = 0.0f;  // a span too small to divide: one bin
+        if (!(sc > 0.0f && sc < 1.0e30f)) sc = 1.0e-30f;  // no span to divide: every finite value lands in bin 0
         const float off = -(lo_s * sc);
         auto bin1 = [&](float x) __attribute__((always_inline)) {  // (clamped before the conversion: always in range)
-            return sc > 0.0f ? (uint32_t)(int)__builtin_amdgcn_fmed3f(__fmaf_rn(x, sc, off), 0.0f, 15.0f) : 0u;
+            return (uint32_t)(int)__builtin_amdgcn_fmed3f(__fmaf_rn(x, sc, off), 0.0f, 15.0f);
         };
         clear_bins();
         // largest and smallest key met (bf16: of the even and of the odd entries, packed)
