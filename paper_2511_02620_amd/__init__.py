@@ -1,10 +1,12 @@
 """MI355X-native scoring of claimed sampled tokens against verifier logits.
 
 The product is ``libdifr.so`` (hand-written HIP kernels for gfx950 behind the C ABI of
-``include/difr.h``).  This package is only its Python binding: ``gumbel_score``,
-``ipt_score`` and ``seq_reduce`` marshal torch device tensors into the C calls and
-return torch tensors.  There is no CPU fallback; if the library is missing the import
-of :mod:`paper_2511_02620_amd.binding` fails loudly.
+``include/difr.h``).  This package is only its Python binding: one function per entry
+point, with the entry point's name less the ``difr_`` prefix (``score_both``,
+``gumbel_score``, ``ipt_score``, ``seq_reduce``, ``classify``, ``lmhead_score``, ...).
+Each marshals torch device tensors into the C call and returns torch tensors; every step
+of the computation runs in the library's kernels.  There is no CPU fallback: if the
+library is missing, ``load_library()`` - and with it every call - fails loudly.
 """
 from .binding import (  # noqa: F401
     admissible_count,
