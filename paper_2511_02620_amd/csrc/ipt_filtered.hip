@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
         lx.push_vector(q, vec * E, vec < nvec);
     };
     // epochs without barriers, as in the likelihood kernel: the first round alone, then eight at a time, with a
-    // rewind and a round-by-round repeat if some thread had more candidates than its quota
+    // rewind and a round-by-round repeat if the buffer ran full
     // priming run of the first round (topn.hpp): a threshold before anything is pushed
     if (n_rounds > 0) {
         lx.top.begin_prime();
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     int round = 0;
     while (round < n_rounds) {
         const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));
-        lx.top.new_epoch(kTopQuota);
+        lx.top.new_epoch();
         // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
         // nothing else would hide the load latency (fetch() of a round past the end returns zeros without a load)
         u32x4 qv[kTopEpoch];
@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
             if (round + i < r_end) do_round(qv[i], round + i);
         if (__syncthreads_or((int)lx.top.over)) {
             if (tid == 0) cnt_x = snap_x;
-            lx.top.new_epoch(0x7FFFFFFF);
+            lx.top.new_epoch();
             lx.top.full = false;
             __syncthreads();
             for (int r = round; r < r_end; ++r) {
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
         __syncthreads();
         round = r_end;
     }
-    lx.top.new_epoch(kTopQuota);
+    lx.top.new_epoch();
     {
         const int64_t v = nvec * E + tid;  // ragged tail: V % E entries
         if (v < V) lx.push_entry(Elem<DT>::to_float(x_row[v]), (int32_t)v);

@@ -116,8 +116,8 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
             if (p.top_k > 0) lx.push_vector(q, ((int64_t)r * kBlock + tid) * E, true);
         }
     };
-    // Epochs: the first round alone (every entry is a candidate while there is no threshold: exactly the
-    // quota), then kTopEpoch rounds at a time without a barrier; the partly filled round is an epoch of its own.
+    // Epochs: the first round alone, then kTopEpoch rounds at a time without a barrier; the partly filled round is
+    // an epoch of its own.
     // priming run of the first round (topn.hpp): thresholds for both selections before anything is pushed
     if (n_rounds > 0) {
         top_y.begin_prime();
@@ -129,8 +129,8 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     int round = 0;
     while (round < n_rounds) {
         const int r_end = round < n_main ? min(n_main, round + (round == 0 ? 1 : kTopEpoch)) : n_rounds;
-        top_y.new_epoch(kTopQuota);
-        top_x.new_epoch(kTopQuota);
+        top_y.new_epoch();
+        top_x.new_epoch();
         if (round >= n_main)
             do_round(round);
         else if (g.gate.mode == 0)
@@ -140,14 +140,14 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         else
             run_rounds(std::integral_constant<int, 2>(), round, r_end);
         if (__syncthreads_or((int)(top_y.over || top_x.over))) {
-            // some thread had more candidates than its quota (data in ascending order, for instance):
+            // the buffer ran full (data in ascending order, for instance):
             // forget the epoch and repeat it round by round, compacting whenever a trigger is reached
             if (tid == 0) {
                 cnt_y = snap_y;
                 cnt_x = snap_x;
             }
-            top_y.new_epoch(0x7FFFFFFF);
-            top_x.new_epoch(0x7FFFFFFF);
+            top_y.new_epoch();
+            top_x.new_epoch();
             top_y.full = top_x.full = false;
             __syncthreads();
             for (int r = round; r < r_end; ++r) {
@@ -164,8 +164,8 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         __syncthreads();
         round = r_end;
     }
-    top_y.new_epoch(kTopQuota);  // the tail: at most one entry per thread
-    top_x.new_epoch(kTopQuota);
+    top_y.new_epoch();  // the tail: at most one entry per thread
+    top_x.new_epoch();
     // ragged tail: V % E entries, one lane each
     g.tail(&top_y);
     {

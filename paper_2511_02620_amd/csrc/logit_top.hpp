@@ -61,26 +61,52 @@ struct LogitTop {
                   !(__uint_as_float(q.z) < floor) || !(__uint_as_float(q.w) < floor);
         }
         hit = hit && active;
-        if (__builtin_amdgcn_ballot_w64(hit) != 0ull) {
+        const uint64_t m = __builtin_amdgcn_ballot_w64(hit);
+        if (m == 0ull) return;
+        const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+        if (hit && DT == 0) {
+            // +inf or a NaN with the sign bit clear: the largest pattern, as signed 16-bit, is >= 0x7F80
+            i16x2 mx = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+            mx = __builtin_elementwise_max(mx, as_i16x2(q.z));
+            mx = __builtin_elementwise_max(mx, as_i16x2(q.w));
+            bad |= (uint32_t)((mx.x > mx.y ? mx.x : mx.y) >= (int16_t)0x7F80);
+        }
+        if (top.priming) {  // every lane has a vector to look at and a push is a comparison: each lane its own
             if (hit) {
-                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
-                if (DT == 0) {
-                    // +inf or a NaN with the sign bit clear: the largest pattern, as signed 16-bit, is >= 0x7F80
-                    i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
-                    m = __builtin_elementwise_max(m, as_i16x2(q.z));
-                    m = __builtin_elementwise_max(m, as_i16x2(q.w));
-                    bad |= (uint32_t)((m.x > m.y ? m.x : m.y) >= (int16_t)0x7F80);
 #pragma unroll
-                    for (int j = 0; j < E; ++j) {
-                        const uint32_t w = qw[j >> 1];
-                        const float xv = __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16));
-                        if (xv >= floor) top.push(top_composite(xv, (int32_t)(v0 + j)));
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < E; ++j) push_entry(__uint_as_float(qw[j]), (int32_t)(v0 + j));
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+                    if (DT != 0) bad |= (uint32_t)!(xv < __builtin_inff());
+                    if (xv >= floor) top.push(top_composite(xv, (int32_t)(v0 + j)));
                 }
             }
+            return;
+        }
+        // A few lanes have a vector with a candidate in it.  Left to themselves they would walk their E entries
+        // while the rest of the wave waits, and the wave would run the push once for every entry position at
+        // which any of them has a candidate.  Instead the wave shares the work: the lanes with a hit are numbered
+        // (their lane ids gathered into lanes 0, 1, ...), and in each pass 64 / E of them are served, lane L
+        // looking at entry L % E of the (L / E)-th of them - one test and one push per pass for the whole wave.
+        const int lane = (int)threadIdx.x & 63;
+        const int rank = (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        const int nh = (int)__builtin_popcountll(m);
+        // a permutation of the lanes: those with a hit first, in lane order
+        const int ids = __builtin_amdgcn_ds_permute((hit ? rank : nh + lane - rank) << 2, lane);
+        const int e = lane & (E - 1), g = lane / E;
+        for (int base = 0; base < nh; base += 64 / E) {  // (wave-uniform)
+            const int k = base + g;
+            const int src = __builtin_amdgcn_ds_bpermute((k & 63) << 2, ids);
+            const uint32_t w0 = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)qw[0]);
+            const uint32_t w1 = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)qw[1]);
+            const uint32_t w2 = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)qw[2]);
+            const uint32_t w3 = (uint32_t)__builtin_amdgcn_ds_bpermute(src << 2, (int)qw[3]);
+            const int d = DT == 0 ? e >> 1 : e;
+            const uint32_t w = d == 0 ? w0 : (d == 1 ? w1 : (d == 2 ? w2 : w3));
+            const float xv = DT == 0 ? __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+            const bool have = k < nh;
+            if (DT != 0) bad |= (uint32_t)(have && !(xv < __builtin_inff()));
+            if (have && xv >= floor) top.push(top_composite(xv, (int32_t)v0 + (src - lane) * E + e));
         }
     }
 };

@@ -10,12 +10,11 @@
 // all 8 passes, down to the exact n-th composite, run at the end of the row.  Nothing that belongs to the
 // final top n is ever dropped: the threshold is a lower bound of the n-th largest of what has been seen.
 //
-// Capacity.  The caller works in epochs of a few stream rounds without any barrier.  Within an epoch a
-// thread may push at most kTopQuota entries; one that needs more raises `over` instead, and the caller
-// rewinds the epoch (resets the counter to its value at the epoch's start) and repeats it round by round
-// with a compaction check after every round.  An epoch starts with fewer than kTopTrigger entries, so
-// the buffer never holds more than kTopTrigger + 256 * kTopQuota = kTopCap entries either way (a round
-// is at most 8 entries per thread), whatever the order of the data.
+// Capacity.  The caller works in epochs of a few stream rounds without any barrier.  A push that finds the
+// buffer full raises `over` instead of storing its entry, and the caller then rewinds the epoch (resets the
+// counter to its value at the epoch's start) and repeats it round by round with a compaction check after every
+// round.  A round starts with fewer than kTopTrigger entries and adds at most 8 per thread, so in that mode the
+// kTopCap = kTopTrigger + 256 * 8 slots always suffice, whatever the order of the data.
 #pragma once
 
 #include "difr_device.hpp"
@@ -24,9 +23,8 @@ namespace difr {
 
 constexpr int kTopEpoch = 8;       // stream rounds per epoch (measured: 4 and 16 are both slower)
 constexpr int kTopFresh = 16;      // a compaction is due after max(n, kTopFresh) pushes
-constexpr int kTopQuota = 8;       // pushes per thread and epoch
 constexpr int kTopTrigger = 512;   // a compaction is due at the latest when this many slots are used
-constexpr int kTopCap = kTopTrigger + 256 * kTopQuota;  // slots per buffer
+constexpr int kTopCap = kTopTrigger + 256 * 8;  // slots per buffer: the trigger plus one round of one vector per thread
 constexpr int kTopMaxN = 256;      // largest n supported
 constexpr int kTopKeep = 256;      // a coarse compaction may leave up to this many entries
 
@@ -65,8 +63,7 @@ struct TopN {
                      // that the threshold, which is also the bound of the stream's gates, stays fresh
     bool full;       // this thread's push took the buffer to the compaction trigger (combine over the workgroup
                      // with __syncthreads_or: reading the counter instead would race with the next round's pushes)
-    int quota;       // pushes this thread may still make in the current epoch
-    bool over;       // this thread had a candidate beyond its quota: the epoch must be repeated
+    bool over;       // a push of this thread found the buffer full: the epoch must be repeated
     bool priming;    // see begin_prime()
     uint64_t prime_best;
 
@@ -78,18 +75,13 @@ struct TopN {
         theta = n_ > 0 ? 0ull : ~0ull;  // nothing wanted: nothing is ever pushed
         trigger = n_ > kTopFresh ? n_ : kTopFresh;
         full = false;
-        quota = kTopQuota;
         over = false;
         priming = false;
         prime_best = 0ull;
         if (threadIdx.x == 0) *count = 0;
     }
 
-    __device__ __forceinline__ void new_epoch(int quota_)
-    {
-        quota = quota_;
-        over = false;
-    }
+    __device__ __forceinline__ void new_epoch() { over = false; }
 
     // Priming.  While there is no threshold every entry of the first round is a candidate: 2048 pushes through
     // one counter and a compaction over all of them.  Instead the first round is run twice: the first time each
@@ -129,13 +121,11 @@ struct TopN {
             return;
         }
         if (c > theta) {
-            if (quota <= 0) {
-                over = true;
-                return;
-            }
-            --quota;
             const int32_t i = atomicAdd(count, 1);
-            if (i < kTopCap) buf[i] = c;  // always true by construction (see the header comment)
+            if (i < kTopCap)
+                buf[i] = c;
+            else
+                over = true;  // no room: the entry is dropped and the epoch has to be repeated
             if (i >= trigger - 1) full = true;
         }
     }
