@@ -152,21 +152,35 @@ struct TopN {
             __syncthreads();
             return false;
         }
+        if (cnt <= kBlock) {
+            // Few entries: every entry finds its rank by counting the entries above it (broadcast reads), the n
+            // best move to the front in rank order and the n-th of them is the new, exact threshold.  Three
+            // barriers instead of the dozen of the radix select below.
+            const uint64_t mine = tid < cnt ? buf[tid] : 0ull;
+            int r = 0;
+            for (int i = 0; i < cnt; ++i) r += (int)(buf[i] > mine);
+            if (tid < cnt && r == n - 1) s.sel64 = mine;
+            __syncthreads();
+            if (tid < cnt && r < n) buf[r] = mine;
+            if (tid == 0) *count = n;
+            theta = s.sel64;
+            trigger = min(kTopTrigger, n + (n > kTopFresh ? n : kTopFresh));
+            __syncthreads();
+            return true;
+        }
         if (cnt <= 2 * kBlock) {
-            // Few entries: every entry finds its rank by counting the entries above it (one broadcast read serves
-            // both entries of a thread), the n best move to the front in rank order and the n-th of them is the new,
-            // exact threshold.  Three barriers instead of the dozen of the radix select below.
-            uint64_t mine0 = tid < cnt ? buf[tid] : 0ull, mine1 = tid + kBlock < cnt ? buf[tid + kBlock] : 0ull;
+            // the same with two entries per thread: one broadcast read serves both
+            uint64_t mine0 = buf[tid], mine1 = tid + kBlock < cnt ? buf[tid + kBlock] : 0ull;
             int r0 = 0, r1 = 0;
             for (int i = 0; i < cnt; ++i) {
                 const uint64_t c = buf[i];
                 r0 += (int)(c > mine0);
                 r1 += (int)(c > mine1);
             }
-            if (tid < cnt && r0 == n - 1) s.sel64 = mine0;
+            if (r0 == n - 1) s.sel64 = mine0;
             if (tid + kBlock < cnt && r1 == n - 1) s.sel64 = mine1;
             __syncthreads();
-            if (tid < cnt && r0 < n) buf[r0] = mine0;
+            if (r0 < n) buf[r0] = mine0;
             if (tid + kBlock < cnt && r1 < n) buf[r1] = mine1;
             if (tid == 0) *count = n;
             theta = s.sel64;
