@@ -76,7 +76,9 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     }
     int round = 0;
     while (round < n_rounds) {
-        const int r_end = min(n_rounds, round + (round == 0 ? 1 : kTopEpoch));
+        // epochs of 1, 1, 2, 4 rounds, then 8 at a time: the threshold moves only between epochs, and while little
+        // of the row has been seen it moves a lot (each doubling of what has been seen brings about top_k pushes)
+        const int r_end = min(n_rounds, round + (round < 2 ? 1 : (round < 4 ? 2 : (round < 8 ? 4 : kTopEpoch))));
         lx.top.new_epoch();
         // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
         // nothing else would hide the load latency (fetch() of a round past the end returns zeros without a load)
