@@ -66,8 +66,8 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
         const int64_t vec = (int64_t)round * kBlock + tid;
         lx.push_vector(q, vec * E, vec < nvec);
     };
-    // epochs without barriers, as in the likelihood kernel: the first round alone, then eight at a time, with a
-    // rewind and a round-by-round repeat if the buffer ran full
+    // epochs without barriers, as in the likelihood kernel, with a rewind and a round-by-round repeat if the buffer
+    // ran full
     // priming run of the first round (topn.hpp): a threshold before anything is pushed
     if (n_rounds > 0) {
         lx.top.begin_prime();
