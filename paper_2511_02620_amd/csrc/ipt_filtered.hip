@@ -16,13 +16,13 @@
 
 namespace difr {
 
-template <int DT>
+template <int DT, int CAP>
 __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int top_k, float top_p, IptOutputs o,
                                                               int32_t *__restrict__ kept_out)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
-    __shared__ uint64_t buf_x[kTopCap];
+    __shared__ uint64_t buf_x[CAP];
     __shared__ TopScratch scratch;
     __shared__ int32_t cnt_x, snap_x, s_bad, s_tok;
     __shared__ double lds_d[kWaves];
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
 
     LogitTop<DT> lx;
-    lx.init(buf_x, &cnt_x, top_k);
+    lx.init(buf_x, &cnt_x, top_k, CAP);
     if (tid == 0) {
         s_bad = 0;
         snap_x = 0;
@@ -62,9 +62,10 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
         if ((int64_t)round * kBlock + tid < nvec) q = load_round(x_row, round);
         return q;
     };
-    auto do_round = [&](u32x4 q, int round) {
+    // `only_wave` >= 0: only that wave's lanes take part (the repeat of an epoch, see topn.hpp)
+    auto do_round = [&](u32x4 q, int round, int only_wave = -1) {
         const int64_t vec = (int64_t)round * kBlock + tid;
-        lx.push_vector(q, vec * E, vec < nvec);
+        lx.push_vector(q, vec * E, vec < nvec && (only_wave < 0 || (tid >> 6) == only_wave));
     };
     // epochs without barriers, as in the likelihood kernel, with a rewind and a round-by-round repeat if the buffer
     // ran full
@@ -94,8 +95,11 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
             lx.top.full = false;
             __syncthreads();
             for (int r = round; r < r_end; ++r) {
-                do_round(fetch(r), r);
-                settle();
+                const u32x4 q = fetch(r);
+                for (int w = 0; w < kWaves; ++w) {
+                    do_round(q, r, w);
+                    settle();
+                }
             }
         } else {
             settle();
@@ -175,10 +179,18 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
 int launch_ipt_filtered(const RowBatch &b, int top_k, float top_p, const IptOutputs &o, int32_t *kept, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
-    if (b.dtype == 0)
-        ipt_filtered_kernel<0><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
-    else
-        ipt_filtered_kernel<1><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+    const bool small = top_k <= kTopSmallN;
+    if (b.dtype == 0) {
+        if (small)
+            ipt_filtered_kernel<0, kTopCapSmall><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+        else
+            ipt_filtered_kernel<0, kTopCapBig><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+    } else {
+        if (small)
+            ipt_filtered_kernel<1, kTopCapSmall><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+        else
+            ipt_filtered_kernel<1, kTopCapBig><<<grid, block, 0, stream>>>(b, top_k, top_p, o, kept);
+    }
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

@@ -31,13 +31,13 @@ __device__ __forceinline__ double gumbel_f64(const RowInfo &ri, int32_t v)
 
 __device__ __forceinline__ float normal_cdf_f32(float z) { return 0.5f * erfcf(-z * 0.70710678118654752f); }
 
-template <int DT>
-__global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, LikelihoodParams p, LikelihoodOutputs o)
+template <int DT, int CAP>
+__device__ __forceinline__ void likelihood_row(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
-    __shared__ uint64_t buf_y[kTopCap];
-    __shared__ uint64_t buf_x[kTopCap];
+    __shared__ uint64_t buf_y[CAP];
+    __shared__ uint64_t buf_x[CAP];
     __shared__ TopScratch scratch;
     __shared__ int32_t cnt_y, cnt_x, snap_y, snap_x;
     __shared__ float lds_L[kWaves];
@@ -69,8 +69,8 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     TopN top_y;
     LogitTop<DT> lx;
     TopN &top_x = lx.top;
-    top_y.init(buf_y, &cnt_y, valid ? p.s : 0);
-    lx.init(buf_x, &cnt_x, p.top_k);
+    top_y.init(buf_y, &cnt_y, valid ? p.s : 0, CAP);
+    lx.init(buf_x, &cnt_x, p.top_k, CAP);
     if (tid == 0) {
         s_bad = 0;
         snap_y = snap_x = 0;
@@ -94,11 +94,13 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     const int n_main = (int)(nvec / kBlock);                       // rounds in which every lane has a vector
     const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);      // plus a last, partly filled one
     // one round, any gate mode, lanes past the end of the row idle (the partly filled round, and repeats)
-    auto do_round = [&](int round) __attribute__((always_inline)) {
+    // (`only_wave` >= 0: only that wave's lanes take part - the repeat of an epoch, see topn.hpp)
+    auto do_round = [&](int round, int only_wave = -1) __attribute__((always_inline)) {
         const int64_t vec = (int64_t)round * kBlock + tid;
-        const bool active = vec < nvec;
+        const bool in_row = vec < nvec;
+        const bool active = in_row && (only_wave < 0 || (tid >> 6) == only_wave);
         u32x4 q = u32x4{0u, 0u, 0u, 0u};
-        if (active) q = load_round(x_row, round);
+        if (in_row) q = load_round(x_row, round);
         g.process_any(q, round, active, &top_y);
         if (p.top_k > 0) lx.push_vector(q, vec * E, active);
     };
@@ -126,9 +128,13 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
         if (top_y.end_prime(scratch)) g.retarget(top_y);
         if (top_x.end_prime(scratch)) lx.retarget();
     }
+    const bool big_n = p.s > kTopSmallN || p.top_k > kTopSmallN;
     int round = 0;
     while (round < n_rounds) {
-        const int r_end = round < n_main ? min(n_main, round + (round == 0 ? 1 : kTopEpoch)) : n_rounds;
+        // (large selections start with epochs of 1, 1, 2, 4 rounds: early in the row each doubling of what has been
+        // seen brings about n pushes, and the buffers hold kTopCap)
+        const int len = round == 0 ? 1 : (!big_n || round >= 8 ? kTopEpoch : (round < 2 ? 1 : (round < 4 ? 2 : 4)));
+        const int r_end = round < n_main ? min(n_main, round + len) : n_rounds;
         top_y.new_epoch();
         top_x.new_epoch();
         if (round >= n_main)
@@ -151,8 +157,10 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
             top_y.full = top_x.full = false;
             __syncthreads();
             for (int r = round; r < r_end; ++r) {
-                do_round(r);
-                settle();
+                for (int w = 0; w < kWaves; ++w) {
+                    do_round(r, w);
+                    settle();
+                }
             }
         } else {
             settle();
@@ -229,13 +237,35 @@ __global__ __launch_bounds__(kBlock) void likelihood_kernel(RowBatch b, Likeliho
     }
 }
 
+// Small selections (s and top_k up to kTopSmallN): 24 KB of LDS per workgroup, and the register budget of five
+// waves per SIMD (the few spills that costs are worth the fifth workgroup: measured).  Large ones: big buffers.
+template <int DT>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void likelihood_small_kernel(RowBatch b, LikelihoodParams p,
+                                                                                                         LikelihoodOutputs o)
+{
+    likelihood_row<DT, kTopCapSmall>(b, p, o);
+}
+template <int DT>
+__global__ __launch_bounds__(kBlock) void likelihood_big_kernel(RowBatch b, LikelihoodParams p, LikelihoodOutputs o)
+{
+    likelihood_row<DT, kTopCapBig>(b, p, o);
+}
+
 int launch_likelihood(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
-    if (b.dtype == 0)
-        likelihood_kernel<0><<<grid, block, 0, stream>>>(b, p, o);
-    else
-        likelihood_kernel<1><<<grid, block, 0, stream>>>(b, p, o);
+    const bool small = p.s <= kTopSmallN && p.top_k <= kTopSmallN;
+    if (b.dtype == 0) {
+        if (small)
+            likelihood_small_kernel<0><<<grid, block, 0, stream>>>(b, p, o);
+        else
+            likelihood_big_kernel<0><<<grid, block, 0, stream>>>(b, p, o);
+    } else {
+        if (small)
+            likelihood_small_kernel<1><<<grid, block, 0, stream>>>(b, p, o);
+        else
+            likelihood_big_kernel<1><<<grid, block, 0, stream>>>(b, p, o);
+    }
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

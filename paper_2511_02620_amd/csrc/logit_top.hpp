@@ -17,9 +17,9 @@ struct LogitTop {
     bool floor_pos;
     uint32_t bad;      // a NaN (sign bit clear) or +inf logit was seen
 
-    __device__ __forceinline__ void init(uint64_t *buf, int32_t *count, int k)
+    __device__ __forceinline__ void init(uint64_t *buf, int32_t *count, int k, int cap)
     {
-        top.init(buf, count, k);
+        top.init(buf, count, k, cap);
         bad = 0;
         set_floor(-__builtin_inff());
     }

@@ -12,9 +12,12 @@
 //
 // Capacity.  The caller works in epochs of a few stream rounds without any barrier.  A push that finds the
 // buffer full raises `over` instead of storing its entry, and the caller then rewinds the epoch (resets the
-// counter to its value at the epoch's start) and repeats it round by round with a compaction check after every
-// round.  A round starts with fewer than kTopTrigger entries and adds at most 8 per thread, so in that mode the
-// kTopCap = kTopTrigger + 256 * 8 slots always suffice, whatever the order of the data.
+// counter to its value at the epoch's start) and repeats it one wave and one round at a time, with a compaction
+// check after each such step.  A step starts with fewer than kTopTrigger entries and adds at most 8 per thread
+// of one wave, so in that mode kTopCapSmall = kTopTrigger + 64 * 8 slots always suffice, whatever the order of
+// the data.  Small buffers are what lets five workgroups share a compute unit; selections of more than
+// kTopSmallN entries push so much in an ordinary epoch that they get kTopCapBig slots instead (the kernels
+// are instantiated for both).
 #pragma once
 
 #include "difr_device.hpp"
@@ -24,7 +27,9 @@ namespace difr {
 constexpr int kTopEpoch = 8;       // stream rounds per epoch (measured: 4 and 16 are both slower)
 constexpr int kTopFresh = 16;      // a compaction is due after max(n, kTopFresh) pushes
 constexpr int kTopTrigger = 512;   // a compaction is due at the latest when this many slots are used
-constexpr int kTopCap = kTopTrigger + 256 * 8;  // slots per buffer: the trigger plus one round of one vector per thread
+constexpr int kTopCapSmall = kTopTrigger + 64 * 8;   // slots per buffer: the trigger plus one round of one wave
+constexpr int kTopCapBig = kTopTrigger + 256 * 8;    // ... of the whole workgroup
+constexpr int kTopSmallN = 64;     // largest n served with the small buffer
 constexpr int kTopMaxN = 256;      // largest n supported
 constexpr int kTopKeep = 256;      // a coarse compaction may leave up to this many entries
 
@@ -55,7 +60,8 @@ struct TopScratch {
 };
 
 struct TopN {
-    uint64_t *buf;   // kTopCap slots in LDS
+    uint64_t *buf;   // `cap` slots in LDS
+    int cap;
     int32_t *count;  // in LDS
     int n;
     uint64_t theta;  // wave-uniform copy of the threshold: only composites above it are pushed
@@ -67,9 +73,10 @@ struct TopN {
     bool priming;    // see begin_prime()
     uint64_t prime_best;
 
-    __device__ __forceinline__ void init(uint64_t *buf_, int32_t *count_, int n_)
+    __device__ __forceinline__ void init(uint64_t *buf_, int32_t *count_, int n_, int cap_)
     {
         buf = buf_;
+        cap = cap_;
         count = count_;
         n = n_;
         theta = n_ > 0 ? 0ull : ~0ull;  // nothing wanted: nothing is ever pushed
@@ -122,7 +129,7 @@ struct TopN {
         }
         if (c > theta) {
             const int32_t i = atomicAdd(count, 1);
-            if (i < kTopCap)
+            if (i < cap)
                 buf[i] = c;
             else
                 over = true;  // no room: the entry is dropped and the epoch has to be repeated
@@ -138,7 +145,7 @@ struct TopN {
     __device__ __forceinline__ bool compact(TopScratch &s, bool coarse = false)
     {
         const int tid = threadIdx.x;
-        const int cnt = min(*count, kTopCap);
+        const int cnt = min(*count, cap);
         full = false;
         if (n <= 0) {  // nothing wanted: an impossible threshold
             __syncthreads();
@@ -253,7 +260,7 @@ struct TopN {
         const int tid = threadIdx.x;
         __syncthreads();
         compact(s, false);
-        const int m = min(min(*count, kTopCap), n);
+        const int m = min(min(*count, cap), n);
         if (tid < m) {
             const uint64_t mine = buf[tid];
             int rank = 0;
