@@ -57,6 +57,8 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, k, p, temps=None):
     (torch.bfloat16, 20504, 50, 0.95, "random"),
     (torch.bfloat16, 20504, 50, 1.0, "random"),
     (torch.bfloat16, 20504, 256, 0.5, "ascending"),
+    (torch.bfloat16, 20504, 50, 0.9, "ascending"),   # small buffers: every epoch runs full and is repeated wave by wave
+    (torch.float32, 9004, 64, 0.95, "ascending"),
     (torch.bfloat16, 16384, 1, 1.0, "random"),
     (torch.bfloat16, 2056, 7, 0.8, "descending"),
     (torch.bfloat16, 296, 50, 0.95, "random"),

@@ -70,6 +70,8 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, k, p, s, sigma, M=384,
     (torch.bfloat16, 16384, 256, 0.5, 64, 0.05, "random"),
     (torch.bfloat16, 20504, 50, 0.9, 0, 0.5, "random"),
     (torch.bfloat16, 20504, 50, 0.95, 256, 0.5, "ascending"),      # every entry is a new maximum: worst case for the selection
+    (torch.bfloat16, 20504, 50, 0.95, 16, 0.5, "ascending"),       # the same with the small buffers: epochs repeated wave by wave
+    (torch.float32, 9004, 64, 0.9, 64, 0.5, "ascending"),
     (torch.bfloat16, 20504, 50, 0.95, 16, 0.5, "descending"),
     (torch.bfloat16, 2056, 7, 0.8, 5, 0.01, "random"),             # one round and a tail
     (torch.bfloat16, 296, 50, 0.95, 16, 0.5, "random"),            # fewer entries than one round
