@@ -350,8 +350,11 @@ def main():
         t_l = time_alone(lambda: difr.gumbel_likelihood(*row_args, data["claims_g"], zl, top_k=LIKELIHOOD["top_k"],
                                                         top_p=LIKELIHOOD["top_p"], s=LIKELIHOOD["s"],
                                                         sigma=LIKELIHOOD["sigma"]), reps)
+        t_bf = time_alone(lambda: difr.score_both_filtered(*row_args, data["claims_g"], data["claims_i"], zl,
+                                                           top_k=LIKELIHOOD["top_k"], top_p=LIKELIHOOD["top_p"],
+                                                           s=LIKELIHOOD["s"], sigma=LIKELIHOOD["sigma"]), reps)
     else:
-        t_b = t_a = t_l = t_f = t_ba = t_n = None
+        t_b = t_a = t_l = t_f = t_ba = t_n = t_bf = None
         t_g = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     g, i, sg, si = out
@@ -430,7 +433,10 @@ def main():
                      "tokens_per_s": round(wl.N / (t_n * 1e-3), 1)},
                     "difr_gumbel_likelihood": None if t_l is None else
                     dict(LIKELIHOOD, ms=round(t_l, 4), tokens_per_s=round(wl.N / (t_l * 1e-3), 1),
-                         hbm_gbs=round(wl.N * (wl.V * esz + 24) / (t_l * 1e-3) / 1e9, 1))},
+                         hbm_gbs=round(wl.N * (wl.V * esz + 24) / (t_l * 1e-3) / 1e9, 1)),
+                    "difr_score_both_filtered": None if t_bf is None else
+                    dict(LIKELIHOOD, ms=round(t_bf, 4), tokens_per_s=round(wl.N / (t_bf * 1e-3), 1),
+                         hbm_gbs=round(wl.N * (wl.V * esz + 48) / (t_bf * 1e-3) / 1e9, 1))},
         "match_rate": {"gumbel": round(match_g, 5), "ipt": round(match_i, 5)},
     }
     if args.cpu_rows > 0:

@@ -178,8 +178,8 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
  * 1 <= top_k <= 256; top_p > 0; rows 16-byte aligned (DIFR_ERR_ALIGN).  Outputs as difr_ipt_score (all
  * optional ones may be NULL) plus kept [N] int32 or NULL = |K|.  One pass over the logits.
  * top_k = 0 with top_p < 1 is the bare nucleus filter: the prefix is taken over the WHOLE vocabulary and may hold
- * tens of thousands of tokens.  The library then searches for the last (logit, index) pair inside K with a radix
- * search on the logit keys weighted by probability mass: four to six passes over the row instead of one.  The
+ * tens of thousands of tokens.  The library then searches for the last (logit, index) pair inside K with a search
+ * over the logit keys weighted by probability mass: three to five passes over the row instead of one.  The
  * marginal tokens of such a nucleus have probabilities around 1e-6, the accuracy of the fp32 exponentials the mass
  * is summed from, so kept[n] may differ from an evaluation in double by those few tokens; a, b and d keep the 1e-4
  * contract.  ipt_token is not offered on this path (DIFR_ERR_UNSUPPORTED), nor is top_k = 0 with top_p >= 1 (no
@@ -222,6 +222,21 @@ typedef struct {
 
 int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p, float *pi, float *log_pi, float *tau,
                            int32_t *active, uint8_t *flags, void *hip_stream);
+
+/*
+ * difr_gumbel_likelihood and difr_ipt_score_filtered in one pass over the logits, for the verifier that scores both
+ * estimators under the sampler's top-k / top-p policy [Sec. 6.2 and Sec. 6.3 with the generation policy of Sec. 3.2]:
+ * the k largest logits that fix the likelihood's threshold tau ARE the filtered distribution Token-IPT-DiFR works
+ * on, so they are collected once and each row is read from HBM once instead of twice.  in->claimed are the
+ * Token-DiFR claims, claimed_ipt (DEVICE [N] or NULL for sampling mode) the Token-IPT-DiFR claims; p as in
+ * difr_gumbel_likelihood with 1 <= top_k <= 256 (top_k = 0: DIFR_ERR_UNSUPPORTED, use the two single calls).
+ * Outputs have the meaning, layout and optionality of the two single calls and are bit-identical to theirs;
+ * flags_gumbel and flags_ipt are the two calls' `flags`; sigma_ipt, eps belong to log_mass.
+ */
+int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, const difr_likelihood_params *p, float *pi,
+                             float *log_pi, float *tau, int32_t *active, uint8_t *flags_gumbel, float *dist,
+                             float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token, double sigma_ipt, double eps,
+                             float *log_mass, int32_t *kept, uint8_t *flags_ipt, void *hip_stream);
 
 /*
  * Size of each row's admissible set.  [Sec. 7, "admissible set" A_t(tau) = { i : FSSL_t(i) >= tau }: an accepted

@@ -29,6 +29,7 @@ from .binding import (  # noqa: F401
     philox4x32_10,
     score_both,
     score_both_admissible,
+    score_both_filtered,
     seq_reduce,
     version,
 )

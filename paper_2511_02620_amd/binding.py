@@ -73,7 +73,7 @@ class _LikelihoodParams(C.Structure):
                 ("M", C.c_int32), ("z", C.c_void_p)]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_score_both_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -105,6 +105,9 @@ def load_library():
     lib.difr_ipt_score_filtered.restype = C.c_int
     lib.difr_gumbel_likelihood.argtypes = [C.POINTER(_Rows), C.POINTER(_LikelihoodParams), vp, vp, vp, vp, vp, vp]
     lib.difr_gumbel_likelihood.restype = C.c_int
+    lib.difr_score_both_filtered.argtypes = [C.POINTER(_Rows), vp, C.POINTER(_LikelihoodParams)] + [vp] * 10 + [
+        C.c_double, C.c_double, vp, vp, vp, vp]
+    lib.difr_score_both_filtered.restype = C.c_int
     lib.difr_admissible_count.argtypes = [C.POINTER(_Rows), vp, C.c_float, vp, vp, vp]
     lib.difr_admissible_count.restype = C.c_int
     lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
@@ -335,6 +338,41 @@ def gumbel_likelihood(logits, temperature, seeds, seq_ids, positions, claimed, z
     if rc:
         raise DifrError(rc, "difr_gumbel_likelihood")
     return out
+
+
+def score_both_filtered(logits, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt, z, top_k=50,
+                        top_p=1.0, s=16, sigma=1.0, temperatures=None, V=None, want_active=False, want_token=False,
+                        want_log_mass=False, sigma_ipt=0.01, eps=1e-30):
+    """difr_score_both_filtered: gumbel_likelihood and ipt_score_filtered in one pass over the logits.
+    Returns (likelihood dict, filtered-IPT dict), each as the single call returns it."""
+    lib = load_library()
+    r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
+    _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
+    if z.device != dev or z.dtype != torch.float32 or z.dim() != 1 or not z.is_contiguous():
+        raise ValueError("z must be a contiguous 1-D float32 tensor on the device of logits")
+    p = _LikelihoodParams(int(top_k), float(top_p), int(s), float(sigma), z.shape[0], z.data_ptr())
+    f32 = dict(dtype=torch.float32, device=dev)
+    lik = dict(pi=torch.empty(N, **f32), log_pi=torch.empty(N, **f32), tau=torch.empty(N, **f32),
+               flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_active:
+        lik["active"] = torch.empty(N, max(int(s), 1), dtype=torch.int32, device=dev)[:, :int(s)].contiguous()
+    ipt = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
+               u=torch.empty(N, **f32), kept=torch.empty(N, dtype=torch.int32, device=dev),
+               flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_token:
+        ipt["ipt_token"] = torch.empty(N, dtype=torch.int32, device=dev)
+    if want_log_mass:
+        ipt["log_mass"] = torch.empty(N, **f32)
+    with torch.cuda.device(dev):
+        rc = lib.difr_score_both_filtered(C.byref(r), _ptr(claimed_ipt), C.byref(p), _ptr(lik["pi"]), _ptr(lik["log_pi"]),
+                                          _ptr(lik["tau"]), _ptr(lik.get("active")) if int(s) > 0 else None,
+                                          _ptr(lik["flags"]), _ptr(ipt["dist"]), _ptr(ipt["cdf_lo"]), _ptr(ipt["cdf_hi"]),
+                                          _ptr(ipt["u"]), _ptr(ipt.get("ipt_token")), float(sigma_ipt), float(eps),
+                                          _ptr(ipt.get("log_mass")), _ptr(ipt["kept"]), _ptr(ipt["flags"]),
+                                          _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_score_both_filtered")
+    return lik, ipt
 
 
 def admissible_count(logits, temperature, seeds, seq_ids, positions, max_score, delta, temperatures=None, V=None,

@@ -256,6 +256,30 @@ int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p,
     return difr::launch_likelihood(b, lp, lo, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 
+int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, const difr_likelihood_params *p, float *pi,
+                             float *log_pi, float *tau, int32_t *active, uint8_t *flags_gumbel, float *dist,
+                             float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token, double sigma_ipt, double eps,
+                             float *log_mass, int32_t *kept, uint8_t *flags_ipt, void *hip_stream)
+{
+    difr::RowBatch b;
+    bool aligned = false;
+    int rc = validate_rows(in, &b, &aligned);
+    if (rc != DIFR_OK) return rc;
+    if (!p) return DIFR_ERR_NULL;
+    if (p->s < 0 || p->s > 256 || p->top_k < 0 || p->top_k > 256 || p->M < 1) return DIFR_ERR_ARGUMENT;
+    if (!(p->sigma > 0.0f) || !isfinite(p->sigma) || !(p->top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
+    if (log_mass && (!(sigma_ipt > 0.0) || !isfinite(sigma_ipt) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
+    if (p->top_k == 0) return DIFR_ERR_UNSUPPORTED;
+    if (b.N == 0) return DIFR_OK;
+    if (!pi || !flags_gumbel || !p->z || !dist || !flags_ipt) return DIFR_ERR_NULL;
+    if (!aligned) return DIFR_ERR_ALIGN;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z, nullptr};
+    const difr::LikelihoodOutputs lo{pi, log_pi, tau, active, flags_gumbel};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, ipt_token, sigma_ipt, eps, log_mass, flags_ipt, nullptr};
+    return difr::launch_score_both_filtered(b, lp, lo, claimed_ipt, oi, kept, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
+
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                     uint8_t *flags_ipt, void *hip_stream)

@@ -43,6 +43,9 @@ struct LikelihoodOutputs {
     uint8_t *flags;
 };
 int launch_likelihood(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o, hipStream_t stream);
+// The same pass with Token-IPT-DiFR under the same filter beside it (1 <= top_k <= 256); outputs as the two single calls.
+int launch_score_both_filtered(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o,
+                               const int32_t *claimed_ipt, const IptOutputs &oi, int32_t *kept, hipStream_t stream);
 // Token-IPT-DiFR under the sampler's top-k / top-p filter (aligned rows only; 1 <= top_k <= 256).
 int launch_ipt_filtered(const RowBatch &b, int top_k, float top_p, const IptOutputs &o, int32_t *kept, hipStream_t stream);
 struct LmHeadBatch;

@@ -36,10 +36,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
         if (kept_out && tid == 0) kept_out[row] = 0;
         return;
     }
-    const float nan = __builtin_nanf("");
     const int64_t V = b.V;
-    const int64_t t = ri.claimed;
-    const bool valid = t >= 0 && t < V;
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
 
     LogitTop<DT> lx;
@@ -116,64 +113,7 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     if (lx.bad) s_bad = 1;
     const int nk = lx.top.finish_sorted(scratch);  // buf_x[0 .. nk): the top_k logits in rank order
     const int kc = filter_prefix_length(buf_x, nk, (double)ri.T, top_p, scratch);
-
-    // K in ascending vocabulary index: each member finds its place by counting the members with a smaller index
-    const double x0 = kc > 0 ? (double)top_key(buf_x[0]) : 0.0;
-    if (tid < kc) {
-        const int32_t mine = top_index(buf_x[tid]);
-        int place = 0;
-        for (int r = 0; r < kc; ++r) place += (int)(top_index(buf_x[r]) < mine);
-        s_idx[place] = mine;
-        s_e[place] = exp(((double)top_key(buf_x[tid]) - x0) / (double)ri.T);
-    }
-    __syncthreads();
-    const double e = tid < kc ? s_e[tid] : 0.0;
-    const int32_t idx = tid < kc ? s_idx[tid] : 0x7FFFFFFF;
-    double Z;
-    const double incl = block_inclusive_scan(e, lds_d, Z);  // CDF numerators in index order
-
-    uint32_t r4[4];
-    noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r4);
-    const float u = uniform_from_bits(r4[0]);
-    const double ud = (double)u;
-    const bool bad = s_bad != 0 || !(Z > 0.0) || !(Z < (double)__builtin_inff());
-
-    // the sampler's token: the first member whose cumulative mass exceeds u (the last member if rounding leaves none)
-    if (tid < kc && !bad) {
-        const double before = incl - e;
-        if (incl / Z > ud && !(before / Z > ud)) s_tok = idx;
-    }
-    // the claimed token's interval
-    const double below = block_sum_f64((tid < kc && (int64_t)idx < t) ? e : 0.0, lds_d);
-    const double own = block_sum_f64((tid < kc && (int64_t)idx == t) ? e : 0.0, lds_d);
-    __syncthreads();
-    if (tid == 0) {
-        float a = nan, bb = nan, d = nan;
-        double ad = 0.0, bd = 0.0;
-        bool match = false;
-        if (valid && !bad) {
-            ad = below / Z;
-            bd = ad + own / Z;
-            a = (float)ad;
-            bb = (float)bd;
-            d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
-            match = (ad <= ud) && (ud < bd);
-        }
-        uint32_t f = 0;
-        if (!valid) f |= kFlagInvalidClaim;
-        if (bad) f |= kFlagNonfinite;
-        if (match) f |= kFlagMatch;
-        int32_t tok = s_tok;
-        if (tok < 0 && kc > 0) tok = s_idx[kc - 1];
-        o.dist[row] = d;
-        if (o.cdf_lo) o.cdf_lo[row] = a;
-        if (o.cdf_hi) o.cdf_hi[row] = bb;
-        if (o.u) o.u[row] = u;
-        if (o.ipt_token) o.ipt_token[row] = bad ? -1 : tok;
-        if (o.log_mass) o.log_mass[row] = (valid && !bad) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
-        if (kept_out) kept_out[row] = kc;
-        o.flags[row] = (uint8_t)f;
-    }
+    ipt_filtered_finish<DT>(ri, row, V, buf_x, kc, s_bad != 0, o, kept_out, s_e, s_idx, lds_d, &s_tok);
 }
 
 int launch_ipt_filtered(const RowBatch &b, int top_k, float top_p, const IptOutputs &o, int32_t *kept, hipStream_t stream)

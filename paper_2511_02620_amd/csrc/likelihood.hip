@@ -31,8 +31,17 @@ __device__ __forceinline__ double gumbel_f64(const RowInfo &ri, int32_t v)
 
 __device__ __forceinline__ float normal_cdf_f32(float z) { return 0.5f * erfcf(-z * 0.70710678118654752f); }
 
-template <int DT, int CAP>
-__device__ __forceinline__ void likelihood_row(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o)
+// BOTH: the same pass also scores Token-IPT-DiFR on the distribution the filter leaves (the top-k logits are
+// being collected anyway), with outputs identical to ipt_filtered_kernel's.
+struct FilteredIptSide {
+    const int32_t *claimed;  // [N] the Token-IPT-DiFR claims, or null
+    IptOutputs o;
+    int32_t *kept;
+};
+
+template <int DT, int CAP, bool BOTH>
+__device__ __forceinline__ void likelihood_row(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o,
+                                               const FilteredIptSide &ipt)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
@@ -43,7 +52,9 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     __shared__ float lds_L[kWaves];
     __shared__ double lds_d[kWaves];
     __shared__ double sA[kTopMaxN], sB[kTopMaxN];
-    __shared__ int32_t s_bad;
+    __shared__ int32_t s_bad, s_tok;
+    __shared__ double s_e[BOTH ? kTopMaxN : 1];     // the IPT side's kept set in ascending vocabulary index
+    __shared__ int32_t s_idx[BOTH ? kTopMaxN : 1];
 
     const int64_t row = blockIdx.x;
     const RowInfo ri = load_row_info(b, row);
@@ -61,6 +72,12 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
         }
         if (o.active)
             for (int j = tid; j < p.s; j += kBlock) o.active[row * p.s + j] = -1;
+        if (BOTH) {
+            RowInfo ri_ipt = ri;
+            ri_ipt.claimed = ipt.claimed ? ipt.claimed[row] : -1;
+            ipt_row_rejected(ri_ipt, row, ipt.o);
+            if (ipt.kept && tid == 0) ipt.kept[row] = 0;
+        }
         return;
     }
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
@@ -73,6 +90,7 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     lx.init(buf_x, &cnt_x, p.top_k, CAP);
     if (tid == 0) {
         s_bad = 0;
+        s_tok = -1;
         snap_y = snap_x = 0;
     }
     __syncthreads();
@@ -186,7 +204,16 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
 
     // filter threshold: top-k first, then top-p on the distribution renormalised over those k (fp64)
     double tau = -(double)__builtin_inff();
-    if (p.top_k > 0 && nk > 0) tau = (double)top_key(buf_x[filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p, scratch) - 1]);
+    int kc = 0;  // length of the filter's prefix of the ranked top-k logits
+    if (p.top_k > 0) kc = filter_prefix_length(buf_x, nk, (double)ri.T, p.top_p, scratch);
+    if (kc > 0) tau = (double)top_key(buf_x[kc - 1]);
+    if (BOTH) {
+        RowInfo ri_ipt = ri;
+        ri_ipt.claimed = ipt.claimed ? ipt.claimed[row] : -1;
+        __syncthreads();  // s_bad is final
+        ipt_filtered_finish<DT>(ri_ipt, row, V, buf_x, kc, s_bad != 0, ipt.o, ipt.kept, s_e, s_idx, lds_d, &s_tok);
+        __syncthreads();
+    }
     if (p.tau_in) tau = (double)p.tau_in[row];  // found beforehand by the nucleus kernel (NaN if it could not: pi becomes NaN)
     double xt = 0.0, gt = 0.0;
     if (valid) {
@@ -239,34 +266,50 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
 
 // Small selections (s and top_k up to kTopSmallN): 24 KB of LDS per workgroup, and the register budget of five
 // waves per SIMD (the few spills that costs are worth the fifth workgroup: measured).  Large ones: big buffers.
-template <int DT>
+template <int DT, bool BOTH>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(5))) void likelihood_small_kernel(RowBatch b, LikelihoodParams p,
-                                                                                                         LikelihoodOutputs o)
+                                                                                                         LikelihoodOutputs o,
+                                                                                                         FilteredIptSide ipt)
 {
-    likelihood_row<DT, kTopCapSmall>(b, p, o);
+    likelihood_row<DT, kTopCapSmall, BOTH>(b, p, o, ipt);
 }
-template <int DT>
-__global__ __launch_bounds__(kBlock) void likelihood_big_kernel(RowBatch b, LikelihoodParams p, LikelihoodOutputs o)
+template <int DT, bool BOTH>
+__global__ __launch_bounds__(kBlock) void likelihood_big_kernel(RowBatch b, LikelihoodParams p, LikelihoodOutputs o, FilteredIptSide ipt)
 {
-    likelihood_row<DT, kTopCapBig>(b, p, o);
+    likelihood_row<DT, kTopCapBig, BOTH>(b, p, o, ipt);
 }
 
-int launch_likelihood(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o, hipStream_t stream)
+template <bool BOTH>
+static int launch_likelihood_any(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o,
+                                 const FilteredIptSide &ipt, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
     const bool small = p.s <= kTopSmallN && p.top_k <= kTopSmallN;
     if (b.dtype == 0) {
         if (small)
-            likelihood_small_kernel<0><<<grid, block, 0, stream>>>(b, p, o);
+            likelihood_small_kernel<0, BOTH><<<grid, block, 0, stream>>>(b, p, o, ipt);
         else
-            likelihood_big_kernel<0><<<grid, block, 0, stream>>>(b, p, o);
+            likelihood_big_kernel<0, BOTH><<<grid, block, 0, stream>>>(b, p, o, ipt);
     } else {
         if (small)
-            likelihood_small_kernel<1><<<grid, block, 0, stream>>>(b, p, o);
+            likelihood_small_kernel<1, BOTH><<<grid, block, 0, stream>>>(b, p, o, ipt);
         else
-            likelihood_big_kernel<1><<<grid, block, 0, stream>>>(b, p, o);
+            likelihood_big_kernel<1, BOTH><<<grid, block, 0, stream>>>(b, p, o, ipt);
     }
     return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int launch_likelihood(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o, hipStream_t stream)
+{
+    const FilteredIptSide none{nullptr, IptOutputs{nullptr, nullptr, nullptr, nullptr, nullptr, 0.0, 0.0, nullptr, nullptr, nullptr}, nullptr};
+    return launch_likelihood_any<false>(b, p, o, none, stream);
+}
+
+int launch_score_both_filtered(const RowBatch &b, const LikelihoodParams &p, const LikelihoodOutputs &o,
+                               const int32_t *claimed_ipt, const IptOutputs &oi, int32_t *kept, hipStream_t stream)
+{
+    const FilteredIptSide side{claimed_ipt, oi, kept};
+    return launch_likelihood_any<true>(b, p, o, side, stream);
 }
 
 }  // namespace difr

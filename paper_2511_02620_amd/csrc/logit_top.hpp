@@ -4,6 +4,7 @@
 #pragma once
 
 #include "gumbel_stream.hpp"
+#include "ipt_stream.hpp"
 #include "topn.hpp"
 
 namespace difr {
@@ -141,6 +142,79 @@ __device__ __forceinline__ int filter_prefix_length(const uint64_t *buf, int nk,
     const int kept = s.kept;
     __syncthreads();
     return kept;
+}
+
+// Token-IPT-DiFR on the kept set K = buf[0 .. kc) (the filter's prefix of the top-k logits, in rank order): the
+// members are put in ascending vocabulary index, their renormalised CDF is formed in fp64, and the claimed
+// token's interval, the distance of the regenerated uniform from it, the sampler's own token and the
+// Gaussian log-mass are written (Sec. 3.2, Sec. 6.2, appendix "convolved Gaussian score").  All 256 threads;
+// s_e / s_idx: kTopMaxN entries of LDS each, lds_d: kWaves doubles, s_tok: one int preset to -1.
+template <int DT>
+__device__ __forceinline__ void ipt_filtered_finish(const RowInfo &ri, int64_t row, int64_t V, const uint64_t *buf, int kc,
+                                                    bool bad_seen, const IptOutputs &o, int32_t *kept_out, double *s_e,
+                                                    int32_t *s_idx, double *lds_d, int32_t *s_tok)
+{
+    const int tid = threadIdx.x;
+    const float nan = __builtin_nanf("");
+    const int64_t t = ri.claimed;
+    const bool valid = t >= 0 && t < V;
+    // K in ascending vocabulary index: each member finds its place by counting the members with a smaller index
+    const double x0 = kc > 0 ? (double)top_key(buf[0]) : 0.0;
+    if (tid < kc) {
+        const int32_t mine = top_index(buf[tid]);
+        int place = 0;
+        for (int r = 0; r < kc; ++r) place += (int)(top_index(buf[r]) < mine);
+        s_idx[place] = mine;
+        s_e[place] = exp(((double)top_key(buf[tid]) - x0) / (double)ri.T);
+    }
+    __syncthreads();
+    const double e = tid < kc ? s_e[tid] : 0.0;
+    const int32_t idx = tid < kc ? s_idx[tid] : 0x7FFFFFFF;
+    double Z;
+    const double incl = block_inclusive_scan(e, lds_d, Z);  // CDF numerators in index order
+
+    uint32_t r4[4];
+    noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r4);
+    const float u = uniform_from_bits(r4[0]);
+    const double ud = (double)u;
+    const bool bad = bad_seen || !(Z > 0.0) || !(Z < (double)__builtin_inff());
+
+    // the sampler's token: the first member whose cumulative mass exceeds u (the last member if rounding leaves none)
+    if (tid < kc && !bad) {
+        const double before = incl - e;
+        if (incl / Z > ud && !(before / Z > ud)) *s_tok = idx;
+    }
+    // the claimed token's interval
+    const double below = block_sum_f64((tid < kc && (int64_t)idx < t) ? e : 0.0, lds_d);
+    const double own = block_sum_f64((tid < kc && (int64_t)idx == t) ? e : 0.0, lds_d);
+    __syncthreads();
+    if (tid == 0) {
+        float a = nan, bb = nan, d = nan;
+        double ad = 0.0, bd = 0.0;
+        bool match = false;
+        if (valid && !bad) {
+            ad = below / Z;
+            bd = ad + own / Z;
+            a = (float)ad;
+            bb = (float)bd;
+            d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+            match = (ad <= ud) && (ud < bd);
+        }
+        uint32_t f = 0;
+        if (!valid) f |= kFlagInvalidClaim;
+        if (bad) f |= kFlagNonfinite;
+        if (match) f |= kFlagMatch;
+        int32_t tok = *s_tok;
+        if (tok < 0 && kc > 0) tok = s_idx[kc - 1];
+        o.dist[row] = d;
+        if (o.cdf_lo) o.cdf_lo[row] = a;
+        if (o.cdf_hi) o.cdf_hi[row] = bb;
+        if (o.u) o.u[row] = u;
+        if (o.ipt_token) o.ipt_token[row] = bad ? -1 : tok;
+        if (o.log_mass) o.log_mass[row] = (valid && !bad) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
+        if (kept_out) kept_out[row] = kc;
+        o.flags[row] = (uint8_t)f;
+    }
 }
 
 }  // namespace difr

@@ -148,6 +148,21 @@ def test_argument_validation_needs_no_device(lib):
     assert lik(rows(V=0)) == SHAPE and lik(rows(N=0), pi=None, fl=None, z=None) == OK
     assert lik(rows(V=15, ld=15)) == ALIGN                   # rows not 16-byte aligned
     assert lib.difr_gumbel_likelihood(C.byref(rows()), None, fake, None, None, None, fake, None) == NULL
+    # likelihood + filtered IPT in one pass
+    def sbf(r=None, pi=fake, dist=fake, fg=fake, fi=fake, lm=None, sigma_ipt=0.01, **kw):
+        prm = dict(top_k=50, top_p=0.95, s=16, sigma=0.5, M=64, z=fake)
+        prm.update(kw)
+        p = _LikelihoodParams(prm["top_k"], prm["top_p"], prm["s"], prm["sigma"], prm["M"], prm["z"])
+        return lib.difr_score_both_filtered(C.byref(r or rows()), None, C.byref(p), pi, None, None, None, fg, dist, None,
+                                            None, None, None, sigma_ipt, 1e-30, lm, None, fi, None)
+
+    for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0), dict(top_p=0.0)):
+        assert sbf(**kw) == ARG, kw
+    assert sbf(lm=fake, sigma_ipt=0.0) == ARG
+    assert sbf(top_k=0) == 7                                 # DIFR_ERR_UNSUPPORTED: the shared top-k list is the point
+    assert sbf(pi=None) == NULL and sbf(dist=None) == NULL and sbf(fg=None) == NULL and sbf(fi=None) == NULL
+    assert sbf(z=None) == NULL and sbf(rows(V=15, ld=15)) == ALIGN and sbf(rows(V=0)) == SHAPE
+    assert sbf(rows(N=0), pi=None, dist=None, fg=None, fi=None, z=None) == OK
     # both estimators + admissible-set size in one pass
     def sba(r=None, delta=1.0, margin=fake, count=fake):
         return lib.difr_score_both_admissible(C.byref(r or rows()), None, C.c_float(delta), margin, fake, None, None, fake,

@@ -40,6 +40,7 @@ def test_row_path_replays_match_eager(difr):
     logits = torch.empty(N, V, dtype=torch.bfloat16, device=DEV)
     cg = torch.empty(N, dtype=torch.int32, device=DEV)
     ci = torch.empty(N, dtype=torch.int32, device=DEV)
+    zdraws = torch.randn(64, generator=torch.Generator().manual_seed(4)).to(DEV)
 
     def step():
         g, i = difr.score_both(logits, 0.8, seeds, sid, pos, cg, ci)
@@ -47,7 +48,8 @@ def test_row_path_replays_match_eager(difr):
         pi = difr.seq_reduce(i["dist"], i["flags"], off, 0.01)
         a = difr.admissible_count(logits, 0.8, seeds, sid, pos, g["max_score"], 2.0)
         f = difr.ipt_score_filtered(logits, 0.8, seeds, sid, pos, ci, top_k=20, top_p=0.9)
-        return g, i, pg, pi, a, f
+        lk, fi = difr.score_both_filtered(logits, 0.8, seeds, sid, pos, cg, ci, zdraws, top_k=20, top_p=0.9, s=8, sigma=0.3)
+        return g, i, pg, pi, a, f, lk, fi
 
     def load(seed):
         x, a, b = _inputs(seed, N, V, S)
@@ -73,7 +75,7 @@ def test_row_path_replays_match_eager(difr):
         got = [{k: v.clone() for k, v in d.items()} for d in captured]
         eager = step()                 # the program's own eager work between replays
         torch.cuda.synchronize()
-        for d_got, d_eager, name in zip(got, eager, ("gumbel", "ipt", "pool_g", "pool_i", "admissible", "filtered")):
+        for d_got, d_eager, name in zip(got, eager, ("gumbel", "ipt", "pool_g", "pool_i", "admissible", "filtered", "likelihood", "filtered_fused")):
             _same(d_got, d_eager, "replay %d %s" % (rep, name))
 
 
