@@ -194,6 +194,14 @@ def _score_and_compare(difr, wl, logits, seeds, sid, pos, cg, ci, sample_rows, t
     assert np.array_equal(fi["kept"][ssel].cpu().numpy(), ofi["kept"])
     st_f = parity.compare_ipt({k: v[ssel] for k, v in fi.items() if k != "kept"}, ofi)
     say(wl.name, "T=%g" % T, "filtered ipt:", st_f, "mean kept %.1f" % float(fi["kept"].float().mean()))
+    # the two filtered estimators from one read of the logits: identical to the two calls on every row
+    lk2, fi2 = difr.score_both_filtered(logits, T, seeds, sid, pos, cg, ci, z.to(DEV), top_k=50, top_p=0.95, s=16,
+                                        sigma=0.3, want_active=True)
+    torch.cuda.synchronize()
+    for name, a_, b_ in (("likelihood", lk, lk2), ("filtered ipt", fi, fi2)):
+        for k in a_:
+            assert torch.equal(torch.nan_to_num(a_[k].float(), nan=-7.0), torch.nan_to_num(b_[k].float(), nan=-7.0)), (name, k)
+    del lk2, fi2
     # the bare nucleus (no top-k): every row, the oracle on the first 128 sampled rows at top_p and top_p -/+ 2e-6
     # (the kept-set size of a nucleus of tens of thousands of tokens is decided by fp32 masses)
     nu = difr.ipt_score_filtered(logits, T, seeds, sid, pos, ci, top_k=0, top_p=0.9)
