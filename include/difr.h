@@ -158,13 +158,16 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
  * difr_ipt_score with the claims claimed_ipt (DEVICE [N], or NULL for sampling mode), reading each
  * row from HBM once instead of twice.  Outputs have the meaning, layout and optionality of the
  * two single-estimator calls and are bit-identical to theirs; flags_gumbel and flags_ipt are the
- * two calls' `flags`.  The optional honest-token, log-mass and logit-rank outputs are not offered
+ * two calls' `flags`.  logit_rank [N] int32 or NULL is the logit rank of the Token-DiFR claim
+ * in->claimed as in difr_gumbel_score (counted in the same pass, only when asked for: it costs a few
+ * per cent), so that one read of the logits feeds the score-and-rank classifier of difr_classify
+ * [Sec. 7.1].  The optional honest-token and log-mass outputs of difr_ipt_score are not offered
  * here.  [Sec. 6.2 and Sec. 6.3 together: a verifier that does not know which sampler the server
  * ran, or that feeds both scores to one classifier.]
  */
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
-                    float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                    uint8_t *flags_ipt, void *hip_stream);
+                    float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
+                    float *cdf_hi, float *u, uint8_t *flags_ipt, void *hip_stream);
 
 /*
  * Token-IPT-DiFR on the distribution a filtering sampler used.  [Sec. 3.2: the IPT sampler applied under the

@@ -96,7 +96,7 @@ def load_library():
     lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.difr_debug_gumbel_score_unfiltered.restype = C.c_int
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
-    lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12
+    lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 13
     lib.difr_score_both.restype = C.c_int
     lib.difr_score_both_admissible.argtypes = [C.POINTER(_Rows), vp, C.c_float] + [vp] * 13
     lib.difr_score_both_admissible.restype = C.c_int
@@ -249,8 +249,9 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
 
 
 def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-               temperatures=None, V=None):
-    """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors."""
+               temperatures=None, V=None, want_rank=False):
+    """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
+    want_rank adds logit_rank (of the Token-DiFR claim) to the first."""
     lib = load_library()
     r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
     _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
@@ -260,9 +261,12 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
              flags=torch.empty(N, dtype=torch.uint8, device=dev))
     i = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
              u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    if want_rank:
+        g["logit_rank"] = torch.empty(N, dtype=torch.int32, device=dev)
     with torch.cuda.device(dev):
         rc = lib.difr_score_both(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
-                                 _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]),
+                                 _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]),
+                                 _ptr(g.get("logit_rank")), _ptr(i["dist"]),
                                  _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]),
                                  _stream_ptr(dev))
     if rc:

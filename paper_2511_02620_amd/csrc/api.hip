@@ -281,8 +281,8 @@ int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, co
 }
 
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
-                    float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                    uint8_t *flags_ipt, void *hip_stream)
+                    float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
+                    float *cdf_hi, float *u, uint8_t *flags_ipt, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
@@ -293,12 +293,12 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
     if ((rc = check_device()) != DIFR_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
     if (aligned) {
-        const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
+        const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
         const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
         return difr::launch_score_both(b, claimed_ipt, og, oi, stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
     }
     // rows that are not 16-byte aligned: the two generic kernels, one after the other
-    if (difr::launch_gumbel_score(b, false, true, margin, argmax, max_score, claimed_score, flags_gumbel, nullptr, stream))
+    if (difr::launch_gumbel_score(b, false, true, margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank, stream))
         return DIFR_ERR_LAUNCH;
     difr::RowBatch bi = b;
     bi.claimed = claimed_ipt;

@@ -441,6 +441,13 @@ def test_score_both_equals_the_two_single_calls(difr, dtype, V, ld, offset, case
     torch.cuda.synchronize()
     _same_outputs(fa, {k: a[k] for k in fa})
     _same_outputs(fb, {k: b[k] for k in fb})
+    # the same with the logit rank of the Token-DiFR claim counted in the pass: everything else unchanged
+    ar = difr.gumbel_score(logits, T, seeds, sid, pos, cg, V=V, temperatures=temps, want_rank=True)
+    ra, rb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps, want_rank=True)
+    torch.cuda.synchronize()
+    assert "logit_rank" in ra
+    _same_outputs(ra, {k: ar[k] for k in ra})
+    _same_outputs(rb, {k: b[k] for k in rb})
     if case == "honest":
         assert (fa["flags"] & 1).all()
         assert int((fb["flags"] & 1).sum()) >= N - 2     # u within rounding of an interval end may fall either way
