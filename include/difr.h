@@ -185,8 +185,8 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
  * over the logit keys weighted by probability mass: three to five passes over the row instead of one.  The
  * marginal tokens of such a nucleus have probabilities around 1e-6, the accuracy of the fp32 exponentials the mass
  * is summed from, so kept[n] may differ from an evaluation in double by those few tokens; a, b and d keep the 1e-4
- * contract.  ipt_token is not offered on this path (DIFR_ERR_UNSUPPORTED), nor is top_k = 0 with top_p >= 1 (no
- * filter at all: call difr_ipt_score).
+ * contract.  The sampler's own token, when asked for and not the claim, costs one more (early-exit) pass.
+ * top_k = 0 with top_p >= 1 is refused (DIFR_ERR_UNSUPPORTED: no filter at all, call difr_ipt_score).
  */
 int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, float *dist, float *cdf_lo, float *cdf_hi,
                             float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass, int32_t *kept,

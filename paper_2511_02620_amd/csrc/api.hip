@@ -217,9 +217,8 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
     if (rc != DIFR_OK) return rc;
     if (top_k < 0 || top_k > 256 || !(top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
     if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
-    // no top-k: a nucleus over the whole vocabulary (without top-p either there is no filter: difr_ipt_score);
-    // the sampler's own token is not offered on that path
-    if (top_k == 0 && (!(top_p < 1.0f) || ipt_token)) return DIFR_ERR_UNSUPPORTED;
+    // no top-k: a nucleus over the whole vocabulary (without top-p either there is no filter: difr_ipt_score)
+    if (top_k == 0 && !(top_p < 1.0f)) return DIFR_ERR_UNSUPPORTED;
     if (b.N == 0) return DIFR_OK;
     if (!dist || !flags) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;

@@ -96,6 +96,22 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     const int32_t nvec = (int32_t)((V + E - 1) / E);  // V < 2^31
     const uint32_t V32 = (uint32_t)V;
     auto fetch = [&](int32_t vec) { return *reinterpret_cast<const ipt_u32x4 *>(x_row + (size_t)vec * E); };
+    // the last vector of a ragged row: entries past the end become -inf
+    auto ragged_patched = [&](ipt_u32x4 q, uint32_t base) __attribute__((always_inline)) {
+        if (base + E > V32) {
+            uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                if (base + j < V32) continue;
+                if (DT == 0)
+                    w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[j >> 1] & 0xFFFF0000u) | 0x0000FF80u);
+                else
+                    w[j] = 0xFF800000u;
+            }
+            q = ipt_u32x4{w[0], w[1], w[2], w[3]};
+        }
+        return q;
+    };
     auto for_each_vector = [&](auto &&f) __attribute__((always_inline)) {
         int32_t vec = tid;
         ipt_u32x4 q_next = ipt_u32x4{0u, 0u, 0u, 0u};
@@ -105,18 +121,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             const int32_t next = vec + kBlock;
             if (next < nvec) q_next = fetch(next);
             const uint32_t base = (uint32_t)vec * E;
-            if (base + E > V32) {  // the last vector of a ragged row
-                uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    if (base + j < V32) continue;
-                    if (DT == 0)
-                        w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[j >> 1] & 0xFFFF0000u) | 0x0000FF80u);
-                    else
-                        w[j] = 0xFF800000u;
-                }
-                q = ipt_u32x4{w[0], w[1], w[2], w[3]};
-            }
+            q = ragged_patched(q, base);
             f(q, base);
             vec = next;
         }
@@ -158,20 +163,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         }
     };
     if (tid < nvec) {
-        ipt_u32x4 q = fetch(tid);
-        if ((uint32_t)(tid * E + E) > V32) {  // a row shorter than one round: the ragged vector
-            uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-            for (int j = 0; j < E; ++j) {
-                if ((uint32_t)(tid * E + j) < V32) continue;
-                if (DT == 0)
-                    w[j >> 1] = (j & 1) ? ((w[j >> 1] & 0x0000FFFFu) | 0xFF800000u) : ((w[j >> 1] & 0xFFFF0000u) | 0x0000FF80u);
-                else
-                    w[j] = 0xFF800000u;
-            }
-            q = ipt_u32x4{w[0], w[1], w[2], w[3]};
-        }
-        look(q);
+        look(ragged_patched(fetch(tid), (uint32_t)tid * E));  // (ragged only in a row shorter than one round)
     }
     R = block_max(R, lds_f);
     if (!(R > ninf && R < __builtin_inff())) {  // uniform
@@ -508,43 +500,128 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     if (tid == 0) {
         if (kept_out) kept_out[row] = (int32_t)kept;
         if (tau_out) tau_out[row] = tau_val;
-        if (want_ipt) {
-            uint32_t r[4];
-            noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r);
-            const float u = uniform_from_bits(r[0]);
-            const double ud = (double)u;
-            float a = nan, bb = nan, d = nan;
-            double ad = 0.0, bd = 0.0;
-            bool match = false;
-            const bool ok = Zk > 0.0 && Zk < (double)__builtin_inff();
-            if (valid && ok) {
-                const float xt = Elem<DT>::to_float(x_row[t]);
-                bool in_K;
-                if (many_ties) {
-                    const uint32_t kt = float_order_bits(xt) >> (DT == 0 ? 16 : 0);
-                    in_K = kt > khi || (kt == klo && (int64_t)tb < n_tie);
-                } else {
-                    in_K = top_composite(xt, (int32_t)t) >= cut;
-                }
-                const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Rc)) : 0.0;
-                ad = below / Zk;
-                bd = ad + own / Zk;
-                a = (float)ad;
-                bb = (float)bd;
-                d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
-                match = (ad <= ud) && (ud < bd);
-            }
-            uint32_t f = 0;
-            if (!valid) f |= kFlagInvalidClaim;
-            if (!ok) f |= kFlagNonfinite;
-            if (match) f |= kFlagMatch;
-            o.dist[row] = d;
-            if (o.cdf_lo) o.cdf_lo[row] = a;
-            if (o.cdf_hi) o.cdf_hi[row] = bb;
-            if (o.u) o.u[row] = u;
-            if (o.log_mass) o.log_mass[row] = (valid && ok) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
-            o.flags[row] = (uint8_t)f;
+    }
+    if (!want_ipt) return;
+
+    // ---- the interval of the claimed token (every thread forms it: whether the sampler's token has to be
+    //      searched is decided by all of them) ----
+    uint32_t r[4];
+    noise_block(ri.key, ri.pos, ri.seq, kStreamIpt, 0u, r);
+    const float u = uniform_from_bits(r[0]);
+    const double ud = (double)u;
+    float a = nan, bb = nan, d = nan;
+    double ad = 0.0, bd = 0.0;
+    bool match = false;
+    const bool ok = Zk > 0.0 && Zk < (double)__builtin_inff();
+    if (valid && ok) {
+        const float xt = Elem<DT>::to_float(x_row[t]);
+        bool in_K;
+        if (many_ties) {
+            const uint32_t kt = float_order_bits(xt) >> (DT == 0 ? 16 : 0);
+            in_K = kt > khi || (kt == klo && (int64_t)tb < n_tie);
+        } else {
+            in_K = top_composite(xt, (int32_t)t) >= cut;
         }
+        const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Rc)) : 0.0;
+        ad = below / Zk;
+        bd = ad + own / Zk;
+        a = (float)ad;
+        bb = (float)bd;
+        d = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
+        match = (ad <= ud) && (ud < bd);
+    }
+    uint32_t f = 0;
+    if (!valid) f |= kFlagInvalidClaim;
+    if (!ok) f |= kFlagNonfinite;
+    if (match) f |= kFlagMatch;
+
+    // ---- the sampler's own token, when asked for and the claim is not it: one more pass, in vocabulary order, over
+    //      the masses of the members of K until their running sum exceeds u Z_K.  A token above the bracket is a
+    //      member, one inside it is if it ranks no lower than the cut (sorted bracket) or is among the first n_tie
+    //      of the ties in index order; the pass ends with the step that holds the token. ----
+    int32_t tok = match ? (int32_t)t : -1;
+    if (o.ipt_token != nullptr && ok && !match) {  // uniform
+        f |= kFlagSlowPath;
+        const double goal = ud * Zk;
+        double before = 0.0;       // mass of the members in the steps already walked
+        int64_t ties_before = 0;   // many_ties: bracket entries in those steps
+        int32_t last_member = -1;  // the thread's last member so far (rounding can leave the goal just out of reach)
+        if (tid == 0) s_fill = -1;
+        __syncthreads();
+        for (int32_t vec0 = 0; vec0 < nvec; vec0 += kBlock) {
+            const int32_t vec = vec0 + tid;
+            const uint32_t base = (uint32_t)vec * E;
+            ipt_u32x4 q = ipt_u32x4{0u, 0u, 0u, 0u};
+            uint32_t kw[4] = {0u, 0u, 0u, 0u};
+            int32_t my_ties = 0;
+            if (vec < nvec) {
+                q = ragged_patched(fetch(vec), base);
+                keys_of(q, kw);
+                if (many_ties) {
+#pragma unroll
+                    for (int j = 0; j < E; ++j) my_ties += (int32_t)(key_of(kw, j) - klo <= span_c);
+                }
+            }
+            int64_t tie_rank = 0;  // many_ties: bracket entries with a smaller index than this thread's first
+            if (many_ties) {       // uniform
+                double tie_total;
+                const double incl = block_inclusive_scan((double)my_ties, lds_d, tie_total);  // (exact: small integers)
+                tie_rank = ties_before + (int64_t)(incl - (double)my_ties);
+                ties_before += (int64_t)tie_total;
+            }
+            float e[E];
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                e[j] = 0.0f;
+                if (vec >= nvec) continue;
+                const uint32_t key = key_of(kw, j);
+                bool member = key > khi;
+                if (key - klo <= span_c)
+                    member = many_ties ? (tie_rank++ < n_tie) : (top_composite(value_of(q, j), (int32_t)(base + j)) >= cut);
+                if (member) {
+                    e[j] = fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
+                    last_member = (int32_t)(base + j);
+                }
+            }
+            const double ls = (double)tree_sum<E>(e);
+            double total;
+            const double incl = block_inclusive_scan(ls, lds_d, total);
+            if (before + total > goal) {  // uniform: the token is inside this step
+                const double excl = before + (incl - ls);
+                if (excl <= goal && before + incl > goal) {  // exactly one thread
+                    double cacc = excl;
+                    int32_t found = -1;
+#pragma unroll
+                    for (int j = 0; j < E; ++j) {
+                        cacc += (double)e[j];
+                        if (found < 0 && e[j] > 0.0f && cacc > goal) found = (int32_t)(base + j);
+                    }
+                    s_fill = found >= 0 ? found : last_member;  // (found < 0: rounding between the two sums)
+                }
+                break;
+            }
+            before += total;
+        }
+        __syncthreads();
+        tok = s_fill;
+        if (tok < 0) {  // u Z_K at or beyond the accumulated total: the last member of K in vocabulary order
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) last_member = max(last_member, __shfl_xor(last_member, off, 64));
+            __syncthreads();
+            if ((tid & 63) == 0) lds_i[tid >> 6] = last_member;
+            __syncthreads();
+            tok = max(max(lds_i[0], lds_i[1]), max(lds_i[2], lds_i[3]));
+        }
+    }
+
+    if (tid == 0) {
+        o.dist[row] = d;
+        if (o.cdf_lo) o.cdf_lo[row] = a;
+        if (o.cdf_hi) o.cdf_hi[row] = bb;
+        if (o.u) o.u[row] = u;
+        if (o.ipt_token) o.ipt_token[row] = ok ? tok : -1;
+        if (o.log_mass) o.log_mass[row] = (valid && ok) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
+        o.flags[row] = (uint8_t)f;
     }
 }
 

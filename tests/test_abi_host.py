@@ -126,8 +126,6 @@ def test_argument_validation_needs_no_device(lib):
 
     assert iptf(k=-1) == ARG and iptf(k=257) == ARG and iptf(p=0.0) == ARG and iptf(sigma=0.0, lm=fake) == ARG
     assert iptf(k=0, p=1.0) == 7                              # DIFR_ERR_UNSUPPORTED: no filter at all is difr_ipt_score
-    assert lib.difr_ipt_score_filtered(C.byref(rows()), 0, 0.9, fake, None, None, None, fake, 0.01, 1e-30, None, None,
-                                       fake, None) == 7       # the sampler's token is not offered with a bare nucleus
     assert iptf(rows(V=15, ld=15), k=0, p=0.9) == ALIGN and iptf(rows(N=0), k=0, p=0.9, dist=None, fl=None) == OK
     assert iptf(dist=None) == NULL and iptf(fl=None) == NULL
     assert iptf(rows(V=15, ld=15)) == ALIGN and iptf(rows(N=0), dist=None, fl=None) == OK

@@ -40,8 +40,14 @@ def _oracle(host, V, T, seeds, sid, pos, claims, p, temps):
 
 def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
     out = difr.ipt_score_filtered(logits, T, seeds, sid, pos, claims, top_k=0, top_p=p, temperatures=temps, V=V,
-                                  want_log_mass=True, sigma=0.02)
+                                  want_token=True, want_log_mass=True, sigma=0.02)
     torch.cuda.synchronize()
+    plain = difr.ipt_score_filtered(logits, T, seeds, sid, pos, claims, top_k=0, top_p=p, temperatures=temps, V=V,
+                                    want_log_mass=True, sigma=0.02)
+    for name in ("dist", "cdf_lo", "cdf_hi", "u", "log_mass", "kept"):  # asking for the token changes nothing else
+        assert torch.equal(out[name].view(torch.int32), plain[name].view(torch.int32)), name
+    assert torch.equal(out["flags"] & ~8, plain["flags"])              # (but for the second-pass flag)
+    tok = out.pop("ipt_token").cpu().numpy()
     host = parity.to_host_logits(logits)
     p32 = float(np.float32(p))
     ref = _oracle(host, V, T, seeds, sid, pos, claims, p32, temps)
@@ -63,8 +69,23 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
         g_, r_ = out[name].cpu().numpy().astype(np.float64)[~sure], ref[name][~sure]
         both_nan = np.isnan(g_) & np.isnan(r_)
         assert (both_nan | (np.abs(g_ - r_) <= 1e-4)).all(), name
+    # the sampler's own token, on the rows whose kept set is the oracle's: equal, except where u sits on a CDF step
+    # (then the oracle's interval of the GPU's token touches u); a row the library gave up on has none
+    flags = out["flags"].cpu().numpy()
+    excused = 0
+    for r in np.nonzero(sure)[0]:
+        if flags[r] & 4:
+            assert tok[r] == -1
+        elif tok[r] != ref["ipt_token"][r]:
+            one = oracle.ipt_filtered_score(host[r:r + 1], V, np.float32(T) if temps is None else float(temps[r]),
+                                            parity.seeds_u64(seeds), sid.cpu().numpy()[r:r + 1],
+                                            parity.positions_u32(pos)[r:r + 1], np.array([tok[r]], np.int32), 0, p32)
+            assert one["dist"][0] < 1e-5 and one["cdf_hi"][0] > one["cdf_lo"][0], (r, tok[r], ref["ipt_token"][r])
+            excused += 1
+    st["token_excused"] = excused
     st["mean_kept"] = float(kept.mean())
     st["rows_in_doubt"] = int((~sure).sum())
+    out["ipt_token"] = torch.from_numpy(tok).to(DEV)
     return st, out
 
 
@@ -162,6 +183,34 @@ def test_nucleus_zipf_rows_and_per_row_temperatures(difr):
     for p in (0.9, 0.95):
         st, out = _compare(difr, ver, wl.V, 1.0, seeds, sid, pos, claims, p, temps=temps)
         say("nucleus C2 rows p", p, st)
+
+
+@pytest.mark.parametrize("dtype,kind", [(torch.bfloat16, "normal"), (torch.float32, "coarse"), (torch.bfloat16, "coarse")])
+def test_nucleus_sampling_mode_round_trip(difr, dtype, kind):
+    """No claims: the call returns the sampler's token under the bare nucleus.  Scored as claims, those tokens match
+    on every row, with distance 0, and come back as the sampler's token."""
+    N, V = 64, 12296
+    g = torch.Generator().manual_seed(5 + len(kind))
+    x = torch.randn(N, V, generator=g) * 2.0
+    if kind == "coarse":
+        x = torch.round(x * 2) / 2
+    logits = x.to(dtype).to(DEV)
+    seeds = torch.tensor([3, 1 << 40, 99], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 3).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    for p in (0.5, 0.97):
+        drawn = difr.ipt_score_filtered(logits, 0.8, seeds, sid, pos, None, top_k=0, top_p=p, want_token=True)
+        tok = drawn["ipt_token"]
+        assert ((tok >= 0) & (tok < V)).all()
+        assert (drawn["flags"] & 2).all()  # no claim: INVALID_CLAIM, the scores are NaN
+        back = difr.ipt_score_filtered(logits, 0.8, seeds, sid, pos, tok, top_k=0, top_p=p, want_token=True)
+        torch.cuda.synchronize()
+        assert (back["flags"] & 1).all() and (back["dist"] == 0).all()
+        assert torch.equal(back["ipt_token"], tok)
+        assert torch.equal(back["kept"], drawn["kept"])
+        # the token lies inside the nucleus: its logit is no smaller than the smallest kept one
+        st, _ = _compare(difr, logits, V, 0.8, seeds, sid, pos, tok, p)
+        say("nucleus sampling", dtype, kind, p, st)
 
 
 def test_likelihood_with_a_whole_vocabulary_nucleus(difr):
