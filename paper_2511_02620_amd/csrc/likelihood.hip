@@ -150,7 +150,7 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     int round = 0;
     while (round < n_rounds) {
         // (large selections start with epochs of 1, 1, 2, 4 rounds: early in the row each doubling of what has been
-        // seen brings about n pushes, and the buffers hold kTopCap)
+        // seen brings about n pushes, and the buffers hold kTopCapBig)
         const int len = round == 0 ? 1 : (!big_n || round >= 8 ? kTopEpoch : (round < 2 ? 1 : (round < 4 ? 2 : 4)));
         const int r_end = round < n_main ? min(n_main, round + len) : n_rounds;
         top_y.new_epoch();

@@ -126,21 +126,29 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
             vec = next;
         }
     };
-    // Order keys of a vector at the resolution the storage type has.  bf16: two 16-bit keys per dword (the top
-    // halves of float_order_bits of the two entries), formed on the packed patterns; fp32: one 32-bit key each.
-    // field(kw, j, lo, width): bits [lo, lo + width) of entry j's 32-bit key (lo >= 16 for bf16).
+    // Order keys of a vector at the resolution the storage type has: equal logits have equal keys, a larger logit
+    // a larger key.  -0 and +0 are the same logit (ties go by index, not by sign), so they share a key.
+    // bf16: two 16-bit keys per dword, formed on the packed patterns: 0x8000 + magnitude for a clear sign bit,
+    // 0x8000 - magnitude for a set one.  fp32: float_order_bits of the value with -0 read as +0.
     auto keys_of = [&](const ipt_u32x4 &q, uint32_t (&kw)[4]) __attribute__((always_inline)) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (DT == 0) {
                 typedef int16_t i16x2_t __attribute__((ext_vector_type(2)));
-                const i16x2_t sg = __builtin_bit_cast(i16x2_t, w[i]) >> 15;  // 0xFFFF where the sign bit is set
-                kw[i] = w[i] ^ (__builtin_bit_cast(uint32_t, sg) | 0x80008000u);
+                typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+                const uint32_t sg = __builtin_bit_cast(uint32_t, __builtin_bit_cast(i16x2_t, w[i]) >> 15);  // 0xFFFF where the sign bit is set
+                const uint32_t a = (w[i] & 0x7FFF7FFFu) ^ sg ^ 0x80008000u;  // 0x8000 + m, or 0x7FFF - m
+                kw[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) - __builtin_bit_cast(u16x2_t, sg));  // (- 0xFFFF = + 1)
             } else {
-                kw[i] = float_order_bits(__uint_as_float(w[i]));
+                kw[i] = float_order_bits(__uint_as_float(w[i]) + 0.0f);
             }
         }
+    };
+    auto key_of_value = [&](float x) __attribute__((always_inline)) {  // the same key from a single value
+        if (DT != 0) return float_order_bits(x + 0.0f);
+        const uint32_t b = __float_as_uint(x) >> 16, m = b & 0x7FFFu;
+        return (b & 0x8000u) ? 0x8000u - m : 0x8000u + m;
     };
     auto value_of = [&](const ipt_u32x4 &q, int j) __attribute__((always_inline)) {
         const uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -182,9 +190,10 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     // ---- passes B: search for the bracket [klo, khi] of keys that holds the cut ----
     // Keys are the order-preserving images of the logits at the storage type's resolution (16 bits for bf16).
     constexpr uint32_t kKeyPosInf = DT == 0 ? 0xFF80u : 0xFF800000u;  // keys >= this: +inf or a NaN, sign clear
-    constexpr uint32_t kKeyNegInf = DT == 0 ? 0x007Fu : 0x007FFFFFu;  // keys < this: a NaN with the sign bit set
+    constexpr uint32_t kKeyNegInf = DT == 0 ? 0x0080u : 0x007FFFFFu;  // -inf; keys < this: a NaN with the sign bit set
     auto value_of_key = [&](uint32_t k) __attribute__((always_inline)) {
-        return float_from_order_bits(DT == 0 ? ((k << 16) | ((k & 0x8000u) ? 0u : 0xFFFFu)) : k);
+        if (DT != 0) return float_from_order_bits(k);
+        return __uint_as_float((k >= 0x8000u ? k - 0x8000u : 0x8000u | (0x8000u - k)) << 16);
     };
     auto key_of = [&](const uint32_t (&kw)[4], int j) __attribute__((always_inline)) {
         if (DT == 0) return (j & 1) ? (kw[j >> 1] >> 16) : (kw[j >> 1] & 0xFFFFu);
@@ -517,7 +526,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         const float xt = Elem<DT>::to_float(x_row[t]);
         bool in_K;
         if (many_ties) {
-            const uint32_t kt = float_order_bits(xt) >> (DT == 0 ? 16 : 0);
+            const uint32_t kt = key_of_value(xt);
             in_K = kt > khi || (kt == klo && (int64_t)tb < n_tie);
         } else {
             in_K = top_composite(xt, (int32_t)t) >= cut;

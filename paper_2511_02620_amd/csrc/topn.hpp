@@ -2,7 +2,7 @@
 //
 // Candidates are pushed into an LDS buffer as 64-bit composites (order-preserving image of the float
 // key in the high word, complemented index in the low word: a larger composite is a larger key or,
-// for equal keys, a smaller index, so all composites of a row are distinct).  Only composites above the
+// for equal keys - -0 and +0 are equal -, a smaller index, so all composites of a row are distinct).  Only composites above the
 // current threshold are pushed.  A compaction finds a lower bound of the n-th largest composite with a
 // radix select over the buffer, makes it the new threshold and keeps the entries at or above it.  In the
 // stream the select stops after the top 16 bits of the key (2 passes of 8 bits: the n-th largest key at
@@ -43,9 +43,10 @@ __device__ __forceinline__ float float_from_order_bits(uint32_t o)
 {
     return __uint_as_float((o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o);
 }
+// (-0 and +0 are the same key - between them the index decides -, so -0 is read as +0: x + 0 does that)
 __device__ __forceinline__ uint64_t top_composite(float key, int32_t index)
 {
-    return ((uint64_t)float_order_bits(key) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)index);
+    return ((uint64_t)float_order_bits(key + 0.0f) << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)index);
 }
 __device__ __forceinline__ float top_key(uint64_t c) { return float_from_order_bits((uint32_t)(c >> 32)); }
 __device__ __forceinline__ int32_t top_index(uint64_t c) { return (int32_t)(0xFFFFFFFFu - (uint32_t)c); }

@@ -93,6 +93,30 @@ def test_ipt_filtered_every_row(difr, dtype, V, k, p, order):
     assert (out["flags"][honest_rows] & 1).all() and (out["dist"][honest_rows] == 0).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("k,p", [(150, 1.0), (256, 0.8), (101, 1.0)])
+def test_ipt_filtered_signed_zeros_tie_by_index(difr, dtype, k, p):
+    """-0 and +0 are the same logit: a top-k (or top-p) cut that falls among zeros of both signs takes them in index
+    order whatever their sign."""
+    N, V = 32, 4000
+    g = torch.Generator().manual_seed(19)
+    x = torch.full((N, V), -3.0)
+    for r in range(N):
+        perm = torch.randperm(V, generator=g)
+        x[r, perm[:100]] = 2.0
+        x[r, perm[100:2100]] = torch.where(torch.rand(2000, generator=g) < 0.5, torch.tensor(0.0), torch.tensor(-0.0))
+    logits = x.to(dtype).to(DEV)
+    seeds = torch.tensor([23], dtype=torch.int64).to(DEV)
+    sid = torch.zeros(N, dtype=torch.int32, device=DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    honest = difr.ipt_score_filtered(logits, 1.0, seeds, sid, pos, None, top_k=k, top_p=p, want_token=True)["ipt_token"]
+    rnd = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    claims = torch.where(torch.arange(N, device=DEV) % 2 == 0, honest, rnd)
+    st, out = _compare(difr, logits, V, 1.0, seeds, sid, pos, claims, k, p)
+    say("filtered signed zeros", dtype, k, p, st)
+    assert st["token_excused"] == 0
+
+
 def test_ipt_filtered_c2_class_rows(difr):
     wl = W.scaled(W.C2_3B, S=2, L=32, chunk_rows=64)
     ver, prov = wl.logits_chunk(0, DEV)

@@ -213,6 +213,34 @@ def test_nucleus_sampling_mode_round_trip(difr, dtype, kind):
         say("nucleus sampling", dtype, kind, p, st)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("p", [0.6, 0.3, 0.2, 0.99])
+def test_nucleus_signed_zeros_tie_by_index(difr, dtype, p):
+    """-0 and +0 are the same logit: where the cut falls among zeros of both signs, the ties enter the nucleus in
+    index order whatever their sign (p = 0.6 and 0.3; at 0.2 the cut lies above the zeros, at 0.99 below them)."""
+    N, V = 32, 4000
+    g = torch.Generator().manual_seed(17)
+    x = torch.full((N, V), -3.0)
+    for r in range(N):
+        perm = torch.randperm(V, generator=g)
+        x[r, perm[:100]] = 2.0
+        z = perm[100:2100]
+        x[r, z] = torch.where(torch.rand(2000, generator=g) < 0.5, torch.tensor(0.0), torch.tensor(-0.0))
+    logits = x.to(dtype).to(DEV)
+    assert (torch.signbit(logits) & (logits == 0)).any() and (~torch.signbit(logits) & (logits == 0)).any()
+    seeds = torch.tensor([21], dtype=torch.int64).to(DEV)
+    sid = torch.zeros(N, dtype=torch.int32, device=DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    claims = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    st, out = _compare(difr, logits, V, 1.0, seeds, sid, pos, claims, p)
+    say("nucleus signed zeros", dtype, p, st)
+    assert st["rows_in_doubt"] == 0 and st["rows"] == N
+    # and in sampling mode
+    tok = difr.ipt_score_filtered(logits, 1.0, seeds, sid, pos, None, top_k=0, top_p=p, want_token=True)["ipt_token"]
+    st, _ = _compare(difr, logits, V, 1.0, seeds, sid, pos, tok, p)
+    assert st["match_excused"] == 0 and st["token_excused"] == 0
+
+
 def test_likelihood_with_a_whole_vocabulary_nucleus(difr):
     """top_k = 0, top_p < 1 in difr_gumbel_likelihood: tau is the smallest logit of the nucleus; it must be the
     oracle's at top_p, or lie between the oracle's at top_p -/+ 2e-6; pi must then agree wherever tau does."""

@@ -87,3 +87,19 @@ def test_filtered_sampler_follows_the_renormalised_distribution():
     # an honest claim (the sampler's own token) always matches with distance 0
     r2, *_ = batch(x[:500], T, r["ipt_token"][:500].astype(np.int32), k, p, positions=np.arange(500, dtype=np.uint32))
     assert (r2["flags"] & 1).all() and (r2["dist"] == 0).all()
+
+
+def test_signed_zeros_are_equal_logits():
+    """-0 and +0 are the same logit value: between them the lower index ranks first, whatever the sign.  By hand:
+    x = (0, -0, 0, -0, 1), top-3 = {4, 0, 1}; with T = 1 the kept masses are e, 1, 1."""
+    x = np.array([[0.0, -0.0, 0.0, -0.0, 1.0]] * 4, dtype=np.float32)
+    claims = np.array([0, 1, 2, 3], np.int32)
+    out, *_ = batch(x, 1.0, claims, 3, 1.0)
+    assert (out["kept"] == 3).all()
+    Z = np.e + 2.0
+    assert np.allclose(out["cdf_lo"], [0.0, 1 / Z, 2 / Z, 2 / Z], atol=1e-12)
+    assert np.allclose(out["cdf_hi"], [1 / Z, 2 / Z, 2 / Z, 2 / Z], atol=1e-12)   # tokens 2 and 3 are outside: empty
+    # the same under a nucleus: masses (e, 1, 1, 1, 1) / (e + 4), p = 0.7 needs e + 2 of them: tokens 4, 0, 1
+    out, *_ = batch(x, 1.0, claims, 0, 0.7)
+    assert (out["kept"] == 3).all()
+    assert np.allclose(out["cdf_hi"] - out["cdf_lo"], [1 / Z, 1 / Z, 0.0, 0.0], atol=1e-12)
