@@ -209,7 +209,7 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
  *       runs the search described at difr_ipt_score_filtered first; it leaves the threshold in `tau`, which is
  *       then a required output (DIFR_ERR_UNSUPPORTED if NULL).
  * Outputs (DEVICE): pi [N] fp32; log_pi [N] fp32 or NULL (natural log, -inf if pi = 0; this is the FSSL score
- *       the paper thresholds); tau [N] fp32 or NULL; active [N, s] int32 or NULL (S in rank order, -1 padded);
+ *       the paper thresholds); tau [N] fp32 or NULL; active [N, s] int32 or NULL (S in rank order of the fp32 scores, -1 padded);
  *       flags [N] (DIFR_FLAG_INVALID_CLAIM: pi NaN; DIFR_FLAG_NONFINITE).  Which tokens are in S is decided on
  *       fp32 scores; A_i, B_i and the average are then formed in fp64 / fp32 from exact logits and fp64 noise.
  * One pass over the logits.
