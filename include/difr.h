@@ -232,7 +232,10 @@ int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p,
  * the k largest logits that fix the likelihood's threshold tau ARE the filtered distribution Token-IPT-DiFR works
  * on, so they are collected once and each row is read from HBM once instead of twice.  in->claimed are the
  * Token-DiFR claims, claimed_ipt (DEVICE [N] or NULL for sampling mode) the Token-IPT-DiFR claims; p as in
- * difr_gumbel_likelihood with 1 <= top_k <= 256 (top_k = 0: DIFR_ERR_UNSUPPORTED, use the two single calls).
+ * difr_gumbel_likelihood.  top_k = 0 with top_p < 1 (the bare nucleus) is served by the two single calls' kernels
+ * one after the other on the stream - the nucleus search, which scores Token-IPT-DiFR and leaves the threshold in
+ * tau (then required: DIFR_ERR_UNSUPPORTED if NULL), and the estimator's pass -; top_k = 0 with top_p >= 1 is no
+ * filter at all and refused (DIFR_ERR_UNSUPPORTED).
  * Outputs have the meaning, layout and optionality of the two single calls and are bit-identical to theirs;
  * flags_gumbel and flags_ipt are the two calls' `flags`; sigma_ipt, eps belong to log_mass.
  */

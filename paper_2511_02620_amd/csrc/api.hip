@@ -268,14 +268,25 @@ int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, co
     if (p->s < 0 || p->s > 256 || p->top_k < 0 || p->top_k > 256 || p->M < 1) return DIFR_ERR_ARGUMENT;
     if (!(p->sigma > 0.0f) || !isfinite(p->sigma) || !(p->top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
     if (log_mass && (!(sigma_ipt > 0.0) || !isfinite(sigma_ipt) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
-    if (p->top_k == 0) return DIFR_ERR_UNSUPPORTED;
+    // no top-k: without top-p either there is no filter at all; with it, the nucleus over the whole vocabulary
+    // is found by a kernel of its own (which scores Token-IPT-DiFR on it and leaves the threshold in the caller's
+    // tau array, then a required output) and the estimator's pass follows on the same stream
+    const bool nucleus = p->top_k == 0 && p->top_p < 1.0f;
+    if (p->top_k == 0 && (!nucleus || !tau)) return DIFR_ERR_UNSUPPORTED;
     if (b.N == 0) return DIFR_OK;
     if (!pi || !flags_gumbel || !p->z || !dist || !flags_ipt) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z, nullptr};
     const difr::LikelihoodOutputs lo{pi, log_pi, tau, active, flags_gumbel};
     const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, ipt_token, sigma_ipt, eps, log_mass, flags_ipt, nullptr};
+    if (nucleus) {
+        difr::RowBatch bi = b;
+        bi.claimed = claimed_ipt;
+        if (difr::launch_ipt_nucleus(bi, p->top_p, oi, kept, tau, (hipStream_t)hip_stream)) return DIFR_ERR_LAUNCH;
+        const difr::LikelihoodParams ln{0, p->top_p, p->s, p->sigma, p->M, p->z, tau};
+        return difr::launch_likelihood(b, ln, lo, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+    }
+    const difr::LikelihoodParams lp{p->top_k, p->top_p, p->s, p->sigma, p->M, p->z, nullptr};
     return difr::launch_score_both_filtered(b, lp, lo, claimed_ipt, oi, kept, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 

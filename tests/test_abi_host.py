@@ -157,7 +157,8 @@ def test_argument_validation_needs_no_device(lib):
     for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0), dict(top_p=0.0)):
         assert sbf(**kw) == ARG, kw
     assert sbf(lm=fake, sigma_ipt=0.0) == ARG
-    assert sbf(top_k=0) == 7                                 # DIFR_ERR_UNSUPPORTED: the shared top-k list is the point
+    assert sbf(top_k=0) == 7                                 # DIFR_ERR_UNSUPPORTED: a bare nucleus needs the tau array
+    assert sbf(top_k=0, top_p=1.0) == 7                      # ... and no filter at all is not this call
     assert sbf(pi=None) == NULL and sbf(dist=None) == NULL and sbf(fg=None) == NULL and sbf(fi=None) == NULL
     assert sbf(z=None) == NULL and sbf(rows(V=15, ld=15)) == ALIGN and sbf(rows(V=0)) == SHAPE
     assert sbf(rows(N=0), pi=None, dist=None, fg=None, fi=None, z=None) == OK

@@ -32,6 +32,8 @@ def _same(a, b, what):
     (torch.bfloat16, 296, 50, 0.95, 16, "random"),        # fewer entries than one round
     (torch.float32, 5003, 20, 0.9, 8, "ties"),            # coarse logits: many equal keys
     (torch.float32, 9004, 64, 0.95, 64, "descending"),
+    (torch.bfloat16, 20504, 0, 0.9, 16, "random"),        # the bare nucleus: its own search, then the estimator's pass
+    (torch.float32, 5003, 0, 0.6, 8, "ties"),
 ])
 def test_fused_pass_equals_the_two_calls(difr, dtype, V, k, p, s, order):
     N = 40
