@@ -1,0 +1,254 @@
+"""Randomized cross-checks on the GPU: seeded random shapes, value patterns (normal, peaked, Zipf profile, sorted either
+way, coarse values with long runs of ties, masked entries, shifted, constant, wide, signed zeros, denormals, two values),
+temperatures and claim mixes.  Every case checks the kernels against one another bit for bit (gated against plain
+Gumbel stream, the one-pass kernels against the single-estimator ones, the one-pass admissible count against the
+two-pass count, the logit rank against a plain count) and, on a few rows, against the oracle with the tolerances of
+the other parity tests (both estimators, the filtered estimator, the likelihood estimate, the bare nucleus)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def difr():
+    import paper_2511_02620_amd as m
+    m.load_library()
+    return m
+
+
+def eq(a, b, what):
+    for k in a:
+        if k in b:
+            x, y = a[k], b[k]
+            same = torch.equal(x.view(torch.int32) if x.dtype == torch.float32 else x,
+                               y.view(torch.int32) if y.dtype == torch.float32 else y)
+            if not same:
+                xn, yn = x.float(), y.float()
+                both_nan = torch.isnan(xn) & torch.isnan(yn)
+                bad = torch.nonzero(~both_nan & (xn != yn))[:5].flatten().tolist()
+                if bad:
+                    raise AssertionError("%s: %s differs at rows %s: %s vs %s" % (what, k, bad, x[bad].tolist(), y[bad].tolist()))
+
+
+def make_case(rng, big=False):
+    dtype = torch.bfloat16 if rng.random() < 0.7 else torch.float32
+    E = 8 if dtype == torch.bfloat16 else 4
+    V = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 42000)]))
+    if big:
+        V = int(rng.choice([151936, 128256, 100003, 65536 + 8 * int(rng.integers(0, 100))]))
+    ld = ((V + E - 1) // E) * E + (E * int(rng.integers(0, 3)))
+    N = int(rng.integers(1, 17 if big else 97))
+    kind = str(rng.choice(["normal", "peaked", "zipf", "asc", "desc", "coarse", "masked", "shifted_up", "shifted_down", "const", "wide", "zeros", "denorm", "two_values", "halfint"]))
+    g = torch.Generator().manual_seed(int(rng.integers(0, 2**31)))
+    x = torch.randn(N, V, generator=g) * 2.0
+    if kind == "peaked":
+        x = x * 4.0
+    elif kind == "zipf":
+        ranks = torch.argsort(torch.rand(N, V, generator=g), dim=1).float() + 1.0
+        x = -1.1 * ranks.log() + torch.randn(N, V, generator=g)
+    elif kind == "asc":
+        x = x.sort(dim=1).values
+    elif kind == "desc":
+        x = x.sort(dim=1, descending=True).values
+    elif kind == "coarse":
+        x = torch.round(x * 2) / 2
+    elif kind == "masked":
+        m = torch.rand(N, V, generator=g) < 0.6
+        x[m] = float("-inf")
+        x[:, int(rng.integers(0, V))] = 0.5   # at least one finite entry
+    elif kind == "shifted_up":
+        x = x + 40.0
+    elif kind == "shifted_down":
+        x = x - 60.0
+    elif kind == "const":
+        x = torch.full((N, V), float(rng.normal()))
+    elif kind == "wide":
+        x = x * 30.0
+    elif kind == "zeros":
+        x = torch.where(x.abs() < 1.5, torch.where(x < 0, torch.tensor(-0.0), torch.tensor(0.0)), torch.round(x))
+    elif kind == "denorm":
+        x = x * 1e-39
+    elif kind == "two_values":
+        x = torch.where(x < 0.3, torch.tensor(-1.5), torch.tensor(1.25))
+    elif kind == "halfint":
+        x = torch.round(x) / 2
+    logits = torch.full((N, ld), float("nan"), dtype=dtype)
+    logits[:, :V] = x.to(dtype)
+    logits = logits.to(DEV)
+    S = int(rng.integers(1, 5))
+    seeds = torch.from_numpy(rng.integers(-2**63, 2**63 - 1, size=S, dtype=np.int64)).to(DEV)
+    sid = torch.from_numpy(rng.integers(0, S, size=N).astype(np.int32)).to(DEV)
+    pos = torch.from_numpy(rng.integers(0, 2**31 - 1, size=N).astype(np.int32)).to(DEV)
+    T = float(rng.choice([1.0, 0.6, 0.8, 1.3, 0.25, 0.05, 5.0]))
+    temps = None
+    if rng.random() < 0.2:
+        temps = torch.from_numpy(rng.uniform(0.3, 1.5, size=N).astype(np.float32)).to(DEV)
+    ck = str(rng.choice(["honest", "random", "none", "mixed"]))
+    return dict(dtype=dtype, V=V, ld=ld, N=N, kind=kind, logits=logits, seeds=seeds, sid=sid, pos=pos, T=T, temps=temps, ck=ck)
+
+
+def claims_for(difr, c, rng):
+    N, V = c["N"], c["V"]
+    a = (c["logits"], c["T"], c["seeds"], c["sid"], c["pos"])
+    kw = dict(temperatures=c["temps"], V=V)
+    if c["ck"] == "none":
+        return None, None
+    hg = difr.gumbel_score(*a, None, want_scores=False, **kw)["argmax"]
+    hi = difr.ipt_score(*a, None, want_token=True, want_interval=False, **kw)["ipt_token"]
+    hi = torch.where(hi < 0, torch.zeros_like(hi), hi)
+    if c["ck"] == "honest":
+        return hg, hi
+    rnd = torch.from_numpy(rng.integers(-1, V + 1, size=N).astype(np.int32)).to(DEV)
+    if c["ck"] == "random":
+        return rnd, rnd.clone()
+    pick = torch.from_numpy(rng.random(N) < 0.5).to(DEV)
+    return torch.where(pick, hg, rnd), torch.where(pick, hi, rnd)
+
+
+def run_case(difr, c, rng):
+    N, V = c["N"], c["V"]
+    a = (c["logits"], c["T"], c["seeds"], c["sid"], c["pos"])
+    kw = dict(temperatures=c["temps"], V=V)
+    cg, ci = claims_for(difr, c, rng)
+    g1 = difr.gumbel_score(*a, cg, want_rank=True, **kw)
+    g0 = difr.gumbel_score(*a, cg, unfiltered=True, want_rank=True, **kw)
+    eq(g1, g0, "filtered vs unfiltered gumbel")
+    i1 = difr.ipt_score(*a, ci, want_rank=True, **kw)
+    bg, bi = difr.score_both(*a, cg, ci, want_rank=True, **kw)
+    eq(bg, g1, "score_both gumbel side")
+    eq(bi, {k: v for k, v in i1.items() if k != "logit_rank"}, "score_both ipt side")
+    bg2, bi2 = difr.score_both(*a, cg, ci, **kw)
+    eq(bg2, g1, "score_both (no rank) gumbel side")
+    eq(bi2, bi, "score_both (no rank) ipt side")
+    # logit rank against a plain count
+    if cg is not None:
+        xf = c["logits"][:, :V].float()
+        ok = (cg >= 0) & (cg < V)
+        xt = xf.gather(1, cg.clamp(0, V - 1).long().unsqueeze(1))
+        ref_rank = torch.where(ok, (xf > xt).sum(dim=1).to(torch.int32), torch.full_like(cg, -1))
+        nanrow = torch.isnan(xt.squeeze(1))
+        if not torch.equal(g1["logit_rank"][~nanrow], ref_rank[~nanrow]):
+            raise AssertionError("logit rank differs from the plain count")
+    # admissible set
+    delta = float(rng.choice([0.0, 0.5, 2.5, 6.0]))
+    ag, ai, aa = difr.score_both_admissible(*a, delta, cg, ci, **kw)
+    eq(ag, g1, "admissible gumbel side")
+    eq(ai, bi, "admissible ipt side")
+    two = difr.admissible_count(*a, g1["max_score"], delta, **kw)
+    det = aa["count"] >= 0
+    if not torch.equal(aa["count"][det], two["count"][det]):
+        raise AssertionError("one-pass admissible count differs from the two-pass count")
+    # filtered pair
+    k = int(rng.choice([1, 7, 50, 64, 65, 200, 256]))
+    p = float(rng.choice([1.0, 0.95, 0.9, 0.5, 1e-4, 0.999]))
+    s = int(rng.choice([1, 4, 16, 64, 100, 256]))
+    z = torch.randn(int(rng.choice([1, 32, 256])), generator=torch.Generator().manual_seed(int(rng.integers(0, 2**31)))).to(DEV)
+    f1 = difr.ipt_score_filtered(*a, ci, top_k=k, top_p=p, want_token=True, want_log_mass=True, sigma=0.02, **kw)
+    if cg is not None:
+        l1 = difr.gumbel_likelihood(*a, cg, z, top_k=k, top_p=p, s=s, sigma=0.4, **kw)
+        bl, bf = difr.score_both_filtered(*a, cg, ci, z, top_k=k, top_p=p, s=s, sigma=0.4, want_token=True, want_log_mass=True,
+                                          sigma_ipt=0.02, **kw)
+        eq(bl, l1, "score_both_filtered likelihood side")
+        eq(bf, f1, "score_both_filtered ipt side")
+    torch.cuda.synchronize()
+    # oracle spot checks on a few rows (C oracle, V entries per row)
+    rows = rng.choice(N, size=min(N, 6), replace=False)
+    rows.sort()
+    idx = torch.from_numpy(rows).to(DEV)
+    host = parity.to_host_logits(c["logits"][idx])
+    tnp = None if c["temps"] is None else c["temps"][idx].cpu().numpy()
+    sd, sidn, posn = parity.seeds_u64(c["seeds"]), c["sid"][idx].cpu().numpy(), parity.positions_u32(c["pos"][idx])
+    ref = oracle.ipt_filtered_score(host, V, np.float32(c["T"]), sd, sidn, posn, None if ci is None else ci[idx].cpu().numpy(),
+                                    k, float(np.float32(p)), temperatures=tnp, sigma=0.02)
+    keptg = f1["kept"][idx].cpu().numpy()
+    flg = f1["flags"][idx].cpu().numpy()
+    good = (flg & 4) == 0
+    sure = np.abs(ref["gap_p"]) > 1e-6 if "gap_p" in ref else np.ones(len(rows), bool)
+    chk = good & sure
+    if not np.array_equal(keptg[chk], ref["kept"][chk]):
+        raise AssertionError("filtered kept differs from the oracle: %s vs %s" % (keptg, ref["kept"]))
+    for name in ("cdf_lo", "cdf_hi", "dist"):
+        gv, rv = f1[name][idx].cpu().numpy().astype(np.float64)[chk], ref[name][chk]
+        both_nan = np.isnan(gv) & np.isnan(rv)
+        if not (both_nan | (np.abs(gv - rv) <= 1e-4)).all():
+            raise AssertionError("filtered %s differs from the oracle: %s vs %s" % (name, gv, rv))
+    if cg is not None and k > 0:
+        sub = (c["logits"][idx].contiguous(), c["T"], c["seeds"], c["sid"][idx].contiguous(), c["pos"][idx].contiguous())
+        tsub = None if c["temps"] is None else c["temps"][idx].contiguous()
+        lo_ = difr.gumbel_likelihood(*sub, cg[idx].contiguous(), z, top_k=k, top_p=p, s=s, sigma=0.4, temperatures=tsub, V=V, want_active=True)
+        torch.cuda.synchronize()
+        rl = oracle.likelihood(host, V, np.float32(c["T"]), sd, sidn, posn, cg[idx].cpu().numpy(), k, float(np.float32(p)), s,
+                               float(np.float32(0.4)), z.double().cpu().numpy(), temperatures=tnp)
+        pi = lo_["pi"].cpu().numpy().astype(np.float64)
+        fl_ = lo_["flags"].cpu().numpy()
+        # membership of S is decided on fp32 scores: a gap to the best token left out that fp32 cannot resolve at the
+        # scores' magnitude (|x| / T + 17 at most) leaves the last member open
+        finite = np.abs(host[np.isfinite(host)])
+        ymax = (float(finite.max()) if finite.size else 0.0) / (float(c["T"]) if tnp is None else float(tnp.min())) + 17.0
+        gap_ok = rl["gap_s"] > max(1e-5, 4.0 * float(np.spacing(np.float32(ymax))))
+        clear = ((fl_ & 4) == 0) & (rl["gap_p"] > 1e-6) & gap_ok
+        tau_g = lo_["tau"].cpu().numpy()
+        if not np.array_equal(tau_g[clear], rl["tau"].astype(np.float32)[clear]):
+            raise AssertionError("likelihood tau differs: %s vs %s" % (tau_g, rl["tau"]))
+        act = lo_["active"].cpu().numpy()
+        if not np.array_equal(np.sort(act[clear], axis=1), np.sort(rl["active"][clear], axis=1)):
+            raise AssertionError("likelihood active set differs on rows %s" % rows[clear][(np.sort(act[clear], axis=1) != np.sort(rl["active"][clear], axis=1)).any(axis=1)])
+        both_nan = np.isnan(pi) & np.isnan(rl["pi"])
+        err = np.where(both_nan | ~clear, 0.0, np.abs(pi - rl["pi"]))
+        if not (err <= 1e-4).all():
+            raise AssertionError("likelihood pi differs: worst %g gpu %s oracle %s" % (err.max(), pi, rl["pi"]))
+    refg = oracle.gumbel_score(host, V, np.float32(c["T"]), sd, sidn, posn, None if cg is None else cg[idx].cpu().numpy(),
+                               temperatures=tnp)
+    if np.nanmax(np.abs(refg["max_score"])) < 250.0:  # (fp32 scores: half an ulp is 1.5e-5 at 250, 6e-5 at 1000)
+        parity.compare_gumbel({k2: v[idx] for k2, v in g1.items() if k2 != "logit_rank"}, refg)
+    refi = oracle.ipt_score(host, V, np.float32(c["T"]), sd, sidn, posn, None if ci is None else ci[idx].cpu().numpy(),
+                            temperatures=tnp)
+    parity.compare_ipt({k2: v[idx] for k2, v in i1.items() if k2 != "logit_rank"}, refi)
+    # bare nucleus: kept inside the oracle's bracket
+    if p < 1.0:
+        n1 = difr.ipt_score_filtered(*a, ci, top_k=0, top_p=p, want_token=True, **kw)
+        torch.cuda.synchronize()
+        p32 = float(np.float32(p))
+        ci_np = None if ci is None else ci[idx].cpu().numpy()
+        lo = oracle.ipt_filtered_score(host, V, np.float32(c["T"]), sd, sidn, posn, ci_np, 0, p32 - 2e-6, temperatures=tnp)
+        hi = oracle.ipt_filtered_score(host, V, np.float32(c["T"]), sd, sidn, posn, ci_np, 0, p32 + 2e-6, temperatures=tnp)
+        kn = n1["kept"][idx].cpu().numpy()
+        fn = n1["flags"][idx].cpu().numpy()
+        goodn = (fn & 4) == 0
+        if not ((kn[goodn] >= lo["kept"][goodn]) & (kn[goodn] <= hi["kept"][goodn])).all():
+            raise AssertionError("nucleus kept outside the oracle's bracket: %s [%s, %s]" % (kn, lo["kept"], hi["kept"]))
+        surek = goodn & (lo["kept"] == hi["kept"])
+        for name in ("cdf_lo", "cdf_hi", "dist"):
+            gv, rv = n1[name][idx].cpu().numpy().astype(np.float64)[surek], lo[name][surek]
+            both_nan = np.isnan(gv) & np.isnan(rv)
+            if not (both_nan | (np.abs(gv - rv) <= 1e-4)).all():
+                raise AssertionError("nucleus %s differs from the oracle: p=%r rows %s claims %s gpu %s ref %s kept %s flags %s temps %s" % (
+                    name, p, rows[surek], None if ci_np is None else ci_np[surek], gv, rv, kn[surek], fn[surek], None if tnp is None else tnp[surek]))
+    return dict(k=k, p=p, s=s, delta=delta, M=int(z.shape[0]))
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_case(difr, case):
+    rng = np.random.default_rng(1000 + case)
+    c = make_case(rng)
+    print("case", case, c["dtype"], "V", c["V"], "ld", c["ld"], "N", c["N"], c["kind"], "T", c["T"], "claims", c["ck"],
+          file=sys.stderr, flush=True)
+    run_case(difr, c, rng)
+
+
+@pytest.mark.parametrize("case", range(4))
+def test_random_case_full_width(difr, case):
+    """The same on vocabularies of the paper's model families (tens of stream rounds per row)."""
+    rng = np.random.default_rng(300000 + case)
+    c = make_case(rng, big=True)
+    print("case", case, c["dtype"], "V", c["V"], "ld", c["ld"], "N", c["N"], c["kind"], "T", c["T"], "claims", c["ck"],
+          file=sys.stderr, flush=True)
+    run_case(difr, c, rng)
