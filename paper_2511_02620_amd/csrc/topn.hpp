@@ -25,7 +25,7 @@
 namespace difr {
 
 constexpr int kTopEpoch = 8;       // stream rounds per epoch (measured: 4 and 16 are both slower)
-constexpr int kTopFresh = 16;      // a compaction is due after max(n, kTopFresh) pushes
+constexpr int kTopFresh = 16;      // a compaction is due after max(n, kTopFresh) pushes (measured: 8 to 64 within 1%)
 constexpr int kTopTrigger = 512;   // a compaction is due at the latest when this many slots are used
 constexpr int kTopCapSmall = kTopTrigger + 64 * 8;   // slots per buffer: the trigger plus one round of one wave
 constexpr int kTopCapBig = kTopTrigger + 256 * 8;    // ... of the whole workgroup
