@@ -161,13 +161,14 @@ int difr_ipt_score(const difr_rows *in, float *dist, float *cdf_lo, float *cdf_h
  * two calls' `flags`.  logit_rank [N] int32 or NULL is the logit rank of the Token-DiFR claim
  * in->claimed as in difr_gumbel_score (counted in the same pass, only when asked for: it costs a few
  * per cent), so that one read of the logits feeds the score-and-rank classifier of difr_classify
- * [Sec. 7.1].  The optional honest-token and log-mass outputs of difr_ipt_score are not offered
- * here.  [Sec. 6.2 and Sec. 6.3 together: a verifier that does not know which sampler the server
+ * [Sec. 7.1].  ipt_token, sigma, eps and log_mass are difr_ipt_score's (the sampler's own token costs its second,
+ * early-exit pass on the rows whose claim does not match; log_mass is the paper's Token-IPT-DiFR score).  [Sec. 6.2 and Sec. 6.3 together: a verifier that does not know which sampler the server
  * ran, or that feeds both scores to one classifier.]
  */
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
-                    float *cdf_hi, float *u, uint8_t *flags_ipt, void *hip_stream);
+                    float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass,
+                    uint8_t *flags_ipt, void *hip_stream);
 
 /*
  * Token-IPT-DiFR on the distribution a filtering sampler used.  [Sec. 3.2: the IPT sampler applied under the

@@ -96,7 +96,7 @@ def load_library():
     lib.difr_debug_gumbel_score_unfiltered.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, vp, vp]
     lib.difr_debug_gumbel_score_unfiltered.restype = C.c_int
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
-    lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 13
+    lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12 + [C.c_double, C.c_double, vp, vp, vp]
     lib.difr_score_both.restype = C.c_int
     lib.difr_score_both_admissible.argtypes = [C.POINTER(_Rows), vp, C.c_float] + [vp] * 13
     lib.difr_score_both_admissible.restype = C.c_int
@@ -249,9 +249,10 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
 
 
 def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-               temperatures=None, V=None, want_rank=False):
+               temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30):
     """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
-    want_rank adds logit_rank (of the Token-DiFR claim) to the first."""
+    want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_token / want_log_mass add ipt_token /
+    log_mass to the second (as in :func:`ipt_score`)."""
     lib = load_library()
     r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
     _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
@@ -263,12 +264,16 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
              u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
     if want_rank:
         g["logit_rank"] = torch.empty(N, dtype=torch.int32, device=dev)
+    if want_token:
+        i["ipt_token"] = torch.empty(N, dtype=torch.int32, device=dev)
+    if want_log_mass:
+        i["log_mass"] = torch.empty(N, **f32)
     with torch.cuda.device(dev):
         rc = lib.difr_score_both(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
                                  _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]),
                                  _ptr(g.get("logit_rank")), _ptr(i["dist"]),
-                                 _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]),
-                                 _stream_ptr(dev))
+                                 _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i.get("ipt_token")),
+                                 float(sigma), float(eps), _ptr(i.get("log_mass")), _ptr(i["flags"]), _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_score_both")
     return g, i

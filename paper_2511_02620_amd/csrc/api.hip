@@ -292,19 +292,21 @@ int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, co
 
 int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
                     float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
-                    float *cdf_hi, float *u, uint8_t *flags_ipt, void *hip_stream)
+                    float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass,
+                    uint8_t *flags_ipt, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
     int rc = validate_rows(in, &b, &aligned);
     if (rc != DIFR_OK) return rc;
+    if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt) return DIFR_ERR_NULL;
     if ((rc = check_device()) != DIFR_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
     if (aligned) {
         const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
-        const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+        const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, nullptr};
         return difr::launch_score_both(b, claimed_ipt, og, oi, stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
     }
     // rows that are not 16-byte aligned: the two generic kernels, one after the other
@@ -312,7 +314,7 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
         return DIFR_ERR_LAUNCH;
     difr::RowBatch bi = b;
     bi.claimed = claimed_ipt;
-    return difr::launch_ipt_score(bi, false, dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr,
+    return difr::launch_ipt_score(bi, false, dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, nullptr,
                                   stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;

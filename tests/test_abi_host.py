@@ -82,11 +82,14 @@ def test_argument_validation_needs_no_device(lib):
     def i(r, dist=fake, flags=fake, sigma=0.01, eps=1e-30, log_mass=None):
         return lib.difr_ipt_score(C.byref(r), dist, None, None, None, None, sigma, eps, log_mass, flags, None, None)
 
-    def both(r, margin=fake, argmax=fake, fg=fake, dist=fake, fi=fake):
-        return lib.difr_score_both(C.byref(r), fake, margin, argmax, None, None, fg, None, dist, None, None, None, fi, None)
+    def both(r, margin=fake, argmax=fake, fg=fake, dist=fake, fi=fake, sigma=0.01, lm=None):
+        return lib.difr_score_both(C.byref(r), fake, margin, argmax, None, None, fg, None, dist, None, None, None, None,
+                                   sigma, 1e-30, lm, fi, None)
 
     assert lib.difr_gumbel_score(None, fake, fake, None, None, fake, None, None) == NULL
-    assert lib.difr_score_both(None, fake, fake, fake, None, None, fake, None, fake, None, None, None, fake, None) == NULL
+    assert lib.difr_score_both(None, fake, fake, fake, None, None, fake, None, fake, None, None, None, None, 0.01, 1e-30,
+                               None, fake, None) == NULL
+    assert both(rows(), sigma=0.0, lm=fake) == ARG and both(rows(), sigma=float("nan"), lm=fake) == ARG
     for bad, want in ((rows(N=-1), SHAPE), (rows(V=0), SHAPE), (rows(ld=15), SHAPE), (rows(S=0), SHAPE),
                       (rows(N=1 << 31), SHAPE), (rows(V=1 << 31, ld=1 << 31), SHAPE), (rows(dtype=2), DTYPE),
                       (rows(temperature=0.0), TEMP), (rows(temperature=-1.0), TEMP),

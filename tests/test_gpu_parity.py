@@ -448,6 +448,14 @@ def test_score_both_equals_the_two_single_calls(difr, dtype, V, ld, offset, case
     assert "logit_rank" in ra
     _same_outputs(ra, {k: ar[k] for k in ra})
     _same_outputs(rb, {k: b[k] for k in rb})
+    # and with the sampler's own token and the Gaussian log-mass of the Token-IPT-DiFR side
+    bt = difr.ipt_score(logits, T, seeds, sid, pos, ci, V=V, temperatures=temps, want_token=True, want_log_mass=True, sigma=0.05)
+    ta, tb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps, want_token=True, want_log_mass=True,
+                             sigma=0.05)
+    torch.cuda.synchronize()
+    assert "ipt_token" in tb and "log_mass" in tb
+    _same_outputs(ta, {k: a[k] for k in ta})
+    _same_outputs(tb, {k: bt[k] for k in tb})
     if case == "honest":
         assert (fa["flags"] & 1).all()
         assert int((fb["flags"] & 1).sum()) >= N - 2     # u within rounding of an interval end may fall either way
