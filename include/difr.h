@@ -171,6 +171,20 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                     uint8_t *flags_ipt, void *hip_stream);
 
 /*
+ * difr_score_both for rows the caller knows to be concentrated (a confident model: most of a row's logits lie more
+ * than 24 ln 2 = 16.6 score units below its best perturbed score).  Same arguments, same results bit for bit.  The
+ * kernel tests each wave's 512 logits before it regenerates their noise and skips the noise where none of them can
+ * reach the running maximum whatever its Gumbel variate [Sec. 6.3: the variates are bounded once the uniforms are
+ * quantised]; on such rows the pass approaches the speed of reading them (a quarter to 40% faster when the logits fall
+ * off as -3 ln rank or steeper), on flat rows (where the test never fires) it is 1-2% slower than difr_score_both.  With logit_rank != NULL, and for rows that are not 16-byte
+ * aligned, it is difr_score_both.
+ */
+int difr_score_both_peaked(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax,
+                           float *max_score, float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist,
+                           float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps,
+                           float *log_mass, uint8_t *flags_ipt, void *hip_stream);
+
+/*
  * Token-IPT-DiFR on the distribution a filtering sampler used.  [Sec. 3.2: the IPT sampler applied under the
  * generation policy's top-k / top-p filter; Sec. 6.2 and the appendix "convolved Gaussian score", whose input p is
  * the probabilities the sampler actually used.]  The kept set K is a prefix of the tokens ranked by logit (ties to

@@ -73,7 +73,7 @@ class _LikelihoodParams(C.Structure):
                 ("M", C.c_int32), ("z", C.c_void_p)]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_score_both_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_peaked", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_score_both_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -98,6 +98,8 @@ def load_library():
     lib.difr_ipt_score.argtypes = [C.POINTER(_Rows), vp, vp, vp, vp, vp, C.c_double, C.c_double, vp, vp, vp, vp]
     lib.difr_score_both.argtypes = [C.POINTER(_Rows)] + [vp] * 12 + [C.c_double, C.c_double, vp, vp, vp]
     lib.difr_score_both.restype = C.c_int
+    lib.difr_score_both_peaked.argtypes = lib.difr_score_both.argtypes
+    lib.difr_score_both_peaked.restype = C.c_int
     lib.difr_score_both_admissible.argtypes = [C.POINTER(_Rows), vp, C.c_float] + [vp] * 13
     lib.difr_score_both_admissible.restype = C.c_int
     lib.difr_ipt_score_filtered.argtypes = [C.POINTER(_Rows), C.c_int32, C.c_float, vp, vp, vp, vp, vp, C.c_double,
@@ -249,8 +251,9 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
 
 
 def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-               temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30):
-    """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
+               temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30,
+               peaked=False):
+    """difr_score_both (peaked=True: difr_score_both_peaked, the variant for concentrated rows): both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
     want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_token / want_log_mass add ipt_token /
     log_mass to the second (as in :func:`ipt_score`)."""
     lib = load_library()
@@ -269,7 +272,8 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if want_log_mass:
         i["log_mass"] = torch.empty(N, **f32)
     with torch.cuda.device(dev):
-        rc = lib.difr_score_both(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
+        entry = lib.difr_score_both_peaked if peaked else lib.difr_score_both
+        rc = entry(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
                                  _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]),
                                  _ptr(g.get("logit_rank")), _ptr(i["dist"]),
                                  _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i.get("ipt_token")),

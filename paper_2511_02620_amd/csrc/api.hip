@@ -290,10 +290,10 @@ int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, co
     return difr::launch_score_both_filtered(b, lp, lo, claimed_ipt, oi, kept, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 
-int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
-                    float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
-                    float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass,
-                    uint8_t *flags_ipt, void *hip_stream)
+static int score_both_any(bool peaked, const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax,
+                          float *max_score, float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist,
+                          float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps,
+                          float *log_mass, uint8_t *flags_ipt, void *hip_stream)
 {
     difr::RowBatch b;
     bool aligned = false;
@@ -307,7 +307,7 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
     if (aligned) {
         const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
         const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, nullptr};
-        return difr::launch_score_both(b, claimed_ipt, og, oi, stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+        return difr::launch_score_both(b, claimed_ipt, og, oi, peaked, stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
     }
     // rows that are not 16-byte aligned: the two generic kernels, one after the other
     if (difr::launch_gumbel_score(b, false, true, margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank, stream))
@@ -318,6 +318,24 @@ int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *marg
                                   stream)
                ? DIFR_ERR_LAUNCH
                : DIFR_OK;
+}
+
+int difr_score_both(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax, float *max_score,
+                    float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
+                    float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass,
+                    uint8_t *flags_ipt, void *hip_stream)
+{
+    return score_both_any(false, in, claimed_ipt, margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank, dist,
+                          cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, hip_stream);
+}
+
+int difr_score_both_peaked(const difr_rows *in, const int32_t *claimed_ipt, float *margin, int32_t *argmax,
+                           float *max_score, float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist,
+                           float *cdf_lo, float *cdf_hi, float *u, int32_t *ipt_token, double sigma, double eps,
+                           float *log_mass, uint8_t *flags_ipt, void *hip_stream)
+{
+    return score_both_any(true, in, claimed_ipt, margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank, dist,
+                          cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, hip_stream);
 }
 
 int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, float delta, float *margin,

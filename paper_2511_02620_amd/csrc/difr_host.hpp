@@ -24,7 +24,7 @@ struct IptOutputs;
 // Both estimators in one pass (aligned rows only).
 int launch_ipt_nucleus(const RowBatch &b, float top_p, const IptOutputs &o, int32_t *kept, float *tau, hipStream_t stream);
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
-                      hipStream_t stream);
+                      bool peaked, hipStream_t stream);
 int launch_score_both_admissible(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og,
                                  const IptOutputs &oi, float delta, int32_t *count, float *log2_count, hipStream_t stream);
 // Token-DiFR likelihood estimate (aligned rows only).

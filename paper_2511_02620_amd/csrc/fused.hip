@@ -22,7 +22,7 @@ struct AdmissibleOutputs {
 
 // With the rank count the body needs 97 registers, one too many for five waves per SIMD; asked for five it fits in 96
 // without spills and runs 5% faster.  The other variants ask for one wave, which is no constraint.
-template <int DT, bool ADM, bool RANK>
+template <int DT, bool ADM, bool RANK, bool PEAKED = false>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RANK ? 5 : 1))) void score_both_kernel(
     RowBatch b, const int32_t *__restrict__ claimed_ipt, GumbelOutputs og, IptOutputs oi, AdmissibleOutputs oa)
 {
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RANK ? 5
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
     const int64_t V = b.V;
 
-    GumbelStream<DT, RANK, false, false, ADM> g(ri, x_row, V, lds_L);
+    GumbelStream<DT, RANK, false, false, ADM, PEAKED> g(ri, x_row, V, lds_L);
     IptStream<DT> s(ri_ipt, x_row, V, false);
     __syncthreads();
     if (ADM) {
@@ -137,11 +137,18 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RANK ? 5
 }
 
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,
-                      hipStream_t stream)
+                      bool peaked, hipStream_t stream)
 {
     const dim3 grid((unsigned)b.N), block(kBlock);
     const AdmissibleOutputs none{0.0f, nullptr, nullptr};
     const bool rank = og.logit_rank != nullptr;  // counted in the same stream, only when asked for
+    if (peaked && !rank) {  // (with the rank count every round is looked at anyway: the ordinary kernel)
+        if (b.dtype == 0)
+            score_both_kernel<0, false, false, true><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, none);
+        else
+            score_both_kernel<1, false, false, true><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, none);
+        return hipGetLastError() == hipSuccess ? 0 : 1;
+    }
     if (b.dtype == 0) {
         if (rank)
             score_both_kernel<0, false, true><<<grid, block, 0, stream>>>(b, claimed_ipt, og, oi, none);

@@ -37,6 +37,8 @@ constexpr uint32_t kGateLo = 0xFFFFFFFFu << (32 - kGateLoBits);  // r >= kGateLo
 constexpr uint32_t kGateHi = 0xFFFFFFFFu << (32 - kGateHiBits);  // r >= kGateHi: top 13 bits are ones
 // sup of g over r < gate, -ln(-ln(1 - (2^(24-bits)+1) 2^-24)), rounded up: 8 bits 5.543206, 13 bits 9.010365
 constexpr float kGumbelLo = 5.5433f, kGumbelHi = 9.0104f;
+// sup of g over all words: -ln(-ln(1 - 2^-24)) = 24 ln 2 - O(2^-25), rounded up (PEAKED streams, see GumbelStream)
+constexpr float kGumbelMax = 16.6356f;
 
 typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 typedef int16_t i16x2 __attribute__((ext_vector_type(2)));
@@ -142,10 +144,17 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 // L <= max y at all times, nothing within delta of the maximum is ever skipped or dropped.  A wave prunes
 // its own list against its current L - delta whenever it is half full (wave-synchronous, no barrier); if
 // pruning cannot get it below half, the row is reported as undetermined (count -1) rather than risk a miss.
+//
+// PEAKED: one more test, in FRONT of the noise generation: no noise word lifts an entry by more than g_max, so a
+// wave none of whose logits reaches T (L - g_max) skips the round without running Philox at all.  On rows much more
+// concentrated than a Zipf profile (a confident model's) most rounds go that way and the stream runs at the speed
+// of reading them; on flat rows the test never fires and costs a few per cent (the noise generation can no longer
+// start before the vector has arrived), which is why it is a variant the caller asks for.  Same outputs, bit for bit.
 constexpr int kAdmCap = 1024;  // list entries per wave
 
-template <int DT, bool RANK, bool COUNT = false, bool TOPN = false, bool ADM = false>
+template <int DT, bool RANK, bool COUNT = false, bool TOPN = false, bool ADM = false, bool PEAKED = false>
 struct GumbelStream {
+    static_assert(!PEAKED || (!COUNT && !TOPN && !ADM), "the early test is kept up to date for the plain argmax stream only");
     typedef typename Elem<DT>::type elt_t;
     static constexpr int E = Elem<DT>::kPerVec;
 
@@ -175,7 +184,11 @@ struct GumbelStream {
     float *adm_list;    // this wave's kAdmCap floats in LDS
     int32_t *adm_fill;  // this wave's fill counter in LDS
     uint32_t adm_over;  // the list could not be kept below half: the count is not to be trusted
-    // TOPN mode
+    // PEAKED streams: T (L - g_max - slack), no entry below it can reach L whatever its noise; its bf16 pattern;
+    // whether it is <= 0 (always so in gate modes 0 and 2).  Follows the gate: peak_cap() after every change of it.
+    float xcap_max;
+    uint32_t cap16_max;
+    bool max_neg;
 
     // Computes the claimed token's score with the same function the stream uses (the first lower
     // bound) and publishes it.  The caller must __syncthreads() before the first process().
@@ -213,6 +226,18 @@ struct GumbelStream {
         adm_list = nullptr;
         adm_fill = nullptr;
         adm_over = 0;
+        if (PEAKED) peak_cap();
+    }
+
+    __device__ __forceinline__ void peak_cap()
+    {
+        const float Lr = gate.L - adm_delta;
+        const float slack = 0.01f + 1e-5f * fabsf(Lr);
+        float mx = (Lr - kGumbelMax - slack) * T;
+        if (!(mx == mx)) mx = -__builtin_inff();
+        xcap_max = mx;
+        max_neg = !(mx > 0.0f);
+        cap16_max = cap_bits(mx, max_neg);
     }
 
     // ADM mode: lists = kWaves * kAdmCap floats, fills = kWaves counters, both in LDS.  Call after the
@@ -358,6 +383,29 @@ struct GumbelStream {
     template <int MODE>
     __device__ __forceinline__ void process(u32x4 q, int round, bool active, TopN *top = nullptr)
     {
+        if (PEAKED) {
+            bool reach;
+            if (DT == 0) {
+                if (MODE == 1 && !max_neg) {
+                    i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                    reach = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)cap16_max;
+                } else {
+                    u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                    reach = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)cap16_max;
+                }
+            } else {
+                reach = !(__uint_as_float(q.x) < xcap_max) || !(__uint_as_float(q.y) < xcap_max) ||
+                        !(__uint_as_float(q.z) < xcap_max) || !(__uint_as_float(q.w) < xcap_max);
+            }
+            if (__builtin_amdgcn_ballot_w64(active && reach) == 0ull) {
+                if (RANK) count_above(q, active);
+                return;
+            }
+        }
         const uint64_t round_prod = (uint64_t)kPhiloxM0 * (uint32_t)(round * kBlock * (E / 4));
         const uint64_t p0 = round_prod + lane_prod;
         uint32_t r[E];
@@ -418,6 +466,7 @@ struct GumbelStream {
                 float L = fmaxf(wave_max(best_y), gate.L);
                 L = fmaxf(fmaxf(L, lds_L[0]), fmaxf(lds_L[1], fmaxf(lds_L[2], lds_L[3])));
                 gate = make_gate(L, T, ADM ? adm_delta : 0.0f);
+                if (PEAKED) peak_cap();
                 if ((tid & 63) == 0) lds_L[wave] = gate.L;
             }
             if (ADM) adm_prune();
@@ -439,7 +488,10 @@ struct GumbelStream {
     __device__ __forceinline__ void pickup()
     {
         const float L = fmaxf(fmaxf(lds_L[0], lds_L[1]), fmaxf(lds_L[2], lds_L[3]));
-        if (L > gate.L) gate = make_gate(L, T, ADM ? adm_delta : 0.0f);
+        if (L > gate.L) {
+            gate = make_gate(L, T, ADM ? adm_delta : 0.0f);
+            if (PEAKED) peak_cap();
+        }
     }
 
     // the ragged tail: V % E entries, one lane each, evaluated exactly

@@ -448,6 +448,11 @@ def test_score_both_equals_the_two_single_calls(difr, dtype, V, ld, offset, case
     assert "logit_rank" in ra
     _same_outputs(ra, {k: ar[k] for k in ra})
     _same_outputs(rb, {k: b[k] for k in rb})
+    # the variant for concentrated rows (a test in front of the noise generation): the same, bit for bit
+    pa, pb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps, peaked=True)
+    torch.cuda.synchronize()
+    _same_outputs(pa, {k: a[k] for k in pa})
+    _same_outputs(pb, {k: b[k] for k in pb})
     # and with the sampler's own token and the Gaussian log-mass of the Token-IPT-DiFR side
     bt = difr.ipt_score(logits, T, seeds, sid, pos, ci, V=V, temperatures=temps, want_token=True, want_log_mass=True, sigma=0.05)
     ta, tb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps, want_token=True, want_log_mass=True,
@@ -512,3 +517,30 @@ def test_logit_rank_and_classifier(difr, dtype, V, ld, offset):
     got = difr.classify(a["margin"], a["logit_rank"], float(tau), 8, V, adm)
     ref = oracle.classify(og["margin"], want, tau, 8, V, adm.cpu().numpy().astype(np.float64))
     assert np.allclose(got["bits"].cpu().numpy(), ref["bits"], atol=1e-6)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("slope,shift", [(3.0, 0.0), (6.0, 30.0), (3.0, -50.0), (0.5, 0.0)])
+def test_score_both_peaked_on_concentrated_rows(difr, dtype, slope, shift):
+    """difr_score_both_peaked on the rows it is meant for (logits falling off as -slope ln rank: most wave-rounds are
+    skipped before their noise is generated), shifted up and down (the test's cap on either side of zero), and on
+    flat rows: bit-identical to difr_score_both, claims honest, random and absent."""
+    N, V = 48, 20504
+    g = torch.Generator().manual_seed(int(slope * 10) + int(shift) + 200)
+    ranks = torch.argsort(torch.rand(N, V, generator=g), dim=1).float() + 1.0
+    x = -slope * ranks.log() + torch.randn(N, V, generator=g) + shift
+    E = 8 if dtype == torch.bfloat16 else 4
+    logits = x.to(dtype).to(DEV)
+    assert V % E == 0
+    seeds = torch.tensor([77, -3], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    for T in (1.0, 0.3):
+        honest = difr.gumbel_score(logits, T, seeds, sid, pos, None, want_scores=False)["argmax"]
+        rnd = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+        for cg in (honest, rnd, None):
+            a, b = difr.score_both(logits, T, seeds, sid, pos, cg, cg, want_token=True)
+            pa, pb = difr.score_both(logits, T, seeds, sid, pos, cg, cg, want_token=True, peaked=True)
+            torch.cuda.synchronize()
+            _same_outputs(pa, a)
+            _same_outputs(pb, b)
