@@ -69,7 +69,9 @@ typedef enum {
     DIFR_ERR_ALIGN = 5,       /* logits base not aligned to its element size         */
     DIFR_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
     DIFR_ERR_UNSUPPORTED = 7, /* the current device is not gfx950                    */
-    DIFR_ERR_ARGUMENT = 8     /* sigma <= 0, eps < 0, or NaN where a number is needed */
+    DIFR_ERR_ARGUMENT = 8,    /* sigma <= 0, eps < 0, or NaN where a number is needed */
+    DIFR_ERR_CAPACITY = 9     /* the batch needs more scratch memory than the library's */
+                              /* built-in buffer holds (difr_lmhead_score_static)       */
 } difr_status;
 
 typedef enum { DIFR_BF16 = 0, DIFR_F32 = 1 } difr_dtype;
@@ -340,6 +342,27 @@ size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d);
 int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
                       uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
                       uint8_t *flags_ipt, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * difr_lmhead_score for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same
+ * outputs, same kernels; the partial results of the vocabulary ranges go to a buffer that is part of
+ * the library's device image (DIFR_LMHEAD_STATIC_SCRATCH_BYTES per GPU the library runs on, held until
+ * the process ends) instead of a caller workspace.  The call allocates and frees nothing.
+ *   - A batch with difr_lmhead_workspace_bytes(N, V, d) > DIFR_LMHEAD_STATIC_SCRATCH_BYTES is refused
+ *     with DIFR_ERR_CAPACITY and nothing is launched.  The 4 MiB hold every batch of up to 104,000
+ *     tokens at any V (28 bytes per token and vocabulary range, at most 65,536 such pairs below
+ *     65,536 tokens and one range per token above, plus 12 bytes per token).
+ *   - Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it and give wrong results.  Calls in order on one stream are safe;
+ *     nothing in the buffer has to survive from one call to the next and nothing has to be cleared.
+ *   - The first call on a device resolves the buffer's address (hipGetSymbolAddress); make that call
+ *     outside graph capture.  Later calls on that device only enqueue the three kernels.
+ */
+#define DIFR_LMHEAD_STATIC_SCRATCH_BYTES (4u << 20)
+int difr_lmhead_score_static(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score,
+                             float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi,
+                             float *u, uint8_t *flags_ipt, void *hip_stream);
 
 /*
  * Three-class token classification and per-token exfiltratable information.  [Sec. 7.1 and the

@@ -23,7 +23,9 @@ from .binding import (  # noqa: F401
     ipt_score,
     ipt_score_filtered,
     lib_path,
+    lmhead_outputs,
     lmhead_score,
+    lmhead_score_static,
     lmhead_workspace_bytes,
     load_library,
     philox4x32_10,

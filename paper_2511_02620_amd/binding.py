@@ -73,7 +73,7 @@ class _LikelihoodParams(C.Structure):
                 ("M", C.c_int32), ("z", C.c_void_p)]
 
 
-EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_peaked", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_score_both_filtered", "difr_lmhead_score", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
+EXPORTS = ("difr_gumbel_score", "difr_debug_gumbel_score_unfiltered", "difr_ipt_score", "difr_score_both", "difr_score_both_peaked", "difr_score_both_admissible", "difr_admissible_count", "difr_gumbel_likelihood", "difr_ipt_score_filtered", "difr_score_both_filtered", "difr_lmhead_score", "difr_lmhead_score_static", "difr_lmhead_workspace_bytes", "difr_classify", "difr_seq_reduce", "difr_debug_noise", "difr_debug_gumbel_map",
            "difr_philox4x32_10", "difr_status_string", "difr_version")
 
 
@@ -116,6 +116,8 @@ def load_library():
     lib.difr_lmhead_workspace_bytes.restype = C.c_size_t
     lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 11 + [C.c_size_t, vp]
     lib.difr_lmhead_score.restype = C.c_int
+    lib.difr_lmhead_score_static.argtypes = [C.POINTER(_LmHead)] + [vp] * 11
+    lib.difr_lmhead_score_static.restype = C.c_int
     lib.difr_classify.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_int64, C.c_int64, vp, vp, vp, vp]
     lib.difr_classify.restype = C.c_int
     lib.difr_ipt_score.restype = C.c_int
@@ -409,11 +411,7 @@ def lmhead_workspace_bytes(N, V, d) -> int:
     return int(load_library().difr_lmhead_workspace_bytes(int(N), int(V), int(d)))
 
 
-def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-                 temperatures=None, workspace=None):
-    """difr_lmhead_score: both estimators on logits = hidden @ weight.T that are never stored.
-    hidden [N, d], weight [V, d] bf16 on the GPU (unit column stride).  Returns (gumbel dict, ipt dict)."""
-    lib = load_library()
+def _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt, temperatures):
     for name, t in (("hidden", hidden), ("weight", weight)):
         if not t.is_cuda or t.dtype != torch.bfloat16 or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
             raise ValueError("%s must be a 2-D bfloat16 GPU tensor with unit column stride" % name)
@@ -429,11 +427,6 @@ def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed
     _check(temperatures, torch.float32, N, "temperatures", dev)
     if seeds.device != dev or seeds.dtype != torch.int64 or seeds.dim() != 1 or not seeds.is_contiguous():
         raise ValueError("seeds must be a contiguous 1-D int64 GPU tensor (uint64 bit patterns)")
-    need = lmhead_workspace_bytes(N, V, d)
-    if workspace is None:
-        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
-    elif workspace.device != dev or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
-        raise ValueError("workspace must be a contiguous uint8 tensor on the device of hidden")
     r = _LmHead()
     r.hidden, r.weight = hidden.data_ptr(), weight.data_ptr()
     r.N, r.V, r.d = N, V, d
@@ -445,12 +438,44 @@ def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed
     r.seq_ids, r.positions = seq_ids.data_ptr(), positions.data_ptr()
     r.claimed_gumbel = None if claimed_gumbel is None else claimed_gumbel.data_ptr()
     r.claimed_ipt = None if claimed_ipt is None else claimed_ipt.data_ptr()
-    f32 = dict(dtype=torch.float32, device=dev)
-    g = dict(margin=torch.empty(N, **f32), argmax=torch.empty(N, dtype=torch.int32, device=dev),
-             max_score=torch.empty(N, **f32), claimed_score=torch.empty(N, **f32),
-             flags=torch.empty(N, dtype=torch.uint8, device=dev))
-    i = dict(dist=torch.empty(N, **f32), cdf_lo=torch.empty(N, **f32), cdf_hi=torch.empty(N, **f32),
-             u=torch.empty(N, **f32), flags=torch.empty(N, dtype=torch.uint8, device=dev))
+    return r, dev, N, V, d
+
+
+_LMHEAD_OUT = (("margin", torch.float32), ("argmax", torch.int32), ("max_score", torch.float32),
+               ("claimed_score", torch.float32), ("flags", torch.uint8)), (
+    ("dist", torch.float32), ("cdf_lo", torch.float32), ("cdf_hi", torch.float32), ("u", torch.float32),
+    ("flags", torch.uint8))
+
+
+def lmhead_outputs(N, device):
+    """Output buffers of lmhead_score / lmhead_score_static, allocated once and reusable across calls."""
+    return tuple({k: torch.empty(N, dtype=dt, device=device) for k, dt in part} for part in _LMHEAD_OUT)
+
+
+def _lmhead_out(out, N, dev):
+    if out is None:
+        return lmhead_outputs(N, dev)
+    g, i = out
+    for part, spec in zip((g, i), _LMHEAD_OUT):
+        for k, dt in spec:
+            _check(part[k], dt, N, k, dev)
+    return g, i
+
+
+def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+                 temperatures=None, workspace=None, out=None):
+    """difr_lmhead_score: both estimators on logits = hidden @ weight.T that are never stored.
+    hidden [N, d], weight [V, d] bf16 on the GPU (unit column stride).  Returns (gumbel dict, ipt dict);
+    `out` = a pair from lmhead_outputs() to write into instead of new tensors."""
+    lib = load_library()
+    r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
+                                   temperatures)
+    need = lmhead_workspace_bytes(N, V, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
+    elif workspace.device != dev or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 tensor on the device of hidden")
+    g, i = _lmhead_out(out, N, dev)
     with torch.cuda.device(dev):
         rc = lib.difr_lmhead_score(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
                                    _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]), _ptr(i["cdf_lo"]),
@@ -458,6 +483,27 @@ def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed
                                    workspace.numel(), _stream_ptr(dev))
     if rc:
         raise DifrError(rc, "difr_lmhead_score")
+    return g, i
+
+
+LMHEAD_STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def lmhead_score_static(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+                        temperatures=None, out=None):
+    """difr_lmhead_score_static: lmhead_score without a workspace (the library's built-in buffer serves; calls that
+    overlap in time on one GPU race on it).  With `out` given (lmhead_outputs()) nothing is allocated at all."""
+    lib = load_library()
+    r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
+                                   temperatures)
+    g, i = _lmhead_out(out, N, dev)
+    with torch.cuda.device(dev):
+        rc = lib.difr_lmhead_score_static(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
+                                          _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]),
+                                          _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]),
+                                          _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, "difr_lmhead_score_static")
     return g, i
 
 

@@ -12,6 +12,11 @@
 #include "ipt_stream.hpp"
 #include "lmhead.hpp"
 
+// Built-in workspace of difr_lmhead_score_static: every GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  In host code the name `scratch` is only a handle for hipGetSymbolAddress;
+// the device address that call yields (one per device, cached below) is what kernels are given.
+static __device__ __align__(256) unsigned char scratch[DIFR_LMHEAD_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kMaxDevices = 64;
@@ -32,6 +37,25 @@ int check_device()
     const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
     if (dev < kMaxDevices) g_arch_ok[dev].store(ok ? 1 : 2, std::memory_order_relaxed);
     return ok ? DIFR_OK : DIFR_ERR_UNSUPPORTED;
+}
+
+constexpr size_t kStaticScratchBytes = DIFR_LMHEAD_STATIC_SCRATCH_BYTES;
+// Device address of `scratch` per device, resolved at the first call of difr_lmhead_score_static on that device.
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device, or null if the runtime cannot resolve it.
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) return nullptr;
+    if (dev < kMaxDevices) {
+        void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+        if (p) return p;
+    }
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    if (dev < kMaxDevices) g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
 }
 
 int validate_rows(const difr_rows *in, difr::RowBatch *b, bool *aligned)
@@ -121,6 +145,26 @@ int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, flo
     if (workspace_bytes < difr::lmhead_workspace_bytes(b.N, plan.splits)) return DIFR_ERR_SHAPE;
     if ((rc = check_device()) != DIFR_OK) return rc;
     const difr::LmHeadWorkspace ws = difr::lmhead_carve(workspace, b.N, plan.splits);
+    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+    return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
+}
+
+int difr_lmhead_score_static(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score,
+                             float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi,
+                             float *u, uint8_t *flags_ipt, void *hip_stream)
+{
+    difr::LmHeadBatch b;
+    int rc = validate_lmhead(in, &b);
+    if (rc != DIFR_OK) return rc;
+    if (b.N == 0) return DIFR_OK;
+    if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt) return DIFR_ERR_NULL;
+    const difr::LmHeadPlan plan = difr::lmhead_plan(b.N, b.V);
+    if (difr::lmhead_workspace_bytes(b.N, plan.splits) > kStaticScratchBytes) return DIFR_ERR_CAPACITY;
+    if ((rc = check_device()) != DIFR_OK) return rc;
+    void *ws_base = static_scratch();
+    if (!ws_base) return DIFR_ERR_LAUNCH;
+    const difr::LmHeadWorkspace ws = difr::lmhead_carve(ws_base, b.N, plan.splits);
     const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
     const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
     return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
@@ -431,6 +475,7 @@ const char *difr_status_string(int status)
         case DIFR_ERR_LAUNCH: return "HIP kernel launch failed";
         case DIFR_ERR_UNSUPPORTED: return "current device is not gfx950";
         case DIFR_ERR_ARGUMENT: return "bad scalar argument (sigma, eps or threshold)";
+        case DIFR_ERR_CAPACITY: return "batch needs more scratch memory than the library's built-in buffer holds";
         default: return "unknown status";
     }
 }
