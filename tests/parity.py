@@ -112,25 +112,29 @@ def compare_ipt(gpu: dict, ref: dict, logits_host=None, V=None, row_args=None, l
             excused += 1
         stats["token_excused"] = excused
     if "log_mass" in g and log_mass_sigma is not None:
-        # The log-mass is evaluated in fp64 from the kernel's fp64 interval.  Its position carries the error
-        # of the fp32 exponentials (da, a few 1e-8 absolute), its width the relative error dw of one fp32
-        # exponential.  S = ln(mass + eps), mass = Phi(zb) - Phi(za):
-        #   u inside a narrow interval: mass ~ phi(z) (b-a)/sigma, so |dS| <~ dw + |z| da / sigma;
-        #   u outside (Gaussian tail):  mass ~ phi(z)/|z|,         so |dS| <~ |z| da / sigma, |z| = dist/sigma.
+        # The bar is the reading taken for the printed score: |dS| <= 1e-4 max(1, |S|).  The log-mass is evaluated
+        # in fp64 from the kernel's fp64 interval, whose position carries the error of the fp32 exponentials (da, a
+        # few 1e-8 absolute) and whose width carries the relative error dw of one fp32 exponential; to first order
+        #   dS = (phi(z_b) db - phi(z_a) da) / (sigma (mass + eps))  <~  dw + 4 da (1 + dist/sigma + width/sigma) / sigma.
+        # A row beyond the bar is accepted only if that first-order error alone can exceed the bar there (a sigma
+        # so small that the interval's fp32 position error shows), stays within it, and is counted.
         da, dw = 1e-7, 4e-6
         z = np.nan_to_num(ref["dist"], nan=0.0) / log_mass_sigma
         zin = np.minimum(1.0, np.nan_to_num(ref["cdf_hi"] - ref["cdf_lo"], nan=0.0)) / log_mass_sigma
-        tol = 1e-4 + dw + 4.0 * da * (1.0 + z + zin) / log_mass_sigma
+        first_order = dw + 4.0 * da * (1.0 + z + zin) / log_mass_sigma
         gl, rl = g["log_mass"].astype(np.float64), ref["log_mass"]
         ok = ~(np.isnan(gl) & np.isnan(rl))
         err = np.where(ok, np.abs(gl - rl), 0.0)
-        bound = np.maximum(tol, 1e-4 * np.abs(np.nan_to_num(rl)))
-        worst = int(np.argmax(err - bound))
-        assert (err <= bound).all(), (
-            "log_mass beyond its error bound at row %d: gpu S %.9g oracle S %.9g bound %.3g; gpu a %.9g b %.9g u %.9g; "
-            "oracle a %.12g b %.12g dist %.6g" % (worst, gl[worst], rl[worst], bound[worst], g["cdf_lo"][worst],
+        bar = 1e-4 * np.maximum(1.0, np.abs(np.nan_to_num(rl)))
+        beyond = ~(err <= bar)
+        allowed = (first_order > bar) & (err <= 1e-4 + first_order)
+        worst = int(np.argmax(err - np.where(allowed, 1e-4 + first_order, bar)))
+        assert not (beyond & ~allowed).any(), (
+            "log_mass beyond its bar at row %d: gpu S %.9g oracle S %.9g bar %.3g; gpu a %.9g b %.9g u %.9g; "
+            "oracle a %.12g b %.12g dist %.6g" % (worst, gl[worst], rl[worst], bar[worst], g["cdf_lo"][worst],
                                                    g["cdf_hi"][worst], g["u"][worst], ref["cdf_lo"][worst],
                                                    ref["cdf_hi"][worst], ref["dist"][worst]))
+        stats["log_mass_beyond_bar"] = int(beyond.sum())
         err = err[ok]
         stats["log_mass_err"] = float(err.max()) if err.size else 0.0
     d = g["dist"][~np.isnan(g["dist"])]

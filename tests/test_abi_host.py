@@ -128,7 +128,7 @@ def test_argument_validation_needs_no_device(lib):
                                            1e-30, lm, None, fl, None)
 
     assert iptf(k=-1) == ARG and iptf(k=257) == ARG and iptf(p=0.0) == ARG and iptf(sigma=0.0, lm=fake) == ARG
-    assert iptf(k=0, p=1.0) == 7                              # DIFR_ERR_UNSUPPORTED: no filter at all is difr_ipt_score
+    assert iptf(k=0, p=1.0) == ARG                            # no filter at all is difr_ipt_score
     assert iptf(rows(V=15, ld=15), k=0, p=0.9) == ALIGN and iptf(rows(N=0), k=0, p=0.9, dist=None, fl=None) == OK
     assert iptf(dist=None) == NULL and iptf(fl=None) == NULL
     assert iptf(rows(V=15, ld=15)) == ALIGN and iptf(rows(N=0), dist=None, fl=None) == OK
@@ -144,7 +144,7 @@ def test_argument_validation_needs_no_device(lib):
     for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0),
                dict(sigma=float("nan")), dict(top_p=0.0)):
         assert lik(**kw) == ARG, kw
-    assert lik(top_k=0, top_p=0.9) == 7                      # DIFR_ERR_UNSUPPORTED without the tau output (it carries the nucleus' threshold)
+    assert lik(top_k=0, top_p=0.9) == NULL                   # the tau output is required then (it carries the nucleus' threshold)
     assert lik(z=None) == NULL and lik(pi=None) == NULL and lik(fl=None) == NULL
     assert lik(rows(V=0)) == SHAPE and lik(rows(N=0), pi=None, fl=None, z=None) == OK
     assert lik(rows(V=15, ld=15)) == ALIGN                   # rows not 16-byte aligned
@@ -160,8 +160,8 @@ def test_argument_validation_needs_no_device(lib):
     for kw in (dict(s=-1), dict(s=257), dict(top_k=-1), dict(top_k=257), dict(M=0), dict(sigma=0.0), dict(top_p=0.0)):
         assert sbf(**kw) == ARG, kw
     assert sbf(lm=fake, sigma_ipt=0.0) == ARG
-    assert sbf(top_k=0) == 7                                 # DIFR_ERR_UNSUPPORTED: a bare nucleus needs the tau array
-    assert sbf(top_k=0, top_p=1.0) == 7                      # ... and no filter at all is not this call
+    assert sbf(top_k=0) == NULL                              # a bare nucleus needs the tau array
+    assert sbf(top_k=0, top_p=1.0) == ARG                    # ... and no filter at all is not this call
     assert sbf(pi=None) == NULL and sbf(dist=None) == NULL and sbf(fg=None) == NULL and sbf(fi=None) == NULL
     assert sbf(z=None) == NULL and sbf(rows(V=15, ld=15)) == ALIGN and sbf(rows(V=0)) == SHAPE
     assert sbf(rows(N=0), pi=None, dist=None, fg=None, fi=None, z=None) == OK

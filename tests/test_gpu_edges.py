@@ -153,3 +153,46 @@ def test_random_shapes_alignments_and_temperatures(difr, case):
         ci[3] = -1
     sg, si, was_aligned = _run_all(difr, logits, V, T, seeds, sid, pos, cg, ci, temps=temps)
     assert was_aligned == aligned
+
+
+def test_bf16_nan_with_sign_bit_set(difr):
+    """A bf16 NaN whose sign bit is set (pattern 0xFFC0, the default NaN of x86 arithmetic).  The oracle flags any
+    NaN.  So do the calls that take the exponential of every entry (difr_ipt_score, the Token-IPT-DiFR side of
+    difr_score_both) and the unfiltered Token-DiFR kernel.  The gated Token-DiFR stream orders raw bit patterns, in
+    which such a NaN sorts below -inf: it is documented to treat the entry like a masked one, unless the vector that
+    holds it reaches the exact evaluation for another reason, where it is flagged.  Either way the row never
+    passes silently on the Token-IPT-DiFR side."""
+    N, V, T = 64, 20504, 0.9
+    g = torch.Generator().manual_seed(77)
+    x = (torch.randn(N, V, generator=g) * 2.5).to(torch.bfloat16)
+    bits = x.view(torch.int16)
+    where = torch.randint(0, V, (N,), generator=g)
+    masked = x.clone()
+    for n in range(N):
+        bits[n, where[n]] = -64                      # 0xFFC0
+        masked[n, where[n]] = float("-inf")
+    assert x.float().isnan().sum() == N
+    x, masked = x.to(DEV), masked.to(DEV)
+    seeds = torch.tensor([5, 9], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    c = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
+    host = parity.to_host_logits(x)
+    hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
+    og = oracle.gumbel_score(host, V, np.float32(T), hs, hsid, hpos, c.cpu().numpy())
+    oi = oracle.ipt_score(host, V, np.float32(T), hs, hsid, hpos, c.cpu().numpy())
+    assert (og["flags"] & 4).all() and (oi["flags"] & 4).all()
+    i = difr.ipt_score(x, T, seeds, sid, pos, c)
+    u = difr.gumbel_score(x, T, seeds, sid, pos, c, unfiltered=True)
+    gs = difr.gumbel_score(x, T, seeds, sid, pos, c)
+    gm = difr.gumbel_score(masked, T, seeds, sid, pos, c)
+    fg, fi = difr.score_both(x, T, seeds, sid, pos, c, c)
+    torch.cuda.synchronize()
+    assert (i["flags"] & 4).all() and (fi["flags"] & 4).all()
+    assert (u["flags"] & 4).all()
+    flagged = (gs["flags"] & 4) != 0
+    for k in gs:                                     # not flagged: exactly the row with the entry masked
+        a, b = gs[k][~flagged], gm[k][~flagged]
+        assert torch.equal(torch.nan_to_num(a.float(), nan=-7.0), torch.nan_to_num(b.float(), nan=-7.0)), k
+    for k in fg:                                     # the one-pass call's Token-DiFR side is the same stream
+        assert torch.equal(torch.nan_to_num(fg[k].float(), nan=-7.0), torch.nan_to_num(gs[k].float(), nan=-7.0)), k

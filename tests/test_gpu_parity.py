@@ -449,7 +449,7 @@ def test_score_both_equals_the_two_single_calls(difr, dtype, V, ld, offset, case
     _same_outputs(ra, {k: ar[k] for k in ra})
     _same_outputs(rb, {k: b[k] for k in rb})
     # the variant for concentrated rows (a test in front of the noise generation): the same, bit for bit
-    pa, pb = difr.score_both(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps, peaked=True)
+    pa, pb = difr.score_both_peaked(logits, T, seeds, sid, pos, cg, ci, V=V, temperatures=temps)
     torch.cuda.synchronize()
     _same_outputs(pa, {k: a[k] for k in pa})
     _same_outputs(pb, {k: b[k] for k in pb})
@@ -540,7 +540,7 @@ def test_score_both_peaked_on_concentrated_rows(difr, dtype, slope, shift):
         rnd = torch.randint(0, V, (N,), generator=g, dtype=torch.int32).to(DEV)
         for cg in (honest, rnd, None):
             a, b = difr.score_both(logits, T, seeds, sid, pos, cg, cg, want_token=True)
-            pa, pb = difr.score_both(logits, T, seeds, sid, pos, cg, cg, want_token=True, peaked=True)
+            pa, pb = difr.score_both_peaked(logits, T, seeds, sid, pos, cg, cg, want_token=True)
             torch.cuda.synchronize()
             _same_outputs(pa, a)
             _same_outputs(pb, b)

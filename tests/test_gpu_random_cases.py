@@ -128,7 +128,7 @@ def run_case(difr, c, rng):
     bg2, bi2 = difr.score_both(*a, cg, ci, **kw)
     eq(bg2, g1, "score_both (no rank) gumbel side")
     eq(bi2, bi, "score_both (no rank) ipt side")
-    bg3, bi3 = difr.score_both(*a, cg, ci, peaked=True, **kw)
+    bg3, bi3 = difr.score_both_peaked(*a, cg, ci, **kw)
     eq(bg3, g1, "score_both_peaked gumbel side")
     eq(bi3, bi, "score_both_peaked ipt side")
     # logit rank against a plain count
