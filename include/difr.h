@@ -38,8 +38,10 @@
  *
  * Conventions that hold for every entry point
  *   - Pointers documented DEVICE must be device pointers (HBM) valid on the current
- *     HIP device; the caller owns every buffer; the library allocates nothing, keeps
- *     no state between calls and is thread-safe.
+ *     HIP device; the caller owns every buffer; the library allocates nothing and is
+ *     thread-safe.  It keeps no state between calls but two per-device caches filled at
+ *     the first call on a device: whether the device is gfx950 (asked of the runtime
+ *     once) and, for difr_lmhead_score_static only, the address of its built-in buffer.
  *   - Work is enqueued on the given hipStream_t (passed as void*; NULL = the null
  *     stream) and the call returns without synchronising.  The return value reports
  *     host-side argument validation and the launch status only.
@@ -69,7 +71,9 @@ typedef enum {
     DIFR_ERR_ALIGN = 5,       /* logits base not aligned to its element size         */
     DIFR_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch                  */
     DIFR_ERR_UNSUPPORTED = 7, /* the current device is not gfx950                    */
-    DIFR_ERR_ARGUMENT = 8,    /* sigma <= 0, eps < 0, or NaN where a number is needed */
+    DIFR_ERR_ARGUMENT = 8,    /* sigma <= 0, eps < 0, NaN where a number is needed, or */
+                              /* a top_k / top_p / s / M combination the call does not  */
+                              /* take (stated at each call)                             */
     DIFR_ERR_CAPACITY = 9     /* the batch needs more scratch memory than the library's */
                               /* built-in buffer holds (difr_lmhead_score_static)       */
 } difr_status;
@@ -203,7 +207,7 @@ int difr_score_both_peaked(const difr_rows *in, const int32_t *claimed_ipt, floa
  * marginal tokens of such a nucleus have probabilities around 1e-6, the accuracy of the fp32 exponentials the mass
  * is summed from, so kept[n] may differ from an evaluation in double by those few tokens; a, b and d keep the 1e-4
  * contract.  The sampler's own token, when asked for and not the claim, costs one more (early-exit) pass.
- * top_k = 0 with top_p >= 1 is refused (DIFR_ERR_UNSUPPORTED: no filter at all, call difr_ipt_score).
+ * top_k = 0 with top_p >= 1 is refused (DIFR_ERR_ARGUMENT: no filter at all, call difr_ipt_score).
  */
 int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, float *dist, float *cdf_lo, float *cdf_hi,
                             float *u, int32_t *ipt_token, double sigma, double eps, float *log_mass, int32_t *kept,
@@ -215,8 +219,8 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
  *   S     = the s tokens with the largest x_i + T G_i, the claimed token t left out (ties to the lower index);
  *   tau   = the smallest logit the sampler's filter keeps: top_k largest logits, then top_p on the distribution
  *           renormalised over those (shortest prefix in descending logit order whose softmax(x/T) mass reaches
- *           top_p).  top_k = 0: no top-k; top_p >= 1: no top-p; neither: tau = -inf.  top_p < 1 needs top_k > 0
- *           here (DIFR_ERR_UNSUPPORTED otherwise: a nucleus over the whole vocabulary is not built);
+ *           top_p).  top_k = 0: no top-k; top_p >= 1: no top-p; neither: tau = -inf.  top_k = 0 with top_p < 1
+ *           is the bare nucleus over the whole vocabulary (see Limits);
  *   A_i   = x_t - x_i + T (G_t - G_i),  B_i = tau - x_i   for i in S;
  *   pi    = (1/M) sum_j [x_t + sigma z_j > tau] prod_{i in S} Phi(max(sigma z_j + A_i, B_i) / sigma).
  * p->z  DEVICE [M] fp32 standard normal draws, supplied by the caller and shared by all rows (the algorithm
@@ -224,7 +228,7 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
  * Limits: 0 <= s <= 256, 0 <= top_k <= 256, M >= 1, sigma > 0, top_p > 0 (else DIFR_ERR_ARGUMENT); rows must
  *       be 16-byte aligned (DIFR_ERR_ALIGN).  top_k = 0 with top_p < 1 (a nucleus over the whole vocabulary)
  *       runs the search described at difr_ipt_score_filtered first; it leaves the threshold in `tau`, which is
- *       then a required output (DIFR_ERR_UNSUPPORTED if NULL).
+ *       then a required output (DIFR_ERR_NULL if NULL).
  * Outputs (DEVICE): pi [N] fp32; log_pi [N] fp32 or NULL (natural log, -inf if pi = 0; this is the FSSL score
  *       the paper thresholds); tau [N] fp32 or NULL; active [N, s] int32 or NULL (S in rank order of the fp32 scores, -1 padded);
  *       flags [N] (DIFR_FLAG_INVALID_CLAIM: pi NaN; DIFR_FLAG_NONFINITE).  Which tokens are in S is decided on
@@ -251,8 +255,8 @@ int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p,
  * Token-DiFR claims, claimed_ipt (DEVICE [N] or NULL for sampling mode) the Token-IPT-DiFR claims; p as in
  * difr_gumbel_likelihood.  top_k = 0 with top_p < 1 (the bare nucleus) is served by the two single calls' kernels
  * one after the other on the stream - the nucleus search, which scores Token-IPT-DiFR and leaves the threshold in
- * tau (then required: DIFR_ERR_UNSUPPORTED if NULL), and the estimator's pass -; top_k = 0 with top_p >= 1 is no
- * filter at all and refused (DIFR_ERR_UNSUPPORTED).
+ * tau (then required: DIFR_ERR_NULL if NULL), and the estimator's pass -; top_k = 0 with top_p >= 1 is no
+ * filter at all and refused (DIFR_ERR_ARGUMENT).
  * Outputs have the meaning, layout and optionality of the two single calls and are bit-identical to theirs;
  * flags_gumbel and flags_ipt are the two calls' `flags`; sigma_ipt, eps belong to log_mass.
  */
@@ -287,7 +291,9 @@ int difr_admissible_count(const difr_rows *in, const float *max_score, float del
  * the same delta.  If a row has more candidates than the list holds (a very large delta, or a row whose
  * bound stays far below its maximum for long), count[n] = -1 and log2_count[n] = NaN: call
  * difr_admissible_count for those rows.  With honest claims (the bound starts at the maximum) and delta up
- * to about 5 this does not happen.
+ * to about 5 this does not happen.  Whether a crowded row ends as -1 can differ from run to run: a wavefront
+ * prunes its list against the best bound it has seen, which includes bounds the other wavefronts of the row
+ * publish, and when it sees them is a matter of timing.  A count that is not -1 is always the exact count.
  * delta >= 0, finite (else DIFR_ERR_ARGUMENT); rows must be 16-byte aligned (DIFR_ERR_ALIGN).
  * count DEVICE [N] int32 (required); log2_count DEVICE [N] fp32 or NULL.  All other arguments and outputs as
  * in difr_score_both, bit-identical to it.

@@ -32,6 +32,7 @@ from .binding import (  # noqa: F401
     score_both,
     score_both_admissible,
     score_both_filtered,
+    score_both_peaked,
     seq_reduce,
     version,
 )

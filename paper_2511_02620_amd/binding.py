@@ -253,11 +253,24 @@ def ipt_score(logits, temperature, seeds, seq_ids, positions, claimed=None, temp
 
 
 def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-               temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30,
-               peaked=False):
-    """difr_score_both (peaked=True: difr_score_both_peaked, the variant for concentrated rows): both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
+               temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01, eps=1e-30):
+    """difr_score_both: both estimators in one pass.  Returns (gumbel dict, ipt dict) of device tensors;
     want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_token / want_log_mass add ipt_token /
     log_mass to the second (as in :func:`ipt_score`)."""
+    return _score_both("difr_score_both", logits, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
+                       temperatures, V, want_rank, want_token, want_log_mass, sigma, eps)
+
+
+def score_both_peaked(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
+                      temperatures=None, V=None, want_rank=False, want_token=False, want_log_mass=False, sigma=0.01,
+                      eps=1e-30):
+    """difr_score_both_peaked: :func:`score_both` for rows known to be concentrated; same arguments, same results."""
+    return _score_both("difr_score_both_peaked", logits, temperature, seeds, seq_ids, positions, claimed_gumbel,
+                       claimed_ipt, temperatures, V, want_rank, want_token, want_log_mass, sigma, eps)
+
+
+def _score_both(entry_name, logits, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt, temperatures, V,
+                want_rank, want_token, want_log_mass, sigma, eps):
     lib = load_library()
     r, N, dev = _rows(logits, V, temperature, seeds, seq_ids, positions, claimed_gumbel, temperatures)
     _check(claimed_ipt, torch.int32, N, "claimed_ipt", dev)
@@ -274,14 +287,13 @@ def score_both(logits, temperature, seeds, seq_ids, positions, claimed_gumbel=No
     if want_log_mass:
         i["log_mass"] = torch.empty(N, **f32)
     with torch.cuda.device(dev):
-        entry = lib.difr_score_both_peaked if peaked else lib.difr_score_both
-        rc = entry(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
-                                 _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]),
-                                 _ptr(g.get("logit_rank")), _ptr(i["dist"]),
-                                 _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i.get("ipt_token")),
-                                 float(sigma), float(eps), _ptr(i.get("log_mass")), _ptr(i["flags"]), _stream_ptr(dev))
+        rc = getattr(lib, entry_name)(C.byref(r), _ptr(claimed_ipt), _ptr(g["margin"]), _ptr(g["argmax"]),
+                                      _ptr(g["max_score"]), _ptr(g["claimed_score"]), _ptr(g["flags"]),
+                                      _ptr(g.get("logit_rank")), _ptr(i["dist"]), _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]),
+                                      _ptr(i["u"]), _ptr(i.get("ipt_token")), float(sigma), float(eps),
+                                      _ptr(i.get("log_mass")), _ptr(i["flags"]), _stream_ptr(dev))
     if rc:
-        raise DifrError(rc, "difr_score_both")
+        raise DifrError(rc, entry_name)
     return g, i
 
 

@@ -20,8 +20,8 @@ static __device__ __align__(256) unsigned char scratch[DIFR_LMHEAD_STATIC_SCRATC
 namespace {
 
 constexpr int kMaxDevices = 64;
-// 0 = not checked yet, 1 = gfx950, 2 = something else.  A cache, not state: the answer
-// for a device never changes.
+// 0 = not checked yet, 1 = gfx950, 2 = something else.  The one thing the library remembers between calls
+// (include/difr.h says so): the answer for a device never changes, and asking the runtime costs microseconds.
 std::atomic<int> g_arch_ok[kMaxDevices];
 
 int check_device()
@@ -262,7 +262,7 @@ int difr_ipt_score_filtered(const difr_rows *in, int32_t top_k, float top_p, flo
     if (top_k < 0 || top_k > 256 || !(top_p > 0.0f)) return DIFR_ERR_ARGUMENT;
     if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
     // no top-k: a nucleus over the whole vocabulary (without top-p either there is no filter: difr_ipt_score)
-    if (top_k == 0 && !(top_p < 1.0f)) return DIFR_ERR_UNSUPPORTED;
+    if (top_k == 0 && !(top_p < 1.0f)) return DIFR_ERR_ARGUMENT;
     if (b.N == 0) return DIFR_OK;
     if (!dist || !flags) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
@@ -285,7 +285,7 @@ int difr_gumbel_likelihood(const difr_rows *in, const difr_likelihood_params *p,
     // a nucleus over the whole vocabulary is found by a kernel of its own, which leaves the threshold in the
     // caller's tau array for the estimator to pick up: that output is then required
     const bool nucleus = p->top_k == 0 && p->top_p < 1.0f;
-    if (nucleus && !tau) return DIFR_ERR_UNSUPPORTED;
+    if (nucleus && !tau) return DIFR_ERR_NULL;
     if (b.N == 0) return DIFR_OK;
     if (!pi || !flags || !p->z) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
@@ -316,7 +316,8 @@ int difr_score_both_filtered(const difr_rows *in, const int32_t *claimed_ipt, co
     // is found by a kernel of its own (which scores Token-IPT-DiFR on it and leaves the threshold in the caller's
     // tau array, then a required output) and the estimator's pass follows on the same stream
     const bool nucleus = p->top_k == 0 && p->top_p < 1.0f;
-    if (p->top_k == 0 && (!nucleus || !tau)) return DIFR_ERR_UNSUPPORTED;
+    if (p->top_k == 0 && !nucleus) return DIFR_ERR_ARGUMENT;
+    if (nucleus && !tau) return DIFR_ERR_NULL;
     if (b.N == 0) return DIFR_OK;
     if (!pi || !flags_gumbel || !p->z || !dist || !flags_ipt) return DIFR_ERR_NULL;
     if (!aligned) return DIFR_ERR_ALIGN;
@@ -474,7 +475,7 @@ const char *difr_status_string(int status)
         case DIFR_ERR_ALIGN: return "logits pointer not aligned to its element size";
         case DIFR_ERR_LAUNCH: return "HIP kernel launch failed";
         case DIFR_ERR_UNSUPPORTED: return "current device is not gfx950";
-        case DIFR_ERR_ARGUMENT: return "bad scalar argument (sigma, eps or threshold)";
+        case DIFR_ERR_ARGUMENT: return "bad scalar argument (sigma, eps, threshold, delta, or a top_k / top_p / s / M combination the call does not take)";
         case DIFR_ERR_CAPACITY: return "batch needs more scratch memory than the library's built-in buffer holds";
         default: return "unknown status";
     }
