@@ -383,6 +383,8 @@ struct GumbelStream {
     template <int MODE>
     __device__ __forceinline__ void process(u32x4 q, int round, bool active, TopN *top = nullptr)
     {
+        // a wave without a vector in this round (the last, partly filled round of a row) has nothing to generate
+        if (__builtin_amdgcn_ballot_w64(active) == 0ull) return;
         if (PEAKED) {
             bool reach;
             if (DT == 0) {
@@ -419,8 +421,8 @@ struct GumbelStream {
         const uint64_t amask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateHi);
         const uint64_t cnmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateLo);
         uint64_t bmask, cxmask;
+        uint16_t lo = 0, hi = 0;  // bf16: extreme bit patterns of the vector (see below)
         if (DT == 0) {
-            uint16_t lo = 0, hi = 0;
             if (MODE != 1) {  // smallest bit pattern as unsigned: the largest logit if it is <= 0 ...
                 u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
                 m = __builtin_elementwise_min(m, as_u16x2(q.z));
@@ -449,16 +451,40 @@ struct GumbelStream {
         if (RANK) count_above(q, active);
         if (__builtin_expect(hitmask != 0ull, 0)) {
             if ((hitmask >> (tid & 63)) & 1ull) {
-                // Entries that could matter are those with moderate noise or a moderate logit; each of
-                // them is then tested against its own noise bound before anything exact is computed.
-                const int32_t v0 = (round * kBlock + tid) * E;
-                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+                // The three tests look at the largest word and the largest logit of the vector separately.  Taken
+                // together they bound every entry of it: y_v <= x_max / T + bound(r_max) (both terms are monotone,
+                // and so is the rounding of the sum), so one more test per vector, with the expression the
+                // per-entry test uses, rules out most vectors that tripped a test: the per-entry test below would
+                // fail for each of their entries.  x_max from the extreme bit patterns: the largest signed
+                // pattern if it is a positive number (a NaN with its sign clear stays a NaN and passes), else the
+                // smallest unsigned pattern if all are negative, else something that passes.
+                float xub;
+                if (DT == 0) {
+                    const float f_hi = __uint_as_float((uint32_t)hi << 16), f_lo = __uint_as_float((uint32_t)lo << 16);
+                    if (MODE == 0)
+                        xub = lo < 0x8000u ? __builtin_inff() : f_lo;   // a positive entry: not bounded by lo
+                    else if (MODE == 1)
+                        xub = (int16_t)hi >= 0 ? f_hi : -0.0f;          // all negative: bounded by zero
+                    else
+                        xub = (int16_t)hi >= 0 ? f_hi : f_lo;
+                } else {
+                    const float x0 = __uint_as_float(q.x), x1 = __uint_as_float(q.y), x2 = __uint_as_float(q.z),
+                                x3 = __uint_as_float(q.w);
+                    xub = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+                    if (!(x0 + x1 + x2 + x3 == x0 + x1 + x2 + x3)) xub = __builtin_inff();  // a NaN among them (or both infinities)
+                }
+                if (!(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate)) {
+                    // Entries that could matter are those with moderate noise or a moderate logit; each of
+                    // them is then tested against its own noise bound before anything exact is computed.
+                    const int32_t v0 = (round * kBlock + tid) * E;
+                    const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-                for (int j = 0; j < E; ++j) {
-                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
-                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
-                                             : __uint_as_float(w);
-                    if (r[j] >= kGateLo || !(xv < gate.xcap_lo)) consider(xv, r[j], v0 + j, top);
+                    for (int j = 0; j < E; ++j) {
+                        const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                        const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16))
+                                                 : __uint_as_float(w);
+                        if (r[j] >= kGateLo || !(xv < gate.xcap_lo)) consider(xv, r[j], v0 + j, top);
+                    }
                 }
             }
             // a better score raises the lower bound for this wave; other waves pick it up from LDS
