@@ -320,9 +320,18 @@ int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, 
  *         16-byte aligned (else DIFR_ERR_SHAPE / DIFR_ERR_ALIGN).  N, V < 2^31; ldh, ldw < 2^23.
  * claimed_gumbel / claimed_ipt  DEVICE [N] or NULL: the claims scored by Token-DiFR and by
  *         Token-IPT-DiFR.  The remaining fields are those of difr_rows.
- * Outputs: exactly those of difr_score_both, with the same optionality and flag bits.  Because
+ * Outputs: those of difr_score_both, with the same optionality and flag bits, except the sampler's
+ *         own Token-IPT-DiFR token (it needs the row's total mass before its position in the CDF
+ *         can be found: on logits that are never stored that is a second product).  Because
  *         the fp32 accumulation order of a matrix-core product is not the oracle's, logits carry
  *         an error of a few 1e-6 relative to sum_k |h_k w_k|; scores inherit it.
+ *         logit_rank [N] int32 or NULL: entries whose logit exceeds the Token-DiFR claim's (Sec. 7.1),
+ *         counted in the same pass against the claim's logit formed as a plain fp32 dot product (it has
+ *         to be known before the first tile); the claimed entry is left out by index.  A logit within
+ *         the accumulation error of the claim's may fall on either side: the count is exact up to
+ *         those entries.  -1 for an invalid claim.  Asking for it costs a few per cent.
+ *         sigma, eps, log_mass: as in difr_ipt_score (the paper's Token-IPT-DiFR score, fp64 from the
+ *         fp64 interval).
  * workspace  DEVICE scratch of at least difr_lmhead_workspace_bytes(N, V, d) bytes, 8-byte
  *         aligned, owned by the caller, contents irrelevant before and after the call; calls that
  *         overlap in time need distinct workspaces.  Too small: DIFR_ERR_SHAPE.
@@ -346,8 +355,9 @@ typedef struct {
 size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d);
 
 int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
-                      uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                      uint8_t *flags_ipt, void *workspace, size_t workspace_bytes, void *hip_stream);
+                      uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                      double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
+                      size_t workspace_bytes, void *hip_stream);
 
 /*
  * difr_lmhead_score for callers that cannot allocate device memory or hand over a workspace: code
@@ -356,9 +366,9 @@ int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, flo
  * the library's device image (DIFR_LMHEAD_STATIC_SCRATCH_BYTES per GPU the library runs on, held until
  * the process ends) instead of a caller workspace.  The call allocates and frees nothing.
  *   - A batch with difr_lmhead_workspace_bytes(N, V, d) > DIFR_LMHEAD_STATIC_SCRATCH_BYTES is refused
- *     with DIFR_ERR_CAPACITY and nothing is launched.  The 4 MiB hold every batch of up to 104,000
- *     tokens at any V (28 bytes per token and vocabulary range, at most 65,536 such pairs below
- *     65,536 tokens and one range per token above, plus 12 bytes per token).
+ *     with DIFR_ERR_CAPACITY and nothing is launched.  The 4 MiB hold every batch of up to 87,000
+ *     tokens at any V (32 bytes per token and vocabulary range, at most 65,536 such pairs below
+ *     65,536 tokens and one range per token above, plus 16 bytes per token).
  *   - Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one GPU (two
  *     streams, two threads) race on it and give wrong results.  Calls in order on one stream are safe;
  *     nothing in the buffer has to survive from one call to the next and nothing has to be cleared.
@@ -367,8 +377,9 @@ int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, flo
  */
 #define DIFR_LMHEAD_STATIC_SCRATCH_BYTES (4u << 20)
 int difr_lmhead_score_static(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score,
-                             float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi,
-                             float *u, uint8_t *flags_ipt, void *hip_stream);
+                             float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
+                             float *cdf_hi, float *u, double sigma, double eps, float *log_mass, uint8_t *flags_ipt,
+                             void *hip_stream);
 
 /*
  * Three-class token classification and per-token exfiltratable information.  [Sec. 7.1 and the

@@ -114,9 +114,9 @@ def load_library():
     lib.difr_admissible_count.restype = C.c_int
     lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
     lib.difr_lmhead_workspace_bytes.restype = C.c_size_t
-    lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 11 + [C.c_size_t, vp]
+    lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 10 + [C.c_double, C.c_double, vp, vp, vp, C.c_size_t, vp]
     lib.difr_lmhead_score.restype = C.c_int
-    lib.difr_lmhead_score_static.argtypes = [C.POINTER(_LmHead)] + [vp] * 11
+    lib.difr_lmhead_score_static.argtypes = [C.POINTER(_LmHead)] + [vp] * 10 + [C.c_double, C.c_double, vp, vp, vp]
     lib.difr_lmhead_score_static.restype = C.c_int
     lib.difr_classify.argtypes = [vp, vp, C.c_int64, C.c_float, C.c_int64, C.c_int64, vp, vp, vp, vp]
     lib.difr_classify.restype = C.c_int
@@ -457,29 +457,50 @@ _LMHEAD_OUT = (("margin", torch.float32), ("argmax", torch.int32), ("max_score",
                ("claimed_score", torch.float32), ("flags", torch.uint8)), (
     ("dist", torch.float32), ("cdf_lo", torch.float32), ("cdf_hi", torch.float32), ("u", torch.float32),
     ("flags", torch.uint8))
+_LMHEAD_OPT = (("logit_rank", torch.int32),), (("log_mass", torch.float32),)
 
 
-def lmhead_outputs(N, device):
+def lmhead_outputs(N, device, want_rank=False, want_log_mass=False):
     """Output buffers of lmhead_score / lmhead_score_static, allocated once and reusable across calls."""
-    return tuple({k: torch.empty(N, dtype=dt, device=device) for k, dt in part} for part in _LMHEAD_OUT)
+    g, i = tuple({k: torch.empty(N, dtype=dt, device=device) for k, dt in part} for part in _LMHEAD_OUT)
+    if want_rank:
+        g["logit_rank"] = torch.empty(N, dtype=torch.int32, device=device)
+    if want_log_mass:
+        i["log_mass"] = torch.empty(N, dtype=torch.float32, device=device)
+    return g, i
 
 
-def _lmhead_out(out, N, dev):
+def _lmhead_out(out, N, dev, want_rank, want_log_mass):
     if out is None:
-        return lmhead_outputs(N, dev)
+        return lmhead_outputs(N, dev, want_rank, want_log_mass)
     g, i = out
-    for part, spec in zip((g, i), _LMHEAD_OUT):
+    for part, spec, opt in zip((g, i), _LMHEAD_OUT, _LMHEAD_OPT):
         for k, dt in spec:
             _check(part[k], dt, N, k, dev)
+        for k, dt in opt:
+            _check(part.get(k), dt, N, k, dev)
+    return g, i
+
+
+def _lmhead_call(entry_name, tail, r, g, i, sigma, eps, dev):
+    lib = load_library()
+    with torch.cuda.device(dev):
+        rc = getattr(lib, entry_name)(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
+                                      _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(g.get("logit_rank")),
+                                      _ptr(i["dist"]), _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), float(sigma),
+                                      float(eps), _ptr(i.get("log_mass")), _ptr(i["flags"]), *tail, _stream_ptr(dev))
+    if rc:
+        raise DifrError(rc, entry_name)
     return g, i
 
 
 def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-                 temperatures=None, workspace=None, out=None):
+                 temperatures=None, workspace=None, out=None, want_rank=False, want_log_mass=False, sigma=0.01, eps=1e-30):
     """difr_lmhead_score: both estimators on logits = hidden @ weight.T that are never stored.
     hidden [N, d], weight [V, d] bf16 on the GPU (unit column stride).  Returns (gumbel dict, ipt dict);
-    `out` = a pair from lmhead_outputs() to write into instead of new tensors."""
-    lib = load_library()
+    want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_log_mass adds log_mass to the second;
+    `out` = a pair from lmhead_outputs() to write into instead of new tensors (it decides which optional outputs
+    are produced)."""
     r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
                                    temperatures)
     need = lmhead_workspace_bytes(N, V, d)
@@ -487,36 +508,21 @@ def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     elif workspace.device != dev or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
         raise ValueError("workspace must be a contiguous uint8 tensor on the device of hidden")
-    g, i = _lmhead_out(out, N, dev)
-    with torch.cuda.device(dev):
-        rc = lib.difr_lmhead_score(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
-                                   _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]), _ptr(i["cdf_lo"]),
-                                   _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]), _ptr(workspace),
-                                   workspace.numel(), _stream_ptr(dev))
-    if rc:
-        raise DifrError(rc, "difr_lmhead_score")
-    return g, i
+    g, i = _lmhead_out(out, N, dev, want_rank, want_log_mass)
+    return _lmhead_call("difr_lmhead_score", (_ptr(workspace), workspace.numel()), r, g, i, sigma, eps, dev)
 
 
 LMHEAD_STATIC_SCRATCH_BYTES = 4 << 20
 
 
 def lmhead_score_static(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-                        temperatures=None, out=None):
+                        temperatures=None, out=None, want_rank=False, want_log_mass=False, sigma=0.01, eps=1e-30):
     """difr_lmhead_score_static: lmhead_score without a workspace (the library's built-in buffer serves; calls that
     overlap in time on one GPU race on it).  With `out` given (lmhead_outputs()) nothing is allocated at all."""
-    lib = load_library()
     r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
                                    temperatures)
-    g, i = _lmhead_out(out, N, dev)
-    with torch.cuda.device(dev):
-        rc = lib.difr_lmhead_score_static(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
-                                          _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(i["dist"]),
-                                          _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), _ptr(i["flags"]),
-                                          _stream_ptr(dev))
-    if rc:
-        raise DifrError(rc, "difr_lmhead_score_static")
-    return g, i
+    g, i = _lmhead_out(out, N, dev, want_rank, want_log_mass)
+    return _lmhead_call("difr_lmhead_score_static", (), r, g, i, sigma, eps, dev)
 
 
 def seq_reduce(scores, row_flags, seq_offsets, threshold):

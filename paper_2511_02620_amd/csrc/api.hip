@@ -132,12 +132,14 @@ size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d)
 }
 
 int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
-                      uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                      uint8_t *flags_ipt, void *workspace, size_t workspace_bytes, void *hip_stream)
+                      uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo, float *cdf_hi, float *u,
+                      double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
+                      size_t workspace_bytes, void *hip_stream)
 {
     difr::LmHeadBatch b;
     int rc = validate_lmhead(in, &b);
     if (rc != DIFR_OK) return rc;
+    if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt || !workspace) return DIFR_ERR_NULL;
     const difr::LmHeadPlan plan = difr::lmhead_plan(b.N, b.V);
@@ -145,18 +147,20 @@ int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, flo
     if (workspace_bytes < difr::lmhead_workspace_bytes(b.N, plan.splits)) return DIFR_ERR_SHAPE;
     if ((rc = check_device()) != DIFR_OK) return rc;
     const difr::LmHeadWorkspace ws = difr::lmhead_carve(workspace, b.N, plan.splits);
-    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
-    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, sigma, eps, log_mass, flags_ipt, nullptr};
     return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 
 int difr_lmhead_score_static(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score,
-                             float *claimed_score, uint8_t *flags_gumbel, float *dist, float *cdf_lo, float *cdf_hi,
-                             float *u, uint8_t *flags_ipt, void *hip_stream)
+                             float *claimed_score, uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo,
+                             float *cdf_hi, float *u, double sigma, double eps, float *log_mass, uint8_t *flags_ipt,
+                             void *hip_stream)
 {
     difr::LmHeadBatch b;
     int rc = validate_lmhead(in, &b);
     if (rc != DIFR_OK) return rc;
+    if (log_mass && (!(sigma > 0.0) || !isfinite(sigma) || !(eps >= 0.0) || !isfinite(eps))) return DIFR_ERR_ARGUMENT;
     if (b.N == 0) return DIFR_OK;
     if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt) return DIFR_ERR_NULL;
     const difr::LmHeadPlan plan = difr::lmhead_plan(b.N, b.V);
@@ -165,8 +169,8 @@ int difr_lmhead_score_static(const difr_lmhead *in, float *margin, int32_t *argm
     void *ws_base = static_scratch();
     if (!ws_base) return DIFR_ERR_LAUNCH;
     const difr::LmHeadWorkspace ws = difr::lmhead_carve(ws_base, b.N, plan.splits);
-    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, nullptr};
-    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, 0.0, 0.0, nullptr, flags_ipt, nullptr};
+    const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, sigma, eps, log_mass, flags_ipt, nullptr};
     return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 

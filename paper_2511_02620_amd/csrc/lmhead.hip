@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_prepare_kernel(LmHeadBatch b, L
     const int64_t n = (int64_t)blockIdx.x * kWaves + (threadIdx.x >> 6);
     if (n >= b.N) return;  // uniform per wave
     const TokInfo t = load_tok(b, n);
-    float L0 = -__builtin_inff();
+    float L0 = -__builtin_inff(), x_ref = __builtin_nanf("");
     if (t.ok && t.tg >= 0) {
         const uint16_t *h = b.hidden + n * b.ldh;
         const uint16_t *w = b.weight + (int64_t)t.tg * b.ldw;
@@ -120,6 +120,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_prepare_kernel(LmHeadBatch b, L
         }
         dot = wave_sum(dot);
         mag = wave_sum(mag);
+        x_ref = dot;
         const float y = perturbed_score(dot, t.inv_T, noise_word_of(t, kStreamGumbel, t.tg));
         // any two fp32 summation orders of d products differ by at most ~2 d 2^-24 sum|h w|; twice that here
         const float slack = 1e-3f + 1e-5f * fabsf(y) + t.inv_T * mag * (float)b.d * 0x1p-22f;
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_prepare_kernel(LmHeadBatch b, L
     }
     if (lane == 0) {
         ws.L0[n] = L0;
+        ws.x_claim_ref[n] = x_ref;
         ws.x_claim_gumbel[n] = __builtin_nanf("");
         ws.x_claim_ipt[n] = __builtin_nanf("");
     }
@@ -142,6 +144,7 @@ struct Slot {
     float L;      // lower bound on the row's best score: max(bound from the claim, best seen by this lane)
     float m;      // largest logit seen by this lane for this token
     double Z, P;  // sum of 2^((x - m) c) over all entries seen / over those below the IPT claim
+    uint32_t above;  // RANK: entries seen whose logit exceeds the reference value of the Token-DiFR claim's
 };
 
 // Noise gate: an entry with noise word r < rgate cannot reach L whatever its logit (all logits seen
@@ -163,6 +166,7 @@ struct BlockCtx {
     float Lgate;   // L minus slack
     uint32_t rgate;
     bool live;     // the lane's token row exists (n < N)
+    float x_ref;   // RANK: the Token-DiFR claim's logit as a plain dot product (NaN: no claim, nothing counts)
 };
 
 __device__ __forceinline__ void refresh_gates(const Slot &s, BlockCtx &k)
@@ -173,6 +177,12 @@ __device__ __forceinline__ void refresh_gates(const Slot &s, BlockCtx &k)
 
 // Score one 32x32 accumulator block: this lane's 16 entries are the logits of ONE token at
 // vocabulary rows v(r) = vlane + 8 (r / 4) + (r % 4).
+//
+// RANK: also count the entries whose logit exceeds the Token-DiFR claim's (logit rank, Sec. 7.1).  The claim's
+// logit must be known before the first tile, so the count is made against its plain fp32 dot product from the
+// preparation kernel; the claimed entry itself is left out by index (its matrix-core value may differ from that
+// reference in the last bits).
+template <bool RANK>
 __device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx &k, int32_t vlane, int32_t V,
                                             bool ragged, int64_t n, const LmHeadWorkspace &ws)
 {
@@ -186,6 +196,10 @@ __device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx 
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (vlane + 8 * (r >> 2) + (r & 3) >= V) x[r] = ninf;
+    }
+    if (RANK) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s.above += (uint32_t)(x[r] > k.x_ref);  // rows past V are -inf, a NaN counts nothing
     }
     // ---- Token-IPT-DiFR: online softmax sums ----
     float bm = max3_raw(x[0], x[1], x[2]);
@@ -226,6 +240,7 @@ __device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx 
                 if (straddle && v < k.t.ti) ps += e[r];
                 if (k.live && v == k.t.ti) ws.x_claim_ipt[n] = x[r];
                 if (k.live && v == k.t.tg) ws.x_claim_gumbel[n] = x[r];
+                if (RANK && v == k.t.tg && x[r] > k.x_ref) s.above -= 1u;  // the claim does not outrank itself
             }
         }
     }
@@ -280,13 +295,14 @@ __device__ __forceinline__ void merge_softmax(float &m, double &Z, double &P, fl
 // permuted by (row / 2) % 8 so that both the 16-byte slab writes and the fragment reads of 16
 // consecutive rows spread over all 64 banks.
 // ---------------------------------------------------------------------------------
+template <bool RANK>
 __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, LmHeadWorkspace ws, LmHeadPlan plan)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];  // 32 KB per stage
     __shared__ __attribute__((aligned(16))) uint16_t lds_h[2][kLmTileT * kLmTileK];
     // per-token constants of the workgroup's 256 token rows (one wave per SIMD cannot hide a global load
     // in the epilogue, an LDS read it can): key, position, sequence, 1/T, the two claims
-    __shared__ uint32_t lds_tok[7][kLmTileT];
+    __shared__ uint32_t lds_tok[RANK ? 8 : 7][kLmTileT];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wv = wave >> 1, wt = wave & 1;  // vocabulary half, token half
@@ -400,6 +416,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         lds_tok[4][tid] = __float_as_uint(t.inv_T);
         lds_tok[5][tid] = (uint32_t)t.tg;
         lds_tok[6][tid] = (uint32_t)t.ti;
+        if (RANK) lds_tok[7][tid] = __float_as_uint(ws.x_claim_ref[n]);
     }
     auto tok_from_lds = [&](int i) {
         TokInfo t;
@@ -428,6 +445,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         slot[jb].m = -__builtin_inff();
         slot[jb].Z = 0.0;
         slot[jb].P = 0.0;
+        slot[jb].above = 0u;
     }
 
     // ---- main loop ----
@@ -507,14 +525,15 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         auto score_token = [&](auto JB) {
             constexpr int jb = decltype(JB)::value;
             const TokInfo t = tok_from_lds(wt * 128 + jb * 32 + l32);
-            BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_is_live(jb)};
+            BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_is_live(jb),
+                       RANK ? __uint_as_float(lds_tok[RANK ? 7 : 0][wt * 128 + jb * 32 + l32]) : 0.0f};
             k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
             refresh_gates(slot[jb], k);
             const int32_t vl = (int32_t)v0 + wv * 128 + 4 * lh;
-            score_block(acc[0][jb], slot[jb], k, vl, V, ragged, tok_row(jb), ws);
-            score_block(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_row(jb), ws);
-            score_block(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_row(jb), ws);
-            score_block(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_row(jb), ws);
+            score_block<RANK>(acc[0][jb], slot[jb], k, vl, V, ragged, tok_row(jb), ws);
+            score_block<RANK>(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_row(jb), ws);
+            score_block<RANK>(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_row(jb), ws);
+            score_block<RANK>(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_row(jb), ws);
         };
         score_token(std::integral_constant<int, 0>());
         score_token(std::integral_constant<int, 1>());
@@ -528,6 +547,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
     float *ex_m = reinterpret_cast<float *>(ex_v + 256);
     double *ex_Z = reinterpret_cast<double *>(ex_m + 256);
     double *ex_P = ex_Z + 256;
+    uint32_t *ex_a = reinterpret_cast<uint32_t *>(ex_P + 256);
     float tok_c[4];
 #pragma unroll
     for (int jb = 0; jb < 4; ++jb) {
@@ -537,6 +557,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
         const int32_t ov = __shfl_xor(s.best_v, 32, 64);
         const float om = __shfl_xor(s.m, 32, 64);
         const double oZ = __shfl_xor(s.Z, 32, 64), oP = __shfl_xor(s.P, 32, 64);
+        if (RANK) s.above += (uint32_t)__shfl_xor((int)s.above, 32, 64);
         if (lh == 0) {  // rows 0-3 (mod 8) first, then rows 4-7: a fixed order
             argmax_combine(s.best_y, s.best_v, oy, ov);
             merge_softmax(s.m, s.Z, s.P, om, oZ, oP, tok_c[jb]);
@@ -553,6 +574,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             ex_m[i] = slot[jb].m;
             ex_Z[i] = slot[jb].Z;
             ex_P[i] = slot[jb].P;
+            if (RANK) ex_a[i] = slot[jb].above;
         }
     }
     __syncthreads();
@@ -570,6 +592,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             ws.m[o] = s.m;
             ws.Z[o] = s.Z;
             ws.P[o] = s.P;
+            if (RANK) ws.above[o] = (int32_t)(s.above + ex_a[i]);
         }
     }
 }
@@ -594,10 +617,12 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
         if (og.max_score) og.max_score[n] = nan;
         if (og.claimed_score) og.claimed_score[n] = nan;
         og.flags[n] = f;
+        if (og.logit_rank) og.logit_rank[n] = -1;
         oi.dist[n] = nan;
         if (oi.cdf_lo) oi.cdf_lo[n] = nan;
         if (oi.cdf_hi) oi.cdf_hi[n] = nan;
         if (oi.u) oi.u[n] = nan;
+        if (oi.log_mass) oi.log_mass[n] = nan;
         oi.flags[n] = f;
         return;
     }
@@ -605,10 +630,12 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
     float best_y = ninf, m = ninf;
     int32_t best_v = 0x7FFFFFFF;
     double Z = 0.0, P = 0.0;
+    int32_t above = 0;
     for (int sp = 0; sp < splits; ++sp) {
         const int64_t o = (int64_t)sp * b.N + n;
         argmax_combine(best_y, best_v, ws.best_y[o], ws.best_v[o]);
         merge_softmax(m, Z, P, ws.m[o], ws.Z[o], ws.P[o], c);
+        if (og.logit_rank) above += ws.above[o];
     }
     if (best_v == 0x7FFFFFFF) best_v = 0;
     const bool ipt_bad = !(Z > 0.0) || !(Z < (double)__builtin_inff()) || !(m < __builtin_inff()) || !(m > ninf);
@@ -629,12 +656,13 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
     if (og.max_score) og.max_score[n] = best_y;
     if (og.claimed_score) og.claimed_score[n] = yt;
     og.flags[n] = (uint8_t)fg;
+    if (og.logit_rank) og.logit_rank[n] = t.tg >= 0 ? above : -1;
 
     // Token-IPT-DiFR
     uint32_t r[4];
     noise_block(t.key, t.pos, t.seq, kStreamIpt, 0u, r);
     const float u = uniform_from_bits(r[0]);
-    float a = nan, bb = nan, dd = nan;
+    float a = nan, bb = nan, dd = nan, lm = nan;
     bool match = false;
     if (t.ti >= 0 && !ipt_bad) {
         const double et = (double)fast_exp2(__fmaf_rn(ws.x_claim_ipt[n], c, -(m * c)));
@@ -644,6 +672,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
         bb = (float)bd;
         dd = (float)fmax(fmax(ad - ud, ud - bd), 0.0);
         match = (ad <= ud) && (ud < bd);
+        if (oi.log_mass) lm = (float)gaussian_log_mass(ad, bd, ud, oi.sigma, oi.eps);
     }
     uint32_t fi = 0;
     if (t.ti < 0) fi |= kFlagInvalidClaim;
@@ -653,6 +682,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
     if (oi.cdf_lo) oi.cdf_lo[n] = a;
     if (oi.cdf_hi) oi.cdf_hi[n] = bb;
     if (oi.u) oi.u[n] = u;
+    if (oi.log_mass) oi.log_mass[n] = lm;
     oi.flags[n] = (uint8_t)fi;
 }
 
@@ -661,7 +691,10 @@ int launch_lmhead_score(const LmHeadBatch &b, const LmHeadWorkspace &ws, const L
 {
     lmhead_prepare_kernel<<<dim3((unsigned)((b.N + kWaves - 1) / kWaves)), dim3(kBlock), 0, stream>>>(b, ws);
     if (hipGetLastError() != hipSuccess) return 1;
-    lmhead_score_kernel<<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
+    if (og.logit_rank)  // counted in the scoring pass, only when asked for
+        lmhead_score_kernel<true><<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
+    else
+        lmhead_score_kernel<false><<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
     if (hipGetLastError() != hipSuccess) return 1;
     lmhead_finalize_kernel<<<dim3((unsigned)((b.N + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(b, ws, plan.splits,
                                                                                                     og, oi);

@@ -54,14 +54,16 @@ struct LmHeadWorkspace {
     float *m;              // [splits][N]  largest logit seen
     float *best_y;         // [splits][N]  best perturbed score
     int32_t *best_v;       // [splits][N]  and its token
+    int32_t *above;        // [splits][N]  entries whose logit exceeds the Token-DiFR claim's (logit rank; only if asked for)
     float *L0;             // [N] lower bound on the row's best perturbed score (-inf if none)
     float *x_claim_gumbel; // [N] logit of the Token-DiFR claim as the tile that holds it computed it (NaN until then)
     float *x_claim_ipt;    // [N] same for the Token-IPT-DiFR claim
+    float *x_claim_ref;    // [N] logit of the Token-DiFR claim as a plain fp32 dot product (NaN without a claim)
 };
 
 inline size_t lmhead_workspace_bytes(int64_t N, int splits)
 {
-    return (size_t)N * (size_t)splits * (8 + 8 + 4 + 4 + 4) + (size_t)N * 12 + 64;
+    return (size_t)N * (size_t)splits * (8 + 8 + 4 + 4 + 4 + 4) + (size_t)N * 16 + 64;
 }
 
 inline LmHeadWorkspace lmhead_carve(void *base, int64_t N, int splits)
@@ -79,11 +81,15 @@ inline LmHeadWorkspace lmhead_carve(void *base, int64_t N, int splits)
     p += n * 4;
     w.best_v = (int32_t *)p;
     p += n * 4;
+    w.above = (int32_t *)p;
+    p += n * 4;
     w.L0 = (float *)p;
     p += (size_t)N * 4;
     w.x_claim_gumbel = (float *)p;
     p += (size_t)N * 4;
     w.x_claim_ipt = (float *)p;
+    p += (size_t)N * 4;
+    w.x_claim_ref = (float *)p;
     return w;
 }
 

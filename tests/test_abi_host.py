@@ -192,9 +192,13 @@ def test_argument_validation_needs_no_device(lib):
             setattr(r, k, v)
         return r
 
-    def lms(r, ws=fake, ws_bytes=1 << 20, margin=fake):
-        return lib.difr_lmhead_score(C.byref(r), margin, fake, None, None, fake, fake, None, None, None, fake, ws,
-                                     ws_bytes, None)
+    def lms(r, ws=fake, ws_bytes=1 << 20, margin=fake, sigma=0.01, lm_out=None):
+        return lib.difr_lmhead_score(C.byref(r), margin, fake, None, None, fake, None, fake, None, None, None, sigma, 1e-30,
+                                     lm_out, fake, ws, ws_bytes, None)
+
+    def lmst(r, margin=fake, sigma=0.01, lm_out=None):
+        return lib.difr_lmhead_score_static(C.byref(r), margin, fake, None, None, fake, None, fake, None, None, None, sigma,
+                                            1e-30, lm_out, fake, None)
 
     need = lib.difr_lmhead_workspace_bytes(4, 100, 128)
     assert 0 < need < 1 << 20 and lib.difr_lmhead_workspace_bytes(0, 100, 128) == 0
@@ -208,7 +212,13 @@ def test_argument_validation_needs_no_device(lib):
     assert lms(lm(), ws=None) == NULL and lms(lm(), margin=None) == NULL
     assert lms(lm(), ws=0x1004) == ALIGN and lms(lm(), ws_bytes=need - 1) == SHAPE
     assert lms(lm(N=0, hidden=None), ws=None) == OK
-    assert lib.difr_lmhead_score(None, fake, fake, None, None, fake, fake, None, None, None, fake, fake, 64, None) == NULL
+    assert lms(lm(), sigma=0.0, lm_out=fake) == ARG and lms(lm(), sigma=0.0) != ARG
+    assert lib.difr_lmhead_score(None, fake, fake, None, None, fake, None, fake, None, None, None, 0.01, 1e-30, None, fake,
+                                 fake, 64, None) == NULL
+    # the variant with the built-in buffer: same validation, and a batch beyond its 4 MiB is refused on the host
+    assert lmst(lm(N=-1)) == SHAPE and lmst(lm(hidden=None)) == NULL and lmst(lm(), margin=None) == NULL
+    assert lmst(lm(), sigma=0.0, lm_out=fake) == ARG and lmst(lm(N=0, hidden=None)) == OK
+    assert lmst(lm(N=120000)) == 9 and b"built-in" in lib.difr_status_string(9)
     assert lib.difr_debug_noise(C.byref(rows()), 4, 0, fake, None) == SHAPE
     assert lib.difr_debug_gumbel_map(None, 4, fake, None) == NULL
 

@@ -41,6 +41,29 @@ def _case(S, L, V, d, T=1.0, w_sigma=None):
                                w_sigma=(2.0 / d ** 0.5) if w_sigma is None else w_sigma)
 
 
+def _check_rank(rank, x_oracle, claims, V, tol):
+    """The fused path counts the logits above the claim's against fp32 values that carry the matrix cores'
+    accumulation error: its count must lie between the oracle's counts with the claim's logit moved by -/+ tol
+    (the claimed entry left out), equal the oracle's rank (Sec. 7.1) where those agree, and be -1 without a claim."""
+    n_exact = n_doubt = n_equal = 0
+    for n in range(rank.shape[0]):
+        t = -1 if claims is None else int(claims[n])
+        want = oracle.logit_rank_row(x_oracle[n], t)
+        if want < 0:
+            assert rank[n] == -1, (n, rank[n])
+            continue
+        x = x_oracle[n]
+        others = np.delete(x, t)
+        lo, hi = int((others > x[t] + tol).sum()), int((others > x[t] - tol).sum())
+        assert lo <= want <= hi and lo <= rank[n] <= hi, (n, rank[n], want, lo, hi)
+        n_equal += int(rank[n] == want)
+        if lo == hi:
+            n_exact += 1
+        else:
+            n_doubt += 1
+    return {"rows": int(rank.shape[0]), "pinned": n_exact, "another_logit_within_tol": n_doubt, "equal_to_oracle": n_equal}
+
+
 @pytest.mark.parametrize("S,L,V,d,mode", [
     (2, 150, 1000, 128, "mutated"),       # 2 token blocks (second ragged), 4 tiles (last ragged), 4 ranges
     (1, 256, 2088, 256, "honest"),        # exactly one token block, 9 tiles
@@ -76,20 +99,25 @@ def test_lmhead_every_row(difr, S, L, V, d, mode):
         cg[::3] = -1; ci[1::3] = V; cg[2::3] = V + 7
     elif mode == "sampling":
         cg = ci = None
-    g, i = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, temperatures=temps)
+    g, i = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, temperatures=temps, want_rank=True,
+                             want_log_mass=True, sigma=0.02)
     torch.cuda.synchronize()
-    og, oi = oracle.lmhead_score(bits(Hv), bits(Wm), np.float32(wl.temperature), hs, hsid, hpos,
-                                 None if cg is None else cg.cpu().numpy(), None if ci is None else ci.cpu().numpy(),
-                                 temperatures=htemps)
+    og, oi, ox = oracle.lmhead_score(bits(Hv), bits(Wm), np.float32(wl.temperature), hs, hsid, hpos,
+                                     None if cg is None else cg.cpu().numpy(), None if ci is None else ci.cpu().numpy(),
+                                     temperatures=htemps, sigma=0.02, want_logits=True)
+    rank = g.pop("logit_rank").cpu().numpy()
     sg = parity.compare_gumbel(g, og, tie_rel=TIE)
-    si = parity.compare_ipt(i, oi, tie_rel=TIE)
+    si = parity.compare_ipt(i, oi, tie_rel=TIE, log_mass_sigma=0.02)
     say("  gumbel", sg, "ipt", si)
+    assert si["log_mass_beyond_bar"] == 0
+    say("  logit rank:", _check_rank(rank, ox, None if cg is None else cg.cpu().numpy(), V, TIE))
     if mode == "honest":
         # the verifier's hidden states differ from the prover's by drift only: most claims still match
         assert float((g["flags"] & 1).float().mean()) > 0.9
     # same call again: bit-identical
     g2, i2 = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, temperatures=temps)
     torch.cuda.synchronize()
+    i.pop("log_mass")                        # the optional outputs change nothing else
     for a, b in ((g, g2), (i, i2)):
         for key in a:
             assert torch.equal(torch.nan_to_num(a[key].float(), nan=-7.0), torch.nan_to_num(b[key].float(), nan=-7.0)), key
@@ -220,9 +248,12 @@ def test_lmhead_full_size_sampled_rows(difr):
     claim_range = np.minimum(forced_g // (tiles_per_range * 256), 3)
     assert set(claim_range.tolist()) == {0, 1, 2, 3} and (forced_g >= V - 128).any() and (forced_i >= V - 128).any()
     say("C4 full size: scoring")
-    g, i = difr.lmhead_score(Hv, Wm, T, seeds, sid, pos, cg, ci)
+    g, i = difr.lmhead_score(Hv, Wm, T, seeds, sid, pos, cg, ci, want_rank=True, want_log_mass=True)
     g2, i2 = difr.lmhead_score(Hv, Wm, T, seeds, sid, pos, cg, ci)
     torch.cuda.synchronize()
+    rank_all = g.pop("logit_rank")
+    log_mass_all = i.pop("log_mass")
+    assert ((rank_all >= 0) & (rank_all < V)).all() and torch.isfinite(log_mass_all).all()
     for a, b in ((g, g2), (i, i2)):
         for key in a:
             assert torch.equal(torch.nan_to_num(a[key].float(), nan=-7.0), torch.nan_to_num(b[key].float(), nan=-7.0)), key
@@ -239,11 +270,30 @@ def test_lmhead_full_size_sampled_rows(difr):
     # of the partial sums; near-tie rule at 1e-4 (the same size as the score tolerance).
     say("C4 full size: oracle on %d rows" % len(rows))
     sel = torch.from_numpy(rows).to(DEV)
-    og, oi = oracle.lmhead_score(bits(Hv[sel]), Wb, np.float32(T), hs, hsid[rows], hpos[rows],
-                                 cg[sel].cpu().numpy(), ci[sel].cpu().numpy())
+    og, oi, ox = oracle.lmhead_score(bits(Hv[sel]), Wb, np.float32(T), hs, hsid[rows], hpos[rows],
+                                     cg[sel].cpu().numpy(), ci[sel].cpu().numpy(), want_logits=True)
     sg = parity.compare_gumbel({k2: v[sel] for k2, v in g.items()}, og, tie_rel=1e-4)
-    si = parity.compare_ipt({k2: v[sel] for k2, v in i.items()}, oi)      # CDF values agree to ~1e-7: default tie width
+    i_sel = {k2: v[sel] for k2, v in i.items()}
+    i_sel["log_mass"] = log_mass_all[sel]
+    si = parity.compare_ipt(i_sel, oi, log_mass_sigma=0.01)      # CDF values agree to ~1e-7: default tie width
     say("  gumbel", sg, "ipt", si)
+    assert si["log_mass_beyond_bar"] == 0
+    # logit rank of the Token-DiFR claims: 151,936 logits are about as dense as 50,000 per unit around a typical
+    # claim, so most rows have another logit within 2e-5 (five times the observed accumulation error) of the
+    # claim's and the bracket is all that pins them; how many ranks equal the oracle's exactly is reported
+    st_r = _check_rank(rank_all[sel].cpu().numpy(), ox, cg[sel].cpu().numpy(), V, 2e-5)
+    say("  logit rank:", st_r)
+    # ... which is what feeds the score-and-rank classifier (Sec. 7.1): every row classified from this one call's
+    # outputs; against the oracle's classes on the oracle rows whose rank is not in doubt
+    tau_c, R = np.float32(0.5), 8
+    cl = difr.classify(g["margin"], rank_all, float(tau_c), R, V)
+    want_rank = np.array([oracle.logit_rank_row(ox[j], int(cg[sel][j])) for j in range(len(rows))], dtype=np.int32)
+    ref = oracle.classify(og["margin"], want_rank, tau_c, R, V)
+    sure = (rank_all[sel].cpu().numpy() == want_rank) & (np.abs(og["margin"] - tau_c) > 1e-4)
+    assert np.array_equal(cl["cls"][sel].cpu().numpy()[sure], ref["cls"][sure])
+    say("  classes on %d oracle rows (SAFE/SUSPICIOUS/DANGEROUS):" % int(sure.sum()),
+        np.bincount(ref["cls"][sure], minlength=3).tolist(), "all rows:", torch.bincount(cl["cls"].long(), minlength=3).tolist())
+    del ox
     # the near-tie width here is the size of the logits' fp32 accumulation error, 100 times the stored-logit width:
     # say how many decisions it excused, and how many the stored-logit width would have
     strict = int((og["gap2"] < 1e-6 * np.maximum(1.0, np.abs(og["max_score"]))).sum())

@@ -51,7 +51,7 @@ def test_static_equals_workspace_twice(difr):
     outs = {}
     for name, (wl, Hv, Wm, seeds, sid, pos, cg, ci) in (("big", big), ("small", small)):
         say("no-alloc case", name, wl.N, wl.V, wl.d)
-        outs[name] = difr.lmhead_outputs(wl.N, torch.device(DEV))
+        outs[name] = difr.lmhead_outputs(wl.N, torch.device(DEV), want_rank=True, want_log_mass=True)
     # honest half: the sampler's own tokens as claims on every other row, so that matches occur too
     for wl, Hv, Wm, seeds, sid, pos, cg, ci in (big, small):
         g0, _ = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, None, None)
@@ -64,7 +64,7 @@ def test_static_equals_workspace_twice(difr):
     torch.cuda.synchronize()
     assert torch.cuda.memory_allocated() == before, "the binding allocated device memory around the static call"
     for name, (wl, Hv, Wm, seeds, sid, pos, cg, ci) in (("big", big), ("small", small)):
-        want = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci)
+        want = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, want_rank=True, want_log_mass=True)
         torch.cuda.synchronize()
         _same(got[name], want, name)
         f = got[name][0]["flags"].cpu().numpy()
@@ -72,14 +72,14 @@ def test_static_equals_workspace_twice(difr):
         assert (f & difr.FLAG_MATCH).sum() >= wl.N // 2 - 2
     # and once more in the other order, the big batch over the small one's leftovers
     wl, Hv, Wm, seeds, sid, pos, cg, ci = big
-    again = difr.lmhead_score_static(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci)
+    again = difr.lmhead_score_static(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, want_rank=True, want_log_mass=True)
     torch.cuda.synchronize()
     _same(again, got["big"], "big after small")
 
 
 def test_static_refuses_what_does_not_fit(difr):
     lib = difr.load_library()
-    # 120,000 tokens need 120000 * 40 + 64 bytes > 4 MiB: refused on the host, before any pointer is looked at
+    # 120,000 tokens need 120000 * 48 + 64 bytes > 4 MiB: refused on the host, before any pointer is looked at
     N, V, d = 120000, 4096, 64
     assert difr.lmhead_workspace_bytes(N, V, d) > 4 << 20
     from paper_2511_02620_amd.binding import _LmHead
@@ -89,7 +89,8 @@ def test_static_refuses_what_does_not_fit(difr):
     r.hidden = r.weight = r.seeds = r.seq_ids = r.positions = p
     r.N, r.V, r.d, r.ldh, r.ldw, r.S, r.temperature = N, V, d, d, d, 1, 1.0
     out = C.c_void_p(p)
-    rc = lib.difr_lmhead_score_static(C.byref(r), out, out, None, None, out, out, None, None, None, out, None)
+    rc = lib.difr_lmhead_score_static(C.byref(r), out, out, None, None, out, None, out, None, None, None, 0.01, 1e-30, None,
+                                      out, None)
     assert rc == 9, rc
     assert b"built-in" in lib.difr_status_string(rc)
     torch.cuda.synchronize()
