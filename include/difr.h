@@ -320,11 +320,17 @@ int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, 
  *         16-byte aligned (else DIFR_ERR_SHAPE / DIFR_ERR_ALIGN).  N, V < 2^31; ldh, ldw < 2^23.
  * claimed_gumbel / claimed_ipt  DEVICE [N] or NULL: the claims scored by Token-DiFR and by
  *         Token-IPT-DiFR.  The remaining fields are those of difr_rows.
- * Outputs: those of difr_score_both, with the same optionality and flag bits, except the sampler's
- *         own Token-IPT-DiFR token (it needs the row's total mass before its position in the CDF
- *         can be found: on logits that are never stored that is a second product).  Because
+ * Outputs: those of difr_score_both, with the same optionality and flag bits.  Because
  *         the fp32 accumulation order of a matrix-core product is not the oracle's, logits carry
  *         an error of a few 1e-6 relative to sum_k |h_k w_k|; scores inherit it.
+ *         ipt_token [N] int32 or NULL: the token the honest inverse-CDF sampler draws.  Its position
+ *         needs the row's total mass, which is known only after the last tile of logits that are
+ *         never stored: when asked for, the scoring pass also leaves the softmax mass of every half
+ *         tile (128 entries) of every token in the workspace (16 bytes per token and 256 vocabulary
+ *         entries: 156 MB at N = 16384, V = 151936), the merge finds the half tile in which the CDF
+ *         passes u, and one more kernel forms that half tile's 128 logits again as plain dot products
+ *         (DIFR_FLAG_SLOW_PATH; about 1 MB of LM-head rows read per token) and finds the entry.  Rows
+ *         whose claim matches skip it: their token is the claim.
  *         logit_rank [N] int32 or NULL: entries whose logit exceeds the Token-DiFR claim's (Sec. 7.1),
  *         counted in the same pass against the claim's logit formed as a plain fp32 dot product (it has
  *         to be known before the first tile); the claimed entry is left out by index.  A logit within
@@ -332,10 +338,10 @@ int difr_score_both_admissible(const difr_rows *in, const int32_t *claimed_ipt, 
  *         those entries.  -1 for an invalid claim.  Asking for it costs a few per cent.
  *         sigma, eps, log_mass: as in difr_ipt_score (the paper's Token-IPT-DiFR score, fp64 from the
  *         fp64 interval).
- * workspace  DEVICE scratch of at least difr_lmhead_workspace_bytes(N, V, d) bytes, 8-byte
- *         aligned, owned by the caller, contents irrelevant before and after the call; calls that
- *         overlap in time need distinct workspaces.  Too small: DIFR_ERR_SHAPE.
- * Three kernels are enqueued on hip_stream (claim bound, GEMM + scoring, merge); no sync.
+ * workspace  DEVICE scratch of at least difr_lmhead_workspace_bytes(N, V, d, ipt_token != NULL)
+ *         bytes, 8-byte aligned, owned by the caller, contents irrelevant before and after the call;
+ *         calls that overlap in time need distinct workspaces.  Too small: DIFR_ERR_SHAPE.
+ * Three kernels are enqueued on hip_stream (claim bound, GEMM + scoring, merge), four with ipt_token; no sync.
  */
 typedef struct {
     const void *hidden;
@@ -351,21 +357,22 @@ typedef struct {
     const int32_t *claimed_ipt;
 } difr_lmhead;
 
-/* Host only, no device needed.  0 for N == 0 or arguments difr_lmhead_score would reject. */
-size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d);
+/* Host only, no device needed.  0 for N == 0 or arguments difr_lmhead_score would reject.
+ * want_ipt_token != 0: with room for what the ipt_token output needs. */
+size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d, int32_t want_ipt_token);
 
 int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
                       uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                      double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
+                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
                       size_t workspace_bytes, void *hip_stream);
 
 /*
  * difr_lmhead_score for callers that cannot allocate device memory or hand over a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, same
- * outputs, same kernels; the partial results of the vocabulary ranges go to a buffer that is part of
+ * outputs but ipt_token (what that output needs does not fit a built-in buffer), same kernels; the partial results of the vocabulary ranges go to a buffer that is part of
  * the library's device image (DIFR_LMHEAD_STATIC_SCRATCH_BYTES per GPU the library runs on, held until
  * the process ends) instead of a caller workspace.  The call allocates and frees nothing.
- *   - A batch with difr_lmhead_workspace_bytes(N, V, d) > DIFR_LMHEAD_STATIC_SCRATCH_BYTES is refused
+ *   - A batch with difr_lmhead_workspace_bytes(N, V, d, 0) > DIFR_LMHEAD_STATIC_SCRATCH_BYTES is refused
  *     with DIFR_ERR_CAPACITY and nothing is launched.  The 4 MiB hold every batch of up to 87,000
  *     tokens at any V (32 bytes per token and vocabulary range, at most 65,536 such pairs below
  *     65,536 tokens and one range per token above, plus 16 bytes per token).

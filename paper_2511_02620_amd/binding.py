@@ -112,9 +112,9 @@ def load_library():
     lib.difr_score_both_filtered.restype = C.c_int
     lib.difr_admissible_count.argtypes = [C.POINTER(_Rows), vp, C.c_float, vp, vp, vp]
     lib.difr_admissible_count.restype = C.c_int
-    lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64]
+    lib.difr_lmhead_workspace_bytes.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_int32]
     lib.difr_lmhead_workspace_bytes.restype = C.c_size_t
-    lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 10 + [C.c_double, C.c_double, vp, vp, vp, C.c_size_t, vp]
+    lib.difr_lmhead_score.argtypes = [C.POINTER(_LmHead)] + [vp] * 11 + [C.c_double, C.c_double, vp, vp, vp, C.c_size_t, vp]
     lib.difr_lmhead_score.restype = C.c_int
     lib.difr_lmhead_score_static.argtypes = [C.POINTER(_LmHead)] + [vp] * 10 + [C.c_double, C.c_double, vp, vp, vp]
     lib.difr_lmhead_score_static.restype = C.c_int
@@ -419,8 +419,8 @@ def admissible_count(logits, temperature, seeds, seq_ids, positions, max_score, 
     return out
 
 
-def lmhead_workspace_bytes(N, V, d) -> int:
-    return int(load_library().difr_lmhead_workspace_bytes(int(N), int(V), int(d)))
+def lmhead_workspace_bytes(N, V, d, want_token=False) -> int:
+    return int(load_library().difr_lmhead_workspace_bytes(int(N), int(V), int(d), int(bool(want_token))))
 
 
 def _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt, temperatures):
@@ -457,22 +457,24 @@ _LMHEAD_OUT = (("margin", torch.float32), ("argmax", torch.int32), ("max_score",
                ("claimed_score", torch.float32), ("flags", torch.uint8)), (
     ("dist", torch.float32), ("cdf_lo", torch.float32), ("cdf_hi", torch.float32), ("u", torch.float32),
     ("flags", torch.uint8))
-_LMHEAD_OPT = (("logit_rank", torch.int32),), (("log_mass", torch.float32),)
+_LMHEAD_OPT = (("logit_rank", torch.int32),), (("log_mass", torch.float32), ("ipt_token", torch.int32))
 
 
-def lmhead_outputs(N, device, want_rank=False, want_log_mass=False):
+def lmhead_outputs(N, device, want_rank=False, want_log_mass=False, want_token=False):
     """Output buffers of lmhead_score / lmhead_score_static, allocated once and reusable across calls."""
     g, i = tuple({k: torch.empty(N, dtype=dt, device=device) for k, dt in part} for part in _LMHEAD_OUT)
     if want_rank:
         g["logit_rank"] = torch.empty(N, dtype=torch.int32, device=device)
     if want_log_mass:
         i["log_mass"] = torch.empty(N, dtype=torch.float32, device=device)
+    if want_token:
+        i["ipt_token"] = torch.empty(N, dtype=torch.int32, device=device)
     return g, i
 
 
-def _lmhead_out(out, N, dev, want_rank, want_log_mass):
+def _lmhead_out(out, N, dev, want_rank, want_log_mass, want_token=False):
     if out is None:
-        return lmhead_outputs(N, dev, want_rank, want_log_mass)
+        return lmhead_outputs(N, dev, want_rank, want_log_mass, want_token)
     g, i = out
     for part, spec, opt in zip((g, i), _LMHEAD_OUT, _LMHEAD_OPT):
         for k, dt in spec:
@@ -482,34 +484,38 @@ def _lmhead_out(out, N, dev, want_rank, want_log_mass):
     return g, i
 
 
-def _lmhead_call(entry_name, tail, r, g, i, sigma, eps, dev):
+def _lmhead_call(entry_name, token, tail, r, g, i, sigma, eps, dev):
     lib = load_library()
     with torch.cuda.device(dev):
         rc = getattr(lib, entry_name)(C.byref(r), _ptr(g["margin"]), _ptr(g["argmax"]), _ptr(g["max_score"]),
                                       _ptr(g["claimed_score"]), _ptr(g["flags"]), _ptr(g.get("logit_rank")),
-                                      _ptr(i["dist"]), _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), float(sigma),
-                                      float(eps), _ptr(i.get("log_mass")), _ptr(i["flags"]), *tail, _stream_ptr(dev))
+                                      _ptr(i["dist"]), _ptr(i["cdf_lo"]), _ptr(i["cdf_hi"]), _ptr(i["u"]), *token,
+                                      float(sigma), float(eps), _ptr(i.get("log_mass")), _ptr(i["flags"]), *tail,
+                                      _stream_ptr(dev))
     if rc:
         raise DifrError(rc, entry_name)
     return g, i
 
 
 def lmhead_score(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel=None, claimed_ipt=None,
-                 temperatures=None, workspace=None, out=None, want_rank=False, want_log_mass=False, sigma=0.01, eps=1e-30):
+                 temperatures=None, workspace=None, out=None, want_rank=False, want_log_mass=False, want_token=False,
+                 sigma=0.01, eps=1e-30):
     """difr_lmhead_score: both estimators on logits = hidden @ weight.T that are never stored.
     hidden [N, d], weight [V, d] bf16 on the GPU (unit column stride).  Returns (gumbel dict, ipt dict);
-    want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_log_mass adds log_mass to the second;
+    want_rank adds logit_rank (of the Token-DiFR claim) to the first, want_log_mass / want_token add log_mass /
+    ipt_token (the sampler's own token; it needs a larger workspace: lmhead_workspace_bytes(..., want_token=True)) to the second;
     `out` = a pair from lmhead_outputs() to write into instead of new tensors (it decides which optional outputs
     are produced)."""
     r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
                                    temperatures)
-    need = lmhead_workspace_bytes(N, V, d)
+    g, i = _lmhead_out(out, N, dev, want_rank, want_log_mass, want_token)
+    need = lmhead_workspace_bytes(N, V, d, "ipt_token" in i)
     if workspace is None:
         workspace = torch.empty(max(need, 8), dtype=torch.uint8, device=dev)
     elif workspace.device != dev or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
         raise ValueError("workspace must be a contiguous uint8 tensor on the device of hidden")
-    g, i = _lmhead_out(out, N, dev, want_rank, want_log_mass)
-    return _lmhead_call("difr_lmhead_score", (_ptr(workspace), workspace.numel()), r, g, i, sigma, eps, dev)
+    return _lmhead_call("difr_lmhead_score", (_ptr(i.get("ipt_token")),), (_ptr(workspace), workspace.numel()), r, g, i,
+                        sigma, eps, dev)
 
 
 LMHEAD_STATIC_SCRATCH_BYTES = 4 << 20
@@ -522,7 +528,9 @@ def lmhead_score_static(hidden, weight, temperature, seeds, seq_ids, positions, 
     r, dev, N, V, d = _lmhead_args(hidden, weight, temperature, seeds, seq_ids, positions, claimed_gumbel, claimed_ipt,
                                    temperatures)
     g, i = _lmhead_out(out, N, dev, want_rank, want_log_mass)
-    return _lmhead_call("difr_lmhead_score_static", (), r, g, i, sigma, eps, dev)
+    if "ipt_token" in i:
+        raise ValueError("difr_lmhead_score_static has no ipt_token output")
+    return _lmhead_call("difr_lmhead_score_static", (), (), r, g, i, sigma, eps, dev)
 
 
 def seq_reduce(scores, row_flags, seq_offsets, threshold):

@@ -125,15 +125,16 @@ int validate_lmhead(const difr_lmhead *in, difr::LmHeadBatch *b)
 
 extern "C" {
 
-size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d)
+size_t difr_lmhead_workspace_bytes(int64_t N, int64_t V, int64_t d, int32_t want_ipt_token)
 {
     if (N <= 0 || V <= 0 || d <= 0 || N >= (int64_t)1 << 31 || V >= (int64_t)1 << 31) return 0;
-    return difr::lmhead_workspace_bytes(N, difr::lmhead_plan(N, V).splits);
+    const difr::LmHeadPlan plan = difr::lmhead_plan(N, V);
+    return difr::lmhead_workspace_bytes(N, plan.splits, plan.n_vt, want_ipt_token != 0);
 }
 
 int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, float *max_score, float *claimed_score,
                       uint8_t *flags_gumbel, int32_t *logit_rank, float *dist, float *cdf_lo, float *cdf_hi, float *u,
-                      double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
+                      int32_t *ipt_token, double sigma, double eps, float *log_mass, uint8_t *flags_ipt, void *workspace,
                       size_t workspace_bytes, void *hip_stream)
 {
     difr::LmHeadBatch b;
@@ -144,11 +145,12 @@ int difr_lmhead_score(const difr_lmhead *in, float *margin, int32_t *argmax, flo
     if (!margin || !argmax || !flags_gumbel || !dist || !flags_ipt || !workspace) return DIFR_ERR_NULL;
     const difr::LmHeadPlan plan = difr::lmhead_plan(b.N, b.V);
     if ((uintptr_t)workspace % 8u) return DIFR_ERR_ALIGN;
-    if (workspace_bytes < difr::lmhead_workspace_bytes(b.N, plan.splits)) return DIFR_ERR_SHAPE;
+    const bool tok = ipt_token != nullptr;
+    if (workspace_bytes < difr::lmhead_workspace_bytes(b.N, plan.splits, plan.n_vt, tok)) return DIFR_ERR_SHAPE;
     if ((rc = check_device()) != DIFR_OK) return rc;
-    const difr::LmHeadWorkspace ws = difr::lmhead_carve(workspace, b.N, plan.splits);
+    const difr::LmHeadWorkspace ws = difr::lmhead_carve(workspace, b.N, plan.splits, plan.n_vt, tok);
     const difr::GumbelOutputs og{margin, argmax, max_score, claimed_score, flags_gumbel, logit_rank};
-    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, nullptr, sigma, eps, log_mass, flags_ipt, nullptr};
+    const difr::IptOutputs oi{dist, cdf_lo, cdf_hi, u, ipt_token, sigma, eps, log_mass, flags_ipt, nullptr};
     return difr::launch_lmhead_score(b, ws, plan, og, oi, (hipStream_t)hip_stream) ? DIFR_ERR_LAUNCH : DIFR_OK;
 }
 

@@ -295,7 +295,12 @@ __device__ __forceinline__ void merge_softmax(float &m, double &Z, double &P, fl
 // permuted by (row / 2) % 8 so that both the 16-byte slab writes and the fragment reads of 16
 // consecutive rows spread over all 64 banks.
 // ---------------------------------------------------------------------------------
-template <bool RANK>
+//
+// TOK: also leave, per token and half tile (the 128 vocabulary entries of a tile that one wave scores), the softmax
+// mass of that half tile with its exponent reference.  The sampler's own Token-IPT-DiFR token is the first entry
+// at which the CDF passes u; the CDF needs the row's total mass, known only after the last tile, so the search is
+// made afterwards: over these masses for the half tile, and inside it by forming its 128 logits again.
+template <bool RANK, bool TOK>
 __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, LmHeadWorkspace ws, LmHeadPlan plan)
 {
     __shared__ __attribute__((aligned(16))) uint16_t lds_w[2][kLmTileV * kLmTileK];  // 32 KB per stage
@@ -530,10 +535,27 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
             refresh_gates(slot[jb], k);
             const int32_t vl = (int32_t)v0 + wv * 128 + 4 * lh;
+            const double Z_before = slot[jb].Z;
+            const float m_before = slot[jb].m;
             score_block<RANK>(acc[0][jb], slot[jb], k, vl, V, ragged, tok_row(jb), ws);
             score_block<RANK>(acc[1][jb], slot[jb], k, vl + 32, V, ragged, tok_row(jb), ws);
             score_block<RANK>(acc[2][jb], slot[jb], k, vl + 64, V, ragged, tok_row(jb), ws);
             score_block<RANK>(acc[3][jb], slot[jb], k, vl + 96, V, ragged, tok_row(jb), ws);
+            if (TOK) {
+                // what this lane's 64 entries of the half tile added to its sum, relative to its reference now;
+                // then the two lanes that share the token (rows 0-3 and 4-7 mod 8) combined
+                const float ninf = -__builtin_inff();
+                const Slot &s = slot[jb];
+                double mine = s.Z;
+                if (m_before > ninf)
+                    mine -= Z_before * (s.m == m_before ? 1.0 : (double)fast_exp2((m_before - s.m) * k.c));
+                const float ms = mine > 0.0 ? (float)mine : 0.0f, mm = s.m;
+                const float os = __shfl_xor(ms, 32, 64), om = __shfl_xor(mm, 32, 64);
+                const float M = fmaxf(mm, om);
+                const float both = (mm > ninf ? ms * fast_exp2((mm - M) * k.c) : 0.0f) +
+                                   (om > ninf ? os * fast_exp2((om - M) * k.c) : 0.0f);
+                if (lh == 0 && tok_is_live(jb)) ws.half_sum[(int64_t)(2 * vt + wv) * b.N + tok_row(jb)] = make_float2(both, M);
+            }
         };
         score_token(std::integral_constant<int, 0>());
         score_token(std::integral_constant<int, 1>());
@@ -600,7 +622,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
 // ---------------------------------------------------------------------------------
 // Merge the vocabulary ranges of each token (ascending) and form every output.  One thread per token.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, LmHeadWorkspace ws, int splits,
+__global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, LmHeadWorkspace ws, int splits, int n_vt,
                                                                  GumbelOutputs og, IptOutputs oi)
 {
     const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -623,6 +645,10 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
         if (oi.cdf_hi) oi.cdf_hi[n] = nan;
         if (oi.u) oi.u[n] = nan;
         if (oi.log_mass) oi.log_mass[n] = nan;
+        if (oi.ipt_token) {
+            oi.ipt_token[n] = -1;
+            ws.cross_half[n] = -1;
+        }
         oi.flags[n] = f;
         return;
     }
@@ -683,7 +709,117 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
     if (oi.cdf_hi) oi.cdf_hi[n] = bb;
     if (oi.u) oi.u[n] = u;
     if (oi.log_mass) oi.log_mass[n] = lm;
+    if (oi.ipt_token) {
+        // The sampler's own token: the claim if it matches; else the first entry at which the CDF passes u.  The
+        // half tile in which that happens is found from the masses the scoring pass left (vocabulary order, each
+        // brought to the row's final reference); the entry inside it by the kernel that follows.
+        int32_t tok = -1, half = -1;
+        double rest = 0.0;
+        if (ipt_bad) {
+            tok = -1;
+        } else if (match) {
+            tok = t.ti;
+        } else {
+            const double target = (double)u * Z;
+            double cum = 0.0;
+            int32_t last = -1;  // last half tile with any mass: where rounding puts a u beyond the summed total
+            double cum_last = 0.0;
+            for (int h = 0; h < 2 * n_vt; ++h) {
+                const float2 p = ws.half_sum[(int64_t)h * b.N + n];
+                if (!(p.x > 0.0f)) continue;
+                const double w = (double)p.x * (double)fast_exp2((p.y - m) * c);
+                if (cum + w > target) {
+                    half = h;
+                    rest = target - cum;
+                    break;
+                }
+                if (w > 0.0) {
+                    last = h;
+                    cum_last = cum;
+                }
+                cum += w;
+            }
+            if (half < 0) {
+                half = last;
+                rest = target - cum_last;
+            }
+            if (half >= 0) fi |= kFlagSlowPath;
+        }
+        oi.ipt_token[n] = tok;
+        ws.cross_half[n] = half;
+        ws.cross_rest[n] = rest;
+        ws.final_m[n] = m;
+    }
     oi.flags[n] = (uint8_t)fi;
+}
+
+// ---------------------------------------------------------------------------------
+// The sampler's own Token-IPT-DiFR token inside the half tile the merge kernel found: the 128 logits of that
+// half tile are formed again as plain fp32 dot products (one wave per 32 of them, a row of the LM-head matrix
+// read by the whole wave at a time), turned into softmax terms relative to the row's final reference and scanned
+// in vocabulary order for the first entry at which the running sum passes what was left to cover.  One workgroup
+// per token; tokens that are already known (matching or missing claims, rejected rows) leave at once.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void lmhead_ipt_token_kernel(LmHeadBatch b, LmHeadWorkspace ws, IptOutputs oi)
+{
+    __shared__ float lds_e[128];
+    const int64_t n = blockIdx.x;
+    const int32_t half = ws.cross_half[n];
+    if (half < 0) return;  // uniform
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const TokInfo t = load_tok(b, n);
+    const float c = t.inv_T * kLog2e, m = ws.final_m[n];
+    const int64_t v0 = (int64_t)half * 128;
+    const uint16_t *h = b.hidden + n * b.ldh;
+    for (int r = wave * 32; r < wave * 32 + 32; ++r) {
+        const int64_t v = v0 + r;
+        float e = 0.0f;
+        if (v < b.V) {  // uniform per wave
+            const uint16_t *w = b.weight + v * b.ldw;
+            float dot = 0.0f;
+            for (int64_t q = lane; q < b.d / 8; q += 64) {
+                const uint4 hv = *reinterpret_cast<const uint4 *>(h + 8 * q);
+                const uint4 wv = *reinterpret_cast<const uint4 *>(w + 8 * q);
+                const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w}, ww[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    dot = __fmaf_rn(__uint_as_float(hw[j] << 16), __uint_as_float(ww[j] << 16), dot);
+                    dot = __fmaf_rn(__uint_as_float(hw[j] & 0xFFFF0000u), __uint_as_float(ww[j] & 0xFFFF0000u), dot);
+                }
+            }
+            dot = wave_sum(dot);
+            e = fast_exp2(__fmaf_rn(dot, c, -(m * c)));
+            if (!(e == e)) e = 0.0f;
+        }
+        if (lane == 0) lds_e[r] = e;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // inclusive scan over the 128 terms in vocabulary order: lane l holds entries 2l and 2l + 1
+        const double e0 = (double)lds_e[2 * lane], e1 = (double)lds_e[2 * lane + 1];
+        double incl = e0 + e1;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double o = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += o;
+        }
+        const double before = incl - (e0 + e1), rest = ws.cross_rest[n];
+        int32_t idx = 0x7FFFFFFF;
+        if (e0 > 0.0 && before + e0 > rest)
+            idx = 2 * lane;
+        else if (e1 > 0.0 && before + e0 + e1 > rest)
+            idx = 2 * lane + 1;
+        int32_t last = e1 > 0.0 ? 2 * lane + 1 : (e0 > 0.0 ? 2 * lane : -1);  // rounding may leave `rest` uncovered
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            idx = min(idx, __shfl_xor(idx, off, 64));
+            last = max(last, __shfl_xor(last, off, 64));
+        }
+        if (lane == 0) {
+            if (idx == 0x7FFFFFFF) idx = last >= 0 ? last : 0;
+            oi.ipt_token[n] = (int32_t)(v0 + idx);
+        }
+    }
 }
 
 int launch_lmhead_score(const LmHeadBatch &b, const LmHeadWorkspace &ws, const LmHeadPlan &plan, const GumbelOutputs &og,
@@ -691,14 +827,26 @@ int launch_lmhead_score(const LmHeadBatch &b, const LmHeadWorkspace &ws, const L
 {
     lmhead_prepare_kernel<<<dim3((unsigned)((b.N + kWaves - 1) / kWaves)), dim3(kBlock), 0, stream>>>(b, ws);
     if (hipGetLastError() != hipSuccess) return 1;
-    if (og.logit_rank)  // counted in the scoring pass, only when asked for
-        lmhead_score_kernel<true><<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
+    // the logit rank and the masses behind the sampler's own token are produced in the scoring pass, only when asked for
+    const dim3 grid((unsigned)(plan.n_tb * plan.splits)), block(kBlock);
+    const bool rank = og.logit_rank != nullptr, tok = oi.ipt_token != nullptr;
+    if (rank && tok)
+        lmhead_score_kernel<true, true><<<grid, block, 0, stream>>>(b, ws, plan);
+    else if (rank)
+        lmhead_score_kernel<true, false><<<grid, block, 0, stream>>>(b, ws, plan);
+    else if (tok)
+        lmhead_score_kernel<false, true><<<grid, block, 0, stream>>>(b, ws, plan);
     else
-        lmhead_score_kernel<false><<<dim3((unsigned)(plan.n_tb * plan.splits)), dim3(kBlock), 0, stream>>>(b, ws, plan);
+        lmhead_score_kernel<false, false><<<grid, block, 0, stream>>>(b, ws, plan);
     if (hipGetLastError() != hipSuccess) return 1;
-    lmhead_finalize_kernel<<<dim3((unsigned)((b.N + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream>>>(b, ws, plan.splits,
-                                                                                                    og, oi);
-    return hipGetLastError() == hipSuccess ? 0 : 1;
+    lmhead_finalize_kernel<<<dim3((unsigned)((b.N + kBlock - 1) / kBlock)), block, 0, stream>>>(b, ws, plan.splits, plan.n_vt,
+                                                                                            og, oi);
+    if (hipGetLastError() != hipSuccess) return 1;
+    if (tok) {
+        lmhead_ipt_token_kernel<<<dim3((unsigned)b.N), block, 0, stream>>>(b, ws, oi);
+        if (hipGetLastError() != hipSuccess) return 1;
+    }
+    return 0;
 }
 
 }  // namespace difr

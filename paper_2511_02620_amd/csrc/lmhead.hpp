@@ -2,6 +2,7 @@
 // kernels (lmhead.hip) and the C ABI layer.
 #pragma once
 
+#include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -59,14 +60,22 @@ struct LmHeadWorkspace {
     float *x_claim_gumbel; // [N] logit of the Token-DiFR claim as the tile that holds it computed it (NaN until then)
     float *x_claim_ipt;    // [N] same for the Token-IPT-DiFR claim
     float *x_claim_ref;    // [N] logit of the Token-DiFR claim as a plain fp32 dot product (NaN without a claim)
+    // only when the sampler's own Token-IPT-DiFR token is asked for (null otherwise):
+    float2 *half_sum;      // [2 n_vt][N] softmax mass of each half tile (128 vocabulary entries) and its exponent reference
+    double *cross_rest;    // [N] mass still to be covered inside the half tile in which the CDF passes u, relative to final_m
+    float *final_m;        // [N] the row's final exponent reference
+    int32_t *cross_half;   // [N] that half tile, or -1 if the token is already known
 };
 
-inline size_t lmhead_workspace_bytes(int64_t N, int splits)
+// want_token: room for the per-half-tile masses that the search for the sampler's own token needs
+inline size_t lmhead_workspace_bytes(int64_t N, int splits, int n_vt = 0, bool want_token = false)
 {
-    return (size_t)N * (size_t)splits * (8 + 8 + 4 + 4 + 4 + 4) + (size_t)N * 16 + 64;
+    size_t bytes = (size_t)N * (size_t)splits * (8 + 8 + 4 + 4 + 4 + 4) + (size_t)N * 16 + 64;
+    if (want_token) bytes += (size_t)N * (size_t)n_vt * 16 + (size_t)N * 16;
+    return bytes;
 }
 
-inline LmHeadWorkspace lmhead_carve(void *base, int64_t N, int splits)
+inline LmHeadWorkspace lmhead_carve(void *base, int64_t N, int splits, int n_vt = 0, bool want_token = false)
 {
     LmHeadWorkspace w;
     const size_t n = (size_t)N * (size_t)splits;
@@ -90,6 +99,21 @@ inline LmHeadWorkspace lmhead_carve(void *base, int64_t N, int splits)
     w.x_claim_ipt = (float *)p;
     p += (size_t)N * 4;
     w.x_claim_ref = (float *)p;
+    p += (size_t)N * 4;
+    w.half_sum = nullptr;
+    w.cross_rest = nullptr;
+    w.final_m = nullptr;
+    w.cross_half = nullptr;
+    if (want_token) {
+        p = (char *)(((uintptr_t)p + 7u) & ~(uintptr_t)7u);
+        w.half_sum = (float2 *)p;
+        p += (size_t)N * (size_t)n_vt * 16;
+        w.cross_rest = (double *)p;
+        p += (size_t)N * 8;
+        w.final_m = (float *)p;
+        p += (size_t)N * 4;
+        w.cross_half = (int32_t *)p;
+    }
     return w;
 }
 

@@ -192,17 +192,20 @@ def test_argument_validation_needs_no_device(lib):
             setattr(r, k, v)
         return r
 
-    def lms(r, ws=fake, ws_bytes=1 << 20, margin=fake, sigma=0.01, lm_out=None):
-        return lib.difr_lmhead_score(C.byref(r), margin, fake, None, None, fake, None, fake, None, None, None, sigma, 1e-30,
-                                     lm_out, fake, ws, ws_bytes, None)
+    def lms(r, ws=fake, ws_bytes=1 << 20, margin=fake, sigma=0.01, lm_out=None, tok=None):
+        return lib.difr_lmhead_score(C.byref(r), margin, fake, None, None, fake, None, fake, None, None, None, tok, sigma,
+                                     1e-30, lm_out, fake, ws, ws_bytes, None)
 
     def lmst(r, margin=fake, sigma=0.01, lm_out=None):
         return lib.difr_lmhead_score_static(C.byref(r), margin, fake, None, None, fake, None, fake, None, None, None, sigma,
                                             1e-30, lm_out, fake, None)
 
-    need = lib.difr_lmhead_workspace_bytes(4, 100, 128)
-    assert 0 < need < 1 << 20 and lib.difr_lmhead_workspace_bytes(0, 100, 128) == 0
-    assert lib.difr_lmhead_workspace_bytes(16384, 151936, 4096) < 4 << 20
+    need = lib.difr_lmhead_workspace_bytes(4, 100, 128, 0)
+    assert 0 < need < 1 << 20 and lib.difr_lmhead_workspace_bytes(0, 100, 128, 0) == 0
+    assert lib.difr_lmhead_workspace_bytes(16384, 151936, 4096, 0) < 4 << 20
+    need_tok = lib.difr_lmhead_workspace_bytes(4, 100, 128, 1)          # one tile: 16 bytes per token more, and 16
+    assert need_tok == need + 4 * 16 + 4 * 16
+    assert lms(lm(), tok=fake, ws_bytes=need_tok - 1) == SHAPE and lms(lm(), tok=fake, ws_bytes=need_tok) != SHAPE
     for bad, want in ((lm(N=-1), SHAPE), (lm(V=0), SHAPE), (lm(d=0), SHAPE), (lm(d=96, ldh=96, ldw=96), SHAPE),
                       (lm(ldh=64), SHAPE), (lm(ldw=132), SHAPE), (lm(S=0), SHAPE), (lm(N=1 << 31), SHAPE),
                       (lm(ldh=1 << 23), SHAPE), (lm(ldw=1 << 23), SHAPE),
@@ -213,8 +216,8 @@ def test_argument_validation_needs_no_device(lib):
     assert lms(lm(), ws=0x1004) == ALIGN and lms(lm(), ws_bytes=need - 1) == SHAPE
     assert lms(lm(N=0, hidden=None), ws=None) == OK
     assert lms(lm(), sigma=0.0, lm_out=fake) == ARG and lms(lm(), sigma=0.0) != ARG
-    assert lib.difr_lmhead_score(None, fake, fake, None, None, fake, None, fake, None, None, None, 0.01, 1e-30, None, fake,
-                                 fake, 64, None) == NULL
+    assert lib.difr_lmhead_score(None, fake, fake, None, None, fake, None, fake, None, None, None, None, 0.01, 1e-30, None,
+                                 fake, fake, 64, None) == NULL
     # the variant with the built-in buffer: same validation, and a batch beyond its 4 MiB is refused on the host
     assert lmst(lm(N=-1)) == SHAPE and lmst(lm(hidden=None)) == NULL and lmst(lm(), margin=None) == NULL
     assert lmst(lm(), sigma=0.0, lm_out=fake) == ARG and lmst(lm(N=0, hidden=None)) == OK

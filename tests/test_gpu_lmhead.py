@@ -41,6 +41,21 @@ def _case(S, L, V, d, T=1.0, w_sigma=None):
                                w_sigma=(2.0 / d ** 0.5) if w_sigma is None else w_sigma)
 
 
+def _check_token(tok, oi, x_oracle, T, seeds, seq_ids, positions, flags):
+    """The sampler's own Token-IPT-DiFR token of the fused path against the oracle's: equal, or - where the CDF comes
+    within 1e-6 of u at an interval boundary - a token whose oracle interval touches u within that width.  Rows the
+    search was made for carry DIFR_FLAG_SLOW_PATH; rows whose claim matched do not, and their token is the claim."""
+    differ = np.nonzero(tok != oi["ipt_token"])[0]
+    for n in differ:
+        Tn = float(T[n]) if np.ndim(T) else float(T)
+        alt = oracle.ipt_row(x_oracle[n], Tn, int(seeds[seq_ids[n]]), int(seq_ids[n]), int(positions[n]), int(tok[n]))
+        assert alt["dist"] < parity.TIE_REL and alt["cdf_hi"] > alt["cdf_lo"], (
+            "ipt_token of row %d beyond a near tie: oracle %d, gpu %d, dist %g" % (n, oi["ipt_token"][n], tok[n], alt["dist"]))
+    matched = (flags & 1) != 0
+    assert not ((flags & 8) != 0)[matched].any() and ((flags & 8) != 0)[~matched & ((flags & 4) == 0)].all()
+    return {"rows": int(tok.shape[0]), "searched": int((~matched).sum()), "differ_within_tie": int(differ.size)}
+
+
 def _check_rank(rank, x_oracle, claims, V, tol):
     """The fused path counts the logits above the claim's against fp32 values that carry the matrix cores'
     accumulation error: its count must lie between the oracle's counts with the claim's logit moved by -/+ tol
@@ -100,15 +115,18 @@ def test_lmhead_every_row(difr, S, L, V, d, mode):
     elif mode == "sampling":
         cg = ci = None
     g, i = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, temperatures=temps, want_rank=True,
-                             want_log_mass=True, sigma=0.02)
+                             want_log_mass=True, want_token=True, sigma=0.02)
     torch.cuda.synchronize()
     og, oi, ox = oracle.lmhead_score(bits(Hv), bits(Wm), np.float32(wl.temperature), hs, hsid, hpos,
                                      None if cg is None else cg.cpu().numpy(), None if ci is None else ci.cpu().numpy(),
                                      temperatures=htemps, sigma=0.02, want_logits=True)
     rank = g.pop("logit_rank").cpu().numpy()
+    tok = i.pop("ipt_token").cpu().numpy()
     sg = parity.compare_gumbel(g, og, tie_rel=TIE)
     si = parity.compare_ipt(i, oi, tie_rel=TIE, log_mass_sigma=0.02)
     say("  gumbel", sg, "ipt", si)
+    say("  sampler's own token:", _check_token(tok, oi, ox, np.float32(wl.temperature) if htemps is None else htemps, hs, hsid,
+                                              hpos, i["flags"].cpu().numpy()))
     assert si["log_mass_beyond_bar"] == 0
     say("  logit rank:", _check_rank(rank, ox, None if cg is None else cg.cpu().numpy(), V, TIE))
     if mode == "honest":
@@ -117,7 +135,8 @@ def test_lmhead_every_row(difr, S, L, V, d, mode):
     # same call again: bit-identical
     g2, i2 = difr.lmhead_score(Hv, Wm, wl.temperature, seeds, sid, pos, cg, ci, temperatures=temps)
     torch.cuda.synchronize()
-    i.pop("log_mass")                        # the optional outputs change nothing else
+    i.pop("log_mass")                        # the optional outputs change nothing else (but the SLOW_PATH bit)
+    i["flags"] = i["flags"] & 0xF7
     for a, b in ((g, g2), (i, i2)):
         for key in a:
             assert torch.equal(torch.nan_to_num(a[key].float(), nan=-7.0), torch.nan_to_num(b[key].float(), nan=-7.0)), key
@@ -208,11 +227,11 @@ def test_lmhead_full_size_sampled_rows(difr):
     N, V = wl.N, wl.V
     T = wl.temperature
     say("C4 full size: sampling claims")
-    g0, _ = difr.lmhead_score(Hp, Wm, T, seeds, sid, pos, None, None)
+    # honest claims: the library's own samplers on the prover's hidden states, in sampling mode
+    g0, i0 = difr.lmhead_score(Hp, Wm, T, seeds, sid, pos, None, None, want_token=True)
     cg = g0["argmax"].clone()
-    # IPT claims: the honest sampler's token is not an output of the fused path; take the Gumbel sample for
-    # most rows (a valid, usually non-matching IPT claim) and the oracle's IPT sample on the oracle rows
-    ci = cg.clone()
+    ci = i0["ipt_token"].clone()
+    assert ((ci >= 0) & (ci < V)).all() and (i0["flags"] == (2 | 8)).all()   # no claim; every row searched
     # Oracle rows: four in every one of the 64 token blocks of the launch, at offsets that move through the block
     # (every wavefront and both halves of its 32-row fragments get rows), plus the first and the last row.  Each row's
     # scores merge all four vocabulary ranges of the launch; the claims of the oracle rows are spread so that every
@@ -224,11 +243,15 @@ def test_lmhead_full_size_sampled_rows(difr):
     hs, hsid, hpos = parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos)
     Wb = bits(Wm)
     say("C4 full size: oracle samplers on %d rows (prover's hidden states)" % len(rows))
-    og0, oi0 = oracle.lmhead_score(bits(Hp[rows]), Wb, np.float32(T), hs, hsid[rows], hpos[rows], None, None)
+    og0, oi0, ox0 = oracle.lmhead_score(bits(Hp[rows]), Wb, np.float32(T), hs, hsid[rows], hpos[rows], None, None,
+                                        want_logits=True)
     sel0 = torch.from_numpy(rows).to(DEV)
-    # the library's Gumbel sampler against the oracle's on these rows (the logits carry the matrix cores' rounding)
+    # the library's samplers against the oracle's on these rows (the logits carry the matrix cores' rounding)
     st0 = parity.compare_gumbel({k2: v[sel0] for k2, v in g0.items()}, og0, tie_rel=1e-4)
-    say("  sampler check:", st0)
+    say("  sampler check: gumbel", st0)
+    say("  sampler check: ipt", _check_token(ci[sel0].cpu().numpy(), oi0, ox0, np.float32(T), hs, hsid[rows], hpos[rows],
+                                             i0["flags"][sel0].cpu().numpy()))
+    del ox0
     cg[sel0] = torch.from_numpy(og0["argmax"].copy()).to(DEV)
     ci[sel0] = torch.from_numpy(oi0["ipt_token"].copy()).to(DEV)
     k = torch.arange(N, device=DEV)
