@@ -205,10 +205,11 @@ def bench_lmhead(args, difr, W, dev):
     seeds, sid, pos = wl.seeds().to(dev), wl.seq_ids().to(dev), wl.positions().to(dev)
     off = wl.seq_offsets().to(dev)
     ws = torch.empty(difr.lmhead_workspace_bytes(wl.N, wl.V, wl.d), dtype=torch.uint8, device=dev)
-    # honest claims: the library's own Gumbel-max sampler on the prover's (slightly drifted) hidden states;
-    # the fused path has no IPT sampler output, so the IPT claims are the same tokens (valid, rarely matching)
-    cg = difr.lmhead_score(Hp, Wm, wl.temperature, seeds, sid, pos, None, None, workspace=ws)[0]["argmax"].clone()
-    ci = cg
+    # honest claims: the library's own samplers (both come out of the fused call in sampling mode) on the
+    # prover's slightly drifted hidden states
+    g0, i0 = difr.lmhead_score(Hp, Wm, wl.temperature, seeds, sid, pos, None, None, want_token=True)
+    cg, ci = g0["argmax"].clone(), i0["ipt_token"].clone()
+    del g0, i0
     tau_g, tau_i = 0.05, 0.01
 
     def step(ev=None):
