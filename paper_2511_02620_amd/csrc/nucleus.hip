@@ -40,14 +40,18 @@ namespace difr {
 constexpr int kNucBins = 16;    // 4 key bits per pass
 constexpr int kNucCap = 2048;   // entries gathered and sorted at the end
 
+constexpr int kNucRawBytes = kNucBins * kBlock * 4;  // LDS the multi-pass search needs from its caller
+static_assert(kNucRawBytes >= kNucCap * (int)sizeof(uint64_t), "gather buffer must fit the bin memory");
+
+// One row by the multi-pass search described above.  `raw`: kNucRawBytes of LDS, 16-byte aligned (mass bins
+// [bin][thread] during the search; the gather buffer afterwards).  All 256 threads of the workgroup call it.
 template <int DT>
-__global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float top_p, IptOutputs o,
-                                                             int32_t *__restrict__ kept_out, float *__restrict__ tau_out)
+__device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float top_p, const IptOutputs &o,
+                                                      int32_t *__restrict__ kept_out, float *__restrict__ tau_out,
+                                                      unsigned char *raw)
 {
     typedef typename Elem<DT>::type elt_t;
     constexpr int E = Elem<DT>::kPerVec;
-    // mass bins [bin][thread] during the search; the gather buffer afterwards
-    __shared__ __attribute__((aligned(16))) unsigned char raw[kNucBins * kBlock * 4];
     __shared__ double part_m[16][kNucBins];
     __shared__ double bin_m[kNucBins];
     __shared__ float lds_f[kWaves];
@@ -57,7 +61,6 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     __shared__ float s_xtau;
     __shared__ double s_mass_in;
     __shared__ uint64_t s_cut;
-    static_assert(sizeof(raw) >= kNucCap * sizeof(uint64_t), "gather buffer must fit the bin memory");
     float *mass = reinterpret_cast<float *>(raw);
     uint64_t *buf = reinterpret_cast<uint64_t *>(raw);
 
@@ -186,6 +189,19 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     }
     lo_s = -block_max(-lo_s, lds_f);  // finite and <= R, since R is
     float neg_Rc = -(R * c);
+    // The masses that decide the cut take log2(e) / T in two fp32 pieces, so that what an entry's exponent loses to
+    // the rounding of that constant (a tilt of up to 6e-8 |x| c over the whole row, all to one side) is gone; what
+    // remains per entry is the rounding of the exponent itself and of the hardware exponential, which differ from one
+    // logit value to the next and largely cancel in the sums.
+    const double c64 = 1.4426950408889634074 / (double)ri.T;
+    const float c_hi = (float)c64, c_lo = (float)(c64 - (double)c_hi);
+    auto mass_of = [&](float x) __attribute__((always_inline)) {
+        x = fmaxf(x, -3.0e38f);  // a masked entry (-inf) times the small piece, which may be negative or zero: keep it finite
+        return fast_exp2(__fmaf_rn(x, c_hi, __fmaf_rn(x, c_lo, neg_Rc)));
+    };
+    // (the same real number 2^(x c + neg_Rc), with the rounded neg_Rc as the common reference, in fp64: for the
+    // few masses of the last step)
+    auto mass_of_f64 = [&](float x) __attribute__((always_inline)) { return exp2(fma((double)x, c64, (double)neg_Rc)); };
 
     // ---- passes B: search for the bracket [klo, khi] of keys that holds the cut ----
     // Keys are the order-preserving images of the logits at the storage type's resolution (16 bits for bf16).
@@ -291,7 +307,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
 #pragma unroll
             for (int j = 0; j < E; ++j) {
                 const float x = value_of(q, j);
-                add_mass(bin1(x), fast_exp2(__fmaf_rn(x, c, neg_Rc)));
+                add_mass(bin1(x), mass_of(x));
             }
         });
         if (DT == 0) {
@@ -359,7 +375,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
 #pragma unroll
             for (int j = 0; j < E; ++j) {
                 const uint32_t d = key_of(kw, j) - klo;
-                if (d <= span) add_mass(d >> sh, fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc)));
+                if (d <= span) add_mass(d >> sh, mass_of(value_of(q, j)));
             }
         });
         combine_bins();
@@ -418,7 +434,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
     int32_t tb = 0;       //           and how many ties lie below the claimed token's index
     if (many_ties) {
         tau_val = s_xtau;
-        const double e_tau = (double)fast_exp2(__fmaf_rn(tau_val, c, neg_Rc));
+        const double e_tau = mass_of_f64(tau_val);
         const int64_t bracket = (int64_t)block_sum_i32(ties, lds_i);
         n_tie = e_tau > 0.0 ? (int64_t)ceil((target - mass_above) / e_tau) : bracket;
         n_tie = n_tie < 1 ? 1 : (n_tie > bracket ? bracket : n_tie);
@@ -453,7 +469,7 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         const int per = P / kBlock;
         auto term = [&](int q) {  // mass of the thread's q-th position (0 past the end)
             const int i = tid * per + q;
-            return (q < per && i < n) ? (double)fast_exp2(__fmaf_rn(top_key(buf[i]), c, neg_Rc)) : 0.0;
+            return (q < per && i < n) ? mass_of_f64(top_key(buf[i])) : 0.0;
         };
         double run = 0.0;
 #pragma unroll
@@ -632,6 +648,14 @@ __global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float t
         if (o.log_mass) o.log_mass[row] = (valid && ok) ? (float)gaussian_log_mass(ad, bd, ud, o.sigma, o.eps) : nan;
         o.flags[row] = (uint8_t)f;
     }
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void ipt_nucleus_kernel(RowBatch b, float top_p, IptOutputs o,
+                                                             int32_t *__restrict__ kept_out, float *__restrict__ tau_out)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char raw[kNucRawBytes];
+    nucleus_row_multipass<DT>(b, top_p, o, kept_out, tau_out, raw);
 }
 
 int launch_ipt_nucleus(const RowBatch &b, float top_p, const IptOutputs &o, int32_t *kept, float *tau, hipStream_t stream)

@@ -2,10 +2,13 @@
 threshold difr_gumbel_likelihood uses with top_k = 0) against the oracle.
 
 Whether the marginal token of a nucleus of thousands of tokens is still inside is decided by a cumulative mass
-that the GPU forms from fp32 exponentials (relative accuracy ~1e-7 each) and the oracle in double.  The
-kept-set size must therefore lie between the oracle's sizes at top_p -/+ 2e-6 (and equal the oracle's wherever
-those two agree); interval ends and the distance must agree within 1e-4 absolute (the contract of the
-unfiltered estimator), which the mass of the few tokens in doubt (< 1e-5) does not touch."""
+that the GPU forms from fp32 exponentials and the oracle in double.  What can be PROVEN of the GPU's sum is the
+per-term bound (the exponent of a term is rounded to fp32: up to 7e-7 relative for the small terms), so the
+kept-set size must lie between the oracle's sizes at top_p -/+ 2e-6 and equal the oracle's wherever those two
+agree.  The per-term errors differ from one logit value to the next and largely cancel, so the size nearly
+always IS the oracle's: the rows where it is not are counted (`differs`), and so are the rows that the much
+narrower width 1e-7 would leave in doubt.  Interval ends and the distance must agree within 1e-4 absolute (the
+contract of the unfiltered estimator), which the mass of the few tokens in doubt (< 1e-5) does not touch."""
 import sys
 
 import numpy as np
@@ -18,7 +21,8 @@ from paper_2511_02620_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-EPS_P = 2e-6
+EPS_P = 2e-6          # proven width
+EPS_P_NARROW = 1e-7   # reported only
 
 
 def say(*a):
@@ -39,6 +43,7 @@ def _oracle(host, V, T, seeds, sid, pos, claims, p, temps):
 
 
 def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
+    eps_p = EPS_P
     out = difr.ipt_score_filtered(logits, T, seeds, sid, pos, claims, top_k=0, top_p=p, temperatures=temps, V=V,
                                   want_token=True, want_log_mass=True, sigma=0.02)
     torch.cuda.synchronize()
@@ -51,8 +56,8 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
     host = parity.to_host_logits(logits)
     p32 = float(np.float32(p))
     ref = _oracle(host, V, T, seeds, sid, pos, claims, p32, temps)
-    lo = _oracle(host, V, T, seeds, sid, pos, claims, p32 - EPS_P, temps)["kept"]
-    hi = _oracle(host, V, T, seeds, sid, pos, claims, p32 + EPS_P, temps)["kept"]
+    lo = _oracle(host, V, T, seeds, sid, pos, claims, p32 - eps_p, temps)["kept"]
+    hi = _oracle(host, V, T, seeds, sid, pos, claims, p32 + eps_p, temps)["kept"]
     kept = out["kept"].cpu().numpy()
     assert (kept >= 0).all(), "undetermined rows"
     assert (kept >= lo).all() and (kept <= hi).all(), np.nonzero((kept < lo) | (kept > hi))[0][:10]
@@ -85,6 +90,11 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
     st["token_excused"] = excused
     st["mean_kept"] = float(kept.mean())
     st["rows_in_doubt"] = int((~sure).sum())
+    st["differs"] = int((kept != ref["kept"]).sum())
+    lo_n = _oracle(host, V, T, seeds, sid, pos, claims, p32 - EPS_P_NARROW, temps)["kept"]
+    hi_n = _oracle(host, V, T, seeds, sid, pos, claims, p32 + EPS_P_NARROW, temps)["kept"]
+    st["in_doubt_at_1e-7"] = int((lo_n != hi_n).sum())
+    assert st["differs"] <= max(1, kept.shape[0] // 20)
     out["ipt_token"] = torch.from_numpy(tok).to(DEV)
     return st, out
 
@@ -263,7 +273,7 @@ def test_likelihood_with_a_whole_vocabulary_nucleus(difr):
     tau = out["tau"].cpu().numpy().astype(np.float64)
     assert (tau >= lo).all() and (tau <= hi).all()
     same = tau == ref["tau"]
-    assert same.mean() > 0.8
+    assert same[lo == hi].all() and same.mean() > 0.95
     pi = out["pi"].cpu().numpy().astype(np.float64)
     assert np.abs(pi[same] - ref["pi"][same]).max() < 1e-4
     say("likelihood with nucleus: tau equal on %d of %d rows, pi err %.2e" % (same.sum(), N, np.abs(pi[same] - ref["pi"][same]).max()))
