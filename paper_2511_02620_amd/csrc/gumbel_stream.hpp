@@ -383,8 +383,6 @@ struct GumbelStream {
     template <int MODE>
     __device__ __forceinline__ void process(u32x4 q, int round, bool active, TopN *top = nullptr)
     {
-        // a wave without a vector in this round (the last, partly filled round of a row) has nothing to generate
-        if (__builtin_amdgcn_ballot_w64(active) == 0ull) return;
         if (PEAKED) {
             bool reach;
             if (DT == 0) {
@@ -473,7 +471,9 @@ struct GumbelStream {
                     xub = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
                     if (!(x0 + x1 + x2 + x3 == x0 + x1 + x2 + x3)) xub = __builtin_inff();  // a NaN among them (or both infinities)
                 }
-                if (!(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate)) {
+                // (not in the selection streams: their bound lies well below the maximum, most vectors that trip a test
+                // pass this one too, and the registers it holds on to cost the likelihood kernels more than it saves)
+                if (TOPN || !(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate)) {
                     // Entries that could matter are those with moderate noise or a moderate logit; each of
                     // them is then tested against its own noise bound before anything exact is computed.
                     const int32_t v0 = (round * kBlock + tid) * E;
