@@ -69,7 +69,7 @@ MEASURED_VALU_PER_ENTRY = {
     ("difr_score_both", "c3_30b_moe_class"): 17.34,
     ("difr_ipt_score", "c3_30b_moe_class"): 5.21,
 }
-SCLK_UNDER_LOAD_GHZ = {"difr_gumbel_score": 2.06, "difr_score_both": 2.18, "difr_ipt_score": 2.37}
+SCLK_UNDER_LOAD_GHZ = {"difr_gumbel_score": 2.06, "difr_score_both": 2.20, "difr_ipt_score": 2.39}
 
 
 def probe_clocks(kernels, seconds=3.0):
