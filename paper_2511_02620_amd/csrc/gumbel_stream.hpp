@@ -136,6 +136,13 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 //
 // TOPN: instead of tracking the best score, push every score that may belong to the n largest of the
 // row (the claimed token left out) into a TopN buffer; the gates use the buffer's threshold as the bound.
+// That bound lies well below the row maximum (the n-th best score, not the best), so a wave meets a vector
+// that trips a test in about every second round - in one or two of its 64 lanes.  Looking at those entries
+// on the spot would make the whole wave walk the per-entry code for them.  Instead the lane only notes the
+// vector's number in a per-wave LDS queue; once 64 are waiting (and at the end of every epoch of the caller)
+// the wave drains the queue with one vector per lane: the vector is read again, its noise is generated again,
+// and the per-entry tests run with all lanes busy.  Which entries end up in the selection does not depend on
+// when they are pushed, so the result is the same.
 //
 // ADM: the argmax as usual and, in the same pass, the size of the admissible set { v : max y - y_v <= delta }
 // although the maximum is only known at the end.  The gates test against L - delta instead of L (L = the
@@ -151,6 +158,7 @@ __device__ __forceinline__ bool gumbel_row_rejected(const RowInfo &ri, int64_t r
 // of reading them; on flat rows the test never fires and costs a few per cent (the noise generation can no longer
 // start before the vector has arrived), which is why it is a variant the caller asks for.  Same outputs, bit for bit.
 constexpr int kAdmCap = 1024;  // list entries per wave
+constexpr int kDeferCap = 128; // TOPN streams: queue slots per wave (fewer than 64 waiting + at most 64 new ones)
 
 template <int DT, bool RANK, bool COUNT = false, bool TOPN = false, bool ADM = false, bool PEAKED = false>
 struct GumbelStream {
@@ -184,6 +192,9 @@ struct GumbelStream {
     float *adm_list;    // this wave's kAdmCap floats in LDS
     int32_t *adm_fill;  // this wave's fill counter in LDS
     uint32_t adm_over;  // the list could not be kept below half: the count is not to be trusted
+    // TOPN mode: this wave's queue of vectors waiting for the per-entry look, and how many wait (wave-uniform)
+    int32_t *defer_q;
+    int defer_n;
     // PEAKED streams: T (L - g_max - slack), no entry below it can reach L whatever its noise; its bf16 pattern;
     // whether it is <= 0 (always so in gate modes 0 and 2).  Follows the gate: peak_cap() after every change of it.
     float xcap_max;
@@ -226,6 +237,8 @@ struct GumbelStream {
         adm_list = nullptr;
         adm_fill = nullptr;
         adm_over = 0;
+        defer_q = nullptr;
+        defer_n = 0;
         if (PEAKED) peak_cap();
     }
 
@@ -249,6 +262,58 @@ struct GumbelStream {
         adm_fill = fills + wave;
         if ((tid & 63) == 0) *adm_fill = 0;
         gate = make_gate(gate.L, T, adm_delta);
+    }
+
+    // TOPN mode: queues = kWaves * kDeferCap vector numbers in LDS.  Before the first process(); nothing to synchronise
+    // (a wave only ever touches its own queue).
+    __device__ __forceinline__ void arm_deferred(int32_t *queues)
+    {
+        defer_q = queues + wave * kDeferCap;
+        defer_n = 0;
+    }
+
+    // TOPN mode, whole wave (call from wave-uniform code): the per-entry look at every waiting vector, one vector per
+    // lane, against the gate as it stands now (it only ever rises, so nothing that still matters is missed).  The
+    // caller drains before every barrier that ends an epoch, so that a repeated epoch finds its own pushes only.
+    __device__ __forceinline__ void drain(TopN *top)
+    {
+        const int lane = tid & 63;
+        while (defer_n > 0) {
+            const int take = defer_n < 64 ? defer_n : 64;
+            defer_n -= take;
+            if (lane < take) {
+                const int32_t vec = defer_q[defer_n + lane];
+                const u32x4 q = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(x_row) + (size_t)vec * 16u);
+                uint32_t r[E];
+                const uint64_t p0 = (uint64_t)kPhiloxM0 * (uint32_t)(vec * (E / 4));
+                philox4x32_10_from_product(p0, ri.pos, ri.seq, kStreamGumbel, ri.key, r);
+                if (E == 8) philox4x32_10_from_product(p0 + kPhiloxM0, ri.pos, ri.seq, kStreamGumbel, ri.key, r + (E - 4));
+                const int32_t v0 = vec * E;
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+                float xs[E];
+                uint32_t cand = 0;  // the entries whose own noise bound still reaches the gate
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    xs[j] = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+                    if (!(__fmaf_rn(xs[j], inv_T, gumbel_upper_bound(r[j])) < gate.Lgate)) cand |= 1u << j;
+                }
+                // a lane has few of them, at scattered positions: each lane takes its own next one per turn (walking
+                // the eight positions in step would run the exact evaluation once for every position any lane has one at)
+                while (cand != 0u) {
+                    const int j = __builtin_ctz(cand);
+                    cand &= cand - 1u;
+                    float xv = xs[0];
+                    uint32_t rv = r[0];
+#pragma unroll
+                    for (int k = 1; k < E; ++k) {
+                        xv = j == k ? xs[k] : xv;
+                        rv = j == k ? r[k] : rv;
+                    }
+                    evaluate(xv, rv, v0 + j, top);
+                }
+            }
+        }
     }
 
     // TOPN mode: scores go to the selection handed to process() / tail() (by pointer argument, never stored:
@@ -378,6 +443,26 @@ struct GumbelStream {
         above += n;
     }
 
+    // Upper bound of the logits of one vector from its extreme bf16 bit patterns (lo: smallest as unsigned, known
+    // unless MODE == 1; hi: largest as signed, known unless MODE == 0): the largest signed pattern if it is a positive
+    // number (a NaN with its sign clear stays a NaN and passes every "<" test), else the smallest unsigned pattern
+    // if all are negative, else something that passes.
+    template <int MODE>
+    __device__ __forceinline__ static float vector_upper_bound(uint16_t lo, uint16_t hi)
+    {
+        const float f_hi = __uint_as_float((uint32_t)hi << 16), f_lo = __uint_as_float((uint32_t)lo << 16);
+        if (MODE == 0) return lo < 0x8000u ? __builtin_inff() : f_lo;  // a positive entry: not bounded by lo
+        if (MODE == 1) return (int16_t)hi >= 0 ? f_hi : -0.0f;         // all negative: bounded by zero
+        return (int16_t)hi >= 0 ? f_hi : f_lo;
+    }
+    __device__ __forceinline__ static float vector_upper_bound_f32(u32x4 q)
+    {
+        const float x0 = __uint_as_float(q.x), x1 = __uint_as_float(q.y), x2 = __uint_as_float(q.z), x3 = __uint_as_float(q.w);
+        float xub = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
+        if (!(x0 + x1 + x2 + x3 == x0 + x1 + x2 + x3)) xub = __builtin_inff();  // a NaN among them (or both infinities)
+        return xub;
+    }
+
     // One 16-byte vector per lane; `round` is the vector round (vector index = round * 256 + tid).
     // MODE is the gate's mode, fixed per instantiation so that the loop body carries no mode branches.
     template <int MODE>
@@ -415,6 +500,40 @@ struct GumbelStream {
         uint32_t rmax = r[0];
 #pragma unroll
         for (int j = 1; j < E; ++j) rmax = max(rmax, r[j]);
+        if (TOPN) {
+            // The selection's bound lies several units below the row maximum, where tests A, B and C trip for a fifth
+            // of all vectors and filter nothing.  One test takes their place: y_v <= x_max / T + bound(r_max) for every
+            // entry of the vector (both terms are monotone, and so is the rounding of the sum) - the expression of the
+            // per-entry test, on the vector's largest logit and largest word.  A vector that passes is only noted.
+            float xub;
+            if (DT == 0) {
+                uint16_t lo = 0, hi = 0;
+                if (MODE != 1) {
+                    u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                    lo = m.x < m.y ? m.x : m.y;
+                }
+                if (MODE != 0) {
+                    i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                    hi = (uint16_t)(m.x > m.y ? m.x : m.y);
+                }
+                xub = vector_upper_bound<MODE>(lo, hi);
+            } else {
+                xub = vector_upper_bound_f32(q);
+            }
+            const uint64_t hitmask =
+                __builtin_amdgcn_ballot_w64(active && !(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate));
+            if (hitmask != 0ull) {
+                const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(hitmask >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)hitmask, 0u));
+                if ((hitmask >> (tid & 63)) & 1ull) defer_q[defer_n + (int)before] = round * kBlock + tid;
+                defer_n += (int)__builtin_popcountll(hitmask);
+            }
+            return;
+        }
         // wave-wide masks of the lanes whose vector trips A, B, or both halves of C
         const uint64_t amask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateHi);
         const uint64_t cnmask = __builtin_amdgcn_ballot_w64(active && rmax >= kGateLo);
@@ -456,24 +575,8 @@ struct GumbelStream {
                 // fail for each of their entries.  x_max from the extreme bit patterns: the largest signed
                 // pattern if it is a positive number (a NaN with its sign clear stays a NaN and passes), else the
                 // smallest unsigned pattern if all are negative, else something that passes.
-                float xub;
-                if (DT == 0) {
-                    const float f_hi = __uint_as_float((uint32_t)hi << 16), f_lo = __uint_as_float((uint32_t)lo << 16);
-                    if (MODE == 0)
-                        xub = lo < 0x8000u ? __builtin_inff() : f_lo;   // a positive entry: not bounded by lo
-                    else if (MODE == 1)
-                        xub = (int16_t)hi >= 0 ? f_hi : -0.0f;          // all negative: bounded by zero
-                    else
-                        xub = (int16_t)hi >= 0 ? f_hi : f_lo;
-                } else {
-                    const float x0 = __uint_as_float(q.x), x1 = __uint_as_float(q.y), x2 = __uint_as_float(q.z),
-                                x3 = __uint_as_float(q.w);
-                    xub = fmaxf(fmaxf(x0, x1), fmaxf(x2, x3));
-                    if (!(x0 + x1 + x2 + x3 == x0 + x1 + x2 + x3)) xub = __builtin_inff();  // a NaN among them (or both infinities)
-                }
-                // (not in the selection streams: their bound lies well below the maximum, most vectors that trip a test
-                // pass this one too, and the registers it holds on to cost the likelihood kernels more than it saves)
-                if (TOPN || !(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate)) {
+                const float xub = DT == 0 ? vector_upper_bound<MODE>(lo, hi) : vector_upper_bound_f32(q);
+                if (!(__fmaf_rn(xub, inv_T, gumbel_upper_bound(rmax)) < gate.Lgate)) {
                     // Entries that could matter are those with moderate noise or a moderate logit; each of
                     // them is then tested against its own noise bound before anything exact is computed.
                     const int32_t v0 = (round * kBlock + tid) * E;

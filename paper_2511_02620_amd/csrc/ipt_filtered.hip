@@ -24,7 +24,9 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
     constexpr int E = Elem<DT>::kPerVec;
     __shared__ uint64_t buf_x[CAP];
     __shared__ TopScratch scratch;
-    __shared__ int32_t cnt_x, snap_x, s_bad, s_tok;
+    __shared__ int32_t cnt_x, s_bad, s_tok;
+    __shared__ uint32_t epoch_flags[3];
+    __shared__ int32_t defer_q[kWaves * kDeferCap];
     __shared__ double lds_d[kWaves];
     __shared__ double s_e[kTopMaxN];     // unnormalised probabilities of K in ascending vocabulary index
     __shared__ int32_t s_idx[kTopMaxN];  // and those indices
@@ -41,69 +43,92 @@ __global__ __launch_bounds__(kBlock) void ipt_filtered_kernel(RowBatch b, int to
 
     LogitTop<DT> lx;
     lx.init(buf_x, &cnt_x, top_k, CAP);
+    lx.arm_deferred(defer_q, x_row);
     if (tid == 0) {
         s_bad = 0;
-        snap_x = 0;
         s_tok = -1;
+        epoch_flags[0] = epoch_flags[1] = epoch_flags[2] = 0u;
     }
     __syncthreads();
-    auto settle = [&]() {
-        if (__syncthreads_or((int)lx.top.full)) {
-            if (lx.top.compact(scratch, true)) lx.retarget();
-        }
-    };
     const int64_t nvec = V / E;
-    const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);
+    const int n_main = (int)(nvec / kBlock);                   // rounds in which every lane has a vector
+    const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);  // plus a last, partly filled one
     auto fetch = [&](int round) {
         u32x4 q = u32x4{0u, 0u, 0u, 0u};
         if ((int64_t)round * kBlock + tid < nvec) q = load_round(x_row, round);
         return q;
     };
-    // `only_wave` >= 0: only that wave's lanes take part (the repeat of an epoch, see topn.hpp)
+    // one round looked at on the spot (the priming run, the partly filled round, the careful mode below);
+    // `only_wave` >= 0: only that wave's lanes take part
     auto do_round = [&](u32x4 q, int round, int only_wave = -1) {
         const int64_t vec = (int64_t)round * kBlock + tid;
         lx.push_vector(q, vec * E, vec < nvec && (only_wave < 0 || (tid >> 6) == only_wave));
     };
-    // epochs without barriers, as in the likelihood kernel, with a rewind and a round-by-round repeat if the buffer
-    // ran full
     // priming run of the first round (topn.hpp): a threshold before anything is pushed
     if (n_rounds > 0) {
         lx.top.begin_prime();
         do_round(fetch(0), 0);
         if (lx.top.end_prime(scratch)) lx.retarget();
     }
-    int round = 0;
+    // Epochs without barriers, as in the likelihood kernel: vectors that hold a candidate wait in the wave's queue until
+    // 64 of them make the look at their entries worth the wave's while; one barrier per epoch combines "a push found
+    // the buffer full" and the compaction trigger.
+    int round = 0, epoch = 0;
+    bool ran_full = false;
     while (round < n_rounds) {
         // epochs of 1, 1, 2, 4 rounds, then 8 at a time: the threshold moves only between epochs, and while little
         // of the row has been seen it moves a lot (each doubling of what has been seen brings about top_k pushes)
-        const int r_end = min(n_rounds, round + (round < 2 ? 1 : (round < 4 ? 2 : (round < 8 ? 4 : kTopEpoch))));
-        lx.top.new_epoch();
-        // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
-        // nothing else would hide the load latency (fetch() of a round past the end returns zeros without a load)
-        u32x4 qv[kTopEpoch];
+        const int len = round < 2 ? 1 : (round < 4 ? 2 : (round < 8 ? 4 : kTopEpoch));
+        const int r_end = round < n_main ? min(n_main, round + len) : n_rounds;
+        if (round >= n_main) {
+            do_round(fetch(round), round);
+        } else {
+            // all vectors of the epoch are requested before the first is used: with a handful of workgroups per CU
+            // nothing else would hide the load latency
+            u32x4 qv[kTopEpoch];
 #pragma unroll
-        for (int i = 0; i < kTopEpoch; ++i) qv[i] = (round + i < r_end) ? fetch(round + i) : u32x4{0u, 0u, 0u, 0u};
+            for (int i = 0; i < kTopEpoch; ++i) qv[i] = (round + i < r_end) ? load_round(x_row, round + i) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < kTopEpoch; ++i)
-            if (round + i < r_end) do_round(qv[i], round + i);
-        if (__syncthreads_or((int)lx.top.over)) {
-            if (tid == 0) cnt_x = snap_x;
-            lx.top.new_epoch();
-            lx.top.full = false;
-            __syncthreads();
-            for (int r = round; r < r_end; ++r) {
-                const u32x4 q = fetch(r);
-                for (int w = 0; w < kWaves; ++w) {
-                    do_round(q, r, w);
-                    settle();
+            for (int i = 0; i < kTopEpoch; ++i) {
+                if (round + i < r_end) {
+                    lx.note_vector(qv[i], (round + i) * kBlock + tid);
+                    if (lx.defer_n >= 64) lx.drain();
                 }
             }
-        } else {
-            settle();
         }
-        if (tid == 0) snap_x = cnt_x;
-        __syncthreads();
+        if (r_end == n_rounds) lx.drain();  // the row's last epoch: nothing may be left waiting
+        {
+            const uint32_t mine = (uint32_t)lx.top.over | ((uint32_t)lx.top.full << 1);
+            uint32_t *word = &epoch_flags[epoch % 3];  // (three words in turn, see the likelihood kernel)
+            if (mine) atomicOr(word, mine);
+            if (tid == 0) epoch_flags[(epoch + 1) % 3] = 0u;
+            __syncthreads();
+            const uint32_t all = *word;
+            ++epoch;
+            if (all & 1u) {
+                ran_full = true;
+                break;
+            }
+            if (all & 2u) {
+                if (lx.top.compact(scratch, true)) lx.retarget();
+            }
+        }
         round = r_end;
+    }
+    if (ran_full) {
+        // Careful mode (data in ascending order, for instance): the row again from its start, one wave and one round
+        // at a time with a compaction check after each step, so that the buffer cannot run full (topn.hpp).
+        lx.init(buf_x, &cnt_x, top_k, CAP);
+        __syncthreads();
+        for (int r = 0; r < n_rounds; ++r) {
+            const u32x4 q = fetch(r);
+            for (int w = 0; w < kWaves; ++w) {
+                do_round(q, r, w);
+                if (__syncthreads_or((int)lx.top.full)) {
+                    if (lx.top.compact(scratch, true)) lx.retarget();
+                }
+            }
+        }
     }
     lx.top.new_epoch();
     {

@@ -17,6 +17,10 @@
 
 namespace difr {
 
+// stream rounds per epoch once the thresholds have settled (vectors that trip a test only queue up, so a threshold that
+// is an epoch old costs little; measured: 16, 24 and 32 alike, 8 slower by 4%)
+constexpr int kLikEpoch = 16;
+
 __device__ __forceinline__ double gumbel_f64(const RowInfo &ri, int32_t v)
 {
     uint32_t r[4];
@@ -48,8 +52,10 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     __shared__ uint64_t buf_y[CAP];
     __shared__ uint64_t buf_x[CAP];
     __shared__ TopScratch scratch;
-    __shared__ int32_t cnt_y, cnt_x, snap_y, snap_x;
+    __shared__ int32_t cnt_y, cnt_x;
+    __shared__ uint32_t epoch_flags[3];
     __shared__ float lds_L[kWaves];
+    __shared__ int32_t defer_q[kWaves * kDeferCap], defer_qx[kWaves * kDeferCap];
     __shared__ double lds_d[kWaves];
     __shared__ double sA[kTopMaxN], sB[kTopMaxN];
     __shared__ int32_t s_bad, s_tok;
@@ -83,15 +89,17 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     const elt_t *x_row = reinterpret_cast<const elt_t *>(b.logits) + row * b.ld;
 
     GumbelStream<DT, false, false, true> g(ri, x_row, V, lds_L);
+    g.arm_deferred(defer_q);
     TopN top_y;
     LogitTop<DT> lx;
     TopN &top_x = lx.top;
     top_y.init(buf_y, &cnt_y, valid ? p.s : 0, CAP);
     lx.init(buf_x, &cnt_x, p.top_k, CAP);
+    lx.arm_deferred(defer_qx, x_row);
     if (tid == 0) {
         s_bad = 0;
         s_tok = -1;
-        snap_y = snap_x = 0;
+        epoch_flags[0] = epoch_flags[1] = epoch_flags[2] = 0u;
     }
     __syncthreads();
     g.retarget(top_y);
@@ -111,8 +119,9 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
     const int64_t nvec = V / E;
     const int n_main = (int)(nvec / kBlock);                       // rounds in which every lane has a vector
     const int n_rounds = (int)((nvec + kBlock - 1) / kBlock);      // plus a last, partly filled one
-    // one round, any gate mode, lanes past the end of the row idle (the partly filled round, and repeats)
-    // (`only_wave` >= 0: only that wave's lanes take part - the repeat of an epoch, see topn.hpp)
+    // one round, any gate mode, lanes past the end of the row idle (the priming run, the partly filled round, and
+    // the careful mode below); what the round finds is looked at before it returns
+    // (`only_wave` >= 0: only that wave's lanes take part)
     auto do_round = [&](int round, int only_wave = -1) __attribute__((always_inline)) {
         const int64_t vec = (int64_t)round * kBlock + tid;
         const bool in_row = vec < nvec;
@@ -120,11 +129,13 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
         u32x4 q = u32x4{0u, 0u, 0u, 0u};
         if (in_row) q = load_round(x_row, round);
         g.process_any(q, round, active, &top_y);
+        g.drain(&top_y);
         if (p.top_k > 0) lx.push_vector(q, vec * E, active);
     };
     // full rounds [r0, r1) with the loop body instantiated for the gate's mode (it can only change at a
     // compaction, i.e. between epochs): one copy of the Philox + gate code per mode instead of one per
-    // mode and unrolled round, which did not fit the instruction cache
+    // mode and unrolled round, which did not fit the instruction cache.  Vectors that trip a test wait in the
+    // two per-wave queues, across epochs, until 64 of them make a look at them worth the wave's while.
     auto run_rounds = [&](auto mode_tag, int r0, int r1) __attribute__((always_inline)) {
         constexpr int MODE = decltype(mode_tag)::value;
         u32x4 q_next = load_round(x_row, r0);
@@ -133,11 +144,13 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
             const u32x4 q = q_next;
             if (r + 1 < r1) q_next = load_round(x_row, r + 1);  // keep one vector in flight
             g.template process<MODE>(q, r, true, &top_y);
-            if (p.top_k > 0) lx.push_vector(q, ((int64_t)r * kBlock + tid) * E, true);
+            if (g.defer_n >= 64) g.drain(&top_y);
+            if (p.top_k > 0) {
+                lx.note_vector(q, r * kBlock + tid);
+                if (lx.defer_n >= 64) lx.drain();
+            }
         }
     };
-    // Epochs: the first round alone, then kTopEpoch rounds at a time without a barrier; the partly filled round is
-    // an epoch of its own.
     // priming run of the first round (topn.hpp): thresholds for both selections before anything is pushed
     if (n_rounds > 0) {
         top_y.begin_prime();
@@ -146,15 +159,16 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
         if (top_y.end_prime(scratch)) g.retarget(top_y);
         if (top_x.end_prime(scratch)) lx.retarget();
     }
-    const bool big_n = p.s > kTopSmallN || p.top_k > kTopSmallN;
-    int round = 0;
+    // Epochs: the first round alone, then up to kLikEpoch rounds at a time without a barrier; the partly filled round is
+    // an epoch of its own.  A push that finds a buffer full (data in ascending order, for instance) ends this mode.
+    int round = 0, epoch = 0;
+    bool ran_full = false;
     while (round < n_rounds) {
-        // (large selections start with epochs of 1, 1, 2, 4 rounds: early in the row each doubling of what has been
-        // seen brings about n pushes, and the buffers hold kTopCapBig)
-        const int len = round == 0 ? 1 : (!big_n || round >= 8 ? kTopEpoch : (round < 2 ? 1 : (round < 4 ? 2 : 4)));
+        // (the first epochs are 1, 1, 2 and 4 rounds long: the thresholds move only between epochs, and while little of
+        // the row has been seen they move a lot - a threshold that is one doubling of the data behind lets twice as
+        // many vectors through the tests)
+        const int len = round < 2 ? 1 : (round < 4 ? 2 : (round < 8 ? 4 : kLikEpoch));
         const int r_end = round < n_main ? min(n_main, round + len) : n_rounds;
-        top_y.new_epoch();
-        top_x.new_epoch();
         if (round >= n_main)
             do_round(round);
         else if (g.gate.mode == 0)
@@ -163,32 +177,50 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
             run_rounds(std::integral_constant<int, 1>(), round, r_end);
         else
             run_rounds(std::integral_constant<int, 2>(), round, r_end);
-        if (__syncthreads_or((int)(top_y.over || top_x.over))) {
-            // the buffer ran full (data in ascending order, for instance):
-            // forget the epoch and repeat it round by round, compacting whenever a trigger is reached
-            if (tid == 0) {
-                cnt_y = snap_y;
-                cnt_x = snap_x;
-            }
-            top_y.new_epoch();
-            top_x.new_epoch();
-            top_y.full = top_x.full = false;
+        if (round >= n_main || r_end == n_rounds) {  // the row's last epoch: nothing may be left waiting
+            g.drain(&top_y);
+            lx.drain();
+        }
+        // one barrier per epoch: the workgroup's OR of "a push found a buffer full" and of the two compaction triggers.
+        // (three words in turn: the word of the next epoch is cleared before this epoch's barrier, when every thread
+        // has long read it for the last time, and is written only after that barrier)
+        {
+            const uint32_t mine = (uint32_t)(top_y.over || top_x.over) | ((uint32_t)top_y.full << 1) | ((uint32_t)top_x.full << 2);
+            uint32_t *word = &epoch_flags[epoch % 3];
+            if (mine) atomicOr(word, mine);
+            if (tid == 0) epoch_flags[(epoch + 1) % 3] = 0u;
             __syncthreads();
-            for (int r = round; r < r_end; ++r) {
-                for (int w = 0; w < kWaves; ++w) {
-                    do_round(r, w);
-                    settle();
-                }
+            const uint32_t all = *word;
+            ++epoch;
+            if (all & 1u) {
+                ran_full = true;
+                break;
             }
-        } else {
-            settle();
+            if (all & 2u) {
+                if (top_y.compact(scratch, true)) g.retarget(top_y);
+            }
+            if (all & 4u) {
+                if (top_x.compact(scratch, true)) lx.retarget();
+            }
         }
-        if (tid == 0) {
-            snap_y = cnt_y;
-            snap_x = cnt_x;
-        }
-        __syncthreads();
         round = r_end;
+    }
+    if (ran_full) {
+        // Careful mode: the row again from its start, one wave and one round at a time with a compaction check after
+        // each step.  A step starts with fewer than kTopTrigger entries in a buffer and adds at most 8 per lane of one
+        // wave, so the buffers cannot run full, whatever the order of the data.
+        top_y.init(buf_y, &cnt_y, valid ? p.s : 0, CAP);
+        lx.init(buf_x, &cnt_x, p.top_k, CAP);
+        g.defer_n = 0;
+        __syncthreads();
+        g.retarget(top_y);
+        __syncthreads();
+        for (int r = 0; r < n_rounds; ++r) {
+            for (int w = 0; w < kWaves; ++w) {
+                do_round(r, w);
+                settle();
+            }
+        }
     }
     top_y.new_epoch();  // the tail: at most one entry per thread
     top_x.new_epoch();

@@ -17,12 +17,25 @@ struct LogitTop {
     uint32_t floor16;  // its bf16 bit pattern, rounded so that the packed test never misses an entry
     bool floor_pos;
     uint32_t bad;      // a NaN (sign bit clear) or +inf logit was seen
+    // note_vector() / drain(): this wave's queue of vectors that hold a candidate (kDeferCap vector numbers in LDS),
+    // how many wait (wave-uniform), and the row they are read from again
+    int32_t *defer_q;
+    int defer_n;
+    const void *defer_row;
 
     __device__ __forceinline__ void init(uint64_t *buf, int32_t *count, int k, int cap)
     {
         top.init(buf, count, k, cap);
         bad = 0;
+        defer_n = 0;
         set_floor(-__builtin_inff());
+    }
+    // queues = kWaves * kDeferCap ints in LDS (a wave only ever touches its own part)
+    __device__ __forceinline__ void arm_deferred(int32_t *queues, const void *x_row)
+    {
+        defer_q = queues + ((int)threadIdx.x >> 6) * kDeferCap;
+        defer_n = 0;
+        defer_row = x_row;
     }
     __device__ __forceinline__ void set_floor(float f)
     {
@@ -37,6 +50,62 @@ struct LogitTop {
     {
         bad |= (uint32_t)!(xv < __builtin_inff());
         if (xv >= floor) top.push(top_composite(xv, v));
+    }
+
+    // The test of push_vector() on vector number `vec` of the row, but a vector that passes is only noted in the
+    // wave's queue: a wave in which one or two lanes hold a candidate does not walk the entries for them.  The caller
+    // keeps defer_n below 64 between calls (drain() once it is not) and drains before the selection is finished.
+    __device__ __forceinline__ void note_vector(u32x4 q, int32_t vec)
+    {
+        bool hit;
+        if (DT == 0) {
+            if (floor_pos) {
+                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                hit = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)floor16;
+            } else {
+                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                hit = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)floor16;
+            }
+        } else {
+            hit = !(__uint_as_float(q.x) < floor) || !(__uint_as_float(q.y) < floor) ||
+                  !(__uint_as_float(q.z) < floor) || !(__uint_as_float(q.w) < floor);
+        }
+        const uint64_t m = __builtin_amdgcn_ballot_w64(hit);
+        if (m == 0ull) return;
+        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+        if (hit) defer_q[defer_n + (int)before] = vec;
+        defer_n += (int)__builtin_popcountll(m);
+    }
+
+    // Whole wave, from wave-uniform code: every waiting vector is read again, one per lane, and its entries that
+    // reach the floor as it stands now are pushed.  (+inf and NaNs with the sign bit clear always pass the vector
+    // test, so they are seen - and flagged - here.)
+    __device__ __forceinline__ void drain()
+    {
+        const int lane = (int)threadIdx.x & 63;
+        while (defer_n > 0) {
+            const int take = defer_n < 64 ? defer_n : 64;
+            defer_n -= take;
+            if (lane < take) {
+                const int32_t vec = defer_q[defer_n + lane];
+                const u32x4 q = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(defer_row) + (size_t)vec * 16u);
+                const uint32_t qw[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t w = qw[DT == 0 ? j >> 1 : j];
+                    const float xv = DT == 0 ? __uint_as_float((j & 1) ? (w & 0xFFFF0000u) : (w << 16)) : __uint_as_float(w);
+                    if (DT == 0)
+                        bad |= (uint32_t)((int32_t)__float_as_uint(xv) >= (int32_t)0x7F800000);
+                    else
+                        bad |= (uint32_t)!(xv < __builtin_inff());
+                    if (xv >= floor) top.push(top_composite(xv, vec * E + j));
+                }
+            }
+        }
     }
 
     // One 16-byte vector (entries v0 .. v0 + E - 1).  bf16: packed 16-bit min / max on the raw bit patterns, as

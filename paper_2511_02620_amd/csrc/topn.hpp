@@ -32,6 +32,8 @@ constexpr int kTopCapBig = kTopTrigger + 256 * 8;    // ... of the whole workgro
 constexpr int kTopSmallN = 64;     // largest n served with the small buffer
 constexpr int kTopMaxN = 256;      // largest n supported
 constexpr int kTopKeep = 256;      // a coarse compaction may leave up to this many entries
+constexpr int kTopRankMax = 96;    // a coarse compaction of more entries than this goes by radix passes: counting ranks
+                                   // costs every thread two instructions per entry, two 8-bit passes about 150 in all
 
 // float -> uint32 such that a < b  <=>  image(a) < image(b)  (-0 < +0; NaNs must be kept out by the caller)
 __device__ __forceinline__ uint32_t float_order_bits(float f)
@@ -106,7 +108,19 @@ struct TopN {
     __device__ __forceinline__ bool end_prime(TopScratch &s)
     {
         priming = false;
-        if (prime_best != 0ull) {
+        // (a small selection does not need all 256 candidates: the best of every 4 or 2 neighbouring lanes are real
+        // entries too, and the n-th largest of 64 or 128 of them costs a fraction of the rank count over 256 to find -
+        // it lies a few ranks lower, which lets a few more entries of the first round through)
+        const int group = n <= 32 ? 4 : (n <= 100 ? 2 : 1);
+        if (group >= 2) {
+            const uint64_t o = __shfl_xor(prime_best, 1, 64);
+            if (o > prime_best) prime_best = o;
+        }
+        if (group >= 4) {
+            const uint64_t o = __shfl_xor(prime_best, 2, 64);
+            if (o > prime_best) prime_best = o;
+        }
+        if (prime_best != 0ull && ((int)threadIdx.x & (group - 1)) == 0) {
             const int32_t i = atomicAdd(count, 1);
             buf[i] = prime_best;  // at most one per thread
         }
@@ -160,7 +174,8 @@ struct TopN {
             __syncthreads();
             return false;
         }
-        if (cnt <= kBlock) {
+        const bool by_rank = !coarse || cnt <= kTopRankMax;
+        if (by_rank && cnt <= kBlock) {
             // Few entries: every entry finds its rank by counting the entries above it (broadcast reads), the n
             // best move to the front in rank order and the n-th of them is the new, exact threshold.  Three
             // barriers instead of the dozen of the radix select below.
@@ -176,7 +191,7 @@ struct TopN {
             __syncthreads();
             return true;
         }
-        if (cnt <= 2 * kBlock) {
+        if (by_rank && cnt <= 2 * kBlock) {
             // the same with two entries per thread: one broadcast read serves both
             uint64_t mine0 = buf[tid], mine1 = tid + kBlock < cnt ? buf[tid + kBlock] : 0ull;
             int r0 = 0, r1 = 0;
