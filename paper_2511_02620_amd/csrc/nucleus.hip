@@ -352,6 +352,117 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
         __syncthreads();            // the bins are cleared or reused next
         break;
     }
+    double Zk = 0.0, below = 0.0;  // mass of K; mass of the members of K below the claimed token's index
+    int64_t kept = 0;
+    float tau_val = nan;
+    uint64_t cut = 0ull;   // sorted path: the last member of K in rank order
+    int64_t n_tie = 0;     // tie path: how many of the ties belong to K
+    int32_t tb = 0;        //           and how many ties lie below the claimed token's index
+    bool many_ties = false;
+    const uint32_t t32 = valid ? (uint32_t)t : 0u;  // an invalid claim has nothing below it (its outputs are NaN anyway)
+
+    // bf16 rows whose bracket is a handful of logit values with many entries each (the usual case when K is large:
+    // near the cut a bf16 value is shared by thousands of tokens): ONE more pass finishes the row.  Entries of equal
+    // value have equal mass, so the pass only counts, per value of the bracket and per thread, the entries and those
+    // of them below the claimed token's index (16 + 16 bits in one private LDS word), and sums what lies above the
+    // bracket as the last pass of the general path does.  The values' masses are then taken in fp64, the value at
+    // which the cumulative mass reaches the target is found by walking at most 16 of them, and it is treated as the
+    // general path treats a single-value bracket: its ties enter K in index order.
+    bool provably_small = false;
+    {
+        const double e_lo = (double)fast_exp2(__fmaf_rn(value_of_key(klo), c, neg_Rc));
+        provably_small = e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48);
+    }
+    const bool by_counts = DT == 0 && khi > klo && khi - klo < (uint32_t)kNucBins && !provably_small && V <= (int64_t)(1 << 24);
+    if (by_counts) {  // uniform
+        const uint32_t span = khi - klo;
+        uint32_t *cnt = reinterpret_cast<uint32_t *>(raw);  // [key - klo][thread]; a thread meets fewer than 2^16 entries
+#pragma unroll
+        for (int k = 0; k < kNucBins; ++k) cnt[k * kBlock + tid] = 0u;
+        double below_above = 0.0;
+        int32_t n_above = 0;
+        for_each_vector([&](const ipt_u32x4 &q, uint32_t base) {
+            uint32_t kw[4];
+            keys_of(q, kw);
+            float below_vec = 0.0f;
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                if (base + E > V32 && base + j >= V32) continue;  // (false for every vector but a ragged last one)
+                const uint32_t key = key_of(kw, j);
+                const uint32_t d = key - klo;
+                if (d <= span) {
+                    cnt[(int)d * kBlock + tid] += (base + j < t32) ? 0x10001u : 1u;
+                } else if (key > khi) {
+                    n_above += 1;
+                    if (base + j < t32) below_vec += fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
+                }
+            }
+            below_above += (double)below_vec;
+        });
+        // the 256 x 16 counters -> 16 totals of each kind (exact), through the memory of part_m
+        int32_t(*part_c)[kNucBins][2] = reinterpret_cast<int32_t(*)[kNucBins][2]>(&part_m[0][0]);
+        int32_t *key_cnt = reinterpret_cast<int32_t *>(&bin_m[0]);  // [16][2]
+        __syncthreads();
+        {
+            const int k = tid & 15, grp = tid >> 4;
+            int32_t all = 0, low = 0;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t v = cnt[k * kBlock + grp * 16 + i];
+                all += (int32_t)(v & 0xFFFFu);
+                low += (int32_t)(v >> 16);
+            }
+            part_c[grp][k][0] = all;
+            part_c[grp][k][1] = low;
+        }
+        __syncthreads();
+        if (tid < 2 * kNucBins) {
+            int32_t sm = 0;
+#pragma unroll
+            for (int grp = 0; grp < 16; ++grp) sm += part_c[grp][tid >> 1][tid & 1];
+            key_cnt[tid] = sm;
+        }
+        __syncthreads();
+        const int64_t cnt_above = (int64_t)block_sum_i32(n_above, lds_i);
+        // from the top: the first value at which the cumulative mass reaches the target (every thread walks the
+        // same values in the same order); the values above it belong to K whole
+        double ma = mass_above, below_hi = 0.0, e_cut = 0.0;
+        int64_t cnt_hi = 0;
+        int jcut = -1, jlast = -1;
+        for (int j = (int)span; j >= 0; --j) {
+            const int64_t na = key_cnt[2 * j];
+            if (na == 0) continue;
+            const double e = mass_of_f64(value_of_key(klo + (uint32_t)j));
+            jlast = j;
+            e_cut = e;
+            if (ma + e * (double)na >= target) {
+                jcut = j;
+                break;
+            }
+            ma += e * (double)na;
+            cnt_hi += na;
+            below_hi += e * (double)key_cnt[2 * j + 1];
+        }
+        many_ties = true;
+        if (jcut < 0 && jlast >= 0) {  // rounding left the target just out of reach: the whole bracket
+            jcut = jlast;
+            const int64_t na = key_cnt[2 * jcut];
+            ma -= e_cut * (double)na;
+            cnt_hi -= na;
+            below_hi -= e_cut * (double)key_cnt[2 * jcut + 1];
+        }
+        const int64_t bracket = jcut >= 0 ? (int64_t)key_cnt[2 * jcut] : 0;
+        tb = jcut >= 0 ? key_cnt[2 * jcut + 1] : 0;
+        n_tie = e_cut > 0.0 ? (int64_t)ceil((target - ma) / e_cut) : bracket;
+        n_tie = n_tie < 1 ? 1 : n_tie;
+        n_tie = n_tie > bracket ? bracket : n_tie;
+        klo = khi = klo + (uint32_t)(jcut >= 0 ? jcut : 0);
+        tau_val = value_of_key(klo);
+        below = block_sum_f64(below_above, lds_d) + below_hi + e_cut * (double)((int64_t)tb < n_tie ? (int64_t)tb : n_tie);
+        Zk = ma + e_cut * (double)n_tie;
+        kept = cnt_above + cnt_hi + n_tie;
+        mass_above = ma;
+    } else {
     // Further passes: the bracket's key range divided evenly into at most 16 bins, until it is a single key (one
     // logit value) or provably small enough to sort.  No counts are kept: every entry of the bracket weighs at
     // least as much as the bracket's smallest key would, so mass / that weight bounds the number of entries.
@@ -387,7 +498,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
     }
     // A single logit value shared by the whole bracket (possibly thousands of tokens) needs no sorting: the ties
     // enter K in index order, each with the same mass, and how many of them do is a division.
-    const bool many_ties = single_value;
+    many_ties = single_value;
 
     // ---- pass C: gather the bracket (or count the ties below the claimed token), and sum what lies above the
     //      bracket and below the claimed token's index ----
@@ -398,7 +509,6 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
     int32_t ties = 0;          // ... and all of them
     int32_t n_above = 0;       // entries above the bracket
     const uint32_t span_c = khi - klo;
-    const uint32_t t32 = valid ? (uint32_t)t : 0u;  // an invalid claim has nothing below it (its outputs are NaN anyway)
     for_each_vector([&](const ipt_u32x4 &q, uint32_t base) {
         uint32_t kw[4];
         keys_of(q, kw);
@@ -426,12 +536,6 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
     __syncthreads();
     const int64_t cnt_above = (int64_t)block_sum_i32(n_above, lds_i);
 
-    double Zk, below;     // mass of K; mass of the members of K below the claimed token's index
-    int64_t kept;
-    float tau_val;
-    uint64_t cut = 0ull;  // sorted path: the last member of K in rank order
-    int64_t n_tie = 0;    // tie path: how many of the ties belong to K
-    int32_t tb = 0;       //           and how many ties lie below the claimed token's index
     if (many_ties) {
         tau_val = s_xtau;
         const double e_tau = mass_of_f64(tau_val);
@@ -521,6 +625,8 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
         kept = cnt_above + (int64_t)(n > 0 ? pos + 1 : 0);
         tau_val = n > 0 ? top_key(cut) : nan;
     }
+    }  // (the general path)
+    const uint32_t span_c = khi - klo;  // for the sampler's token below
 
     if (tid == 0) {
         if (kept_out) kept_out[row] = (int32_t)kept;
