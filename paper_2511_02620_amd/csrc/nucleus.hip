@@ -17,6 +17,11 @@
 //        mass from the top reaches it becomes the bracket: bin1 is monotone in the logit, so its first key is
 //        found by bisection.  (If M lies so far above R that terms could overflow, the pass is repeated with
 //        R = M.)
+//   BC   bf16 rows whose bracket is now at most 16 logit values with many entries each (the usual case when K is
+//        large: near the cut a bf16 value is shared by thousands of tokens) are finished by one counting pass:
+//        per value of the bracket and per thread the number of entries, and of entries below the claimed token's
+//        index; entries of equal value have equal mass, which is taken per value in fp64.  Two reads in all.
+//        Every other row goes on with B2 and C:
 //   B2.. the bracket's key range is divided evenly into at most 16 bins and searched in the same way, until it
 //        is a single key - one logit value - or provably holds at most kNucCap entries (its mass divided by the
 //        weight of its smallest key bounds their number).  Typically one or two passes;
@@ -193,10 +198,13 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
     // the rounding of that constant (a tilt of up to 6e-8 |x| c over the whole row, all to one side) is gone; what
     // remains per entry is the rounding of the exponent itself and of the hardware exponential, which differ from one
     // logit value to the next and largely cancel in the sums.
+    // (The large piece is rounded DOWN, so that the small one is positive: a masked entry, -inf, then gives -inf in
+    // both products and a mass of zero with no special case.)
     const double c64 = 1.4426950408889634074 / (double)ri.T;
-    const float c_hi = (float)c64, c_lo = (float)(c64 - (double)c_hi);
+    float c_hi = (float)c64;
+    if ((double)c_hi >= c64 && c_hi > 1.0e-30f) c_hi = __uint_as_float(__float_as_uint(c_hi) - 1u);
+    const float c_lo = fmaxf((float)(c64 - (double)c_hi), 1.1754944e-38f);
     auto mass_of = [&](float x) __attribute__((always_inline)) {
-        x = fmaxf(x, -3.0e38f);  // a masked entry (-inf) times the small piece, which may be negative or zero: keep it finite
         return fast_exp2(__fmaf_rn(x, c_hi, __fmaf_rn(x, c_lo, neg_Rc)));
     };
     // (the same real number 2^(x c + neg_Rc), with the rounded neg_Rc as the common reference, in fp64: for the
@@ -288,18 +296,29 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
             return (uint32_t)(int)__builtin_amdgcn_fmed3f(__fmaf_rn(x, sc, off), 0.0f, 15.0f);
         };
         clear_bins();
-        // largest and smallest key met (bf16: of the even and of the odd entries, packed)
+        // Largest and smallest key met.  bf16: three packed extremes of the raw bit patterns (of the even and of the
+        // odd entries) tell as much, at three instructions per two entries: the largest pattern as signed 16-bit is
+        // the largest entry that is not negative (or +inf, or a NaN with the sign clear), the largest as unsigned the
+        // most negative one (or -inf, or a NaN with the sign set), the smallest as unsigned the negative entry nearest
+        // to zero if all are negative, else the smallest non-negative one.
         typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+        typedef int16_t i16x2_t __attribute__((ext_vector_type(2)));
         uint32_t kmax = 0u, kmin = 0xFFFFFFFFu;
+        uint32_t smax = 0x80008000u, umax = 0u, umin = 0xFFFFFFFFu;
         for_each_vector([&](const ipt_u32x4 &q, uint32_t) {
-            uint32_t kw[4];
-            keys_of(q, kw);
+            if (DT == 0) {
+                const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (DT == 0) {
-                    kmax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, kmax), __builtin_bit_cast(u16x2_t, kw[i])));
-                    kmin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, kmin), __builtin_bit_cast(u16x2_t, kw[i])));
-                } else {
+                for (int i = 0; i < 4; ++i) {
+                    smax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, smax), __builtin_bit_cast(i16x2_t, w[i])));
+                    umax = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, umax), __builtin_bit_cast(u16x2_t, w[i])));
+                    umin = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, umin), __builtin_bit_cast(u16x2_t, w[i])));
+                }
+            } else {
+                uint32_t kw[4];
+                keys_of(q, kw);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
                     kmax = max(kmax, kw[i]);
                     kmin = min(kmin, kw[i]);
                 }
@@ -310,13 +329,23 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
                 add_mass(bin1(x), mass_of(x));
             }
         });
+        bool sign_set_nan = false;
         if (DT == 0) {
-            kmax = max(kmax & 0xFFFFu, kmax >> 16);
-            kmin = min(kmin & 0xFFFFu, kmin >> 16);
+            // (signed maximum through the unsigned reduction: flip the sign bit)
+            const uint32_t sm = block_max_key(max((smax & 0xFFFFu) ^ 0x8000u, (smax >> 16) ^ 0x8000u)) ^ 0x8000u;
+            const uint32_t um = block_max_key(max(umax & 0xFFFFu, umax >> 16));
+            const uint32_t un = block_min_key(min(umin & 0xFFFFu, umin >> 16));
+            auto key_of_pattern = [&](uint32_t p) __attribute__((always_inline)) {
+                return (p & 0x8000u) ? 0x8000u - (p & 0x7FFFu) : 0x8000u + p;
+            };
+            sign_set_nan = um > 0xFF80u;
+            kmax = key_of_pattern(sm < 0x8000u ? sm : un);  // a non-negative entry exists: the largest of them
+            kmin = key_of_pattern(um >= 0x8000u ? um : un);  // a negative entry exists: the most negative of them
+        } else {
+            kmax = block_max_key(kmax);  // (a thread without a vector still holds the neutral values)
+            kmin = block_min_key(kmin);
         }
-        kmax = block_max_key(kmax);  // (a thread without a vector still holds the neutral values)
-        kmin = block_min_key(kmin);
-        if (kmax >= kKeyPosInf || kmin < kKeyNegInf) {  // uniform: NaN or +inf somewhere, no distribution
+        if (kmax >= kKeyPosInf || kmin < kKeyNegInf || sign_set_nan) {  // uniform: NaN or +inf somewhere, no distribution
             give_up(kFlagNonfinite | (valid ? 0u : kFlagInvalidClaim), 0);
             return;
         }

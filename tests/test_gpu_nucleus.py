@@ -70,10 +70,14 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
         idx = torch.from_numpy(np.nonzero(sure)[0]).to(DEV)
         st = parity.compare_ipt({k2: v[idx] for k2, v in out.items() if k2 != "kept"},
                                 {k2: v[sure] for k2, v in ref.items()}, log_mass_sigma=0.02)
+    # (a marginal token is the least probable member of a set of `kept` tokens, so it holds at most 1 / kept of the
+    # renormalised mass: that much an interval end may move per token in doubt - far below 1e-4 unless K is small and
+    # made of ties, e.g. a constant row cut at exactly a whole number of tokens)
+    slack = 1e-4 + (hi - lo)[~sure].astype(np.float64) / np.maximum(lo[~sure], 1)
     for name in ("cdf_lo", "cdf_hi", "dist"):
         g_, r_ = out[name].cpu().numpy().astype(np.float64)[~sure], ref[name][~sure]
         both_nan = np.isnan(g_) & np.isnan(r_)
-        assert (both_nan | (np.abs(g_ - r_) <= 1e-4)).all(), name
+        assert (both_nan | (np.abs(g_ - r_) <= slack)).all(), name
     # the sampler's own token, on the rows whose kept set is the oracle's: equal, except where u sits on a CDF step
     # (then the oracle's interval of the GPU's token touches u); a row the library gave up on has none
     flags = out["flags"].cpu().numpy()
@@ -94,7 +98,10 @@ def _compare(difr, logits, V, T, seeds, sid, pos, claims, p, temps=None):
     lo_n = _oracle(host, V, T, seeds, sid, pos, claims, p32 - EPS_P_NARROW, temps)["kept"]
     hi_n = _oracle(host, V, T, seeds, sid, pos, claims, p32 + EPS_P_NARROW, temps)["kept"]
     st["in_doubt_at_1e-7"] = int((lo_n != hi_n).sum())
-    assert st["differs"] <= max(1, kept.shape[0] // 20)
+    # a row whose cut the oracle itself moves within 1e-7 of top_p - the accuracy of one fp32 exponential - may go
+    # either way (a constant row cut at a whole number of tokens does); of the others, nearly all must be the oracle's
+    st["differs_beyond_1e-7"] = int(((kept != ref["kept"]) & (lo_n == hi_n)).sum())
+    assert st["differs_beyond_1e-7"] <= max(1, kept.shape[0] // 20)
     out["ipt_token"] = torch.from_numpy(tok).to(DEV)
     return st, out
 
