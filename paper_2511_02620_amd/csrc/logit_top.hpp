@@ -43,8 +43,14 @@ struct LogitTop {
         floor_pos = f > 0.0f;
         floor16 = cap_bits(f, !floor_pos);
     }
-    // call after a compaction of `top`
-    __device__ __forceinline__ void retarget() { set_floor(top.theta == 0ull ? -__builtin_inff() : top_key(top.theta)); }
+    // call after a compaction of `top`.  (A coarse compaction leaves a threshold whose low key bits are zero; when the
+    // n-th largest logit so far is a masked entry, -inf, that image is not a number: nothing is below the floor then.)
+    __device__ __forceinline__ void retarget()
+    {
+        float f = top.theta == 0ull ? -__builtin_inff() : top_key(top.theta);
+        if (!(f == f)) f = -__builtin_inff();
+        set_floor(f);
+    }
 
     __device__ __forceinline__ void push_entry(float xv, int32_t v)
     {

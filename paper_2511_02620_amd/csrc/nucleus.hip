@@ -193,23 +193,24 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
         }
     }
     lo_s = -block_max(-lo_s, lds_f);  // finite and <= R, since R is
-    float neg_Rc = -(R * c);
-    // The masses that decide the cut take log2(e) / T in two fp32 pieces, so that what an entry's exponent loses to
-    // the rounding of that constant (a tilt of up to 6e-8 |x| c over the whole row, all to one side) is gone; what
-    // remains per entry is the rounding of the exponent itself and of the hardware exponential, which differ from one
-    // logit value to the next and largely cancel in the sums.
-    // (The large piece is rounded DOWN, so that the small one is positive: a masked entry, -inf, then gives -inf in
-    // both products and a mass of zero with no special case.)
+    // A mass is 2^((x - R) c64), c64 = log2(e) / T.  The difference x - R comes first: for the entries that carry the
+    // mass it is small and exact, so what the fp32 exponent loses is in proportion to it (an exponent formed as
+    // x c - R c would carry the rounding of two products of the size of R c, 1e-5 and more when |R| / T is in the
+    // hundreds, and the masses that decide the cut - fp32 in the search, fp64 in its last step - would disagree by
+    // as much).  The constant is taken in two fp32 pieces, so that what an exponent loses to ITS rounding (a tilt of
+    // up to 6e-8 |x - R| c over the whole row, all to one side) is gone as well; the large piece is rounded DOWN, which
+    // makes the small one positive: a masked entry, -inf, then gives -inf in both products and a mass of zero with no
+    // special case.
     const double c64 = 1.4426950408889634074 / (double)ri.T;
     float c_hi = (float)c64;
     if ((double)c_hi >= c64 && c_hi > 1.0e-30f) c_hi = __uint_as_float(__float_as_uint(c_hi) - 1u);
     const float c_lo = fmaxf((float)(c64 - (double)c_hi), 1.1754944e-38f);
     auto mass_of = [&](float x) __attribute__((always_inline)) {
-        return fast_exp2(__fmaf_rn(x, c_hi, __fmaf_rn(x, c_lo, neg_Rc)));
+        const float d = x - R;
+        return fast_exp2(__fmaf_rn(d, c_hi, d * c_lo));
     };
-    // (the same real number 2^(x c + neg_Rc), with the rounded neg_Rc as the common reference, in fp64: for the
-    // few masses of the last step)
-    auto mass_of_f64 = [&](float x) __attribute__((always_inline)) { return exp2(fma((double)x, c64, (double)neg_Rc)); };
+    // (the same real number in fp64: for the few masses of the last step)
+    auto mass_of_f64 = [&](float x) __attribute__((always_inline)) { return exp2(((double)x - (double)R) * c64); };
 
     // ---- passes B: search for the bracket [klo, khi] of keys that holds the cut ----
     // Keys are the order-preserving images of the logits at the storage type's resolution (16 bits for bf16).
@@ -352,7 +353,6 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
         const float M = value_of_key(kmax);
         if ((M - R) * c > 96.0f) {  // uniform; terms of 2^96 and more: start again from M
             R = M;
-            neg_Rc = -(R * c);
             continue;
         }
         combine_bins();
@@ -399,7 +399,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
     // general path treats a single-value bracket: its ties enter K in index order.
     bool provably_small = false;
     {
-        const double e_lo = (double)fast_exp2(__fmaf_rn(value_of_key(klo), c, neg_Rc));
+        const double e_lo = (double)mass_of(value_of_key(klo));
         provably_small = e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48);
     }
     const bool by_counts = DT == 0 && khi > klo && khi - klo < (uint32_t)kNucBins && !provably_small && V <= (int64_t)(1 << 24);
@@ -423,7 +423,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
                     cnt[(int)d * kBlock + tid] += (base + j < t32) ? 0x10001u : 1u;
                 } else if (key > khi) {
                     n_above += 1;
-                    if (base + j < t32) below_vec += fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
+                    if (base + j < t32) below_vec += mass_of(value_of(q, j));
                 }
             }
             below_above += (double)below_vec;
@@ -503,7 +503,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
             break;
         }
         {  // (a bracket whose lower edge is -inf gives no bound)
-            const double e_lo = (double)fast_exp2(__fmaf_rn(value_of_key(klo), c, neg_Rc));
+            const double e_lo = (double)mass_of(value_of_key(klo));
             if (e_lo > 0.0 && e_lo < (double)__builtin_inff() && bracket_mass <= e_lo * (double)(kNucCap - 48)) break;
         }
         const uint32_t span = khi - klo;
@@ -557,7 +557,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
                 }
             } else if (key > khi) {
                 n_above += 1;
-                if (base + j < t32) below_vec += fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
+                if (base + j < t32) below_vec += mass_of(value_of(q, j));
             }
         }
         below_above += (double)below_vec;
@@ -682,7 +682,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
         } else {
             in_K = top_composite(xt, (int32_t)t) >= cut;
         }
-        const double own = in_K ? (double)fast_exp2(__fmaf_rn(xt, c, neg_Rc)) : 0.0;
+        const double own = in_K ? (double)mass_of(xt) : 0.0;
         ad = below / Zk;
         bd = ad + own / Zk;
         a = (float)ad;
@@ -739,7 +739,7 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
                 if (key - klo <= span_c)
                     member = many_ties ? (tie_rank++ < n_tie) : (top_composite(value_of(q, j), (int32_t)(base + j)) >= cut);
                 if (member) {
-                    e[j] = fast_exp2(__fmaf_rn(value_of(q, j), c, neg_Rc));
+                    e[j] = mass_of(value_of(q, j));
                     last_member = (int32_t)(base + j);
                 }
             }

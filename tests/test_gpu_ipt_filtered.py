@@ -117,6 +117,30 @@ def test_ipt_filtered_signed_zeros_tie_by_index(difr, dtype, k, p):
     assert st["token_excused"] == 0
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("V,k", [(107, 50), (107, 65), (3003, 50), (3003, 200), (9007, 256)])
+def test_ipt_filtered_masked_rows_with_a_ragged_end(difr, dtype, V, k):
+    """Rows in which most entries are masked (-inf), so that the k-th largest logit so far is a masked entry for much of
+    the pass (the selection's threshold is then the image of -inf), with finite entries in the ragged last vector:
+    every finite entry must still reach the selection (top_p just below 1 makes the kept count feel each of them)."""
+    N = 48
+    g = torch.Generator().manual_seed(5 + V + k)
+    x = torch.randn(N, V, generator=g) * 2.0
+    x[torch.rand(N, V, generator=g) < 0.6] = float("-inf")
+    x[:, V - 3:] = torch.randn(N, 3, generator=g) + 1.0       # finite, and not small, in the last vector
+    E = 8 if dtype == torch.bfloat16 else 4
+    ld = ((V + E - 1) // E) * E
+    logits = torch.full((N, ld), float("nan"), dtype=dtype, device=DEV)
+    logits[:, :V] = x.to(dtype).to(DEV)
+    seeds = torch.tensor([77, -9], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    temps = torch.linspace(0.5, 1.4, N).to(DEV)
+    for p in (0.999, 0.9):
+        st, out = _compare(difr, logits, V, 1.3, seeds, sid, pos, None, k, p, temps=temps)
+        say("filtered masked ragged", dtype, V, k, p, st)
+
+
 def test_ipt_filtered_c2_class_rows(difr):
     wl = W.scaled(W.C2_3B, S=2, L=32, chunk_rows=64)
     ver, prov = wl.logits_chunk(0, DEV)
