@@ -189,6 +189,33 @@ def test_nucleus_first_round_unlike_the_row(difr, dtype, layout):
         assert not (out["flags"] & 4).any()
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_nucleus_cut_on_a_tie_of_large_logits(difr, dtype):
+    """Logits in the hundreds at T = 0.6: the exponent (x - R) log2(e) / T has to come from the difference, not from two
+    products of that size.  The two largest logits are equal and hold half of the mass each, so top_p = 0.5 needs both
+    (the rest of the row adds a few 1e-6 to the total): a mass that is off by 1e-5 keeps one."""
+    N, V = 32, 1017
+    g = torch.Generator().manual_seed(91)
+    x = (torch.randn(N, V, generator=g) * 60.0).round()
+    top = x.max(dim=1).values + 7.0
+    for r in range(N):
+        i, j = torch.randperm(V, generator=g)[:2].tolist()
+        x[r, i] = x[r, j] = top[r]
+    E = 8 if dtype == torch.bfloat16 else 4
+    ld = ((V + E - 1) // E) * E
+    logits = torch.full((N, ld), float("nan"), dtype=dtype, device=DEV)
+    logits[:, :V] = x.to(dtype).to(DEV)
+    seeds = torch.tensor([17], dtype=torch.int64).to(DEV)
+    sid = torch.zeros(N, dtype=torch.int32, device=DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    claims = logits[:, :V].float().argmax(dim=1).to(torch.int32)
+    for p in (0.5, 0.4, 0.999):
+        st, out = _compare(difr, logits, V, 0.6, seeds, sid, pos, claims, p)
+        say("nucleus tie of large logits", dtype, p, st)
+        if p == 0.5:
+            assert (out["kept"] == 2).all()
+
+
 def test_nucleus_zipf_rows_and_per_row_temperatures(difr):
     """C2-class rows (V = 128256, Zipf profile): flat distributions whose 0.95-nucleus holds tens of thousands of
     tokens; per-row temperatures."""
