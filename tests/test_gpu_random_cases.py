@@ -247,6 +247,30 @@ def test_random_case(difr, case):
     run_case(difr, c, rng)
 
 
+@pytest.mark.parametrize("case", [700182, 702573])
+def test_random_case_found_outside_the_suite(difr, case):
+    """Two draws of the same generator that once failed: masked rows on which the k-th largest logit so far is -inf
+    when a coarse compaction runs (finite entries of the ragged tail were lost), and a nucleus cut on a tie of the
+    two largest logits with logits in the hundreds."""
+    rng = np.random.default_rng(1000 + case)
+    c = make_case(rng)
+    run_case(difr, c, rng)
+
+
+def test_random_cases_in_bulk(difr):
+    """Four hundred more draws in one test (a few seconds): small shapes, every kernel against its counterparts and
+    against the oracle on a few rows."""
+    for case in range(20000, 20400):
+        rng = np.random.default_rng(1000 + case)
+        c = make_case(rng)
+        try:
+            run_case(difr, c, rng)
+        except Exception:
+            print("case", case, c["dtype"], "V", c["V"], "ld", c["ld"], "N", c["N"], c["kind"], "T", c["T"], "claims", c["ck"],
+                  file=sys.stderr, flush=True)
+            raise
+
+
 @pytest.mark.parametrize("case", range(4))
 def test_random_case_full_width(difr, case):
     """The same on vocabularies of the paper's model families (tens of stream rounds per row)."""
