@@ -118,10 +118,18 @@ def compare_ipt(gpu: dict, ref: dict, logits_host=None, V=None, row_args=None, l
         #   dS = (phi(z_b) db - phi(z_a) da) / (sigma (mass + eps))  <~  dw + 4 da (1 + dist/sigma + width/sigma) / sigma.
         # A row beyond the bar is accepted only if that first-order error alone can exceed the bar there (a sigma
         # so small that the interval's fp32 position error shows), stays within it, and is counted.
+        # One more term belongs to the definition itself: a and b are CDF values (the appendix takes them from
+        # F = concat(0, cumsum p)), doubles of size up to 1 whose spacing is 1.1e-16; a claimed token of probability
+        # 1e-14 has an interval that is a hundred such steps wide on either side of the comparison, so its width -
+        # and with it the mass - is only good to a per cent, in the oracle as much as in the kernel.
         da, dw = 1e-7, 4e-6
         z = np.nan_to_num(ref["dist"], nan=0.0) / log_mass_sigma
-        zin = np.minimum(1.0, np.nan_to_num(ref["cdf_hi"] - ref["cdf_lo"], nan=0.0)) / log_mass_sigma
-        first_order = dw + 4.0 * da * (1.0 + z + zin) / log_mass_sigma
+        width = np.nan_to_num(ref["cdf_hi"] - ref["cdf_lo"], nan=0.0)
+        zin = np.minimum(1.0, width) / log_mass_sigma
+        # (a step on either end, on either side, and as much again where the two normal CDF values are subtracted)
+        quant = np.where(width > 0.0, 4.5e-16 / np.maximum(width, 1e-300), 0.0)
+        quant = np.where(width < 2e-15, np.inf, quant)  # under twenty steps wide: either side's width may round to 0
+        first_order = dw + quant + 4.0 * da * (1.0 + z + zin) / log_mass_sigma
         gl, rl = g["log_mass"].astype(np.float64), ref["log_mass"]
         ok = ~(np.isnan(gl) & np.isnan(rl))
         err = np.where(ok, np.abs(gl - rl), 0.0)
@@ -135,6 +143,7 @@ def compare_ipt(gpu: dict, ref: dict, logits_host=None, V=None, row_args=None, l
                                                    g["cdf_hi"][worst], g["u"][worst], ref["cdf_lo"][worst],
                                                    ref["cdf_hi"][worst], ref["dist"][worst]))
         stats["log_mass_beyond_bar"] = int(beyond.sum())
+        stats["log_mass_interval_below_fp64_spacing"] = int(np.isinf(quant).sum())
         err = err[ok]
         stats["log_mass_err"] = float(err.max()) if err.size else 0.0
     d = g["dist"][~np.isnan(g["dist"])]
