@@ -274,7 +274,7 @@ struct GumbelStream {
 
     // TOPN mode, whole wave (call from wave-uniform code): the per-entry look at every waiting vector, one vector per
     // lane, against the gate as it stands now (it only ever rises, so nothing that still matters is missed).  The
-    // caller drains before every barrier that ends an epoch, so that a repeated epoch finds its own pushes only.
+    // queue persists across the caller's epochs; the caller drains it before the selection is finished.
     __device__ __forceinline__ void drain(TopN *top)
     {
         const int lane = tid & 63;

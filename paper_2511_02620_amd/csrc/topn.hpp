@@ -11,13 +11,12 @@
 // final top n is ever dropped: the threshold is a lower bound of the n-th largest of what has been seen.
 //
 // Capacity.  The caller works in epochs of a few stream rounds without any barrier.  A push that finds the
-// buffer full raises `over` instead of storing its entry, and the caller then rewinds the epoch (resets the
-// counter to its value at the epoch's start) and repeats it one wave and one round at a time, with a compaction
-// check after each such step.  A step starts with fewer than kTopTrigger entries and adds at most 8 per thread
-// of one wave, so in that mode kTopCapSmall = kTopTrigger + 64 * 8 slots always suffice, whatever the order of
-// the data.  Small buffers are what lets five workgroups share a compute unit; selections of more than
-// kTopSmallN entries push so much in an ordinary epoch that they get kTopCapBig slots instead (the kernels
-// are instantiated for both).
+// buffer full raises `over` instead of storing its entry, and the caller then starts the row again in a careful
+// mode: one wave and one round at a time, with a compaction check after each such step.  A step starts with
+// fewer than kTopTrigger entries and adds at most 8 per thread of one wave, so in that mode kTopCapSmall =
+// kTopTrigger + 64 * 8 slots always suffice, whatever the order of the data.  Small buffers are what lets five
+// workgroups share a compute unit; selections of more than kTopSmallN entries push so much in an ordinary epoch
+// that they get kTopCapBig slots instead (the kernels are instantiated for both).
 #pragma once
 
 #include "difr_device.hpp"
@@ -72,7 +71,7 @@ struct TopN {
                      // that the threshold, which is also the bound of the stream's gates, stays fresh
     bool full;       // this thread's push took the buffer to the compaction trigger (combine over the workgroup
                      // with __syncthreads_or: reading the counter instead would race with the next round's pushes)
-    bool over;       // a push of this thread found the buffer full: the epoch must be repeated
+    bool over;       // a push of this thread found the buffer full: the row must be started again, carefully
     bool priming;    // see begin_prime()
     uint64_t prime_best;
 
@@ -147,7 +146,7 @@ struct TopN {
             if (i < cap)
                 buf[i] = c;
             else
-                over = true;  // no room: the entry is dropped and the epoch has to be repeated
+                over = true;  // no room: the entry is dropped and the row has to be started again
             if (i >= trigger - 1) full = true;
         }
     }
