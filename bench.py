@@ -69,7 +69,7 @@ MEASURED_VALU_PER_ENTRY = {
     ("difr_score_both", "c3_30b_moe_class"): 17.34,
     ("difr_ipt_score", "c3_30b_moe_class"): 5.21,
 }
-SCLK_UNDER_LOAD_GHZ = {"difr_gumbel_score": 2.06, "difr_score_both": 2.20, "difr_ipt_score": 2.39}
+SCLK_UNDER_LOAD_GHZ = {"difr_gumbel_score": 2.02, "difr_score_both": 2.11, "difr_ipt_score": 2.30}
 
 
 def probe_clocks(kernels, seconds=3.0):
@@ -315,10 +315,11 @@ def main():
                     help="fused: difr_score_both (one read of the logits for both estimators); "
                          "separate: difr_gumbel_score then difr_ipt_score")
     ap.add_argument("--cpu-rows", type=int, default=32768, help="rows of the batch the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--clock-probe", action="store_true",
-                    help="after the timed region, run each row kernel back to back for three seconds while rocm-smi "
-                         "is asked for the shader clock every 0.4 s, and report what it showed (the chip lowers its "
-                         "clock under the Philox multiply load; the ALU roofline is priced at the nominal clock)")
+    ap.add_argument("--clock-probe", dest="clock_probe", action="store_true", default=True,
+                    help="(default) after the timed region, run each row kernel back to back for two seconds while "
+                         "rocm-smi is asked for the shader clock every 0.4 s, and report what it showed (the chip lowers "
+                         "its clock under the Philox multiply load; the ALU roofline is priced at the nominal clock)")
+    ap.add_argument("--no-clock-probe", dest="clock_probe", action="store_false")
     ap.add_argument("--copy-probe", action="store_true",
                     help="before the timed region, run one plain device copy of 4 GiB (a kernel of known HBM "
                          "traffic: 4 GiB read + 4 GiB written) so that counter runs can be scaled against it")
@@ -421,11 +422,23 @@ def main():
         t_i = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     clock_probe = None
     if args.clock_probe:
-        clock_probe = probe_clocks({
-            "idle": None,
-            "difr_gumbel_score": lambda: difr.gumbel_score(*row_args, data["claims_g"]),
-            "difr_ipt_score": lambda: difr.ipt_score(*row_args, data["claims_i"]),
-            "difr_score_both": lambda: difr.score_both(*row_args, data["claims_g"], data["claims_i"])})
+        try:
+            clock_probe = probe_clocks({
+                "idle": None,
+                "difr_gumbel_score": lambda: difr.gumbel_score(*row_args, data["claims_g"]),
+                "difr_ipt_score": lambda: difr.ipt_score(*row_args, data["claims_i"]),
+                "difr_score_both": lambda: difr.score_both(*row_args, data["claims_g"], data["claims_i"])}, seconds=2.0)
+        except Exception as exc:  # the probe is evidence beside the measurement, never a reason to lose it
+            log("clock probe failed: %r" % (exc,))
+            clock_probe = None
+
+    def clock_under(kernel):
+        """GHz rocm-smi showed while `kernel` ran back to back in this run (median of the samples after the first,
+        which still sees the clock coming down), else the stored figure of profiles/c3_clock_under_load.md."""
+        if clock_probe and len(clock_probe.get(kernel, {}).get("sclk_mhz", [])) >= 3:
+            return float(np.median(clock_probe[kernel]["sclk_mhz"][1:])) / 1000.0, "rocm-smi in this run"
+        ghz = SCLK_UNDER_LOAD_GHZ.get(kernel)
+        return ghz, None if ghz is None else "profiles/c3_clock_under_load.md (stored figure)"
     g, i, sg, si = out
     match_g = float((g["flags"] & 1).float().mean())
     match_i = float((i["flags"] & 1).float().mean())
@@ -461,10 +474,11 @@ def main():
             instr = MEASURED_VALU_PER_ENTRY.get((kernel, wl.name))
             if instr is not None:
                 issue = instr * wl.N * wl.V / 64.0 * 4.0 / (ms * 1e-3 * 1024 * 2.4e9)
-                ghz = SCLK_UNDER_LOAD_GHZ.get(kernel)
+                ghz, ghz_source = clock_under(kernel)
                 r["alu"].update({"measured_valu_instr_per_entry": instr,
                                  "measured_source": "rocprofv3 --pmc SQ_INSTS_VALU, profiles/c3_sq_counters.md (stored figure)",
                                  "issue_slots_used_at_2.4GHz": round(issue, 4), "sclk_under_this_kernel_ghz": ghz,
+                                 "sclk_source": ghz_source,
                                  "issue_slots_used_at_that_clock": None if ghz is None else round(issue * 2.4 / ghz, 4)})
         return r
 
