@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(RANK ? 5
             if (oa.log2_count) oa.log2_count[row] = c > 0 ? __log2f((float)c) : __builtin_nanf("");
         }
     }
-    ipt_finish<DT, true>(b, ri_ipt, row, x_row, s.c, s.m, s.Z, s.P, s.mP, 0, oi, lds_f, lds_d, &lds_tok);
+    ipt_finish<DT, true>(b, ri_ipt, row, x_row, s.c, s.ref(), s.Z, s.P, s.refP(), 0, oi, lds_f, lds_d, &lds_tok);
 }
 
 int launch_score_both(const RowBatch &b, const int32_t *claimed_ipt, const GumbelOutputs &og, const IptOutputs &oi,

@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kBlock) void ipt_score_generic_kernel(RowBatch b, I
     __shared__ int32_t lds_rank[kWaves];
     int32_t above = 0;  // entries whose raw logit exceeds the claimed token's (logit rank)
 
-    float m = ninf, neg_mc = 0.0f, mP = ninf;
+    float m = ninf, neg_mc = __builtin_inff(), neg_mcP = __builtin_inff();  // (+inf: no reference yet)
     double Z = 0.0, P = 0.0;
     for (int64_t base = (int64_t)tid * E; base < V; base += (int64_t)kBlock * E) {
         float x[E], e[E];
@@ -49,9 +49,10 @@ __global__ __launch_bounds__(kBlock) void ipt_score_generic_kernel(RowBatch b, I
 #pragma unroll
         for (int j = 1; j < E; ++j) m8 = fmaxf(m8, x[j]);
         if (m8 > m) {  // rebase the running sum (m = -inf: Z is still 0 and stays 0)
-            Z *= (double)fast_exp2((m - m8) * c);
+            const float moved = -(m8 * c);
+            Z *= (double)fast_exp2(moved - neg_mc);  // between the two rounded references (see ipt_finish)
             m = m8;
-            neg_mc = -(m8 * c);
+            neg_mc = moved;
         }
 #pragma unroll
         for (int j = 0; j < E; ++j) e[j] = fast_exp2(__fmaf_rn(x[j], c, neg_mc));
@@ -61,12 +62,12 @@ __global__ __launch_bounds__(kBlock) void ipt_score_generic_kernel(RowBatch b, I
             if (base + j < tcut) pre += e[j];
         if (base < tcut) {
             P = Z + (double)pre;
-            mP = m;
+            neg_mcP = neg_mc;
         }
         Z += (double)tree_sum<E>(e);
     }
     above = block_sum_i32(above, lds_rank);
-    ipt_finish<DT, false>(b, ri, row, x_row, c, m, Z, P, mP, above, o, lds_f, lds_d, &lds_tok);
+    ipt_finish<DT, false>(b, ri, row, x_row, c, -neg_mc, Z, P, -neg_mcP, above, o, lds_f, lds_d, &lds_tok);
 }
 
 // Streaming kernel for 16-byte aligned rows (the streaming state is described in ipt_stream.hpp).
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(kBlock) void ipt_score_kernel(RowBatch b, IptOutput
         if (n_rounds > full_rounds) careful(full_rounds, s.valid);
     }
     const int32_t above = s.total_above(lds_rank);
-    ipt_finish<DT, true>(b, ri, row, x_row, s.c, s.m, s.Z, s.P, s.mP, above, o, lds_f, lds_d, &lds_tok);
+    ipt_finish<DT, true>(b, ri, row, x_row, s.c, s.ref(), s.Z, s.P, s.refP(), above, o, lds_f, lds_d, &lds_tok);
 }
 
 int launch_ipt_score(const RowBatch &b, bool aligned, float *dist, float *cdf_lo, float *cdf_hi, float *u,

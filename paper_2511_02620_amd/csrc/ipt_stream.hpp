@@ -101,8 +101,8 @@ struct IptOutputs {
 
 template <int DT, bool ALIGNED>
 __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri, int64_t row,
-                                           const typename Elem<DT>::type *x_row, float c, float m, double Z,
-                                           double P, float mP, int32_t above, const IptOutputs &o, float *lds_f,
+                                           const typename Elem<DT>::type *x_row, float c, float ref, double Z,
+                                           double P, float refP, int32_t above, const IptOutputs &o, float *lds_f,
                                            double *lds_d, int32_t *lds_tok)
 {
     constexpr int E = Elem<DT>::kPerVec;
@@ -113,12 +113,17 @@ __device__ __forceinline__ void ipt_finish(const RowBatch &b, const RowInfo &ri,
     const int64_t t = ri.claimed;
     const bool valid = (t >= 0 && t < V);
 
-    // Combine the 256 partial (max, sum) pairs in a fixed order.
-    const float M = block_max(m, lds_f);
-    const float neg_Mc = -(M * c);
-    // a thread that saw only masked entries has m = -inf and Z = 0: its scale is 2^-inf = 0
-    const double Zs = Z * (double)fast_exp2((m - M) * c);
-    const double Ps = (mP > ninf) ? P * (double)fast_exp2((mP - M) * c) : 0.0;
+    // Combine the 256 partial (reference, sum) pairs in a fixed order.  `ref` is the exponent a thread's terms were
+    // taken against: they are 2^(x c - ref), with ref the ROUNDED product of the thread's reference logit and c.  The
+    // common reference is the largest of them, and a thread's scale is 2^(ref - M) from the difference of the two
+    // rounded numbers: forming it from the reference logits instead, as 2^((m - M) c), would be off by the rounding
+    // of m c - half a unit in its last place, 1e-5 when |m| / T runs into the hundreds, a different amount in every
+    // thread.
+    const float M = block_max(ref, lds_f);  // (-inf: every entry masked; +inf or NaN: a +inf or NaN logit)
+    const float neg_Mc = -M;
+    // a thread that saw only masked entries has ref = -inf and Z = 0: its scale is 2^-inf = 0
+    const double Zs = Z * (double)fast_exp2(ref - M);
+    const double Ps = (refP > ninf) ? P * (double)fast_exp2(refP - M) : 0.0;
     const double Ztot = block_sum_f64(Zs, lds_d);
     const double Ptot = block_sum_f64(Ps, lds_d);
 
@@ -228,7 +233,7 @@ __device__ __forceinline__ bool ipt_row_rejected(const RowInfo &ri, int64_t row,
 
 // Online softmax statistics per thread: m = the lane's reference logit (see terms()), Z = sum of 2^((x - m) c).  Each
 // vector's terms are summed as an fp32 tree and the vector sums are accumulated in fp64, so the CDF
-// values are good to fp32 rounding.  (P, mP) is the same sum restricted to v < t.  Vector rounds
+// values are good to fp32 rounding.  (P, with its own reference) is the same sum restricted to v < t.  Vector rounds
 // that lie wholly below the claimed token, wholly above it, and are full need no per-entry test:
 // the prefix is simply a snapshot of Z taken between the two groups of rounds.  Only the round
 // that holds the claimed token and the last, partly filled round look at indices.
@@ -244,7 +249,7 @@ struct IptStream {
     float xt;  // claimed token's raw logit (for the logit rank)
     int tid;
     // running state
-    float m, neg_mc, mP;
+    float m, neg_mc, neg_mcP;
     double Z, P;
     uint32_t above;       // wave-uniform ballot counts (full rounds)
     uint32_t lane_above;  // per-lane counts (careful rounds)
@@ -256,7 +261,7 @@ struct IptStream {
         xt = valid ? Elem<DT>::to_float(x_row[t]) : __builtin_nanf("");
         m = -__builtin_inff();
         neg_mc = __builtin_inff();  // no reference yet: see terms()
-        mP = -__builtin_inff();
+        neg_mcP = __builtin_inff();
         Z = 0.0;
         P = 0.0;
         above = 0;
@@ -299,9 +304,10 @@ struct IptStream {
                 else
                     m8 = max3_raw(max3_raw(x[0], x[1], x[2]), x[3], x[3]);
                 if (m8 > m) {  // (m = -inf: Z is still 0 and stays 0)
-                    Z *= (double)fast_exp2((m - m8) * c);
+                    const float moved = -(m8 * c);
+                    Z *= (double)fast_exp2(moved - neg_mc);  // from the old rounded reference to the new one (see ipt_finish)
                     m = m8;
-                    neg_mc = -(m8 * c);
+                    neg_mc = moved;
                 }
                 // a lane that has met only masked entries keeps m = -inf; its terms are 2^(-inf + 0) = 0
                 const float shift = (m > -__builtin_inff()) ? neg_mc : 0.0f;
@@ -331,8 +337,12 @@ struct IptStream {
     __device__ __forceinline__ void snapshot()
     {
         P = Z;
-        mP = m;
+        neg_mcP = neg_mc;
     }
+
+    // the exponents the sums Z and P were taken against (-inf: no reference yet, the sum is 0), for ipt_finish
+    __device__ __forceinline__ float ref() const { return -neg_mc; }
+    __device__ __forceinline__ float refP() const { return -neg_mcP; }
 
     // a round that needs index tests: the one holding the claimed token and the last, ragged one.
     // `q` must have been loaded for every lane whose first entry v0 is below V.
@@ -358,12 +368,12 @@ struct IptStream {
                 for (int j = 0; j < E; ++j)
                     if (v0 + j < t) pre += e[j];
                 P = Z + (double)pre;
-                mP = m;
+                neg_mcP = neg_mc;
             }
             Z += (double)sum;
         } else if (prefix_open) {
             P = Z;
-            mP = m;
+            neg_mcP = neg_mc;
         }
     }
 

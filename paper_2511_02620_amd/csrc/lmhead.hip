@@ -138,6 +138,13 @@ __global__ __launch_bounds__(kBlock) void lmhead_prepare_kernel(LmHeadBatch b, L
 // ---------------------------------------------------------------------------------
 // Per-lane, per-token running state of the epilogue.
 // ---------------------------------------------------------------------------------
+// The exponent a partial softmax sum with reference logit m is taken against: terms are 2^(x c - ref_exp(m, c)).  A
+// whole number, so that moving a sum from one reference to another is a multiplication by an exact power of two
+// and the many partial sums of a token (lanes, half tiles, vocabulary ranges) stay consistent to the last bit;
+// with m c itself, rounded, every partial sum would sit on a reference that is off by the rounding of ITS product -
+// 1e-6 and more once |m| / T reaches a few tens.
+__device__ __forceinline__ float ref_exp(float m, float c) { return ceilf(m * c); }
+
 struct Slot {
     float best_y;
     int32_t best_v;
@@ -162,7 +169,7 @@ __device__ __forceinline__ uint32_t noise_gate(float L, float cap)
 struct BlockCtx {
     const TokInfo &t;
     float c;       // log2(e) / T
-    float neg_mc;  // -(m c)
+    float neg_mc;  // -ref_exp(m, c)
     float Lgate;   // L minus slack
     uint32_t rgate;
     bool live;     // the lane's token row exists (n < N)
@@ -209,11 +216,11 @@ __device__ __forceinline__ void score_block(const f32x16 acc, Slot &s, BlockCtx 
     if (__builtin_amdgcn_ballot_w64(bm > s.m) != 0ull) {
         asm volatile("" ::: "memory");  // keep this a real, rarely taken branch
         if (bm > s.m) {
-            const double f = (s.m > ninf) ? (double)fast_exp2((s.m - bm) * k.c) : 0.0;
+            const double f = (s.m > ninf) ? (double)fast_exp2(ref_exp(s.m, k.c) - ref_exp(bm, k.c)) : 0.0;
             s.Z *= f;
             s.P *= f;
             s.m = bm;
-            k.neg_mc = -(bm * k.c);
+            k.neg_mc = -ref_exp(bm, k.c);
             refresh_gates(s, k);  // the logit cap of the noise gate has moved
         }
     }
@@ -281,8 +288,8 @@ __device__ __forceinline__ void merge_softmax(float &m, double &Z, double &P, fl
 {
     const float ninf = -__builtin_inff();
     const float M = fmaxf(m, om);
-    const double f = (m > ninf) ? (double)fast_exp2((m - M) * c) : 0.0;
-    const double of = (om > ninf) ? (double)fast_exp2((om - M) * c) : 0.0;
+    const double f = (m > ninf) ? (double)fast_exp2(ref_exp(m, c) - ref_exp(M, c)) : 0.0;
+    const double of = (om > ninf) ? (double)fast_exp2(ref_exp(om, c) - ref_exp(M, c)) : 0.0;
     Z = Z * f + oZ * of;
     P = P * f + oP * of;
     m = M;
@@ -532,7 +539,7 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
             const TokInfo t = tok_from_lds(wt * 128 + jb * 32 + l32);
             BlockCtx k{t, t.inv_T * kLog2e, 0.0f, 0.0f, 0u, tok_is_live(jb),
                        RANK ? __uint_as_float(lds_tok[RANK ? 7 : 0][wt * 128 + jb * 32 + l32]) : 0.0f};
-            k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -(slot[jb].m * k.c) : 0.0f;
+            k.neg_mc = (slot[jb].m > -__builtin_inff()) ? -ref_exp(slot[jb].m, k.c) : 0.0f;
             refresh_gates(slot[jb], k);
             const int32_t vl = (int32_t)v0 + wv * 128 + 4 * lh;
             const double Z_before = slot[jb].Z;
@@ -548,12 +555,12 @@ __global__ __launch_bounds__(kBlock, 1) void lmhead_score_kernel(LmHeadBatch b, 
                 const Slot &s = slot[jb];
                 double mine = s.Z;
                 if (m_before > ninf)
-                    mine -= Z_before * (s.m == m_before ? 1.0 : (double)fast_exp2((m_before - s.m) * k.c));
+                    mine -= Z_before * (s.m == m_before ? 1.0 : (double)fast_exp2(ref_exp(m_before, k.c) - ref_exp(s.m, k.c)));
                 const float ms = mine > 0.0 ? (float)mine : 0.0f, mm = s.m;
                 const float os = __shfl_xor(ms, 32, 64), om = __shfl_xor(mm, 32, 64);
                 const float M = fmaxf(mm, om);
-                const float both = (mm > ninf ? ms * fast_exp2((mm - M) * k.c) : 0.0f) +
-                                   (om > ninf ? os * fast_exp2((om - M) * k.c) : 0.0f);
+                const float both = (mm > ninf ? ms * fast_exp2(ref_exp(mm, k.c) - ref_exp(M, k.c)) : 0.0f) +
+                                   (om > ninf ? os * fast_exp2(ref_exp(om, k.c) - ref_exp(M, k.c)) : 0.0f);
                 if (lh == 0 && tok_is_live(jb)) ws.half_sum[(int64_t)(2 * vt + wv) * b.N + tok_row(jb)] = make_float2(both, M);
             }
         };
@@ -691,7 +698,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
     float a = nan, bb = nan, dd = nan, lm = nan;
     bool match = false;
     if (t.ti >= 0 && !ipt_bad) {
-        const double et = (double)fast_exp2(__fmaf_rn(ws.x_claim_ipt[n], c, -(m * c)));
+        const double et = (double)fast_exp2(__fmaf_rn(ws.x_claim_ipt[n], c, -ref_exp(m, c)));
         const double ud = (double)u;
         const double ad = P / Z, bd = (P + et) / Z;
         a = (float)ad;
@@ -727,7 +734,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_finalize_kernel(LmHeadBatch b, 
             for (int h = 0; h < 2 * n_vt; ++h) {
                 const float2 p = ws.half_sum[(int64_t)h * b.N + n];
                 if (!(p.x > 0.0f)) continue;
-                const double w = (double)p.x * (double)fast_exp2((p.y - m) * c);
+                const double w = (double)p.x * (double)fast_exp2(ref_exp(p.y, c) - ref_exp(m, c));
                 if (cum + w > target) {
                     half = h;
                     rest = target - cum;
@@ -788,7 +795,7 @@ __global__ __launch_bounds__(kBlock) void lmhead_ipt_token_kernel(LmHeadBatch b,
                 }
             }
             dot = wave_sum(dot);
-            e = fast_exp2(__fmaf_rn(dot, c, -(m * c)));
+            e = fast_exp2(__fmaf_rn(dot, c, -ref_exp(m, c)));
             if (!(e == e)) e = 0.0f;
         }
         if (lane == 0) lds_e[r] = e;

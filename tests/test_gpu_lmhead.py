@@ -41,15 +41,18 @@ def _case(S, L, V, d, T=1.0, w_sigma=None):
                                w_sigma=(2.0 / d ** 0.5) if w_sigma is None else w_sigma)
 
 
-def _check_token(tok, oi, x_oracle, T, seeds, seq_ids, positions, flags):
+def _check_token(tok, oi, x_oracle, T, seeds, seq_ids, positions, flags, tie=TIE):
     """The sampler's own Token-IPT-DiFR token of the fused path against the oracle's: equal, or - where the CDF comes
-    within 1e-6 of u at an interval boundary - a token whose oracle interval touches u within that width.  Rows the
-    search was made for carry DIFR_FLAG_SLOW_PATH; rows whose claim matched do not, and their token is the claim."""
+    within `tie` of u at an interval boundary - a token whose oracle interval touches u within that width.  The
+    width is the one the MATCH comparison of this path uses: the logits carry the matrix cores' accumulation error,
+    which moves a CDF step by up to that error over T times the mass below it (on a few thousand tokens it does not
+    average out: 1.2e-6 was seen at V = 2464, d = 384).  Rows the search was made for carry DIFR_FLAG_SLOW_PATH; rows
+    whose claim matched do not, and their token is the claim."""
     differ = np.nonzero(tok != oi["ipt_token"])[0]
     for n in differ:
         Tn = float(T[n]) if np.ndim(T) else float(T)
         alt = oracle.ipt_row(x_oracle[n], Tn, int(seeds[seq_ids[n]]), int(seq_ids[n]), int(positions[n]), int(tok[n]))
-        assert alt["dist"] < parity.TIE_REL and alt["cdf_hi"] > alt["cdf_lo"], (
+        assert alt["dist"] < tie and alt["cdf_hi"] > alt["cdf_lo"], (
             "ipt_token of row %d beyond a near tie: oracle %d, gpu %d, dist %g" % (n, oi["ipt_token"][n], tok[n], alt["dist"]))
     matched = (flags & 1) != 0
     assert not ((flags & 8) != 0)[matched].any() and ((flags & 8) != 0)[~matched & ((flags & 4) == 0)].all()
