@@ -196,3 +196,33 @@ def test_bf16_nan_with_sign_bit_set(difr):
         assert torch.equal(torch.nan_to_num(a.float(), nan=-7.0), torch.nan_to_num(b.float(), nan=-7.0)), k
     for k in fg:                                     # the one-pass call's Token-DiFR side is the same stream
         assert torch.equal(torch.nan_to_num(fg[k].float(), nan=-7.0), torch.nan_to_num(gs[k].float(), nan=-7.0)), k
+
+
+@pytest.mark.parametrize("shift", [-60.0, 75.0])
+@pytest.mark.parametrize("aligned", [True, False])
+def test_cdf_accuracy_with_logits_far_from_zero(difr, shift, aligned):
+    """Logits around -60 or +75 at T = 0.58: x c runs into the hundreds, where the product of a reference logit and c
+    is only good to 1e-5.  The softmax terms are taken against that rounded product, so the lanes have to be combined
+    by the rounded products too: the CDF must stay within a few 1e-7 of the oracle's (it was off by 1.3e-6 when the
+    lanes were combined by the reference logits, enough to flip a MATCH the oracle decides by 1.1e-6)."""
+    N, V, T = 24, 40000, 0.58
+    g = torch.Generator().manual_seed(int(abs(shift)) + aligned)
+    x = torch.randn(N, V, generator=g) * 2.0 + shift
+    ld = V if aligned else V + 3
+    buf = torch.full((N, ld), float("nan"), dtype=torch.bfloat16, device=DEV)
+    buf[:, :V] = x.to(torch.bfloat16).to(DEV)
+    logits = buf if aligned else buf
+    seeds = torch.tensor([5, 1 << 33], dtype=torch.int64).to(DEV)
+    sid = (torch.arange(N) % 2).to(torch.int32).to(DEV)
+    pos = torch.arange(N, dtype=torch.int32).to(DEV)
+    temps = torch.linspace(0.35, 1.4, N).to(DEV)
+    claims = difr.ipt_score(logits, T, seeds, sid, pos, None, V=V, temperatures=temps, want_token=True,
+                            want_interval=False)["ipt_token"]
+    out = difr.ipt_score(logits, T, seeds, sid, pos, claims, V=V, temperatures=temps)
+    torch.cuda.synchronize()
+    host = parity.to_host_logits(logits)
+    ref = oracle.ipt_score(host, V, np.float32(T), parity.seeds_u64(seeds), sid.cpu().numpy(), parity.positions_u32(pos),
+                           claims.cpu().numpy(), temps.cpu().numpy())
+    for name in ("cdf_lo", "cdf_hi"):
+        err = np.abs(out[name].cpu().numpy().astype(np.float64) - ref[name])
+        assert err.max() <= 4e-7, (name, err.max())
