@@ -414,16 +414,35 @@ __device__ __forceinline__ void nucleus_row_multipass(const RowBatch &b, float t
             uint32_t kw[4];
             keys_of(q, kw);
             float below_vec = 0.0f;
+            // whether an entry lies below the claimed token's index is the same for a whole vector, but for the one
+            // vector of the row that holds the claim (and a ragged last one is looked at entry by entry as well)
+            const bool all_below = base + E <= t32;
+            const bool mixed = (!all_below && base < t32) || base + E > V32;
+            if (__builtin_amdgcn_ballot_w64(mixed) == 0ull) {
+                const uint32_t inc = all_below ? 0x10001u : 1u;
 #pragma unroll
-            for (int j = 0; j < E; ++j) {
-                if (base + E > V32 && base + j >= V32) continue;  // (false for every vector but a ragged last one)
-                const uint32_t key = key_of(kw, j);
-                const uint32_t d = key - klo;
-                if (d <= span) {
-                    cnt[(int)d * kBlock + tid] += (base + j < t32) ? 0x10001u : 1u;
-                } else if (key > khi) {
-                    n_above += 1;
-                    if (base + j < t32) below_vec += mass_of(value_of(q, j));
+                for (int j = 0; j < E; ++j) {
+                    const uint32_t key = key_of(kw, j);
+                    const uint32_t d = key - klo;
+                    if (d <= span) {
+                        cnt[(int)d * kBlock + tid] += inc;
+                    } else if (key > khi) {
+                        n_above += 1;
+                        if (all_below) below_vec += mass_of(value_of(q, j));
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < E; ++j) {
+                    if (base + E > V32 && base + j >= V32) continue;  // (a ragged last vector)
+                    const uint32_t key = key_of(kw, j);
+                    const uint32_t d = key - klo;
+                    if (d <= span) {
+                        cnt[(int)d * kBlock + tid] += (base + j < t32) ? 0x10001u : 1u;
+                    } else if (key > khi) {
+                        n_above += 1;
+                        if (base + j < t32) below_vec += mass_of(value_of(q, j));
+                    }
                 }
             }
             below_above += (double)below_vec;
