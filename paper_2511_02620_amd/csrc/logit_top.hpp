@@ -202,11 +202,14 @@ __device__ __forceinline__ int filter_prefix_length(const uint64_t *buf, int nk,
     if (tid == 0) {
         double Z = 0.0;
         for (int r = 0; r < nk; ++r) Z += e[r];
+        // (the cumulative mass against top_p Z: the same cut as the cumulative probability against top_p, except
+        // within a rounding of the boundary, and no division per entry on the one thread everybody waits for)
+        const double target = (double)top_p * Z;
         double cum = 0.0;
         int kept = nk;
         for (int r = 0; r < nk; ++r) {
-            cum += e[r] / Z;
-            if (cum >= (double)top_p) {
+            cum += e[r];
+            if (cum >= target) {
                 kept = r + 1;
                 break;
             }
