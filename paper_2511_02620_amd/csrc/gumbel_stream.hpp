@@ -195,6 +195,7 @@ struct GumbelStream {
     // TOPN mode: this wave's queue of vectors waiting for the per-entry look, and how many wait (wave-uniform)
     int32_t *defer_q;
     int defer_n;
+    uint32_t seen_lo, seen_hi;  // the last vector's extreme bf16 patterns, as far as process<MODE>() formed them
     // PEAKED streams: T (L - g_max - slack), no entry below it can reach L whatever its noise; its bf16 pattern;
     // whether it is <= 0 (always so in gate modes 0 and 2).  Follows the gate: peak_cap() after every change of it.
     float xcap_max;
@@ -239,6 +240,7 @@ struct GumbelStream {
         adm_over = 0;
         defer_q = nullptr;
         defer_n = 0;
+        seen_lo = seen_hi = 0u;
         if (PEAKED) peak_cap();
     }
 
@@ -520,6 +522,8 @@ struct GumbelStream {
                     m = __builtin_elementwise_max(m, as_i16x2(q.w));
                     hi = (uint16_t)(m.x > m.y ? m.x : m.y);
                 }
+                seen_lo = lo;  // (a selection of raw logits that runs beside this stream tests the same extremes)
+                seen_hi = hi;
                 xub = vector_upper_bound<MODE>(lo, hi);
             } else {
                 xub = vector_upper_bound_f32(q);

@@ -146,7 +146,7 @@ __device__ __forceinline__ void likelihood_row(const RowBatch &b, const Likeliho
             g.template process<MODE>(q, r, true, &top_y);
             if (g.defer_n >= 64) g.drain(&top_y);
             if (p.top_k > 0) {
-                lx.note_vector(q, r * kBlock + tid);
+                lx.template note_vector<(DT == 0) ? ((MODE != 1 ? 1 : 0) | (MODE != 0 ? 2 : 0)) : 0>(q, r * kBlock + tid, g.seen_lo, g.seen_hi);
                 if (lx.defer_n >= 64) lx.drain();
             }
         }

@@ -61,20 +61,30 @@ struct LogitTop {
     // The test of push_vector() on vector number `vec` of the row, but a vector that passes is only noted in the
     // wave's queue: a wave in which one or two lanes hold a candidate does not walk the entries for them.  The caller
     // keeps defer_n below 64 between calls (drain() once it is not) and drains before the selection is finished.
-    __device__ __forceinline__ void note_vector(u32x4 q, int32_t vec)
+    // HAVE: which of the vector's extreme bf16 patterns the caller has at hand (bit 0: `lo`, the smallest as
+    // unsigned; bit 1: `hi`, the largest as signed) - the Gumbel stream beside this selection forms them for its own
+    // test; the other one, if needed, is formed here.
+    template <int HAVE = 0>
+    __device__ __forceinline__ void note_vector(u32x4 q, int32_t vec, uint32_t lo = 0u, uint32_t hi = 0u)
     {
         bool hit;
         if (DT == 0) {
             if (floor_pos) {
-                i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
-                m = __builtin_elementwise_max(m, as_i16x2(q.z));
-                m = __builtin_elementwise_max(m, as_i16x2(q.w));
-                hit = (int16_t)(m.x > m.y ? m.x : m.y) >= (int16_t)floor16;
+                if (!(HAVE & 2)) {
+                    i16x2 m = __builtin_elementwise_max(as_i16x2(q.x), as_i16x2(q.y));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.z));
+                    m = __builtin_elementwise_max(m, as_i16x2(q.w));
+                    hi = (uint16_t)(m.x > m.y ? m.x : m.y);
+                }
+                hit = (int16_t)hi >= (int16_t)floor16;
             } else {
-                u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
-                m = __builtin_elementwise_min(m, as_u16x2(q.z));
-                m = __builtin_elementwise_min(m, as_u16x2(q.w));
-                hit = (uint16_t)(m.x < m.y ? m.x : m.y) <= (uint16_t)floor16;
+                if (!(HAVE & 1)) {
+                    u16x2 m = __builtin_elementwise_min(as_u16x2(q.x), as_u16x2(q.y));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.z));
+                    m = __builtin_elementwise_min(m, as_u16x2(q.w));
+                    lo = m.x < m.y ? m.x : m.y;
+                }
+                hit = (uint16_t)lo <= (uint16_t)floor16;
             }
         } else {
             hit = !(__uint_as_float(q.x) < floor) || !(__uint_as_float(q.y) < floor) ||
