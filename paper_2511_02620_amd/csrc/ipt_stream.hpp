@@ -237,6 +237,8 @@ __device__ __forceinline__ bool ipt_row_rejected(const RowInfo &ri, int64_t row,
 // that lie wholly below the claimed token, wholly above it, and are full need no per-entry test:
 // the prefix is simply a snapshot of Z taken between the two groups of rounds.  Only the round
 // that holds the claimed token and the last, partly filled round look at indices.
+constexpr float kRefLift = 16.0f;  // see IptStream::terms()
+
 template <int DT>
 struct IptStream {
     typedef typename Elem<DT>::type elt_t;
@@ -304,7 +306,11 @@ struct IptStream {
                 else
                     m8 = max3_raw(max3_raw(x[0], x[1], x[2]), x[3], x[3]);
                 if (m8 > m) {  // (m = -inf: Z is still 0 and stays 0)
-                    const float moved = -(m8 * c);
+                    // The reference exponent is put kRefLift above the vector's largest: an fp32 exponent is good to
+                    // half a unit in its last place, 1e-6 at 16 and beyond, and the entries that lie far above a
+                    // lane's first vector - the few tokens that carry the mass of a peaked row - are the ones whose
+                    // terms have to be exact; the many small ones below average their roundings out.
+                    const float moved = -(m8 * c + kRefLift);
                     Z *= (double)fast_exp2(moved - neg_mc);  // from the old rounded reference to the new one (see ipt_finish)
                     m = m8;
                     neg_mc = moved;
