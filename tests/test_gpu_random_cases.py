@@ -238,6 +238,59 @@ def run_case(difr, c, rng):
     return dict(k=k, p=p, s=s, delta=delta, M=int(z.shape[0]))
 
 
+def run_case_bare_nucleus(difr, c, rng):
+    """The bare nucleus through the likelihood estimate and the one-pass pair (top_k = 0): the pair against the two single
+    calls bit for bit, tau and pi against the oracle where the cut is not in doubt."""
+    N, V = c["N"], c["V"]
+    a = (c["logits"], c["T"], c["seeds"], c["sid"], c["pos"])
+    kw = dict(temperatures=c["temps"], V=V)
+    cg, ci = claims_for(difr, c, rng)
+    if cg is None:
+        cg = torch.from_numpy(rng.integers(0, V, size=N).astype(np.int32)).to(DEV)
+        ci = cg.clone()
+    p = float(rng.choice([0.95, 0.9, 0.5, 0.999, 0.3]))
+    s = int(rng.choice([1, 4, 16, 64, 100]))
+    z = torch.randn(int(rng.choice([1, 32, 256])), generator=torch.Generator().manual_seed(int(rng.integers(0, 2**31)))).to(DEV)
+    f1 = difr.ipt_score_filtered(*a, ci, top_k=0, top_p=p, want_token=True, want_log_mass=True, sigma=0.02, **kw)
+    l1 = difr.gumbel_likelihood(*a, cg, z, top_k=0, top_p=p, s=s, sigma=0.4, want_active=True, **kw)
+    bl, bf = difr.score_both_filtered(*a, cg, ci, z, top_k=0, top_p=p, s=s, sigma=0.4, want_token=True, want_log_mass=True,
+                                      sigma_ipt=0.02, **kw)
+    eq(bl, l1, "score_both_filtered (k=0) likelihood side")
+    eq(bf, f1, "score_both_filtered (k=0) ipt side")
+    torch.cuda.synchronize()
+    rows = rng.choice(N, size=min(N, 6), replace=False)
+    rows.sort()
+    idx = torch.from_numpy(rows).to(DEV)
+    host = parity.to_host_logits(c["logits"][idx])
+    tnp = None if c["temps"] is None else c["temps"][idx].cpu().numpy()
+    sd, sidn, posn = parity.seeds_u64(c["seeds"]), c["sid"][idx].cpu().numpy(), parity.positions_u32(c["pos"][idx])
+    p32 = float(np.float32(p))
+    zz = z.double().cpu().numpy()
+    def orc(pp):
+        return oracle.likelihood(host, V, np.float32(c["T"]), sd, sidn, posn, cg[idx].cpu().numpy(), 0, pp, s,
+                                 float(np.float32(0.4)), zz, temperatures=tnp)
+    rl, lo, hi = orc(p32), orc(p32 - 2e-6), orc(p32 + 2e-6)
+    fl_ = l1["flags"][idx].cpu().numpy()
+    tau_g = l1["tau"][idx].cpu().numpy()
+    good = (fl_ & 4) == 0
+    t_lo, t_hi = np.minimum(lo["tau"], hi["tau"]).astype(np.float32), np.maximum(lo["tau"], hi["tau"]).astype(np.float32)
+    if not ((tau_g[good] >= t_lo[good]) & (tau_g[good] <= t_hi[good])).all():
+        raise AssertionError("nucleus tau outside the oracle's bracket: %s [%s, %s]" % (tau_g, t_lo, t_hi))
+    finite = np.abs(host[np.isfinite(host)])
+    ymax = (float(finite.max()) if finite.size else 0.0) / (float(c["T"]) if tnp is None else float(tnp.min())) + 17.0
+    gap_ok = rl["gap_s"] > max(1e-5, 4.0 * float(np.spacing(np.float32(ymax))))
+    clear = good & (lo["tau"] == hi["tau"]) & gap_ok
+    pi = l1["pi"][idx].cpu().numpy().astype(np.float64)
+    both_nan = np.isnan(pi) & np.isnan(rl["pi"])
+    err = np.where(both_nan | ~clear, 0.0, np.abs(pi - rl["pi"]))
+    if not (err <= 1e-4).all():
+        raise AssertionError("likelihood (k=0) pi differs: worst %g gpu %s oracle %s" % (err.max(), pi, rl["pi"]))
+    act = l1["active"][idx].cpu().numpy()
+    if not np.array_equal(np.sort(act[clear], axis=1), np.sort(rl["active"][clear], axis=1)):
+        raise AssertionError("likelihood (k=0) active set differs")
+    return dict(p=p, s=s, M=int(z.shape[0]), clear=int(clear.sum()))
+
+
 @pytest.mark.parametrize("case", range(48))
 def test_random_case(difr, case):
     rng = np.random.default_rng(1000 + case)
@@ -265,6 +318,19 @@ def test_random_cases_in_bulk(difr):
         c = make_case(rng)
         try:
             run_case(difr, c, rng)
+        except Exception:
+            print("case", case, c["dtype"], "V", c["V"], "ld", c["ld"], "N", c["N"], c["kind"], "T", c["T"], "claims", c["ck"],
+                  file=sys.stderr, flush=True)
+            raise
+
+
+def test_random_cases_bare_nucleus(difr):
+    """A hundred and fifty draws through the bare nucleus (top_k = 0) of the likelihood estimate and of the one-pass pair."""
+    for case in range(30000, 30150):
+        rng = np.random.default_rng(1000 + case)
+        c = make_case(rng)
+        try:
+            run_case_bare_nucleus(difr, c, rng)
         except Exception:
             print("case", case, c["dtype"], "V", c["V"], "ld", c["ld"], "N", c["N"], c["kind"], "T", c["T"], "claims", c["ck"],
                   file=sys.stderr, flush=True)
