@@ -197,6 +197,37 @@ def test_gaussian_log_mass_multiprecision(oracle_lib):
     assert r["log_mass"] == oracle_lib.gaussian_log_mass(r["cdf_lo"], r["cdf_hi"], r["u"], 0.02, 1e-25)
 
 
+def test_log_mass_of_a_very_improbable_claim_is_limited_by_the_spacing_of_the_cdf(oracle_lib):
+    """The appendix takes a and b from F = concat(0, cumsum p): numbers of size up to 1, held in doubles whose spacing
+    there is 1.1e-16.  For a claimed token of probability w that sits after most of the mass, the interval's width
+    is only known to about one step, so the Gaussian mass - and S = ln(mass + eps) - carries a relative error of up
+    to (a step or two) / w whatever the arithmetic.  This pins the term the GPU comparison allows for it
+    (4.5e-16 / width in tests/parity.py): the oracle's S against the exact value, computed in 60 digits from the
+    exact probabilities, stays within that bound, and at w = 1e-6 the effect is far below the 1e-4 bar."""
+    mpmath.mp.dps = 60
+    T, sigma, eps = 1.0, 0.02, 1e-30
+    worst = {}
+    for w_target in (1e-6, 1e-10, 1e-13, 1e-14):
+        # four tokens: 0.3, 0.5 - w, the claim w, 0.2 (logits = ln p, so that softmax returns them)
+        p = [mpmath.mpf("0.3"), mpmath.mpf("0.5") - mpmath.mpf(w_target), mpmath.mpf(w_target), mpmath.mpf("0.2")]
+        x = np.array([float(mpmath.log(q)) for q in p])
+        e = [mpmath.exp(mpmath.mpf(float(v))) for v in x]     # the distribution of the logits as stored
+        Z = sum(e)
+        a_exact, w_exact = (e[0] + e[1]) / Z, e[2] / Z
+        errs = []
+        for pos in range(40):
+            r = oracle_lib.ipt_row(x, T, 1234, 0, pos, 2, sigma=sigma, eps=eps)
+            u = mpmath.mpf(r["u"])
+            za, zb = (a_exact - u) / sigma, (a_exact + w_exact - u) / sigma
+            want = mpmath.log(mpmath.ncdf(zb) - mpmath.ncdf(za) + mpmath.mpf(eps))
+            errs.append(abs(mpmath.mpf(r["log_mass"]) - want))
+            allowed = mpmath.mpf(4.5e-16) / w_exact + mpmath.mpf(1e-9) * max(1, abs(want))
+            assert errs[-1] <= allowed, (w_target, pos, float(errs[-1]), float(allowed))
+        worst[w_target] = float(max(errs))
+    assert worst[1e-6] < 1e-8                      # nothing to see at ordinary probabilities
+    assert worst[1e-14] > 1e-4                     # ... and at 1e-14 the spacing shows, in the oracle itself
+
+
 def test_pooling_and_flagging(oracle_lib):
     rng = np.random.default_rng(28)
     lens = [5, 0, 17, 1, 300]
