@@ -103,3 +103,27 @@ def test_signed_zeros_are_equal_logits():
     out, *_ = batch(x, 1.0, claims, 0, 0.7)
     assert (out["kept"] == 3).all()
     assert np.allclose(out["cdf_hi"] - out["cdf_lo"], [1 / Z, 1 / Z, 0.0, 0.0], atol=1e-12)
+
+
+def test_a_marginal_token_moves_an_interval_end_by_at_most_one_over_kept():
+    """The members of K are the most probable tokens, so the least probable of them - the one a cut that is in doubt adds
+    or drops - holds at most 1 / |K| of the renormalised mass.  That is what the GPU comparison of the bare nucleus
+    allows an interval end to move by per token in doubt (tests/test_gpu_nucleus.py); here it is checked on the oracle
+    itself, between neighbouring values of top_p, on rows of ties (where the bound is attained) and on ordinary rows."""
+    rng = np.random.default_rng(8)
+    N, V = 12, 900
+    rows = {"constant": np.full((N, V), -1.25), "coarse": np.round(rng.normal(0, 2, (N, V)) * 2) / 2,
+            "normal": rng.normal(0, 2, (N, V))}
+    claims = rng.integers(0, V, N).astype(np.int32)
+    checked = 0
+    for name, x in rows.items():
+        for p in (0.3, 0.9, 0.99):
+            base, *_ = batch(x, 0.9, claims, 0, p)
+            for q in (p - 0.004, p + 0.004):
+                other, *_ = batch(x, 0.9, claims, 0, q)
+                dk = np.abs(other["kept"] - base["kept"])
+                room = dk / np.minimum(other["kept"], base["kept"]) + 1e-12
+                for end in ("cdf_lo", "cdf_hi"):
+                    assert (np.abs(other[end] - base[end]) <= room).all(), (name, p, q, end)
+                checked += int((dk > 0).sum())
+    assert checked > 20      # the neighbouring cuts did differ
